@@ -1,0 +1,309 @@
+"""Pins for the CPU oracle: everything here is fixed by mathematics or by values the paper prints,
+never by the oracle's own output."""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import l2l_oracle as O
+
+RNG = np.random.default_rng(7)
+EPS = 1e-5
+
+
+def tiny_model(H=8, A=2, F=16, S=4, V=11, L=2, rng=RNG):
+    def n(*s):
+        return rng.normal(0, 0.3, s)
+    layers = []
+    for _ in range(L):
+        layers.append({"Wqkv": n(H, 3 * H), "bqkv": n(3 * H), "Wo": n(H, H), "bo": n(H),
+                       "g1": 1 + n(H), "be1": n(H), "W1": n(H, F), "b1": n(F),
+                       "W2": n(F, H), "b2": n(H), "g2": 1 + n(H), "be2": n(H)})
+    emb = {"E": n(V, H), "P": n(S, H), "ge": 1 + n(H), "be": n(H), "bv": n(V)}
+    return emb, layers
+
+
+def golden():
+    path = os.path.join(os.path.dirname(__file__), "golden", "paper_facts.txt")
+    out = {}
+    for line in open(path):
+        line = line.split("#")[0].strip()
+        if line:
+            k, v = line.split("=")
+            out[k.strip()] = v.strip()
+    return out
+
+
+# ----------------------------------------------------------------------------- closed forms
+def test_gelu_closed_forms():
+    u = np.linspace(-6, 6, 241)
+    assert O.gelu(np.array([0.0]))[0] == 0.0
+    assert O.gelu_grad(np.array([0.0]))[0] == 0.5
+    np.testing.assert_allclose(O.gelu(u) - O.gelu(-u), u, atol=1e-14)
+    ref = np.array([0.5 * x * (1 + math.erf(x / math.sqrt(2))) for x in u])
+    np.testing.assert_allclose(O.gelu(u), ref, atol=1e-15)
+    h = 1e-6
+    np.testing.assert_allclose(O.gelu_grad(u), (O.gelu(u + h) - O.gelu(u - h)) / (2 * h), atol=1e-9)
+    # differs from the tanh approximation (guards against using the wrong form)
+    tanh_form = 0.5 * u * (1 + np.tanh(math.sqrt(2 / math.pi) * (u + 0.044715 * u ** 3)))
+    assert np.abs(O.gelu(u) - tanh_form).max() > 1e-4
+
+
+def test_softmax_closed_forms():
+    s = RNG.normal(size=(3, 5, 7))
+    p = O.softmax_rows(s)
+    np.testing.assert_allclose(p.sum(-1), 1.0, atol=1e-15)
+    np.testing.assert_allclose(O.softmax_rows(s + 1000.0), p, atol=1e-13)
+    np.testing.assert_allclose(O.softmax_rows(np.zeros((2, 4))), 0.25)
+
+
+def test_layernorm_closed_forms():
+    H = 16
+    r = RNG.normal(size=(5, H)) * 3 + 1
+    y, (xhat, rstd) = O.layer_norm_fwd(r, np.ones(H), np.zeros(H), 1e-12)
+    np.testing.assert_allclose(y.mean(-1), 0, atol=1e-14)
+    var = r.var(axis=-1)
+    np.testing.assert_allclose(y.var(axis=-1), var / (var + 1e-12), rtol=1e-12)
+    y2, _ = O.layer_norm_fwd(r * 7.5, np.ones(H), np.zeros(H), 0.0)
+    y0, _ = O.layer_norm_fwd(r, np.ones(H), np.zeros(H), 0.0)
+    np.testing.assert_allclose(y2, y0, atol=1e-12)
+    g, b = RNG.normal(size=H), RNG.normal(size=H)
+    yg, _ = O.layer_norm_fwd(r, g, b, 1e-12)
+    np.testing.assert_allclose(yg, y * g + b, atol=1e-13)
+    dy = RNG.normal(size=(5, H))
+    dr, dg, db = O.layer_norm_bwd(dy, (xhat, rstd), g)
+    np.testing.assert_allclose(dr.sum(-1), 0, atol=1e-13)
+    np.testing.assert_allclose((dr * xhat).sum(-1), 0, atol=1e-11)    # exact only as eps/var -> 0
+    np.testing.assert_allclose(db, dy.sum(0), atol=1e-14)
+
+
+def test_attention_uniform_when_q_zero():
+    H, A, S = 8, 2, 5
+    emb, (p, _) = tiny_model(H=H, A=A, S=S)
+    p = dict(p)
+    p["Wqkv"] = p["Wqkv"].copy()
+    p["bqkv"] = p["bqkv"].copy()
+    p["Wqkv"][:, :H] = 0
+    p["bqkv"][:H] = 0
+    X = RNG.normal(size=(2, S, H))
+    _, c = O.encoder_layer_fwd(X, p, A, EPS)
+    np.testing.assert_allclose(c["P"], 1.0 / S, atol=1e-15)
+    v = X @ p["Wqkv"][:, 2 * H:] + p["bqkv"][2 * H:]
+    np.testing.assert_allclose(c["C"], np.broadcast_to(v.mean(axis=1, keepdims=True), v.shape), atol=1e-14)
+
+
+def test_layer_reduces_to_double_layernorm():
+    H, A, S = 8, 2, 4
+    _, (p, _) = tiny_model(H=H, A=A, S=S)
+    p = {k: v.copy() for k, v in p.items()}
+    for k in ("Wo", "bo", "W1", "b1", "W2", "b2"):
+        p[k][...] = 0
+    X = RNG.normal(size=(3, S, H))
+    Y, _ = O.encoder_layer_fwd(X, p, A, EPS)
+
+    def ln(r, g, b):
+        mu = r.mean(-1, keepdims=True)
+        return g * (r - mu) / np.sqrt(r.var(-1, keepdims=True) + EPS) + b
+    np.testing.assert_allclose(Y, ln(ln(X, p["g1"], p["be1"]), p["g2"], p["be2"]), atol=1e-13)
+
+
+def test_layer_single_head_single_token_is_gemm_chain():
+    # A = 1, S = 1: softmax over one key is 1, so attention is X Wv Wo -- checked by plain loops
+    H, F = 6, 10
+    _, (p, _) = tiny_model(H=H, A=1, F=F, S=1)
+    X = RNG.normal(size=(4, 1, H))
+    _, c = O.encoder_layer_fwd(X, p, 1, EPS)
+    Wv, bv = p["Wqkv"][:, 2 * H:], p["bqkv"][2 * H:]
+    for b in range(4):
+        v = [sum(X[b, 0, i] * Wv[i, j] for i in range(H)) + bv[j] for j in range(H)]
+        np.testing.assert_allclose(c["C"][b, 0], v, atol=1e-14)
+        r1 = [X[b, 0, j] + sum(v[i] * p["Wo"][i, j] for i in range(H)) + p["bo"][j] for j in range(H)]
+        r1 = np.array(r1)
+        y1 = p["g1"] * (r1 - r1.mean()) / math.sqrt(r1.var() + EPS) + p["be1"]
+        np.testing.assert_allclose(c["Y1"][b, 0], y1, atol=1e-13)
+
+
+def test_head_layout_matches_per_head_loops():
+    # brute force attention for one sequence with explicit head slicing of the fused QKV output
+    H, A, S = 8, 2, 3
+    d = H // A
+    _, (p, _) = tiny_model(H=H, A=A, S=S)
+    X = RNG.normal(size=(1, S, H))
+    _, c = O.encoder_layer_fwd(X, p, A, EPS)
+    qkv = X[0] @ p["Wqkv"] + p["bqkv"]
+    for h in range(A):
+        q = qkv[:, h * d:(h + 1) * d]
+        k = qkv[:, H + h * d:H + (h + 1) * d]
+        v = qkv[:, 2 * H + h * d:2 * H + (h + 1) * d]
+        for s in range(S):
+            w = np.array([math.exp(sum(q[s, j] * k[t, j] for j in range(d)) / math.sqrt(d)) for t in range(S)])
+            w /= w.sum()
+            np.testing.assert_allclose(c["C"][0, s, h * d:(h + 1) * d], w @ v, atol=1e-14)
+
+
+def test_cross_entropy_closed_forms():
+    emb, _ = tiny_model(V=11)
+    emb = {k: v.copy() for k, v in emb.items()}
+    emb["E"][...] = 0
+    emb["bv"][...] = 0
+    x = RNG.normal(size=(2, 4, 8))
+    lab = RNG.integers(0, 11, size=(2, 4))
+    lab[0, 1] = -1
+    loss, dx, g = O.head_loss(x, lab, emb, int((lab >= 0).sum()))
+    assert abs(loss - math.log(11)) < 1e-14
+    emb2, _ = tiny_model(V=11)
+    loss, dx, g = O.head_loss(x, lab, emb2, 7)
+    assert np.all(dx[0, 1] == 0)
+    assert abs(g["bv"].sum()) < 1e-14           # rows of dz sum to zero
+
+
+def test_paper_sizes():
+    g = golden()
+    H, F, S = int(g["bert_large_hidden"]), int(g["bert_large_ffn"]), int(g["bert_large_max_seq"])
+    assert O.boundary_activation_bytes(S, H, 2) == int(g["boundary_activation_bytes_per_sample"])
+    L = int(g["bert_large_layers"])
+    total = L * O.layer_param_count(H, F) + 30522 * H + 512 * H
+    assert abs(total / 1e6 - float(g["bert_large_params_millions"])) < 20     # "350M" to the paper's rounding
+    assert O.layer_param_count(H, F) == 12596224
+    for n_layers, bill in zip(map(int, g["table5_layers"].split()), map(float, g["table5_params_billions"].split())):
+        assert abs(n_layers * O.layer_param_count(H, F) / 1e9 - bill) < 0.06 * bill + 0.01
+
+
+def test_timing_model():
+    g = golden()
+    u = int(g["overhead_example_u"])
+    assert O.transfer_overhead(u, 1.0, 1.0, training=False) <= float(g["overhead_example_bound"]) + 1e-15
+    assert O.transfer_overhead(u, 1.0, 1.0, training=True) < float(g["overhead_example_bound"])
+    assert O.total_time_ms(24, 1, 2.0, 3.0) == 24 * (4 * 2.0 + 2 * 3.0)        # Eq. 1 is Eq. 4 at u = 1
+    assert O.total_time_ms(24, 4, 2.0, 3.0) == 24 * (16 * 2.0 + 2 * 3.0)
+    assert abs(O.throughput_training(24, 4, 64, 2.0, 3.0) - 1000 * 256 / (24 * 38.0)) < 1e-9
+    assert O.throughput_forward(24, 4, 64, 2.0, 0.0) == pytest.approx(1000 * 64 / (24 * 2.0))
+
+
+# ----------------------------------------------------------------------------- finite differences
+def _loss_of(emb, layers, tok, lab, A):
+    n_lab = int((lab >= 0).sum())
+    x, _ = O.embed_fwd(tok, emb, EPS)
+    for p in layers:
+        x, _ = O.encoder_layer_fwd(x, p, A, EPS)
+    return O.head_loss(x, lab, emb, n_lab)[0]
+
+
+def test_all_gradients_by_finite_differences():
+    H, A, F, S, V, L = 8, 2, 16, 4, 11, 2
+    rng = np.random.default_rng(3)
+    emb, layers = tiny_model(H, A, F, S, V, L, rng)
+    tok = rng.integers(0, V, size=(2, S))
+    lab = rng.integers(0, V, size=(2, S))
+    lab[1, 2] = -1
+    loss, gemb, glayers = O.run_conventional(emb, layers, tok[None], lab[None], A, EPS)
+    assert abs(loss - _loss_of(emb, layers, tok, lab, A)) < 1e-13
+    h = 1e-5
+    groups = [("emb", emb, gemb)] + [(f"layer{l}", layers[l], glayers[l]) for l in range(L)]
+    for gname, params, grads in groups:
+        for k, w in params.items():
+            num = np.zeros_like(w)
+            it = np.nditer(w, flags=["multi_index"])
+            for _ in it:
+                i = it.multi_index
+                old = w[i]
+                w[i] = old + h
+                lp = _loss_of(emb, layers, tok, lab, A)
+                w[i] = old - h
+                lm = _loss_of(emb, layers, tok, lab, A)
+                w[i] = old
+                num[i] = (lp - lm) / (2 * h)
+            err = np.linalg.norm(num - grads[k]) / max(np.linalg.norm(num), 1e-30)
+            assert err < 2e-7, (gname, k, err)
+
+
+def test_layer_input_gradient_by_finite_differences():
+    H, A, F, S = 8, 2, 16, 4
+    rng = np.random.default_rng(5)
+    _, (p, _) = tiny_model(H, A, F, S, rng=rng)
+    X = rng.normal(size=(2, S, H))
+    Wt = rng.normal(size=(2, S, H))
+    Y, c = O.encoder_layer_fwd(X, p, A, EPS)
+    dX, _ = O.encoder_layer_bwd(Wt, c, p, A)
+    num = np.zeros_like(X)
+    h = 1e-6
+    for i in np.ndindex(*X.shape):
+        old = X[i]
+        X[i] = old + h
+        lp = (O.encoder_layer_fwd(X, p, A, EPS)[0] * Wt).sum()
+        X[i] = old - h
+        lm = (O.encoder_layer_fwd(X, p, A, EPS)[0] * Wt).sum()
+        X[i] = old
+        num[i] = (lp - lm) / (2 * h)
+    assert np.linalg.norm(num - dX) / np.linalg.norm(num) < 1e-7
+
+
+# ----------------------------------------------------------------------------- the L2L invariant
+@pytest.mark.parametrize("U", [1, 2, 4, 8])
+def test_l2l_equals_conventional_equals_concatenated(U):
+    H, A, F, S, V, L = 16, 4, 32, 6, 23, 3
+    rng = np.random.default_rng(11)
+    emb, layers = tiny_model(H, A, F, S, V, L, rng)
+    B = 8
+    tok = rng.integers(0, V, size=(B, S))
+    lab = np.where(rng.random((B, S)) < 0.4, rng.integers(0, V, size=(B, S)), -1)
+    ref = O.run_conventional(emb, layers, tok[None], lab[None], A, EPS)          # one concatenated minibatch
+    tu, lu = tok.reshape(U, B // U, S), lab.reshape(U, B // U, S)
+    for res in (O.run_conventional(emb, layers, tu, lu, A, EPS), O.run_l2l(emb, layers, tu, lu, A, EPS)):
+        assert abs(res[0] - ref[0]) < 1e-12
+        for k in ref[1]:
+            np.testing.assert_allclose(res[1][k], ref[1][k], atol=1e-12)
+        for a, b in zip(res[2], ref[2]):
+            for k in b:
+                np.testing.assert_allclose(a[k], b[k], atol=1e-12)
+
+
+def test_layer_l2l_helpers_match_drivers():
+    H, A, F, S = 8, 2, 16, 4
+    rng = np.random.default_rng(13)
+    _, (p, _) = tiny_model(H, A, F, S, rng=rng)
+    X = rng.normal(size=(3, 2, S, H))
+    dY = rng.normal(size=(3, 2, S, H))
+    Y = O.layer_l2l_fwd(X, p, A, EPS)
+    Yc, c = O.encoder_layer_fwd(X.reshape(6, S, H), p, A, EPS)
+    np.testing.assert_allclose(Y.reshape(6, S, H), Yc, atol=1e-14)
+    dX, g = O.layer_l2l_bwd(X, dY, p, A, EPS)
+    dXc, gc = O.encoder_layer_bwd(dY.reshape(6, S, H), c, p, A)
+    np.testing.assert_allclose(dX.reshape(6, S, H), dXc, atol=1e-13)
+    for k in gc:
+        np.testing.assert_allclose(g[k], gc[k], atol=1e-12)
+
+
+# ----------------------------------------------------------------------------- Adam and bf16
+def test_adam_closed_forms():
+    g = np.array([0.3, -2.0, 0.0, 1e-3])
+    w = np.array([1.0, 2.0, 3.0, 4.0])
+    z = np.zeros(4)
+    lr, e = 1e-4, 1e-8
+    w1, m1, v1 = O.adam_step(w, g, z, z, 1, lr=lr, eps_a=e)
+    np.testing.assert_allclose(w1 - w, -lr * g / (np.abs(g) + e), rtol=1e-9, atol=1e-15)
+    assert w1[2] == w[2]
+    w2, m2, v2 = O.adam_step(w1, g, m1, v1, 2, lr=lr, eps_a=e)
+    np.testing.assert_allclose(np.abs(w2 - w1)[[0, 1, 3]], lr, rtol=1e-4)
+    np.testing.assert_allclose(m2, (1 - 0.9 ** 2) * g, rtol=1e-12)
+    np.testing.assert_allclose(v2, (1 - 0.999 ** 2) * g * g, rtol=1e-12)
+
+
+def test_bf16_exhaustive_round_trip_and_ties():
+    bits = np.arange(65536, dtype=np.uint16)
+    f = O.bf16_to_f32(bits)
+    finite = np.isfinite(f)
+    assert np.array_equal(O.bf16_bits(f[finite]), bits[finite])
+    assert np.all(np.isnan(O.bf16_to_f32(O.bf16_bits(f[np.isnan(f)]))))
+    # midpoints between neighbouring bf16 values go to the even pattern
+    def f32(u):
+        return np.array([u], np.uint32).view(np.float32)
+    assert O.bf16_bits(f32(0x3F808000))[0] == 0x3F80      # 1 + 2^-8 : tie, lower is even
+    assert O.bf16_bits(f32(0x3F818000))[0] == 0x3F82      # tie, upper is even
+    assert O.bf16_bits(f32(0x3F808001))[0] == 0x3F81      # just above the tie
+    assert O.bf16_bits(f32(0x3F807FFF))[0] == 0x3F80
+    assert O.bf16_bits(f32(0x7F7FFFFF))[0] == 0x7F80      # rounds up to infinity
+    x = np.random.default_rng(0).normal(size=1000).astype(np.float32)
+    r = O.bf16_round(x)
+    assert np.all(np.abs(r - x) <= np.abs(x) * 2.0 ** -8)
