@@ -1,0 +1,133 @@
+"""Benchmark of the L2L hot path on one MI355X: train samples/s of the BERT-Large-shaped workload
+(24 layers, hidden 1024, 16 heads, FFN 4096, seq 128, vocab 30522; device batch 256 = 8 micro-batches
+of 32; bf16 with fp32 accumulation; host EPS Adam), synthetic data, random-init weights.
+
+One step = embedding -> 24 x (param stage, layer forward over all micro-batches) -> head + loss ->
+24 x (param stage, layer backward with recompute, grad drain) -> embedding backward -> host Adam.
+Prints one JSON line (see README for the fields)."""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0       # MI355X dense bf16 MFMA
+
+
+def cpu_baseline(w, budget_s=20.0):
+    """The CPU oracle, untuned, on a bounded sample of the same workload: one encoder layer's
+    forward + backward-with-recompute over one micro-batch, scaled by layers x micro-batches."""
+    import numpy as np
+    import l2l_synth as S
+    from oracle import l2l_oracle as O
+    ub = w.ubatch
+    while True:
+        ws = w.scaled(num_ubatches=1, ubatch=ub)
+        p = {k: O.bf16_round(v).astype(np.float64) for k, v in S.layer_params(ws, 0).items()}
+        X = S.activations(ws).astype(np.float64)
+        dY = S.output_grads(ws).astype(np.float64)
+        t0 = time.perf_counter()
+        O.layer_l2l_fwd(X, p, w.heads, 1e-12)
+        O.layer_l2l_bwd(X, dY, p, w.heads, 1e-12)
+        dt = time.perf_counter() - t0
+        if dt <= budget_s or ub == 1:
+            break
+        ub = max(1, ub // 4)
+    step_s = dt * w.layers * w.num_ubatches * (w.ubatch / ub)
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count()
+    return {"value": w.num_ubatches * w.ubatch / step_s, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"1 encoder layer fwd + bwd-with-recompute on 1 micro-batch of {ub} sequences ({dt:.2f} s), "
+                      f"scaled by {w.layers} layers x {w.num_ubatches} micro-batches x {w.ubatch // ub}; "
+                      "embedding, head and Adam not included"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="workload index (2 = BERT-Large, the headline)")
+    ap.add_argument("--group", type=int, default=0, help="micro-batches per kernel launch (0 = library default)")
+    ap.add_argument("--stash", default="device", choices=["device", "host"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layers", type=int, default=0, help="override depth (memory-vs-depth sweeps)")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+
+    import torch
+    import l2l_synth as S
+    from paper_2002_05645_amd.trainer import L2LTrainer
+
+    w = S.WORKLOADS[a.config]
+    if a.layers:
+        w = w.scaled(layers=a.layers)
+    tr = L2LTrainer(layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, vocab=w.vocab,
+                    ubatch=w.ubatch, num_ubatches=w.num_ubatches, dtype=w.dtype, ubatch_group=a.group, stash=a.stash)
+    tr.load_params(S.embed_params(w), [S.layer_params(w, l) for l in range(w.layers)])
+    tok, lab = S.tokens_and_labels(w)
+    tok, lab = torch.from_numpy(tok).cuda(), torch.from_numpy(lab).cuda()
+
+    loss0 = None
+    for _ in range(a.warmup):
+        loss = tr.step(tok, lab)
+        loss0 = loss if loss0 is None else loss0
+    torch.cuda.synchronize()
+
+    # timed region: K full steps; the GEMM launches are bracketed by HIP events on the compute stream
+    tr.ctx.profile(1)
+    dev_s = 0.0
+    adam_s = 0.0
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        t1 = time.perf_counter()
+        tr.device_pipeline(tok, lab)
+        loss = tr.finish()
+        t2 = time.perf_counter()
+        tr.optimizer_step()
+        t3 = time.perf_counter()
+        dev_s += t2 - t1
+        adam_s += t3 - t2
+    torch.cuda.synchronize()
+    total_s = time.perf_counter() - t0
+    prof = tr.ctx.profile_read()
+    tr.ctx.profile(0)
+
+    samples = w.num_ubatches * w.ubatch
+    ms_step = 1e3 * total_s / a.steps
+    g = prof["gemm"]
+    achieved = g["flops"] / (g["ms"] * 1e-3) / 1e12 if g["ms"] > 0 else 0.0
+    peak_mem = torch.cuda.max_memory_allocated() + tr.ctx.device_bytes()
+    out = {
+        "metric": "train samples/sec, BERT-Large L2L batch 256", "value": samples * a.steps / total_s,
+        "unit": "samples/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if w.dtype == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: L={w.layers} H={w.hidden} A={w.heads} F={w.ffn} S={w.seq} V={w.vocab} "
+                               f"U={w.num_ubatches} x ub={w.ubatch}", "stash": a.stash, "ubatch_group": tr.ctx.cfg.ubatch_group,
+                   "device_pipeline_samples_per_s": samples * a.steps / dev_s, "device_pipeline_ms": 1e3 * dev_s / a.steps,
+                   "host_adam_ms": 1e3 * adam_s / a.steps, "loss_first": loss0, "loss_last": loss,
+                   "peak_device_bytes": int(peak_mem), "ctx_device_bytes": int(tr.ctx.device_bytes()),
+                   "kernel_ms_per_step": {k: v["ms"] / a.steps for k, v in prof.items()},
+                   "kernel_launches_per_step": {k: v["launches"] / a.steps for k, v in prof.items()}},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "kernel": "gemm_mfma_kernel (all layer GEMMs of the step)",
+                     "avg_launch_us": 1e3 * g["ms"] / max(g["launches"], 1),
+                     "flops_per_launch": g["flops"] / max(g["launches"], 1)},
+    }
+    tr.close()
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

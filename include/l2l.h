@@ -1,0 +1,200 @@
+/*
+ * l2l.h -- C ABI of the L2L (layer-to-layer) relay-execution device library for MI355X (gfx950).
+ *
+ * The library runs the hot path of L2L execution (Algorithm 2, Section 2.1-2.2 of the paper): one
+ * transformer encoder layer at a time is resident on the device and runs its forward pass -- and its
+ * backward pass with the layer forward recomputed from the stashed boundary activation -- across
+ * all U micro-batches of the minibatch, while the next layer's parameters stream in from the host
+ * eager param-server (EPS) and the finished layer's gradients stream out.
+ *
+ * Conventions
+ *  - Every function returns L2L_OK (0) or a negative l2l_status; nothing throws or aborts.
+ *    l2l_last_error() gives a human-readable message for the last failure on that context.
+ *  - "device pointer" = memory of the GPU the context was created on (e.g. a torch tensor's
+ *    data_ptr()); "host pointer" = CPU memory, pinned where stated.  The caller owns every buffer it
+ *    passes in; the context owns the two parameter slots, the gradient accumulators and the
+ *    per-launch workspace.
+ *  - All device work is enqueued on the two streams given to l2l_create: kernels on
+ *    `compute_stream`, host<->device copies on `copy_stream`; ordering between them is by events
+ *    inside the library.  No call blocks the host except l2l_sync, l2l_drain_wait, l2l_embed_drain_wait
+ *    and l2l_create/l2l_destroy.
+ *  - Tensors are row-major, token-major.  T = ubatch * seq tokens per micro-batch.  In dtype
+ *    L2L_BF16 activations and parameters are bfloat16 with fp32 accumulation everywhere; in
+ *    L2L_F32 everything is fp32.  Gradients of parameters are always accumulated in fp32.
+ *
+ * Packed parameter block of one encoder layer (one contiguous DMA, Section 2.1 "receives each
+ * layer's weights from EPS one at a time"), in elements of the configured dtype, every sub-block
+ * starting at a multiple of 128 elements:
+ *     Wqkv[H,3H] | bqkv[3H] | Wo[H,H] | bo[H] | g1[H] | be1[H] | W1[H,F] | b1[F] | W2[F,H] | b2[H] | g2[H] | be2[H]
+ * Weight matrices are [in, out] row-major (y = x W + b).  The Q, K and V projections are the three
+ * H-wide column groups of Wqkv; head h owns columns h*d .. h*d+d-1 of its group.  The gradient block
+ * uses the same order and offsets in fp32.  Padding elements must be zero in parameters and are
+ * zero in gradients.
+ *
+ * Packed embedding / head block:  E[V,H] | Ppos[S,H] | ge[H] | be[H] | bv[V]   (same alignment rule).
+ */
+#ifndef L2L_H
+#define L2L_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  L2L_OK = 0,
+  L2L_E_ARG = -1,    /* null pointer, bad index, unsupported shape */
+  L2L_E_STATE = -2,  /* call out of order (slot never staged, nothing to drain, ...) */
+  L2L_E_HIP = -3,    /* a HIP runtime call failed; message carries the HIP error string */
+  L2L_E_NOMEM = -4
+} l2l_status;
+
+enum { L2L_F32 = 0, L2L_BF16 = 1 };
+
+typedef struct l2l_ctx l2l_ctx;
+
+typedef struct {
+  int hidden;        /* H; multiple of 8 */
+  int heads;         /* A; H % A == 0 and d = H / A a multiple of 8 */
+  int ffn;           /* F; multiple of 8 */
+  int seq;           /* S; multiple of 8 */
+  int ubatch;        /* ub: sequences per micro-batch */
+  int num_ubatches;  /* U */
+  int dtype;         /* L2L_F32 or L2L_BF16 */
+  float ln_eps;      /* LayerNorm epsilon */
+  int vocab;         /* V; 0 = no embedding / head buffers */
+  int ubatch_group;  /* micro-batches handed to one kernel launch (rows are independent, so this
+                        changes launch shape and workspace size only); 0 = library default */
+} l2l_config;
+
+/* ---- sizes (host-only, usable without a GPU) --------------------------------------------------- */
+/* Number of tensors in the layer block (12) / embedding block (5). */
+int    l2l_layer_tensor_count(void);
+int    l2l_embed_tensor_count(void);
+/* Element offset / element count / name of tensor `i` inside the packed block. Negative or NULL on
+   a bad index or config. */
+long long   l2l_layer_tensor_offset(const l2l_config*, int i);
+long long   l2l_layer_tensor_size(const l2l_config*, int i);
+const char* l2l_layer_tensor_name(int i);
+long long   l2l_embed_tensor_offset(const l2l_config*, int i);
+long long   l2l_embed_tensor_size(const l2l_config*, int i);
+const char* l2l_embed_tensor_name(int i);
+/* P_l = 4H^2 + 2HF + 9H + F (unpadded parameter count of a layer). */
+size_t l2l_layer_param_count(const l2l_config*);
+/* Elements / bytes of the packed (padded) blocks. grad bytes are fp32. */
+size_t l2l_layer_packed_elems(const l2l_config*);
+size_t l2l_layer_param_bytes(const l2l_config*);
+size_t l2l_layer_grad_bytes(const l2l_config*);
+size_t l2l_embed_packed_elems(const l2l_config*);
+size_t l2l_embed_param_bytes(const l2l_config*);
+size_t l2l_embed_grad_bytes(const l2l_config*);
+/* Returns L2L_OK if the config is supported, else L2L_E_ARG. */
+int    l2l_config_check(const l2l_config*);
+
+/* ---- context ----------------------------------------------------------------------------------- */
+/* compute_stream / copy_stream: hipStream_t handles (may be the same; NULL = the null stream).
+   Allocates slots, accumulators and workspace on the current device. */
+int  l2l_create(const l2l_config*, void* compute_stream, void* copy_stream, l2l_ctx** out);
+int  l2l_destroy(l2l_ctx*);
+/* Device bytes owned by the context (slots + accumulators + workspace): depth-independent. */
+size_t l2l_device_bytes(const l2l_ctx*);
+const char* l2l_last_error(const l2l_ctx*);
+int  l2l_sync(l2l_ctx*);  /* host blocks until both streams are idle */
+
+/* ---- the four calls of the relay (Algorithm 2; Section 2.1) -------------------------------------- */
+
+/* Param stage: asynchronous host->device copy, on copy_stream, of one layer's packed parameters
+   (l2l_layer_param_bytes bytes, host pointer, pinned for the copy to overlap compute) into device
+   slot 0 or 1.  The copy is ordered after every kernel that still reads the slot. `layer` >= 0 is a
+   tag used to match later fwd/bwd calls. */
+int l2l_param_stage(l2l_ctx*, int layer, const void* host_params, int slot);
+
+/* Layer forward over all U micro-batches (inner loop of Algorithm 2's forward phase).
+   x_stash: device, U contiguous [ub, S, H] blocks = the layer's input (stash of layer-1's output).
+   y_out:   device, same shape = this layer's boundary output (the next stash entry).
+   Ordered after the slot's stage; x_stash and y_out must not overlap. */
+int l2l_layer_fwd(l2l_ctx*, int layer, int slot, const void* x_stash, void* y_out);
+
+/* Layer backward over all U micro-batches with layer-forward recompute (Section 2.1).
+   x_stash: as above.  dy_dx: device, U x [ub,S,H]; holds dL/dY on entry and dL/dX on return
+   (in place).  The layer's parameter gradients are summed over the U micro-batches into a
+   context-owned fp32 accumulator that starts from zero at this call. */
+int l2l_layer_bwd(l2l_ctx*, int layer, int slot, const void* x_stash, void* dy_dx);
+
+/* Grad drain: asynchronous device->host copy, on copy_stream, of the gradients accumulated by the
+   last l2l_layer_bwd(layer) (l2l_layer_grad_bytes bytes, fp32, packed order) into host memory
+   (pinned to overlap), ordered after that backward.  The accumulator is reusable once the copy
+   lands; two accumulators alternate so the next layer's backward need not wait. */
+int l2l_grad_drain(l2l_ctx*, int layer, void* host_grads);
+int l2l_drain_wait(l2l_ctx*, int layer);   /* host blocks until that drain has landed */
+
+/* ---- first and last resident "layers": embedding and tied LM head (Section 2.1: "a 3 layer model") */
+/* Async H2D of the packed embedding block (pinned host pointer) on copy_stream. */
+int l2l_embed_stage(l2l_ctx*, const void* host_embed_params);
+/* x0[u][b,s] = LN_e(E[tok] + Ppos[s]).  tokens: device int32 [U, ub, S]; x_out: device U x [ub,S,H].
+   Zeroes the embedding-block gradient accumulator (start of a step). */
+int l2l_embed_fwd(l2l_ctx*, const int32_t* tokens, void* x_out);
+/* Tied head + cross-entropy, forward and backward, over all micro-batches:
+   z = x E^T + bv at positions with label >= 0; loss = -(1/N) sum log softmax(z)[label], N = labelled
+   positions of the whole minibatch.  labels: device int32 [U, ub, S] (-1 = ignore).
+   dy_out: device U x [ub,S,H], receives dL/dx (zero at unlabelled positions).
+   loss_out: device float[1].  Adds dE and dbv into the embedding-block accumulator. */
+int l2l_head_loss(l2l_ctx*, const void* x_last, const int32_t* labels, void* dy_out, float* loss_out);
+/* Backward of l2l_embed_fwd: adds dE (scatter-add over token ids), dPpos, dge, dbe into the
+   embedding-block accumulator.  dy: device U x [ub,S,H] (read only). */
+int l2l_embed_bwd(l2l_ctx*, const int32_t* tokens, const void* dy);
+/* Async D2H of the embedding-block gradients (fp32, packed) into host memory, after the above. */
+int l2l_embed_grad_drain(l2l_ctx*, void* host_grads);
+int l2l_embed_drain_wait(l2l_ctx*);
+
+/* ---- profiling: HIP-event timing of kernel classes on the compute stream ---------------------- */
+enum { L2L_PROF_GEMM = 0, L2L_PROF_ATTN = 1, L2L_PROF_ROWWISE = 2, L2L_PROF_COLSUM = 3, L2L_PROF_OTHER = 4,
+       L2L_PROF_CLASSES = 5 };
+/* on != 0: every launch is bracketed by events (slows the host side); counters are reset. */
+int l2l_profile(l2l_ctx*, int on);
+/* Resolves pending events and returns, for one class: launches, total milliseconds, total
+   algorithmic flops and bytes of those launches. */
+int l2l_profile_read(l2l_ctx*, int cls, long long* launches, double* ms, double* flops, double* bytes);
+
+/* ---- single operations, for kernel-level parity tests and micro-benchmarks --------------------- */
+/* C[M,N] = epilogue(alpha * A B), device pointers, on compute_stream.
+   a_kc: 1 = A stored [M,K] (K contiguous, row stride lda); 0 = A stored [K,M] (row stride lda).
+   b_kc: 1 = B stored [N,K] (row stride ldb); 0 = B stored [K,N].
+   in_dtype: dtype of A, B, bias, resid;  out_f32: 1 = C is fp32, else in_dtype.
+   bias: [N] or NULL; resid: [M,N] with row stride ldc or NULL; accumulate: C += result (needs out_f32).
+   gelu: apply GELU after the bias.  impl: 0 = library's choice, 1 = force the plain kernel,
+   2 = force the MFMA kernel (L2L_E_ARG if the shape does not allow it). */
+int l2l_op_gemm(l2l_ctx*, int in_dtype, int out_f32, int a_kc, int b_kc, int M, int N, int K,
+                const void* A, long long lda, const void* B, long long ldb, void* C, long long ldc,
+                float alpha, const void* bias, const void* resid, int gelu, int accumulate, int impl);
+/* y = LN(x) rows of length n; mean/rstd: device float[rows] or NULL. */
+int l2l_op_layernorm(l2l_ctx*, int dtype, int rows, int n, const void* x, const void* gamma,
+                     const void* beta, float eps, void* y, float* mean, float* rstd);
+
+/* ---- host EPS (Section 2.1, 2.3): fp32 master weights + Adam on host cores ---------------------- */
+typedef struct eps_store eps_store;
+/* n_blocks parameter blocks with elems[i] packed elements each.  ship_dtype: dtype of the copy that
+   is shipped to the device.  Allocates, per block: fp32 master, m, v (pageable) and the shipping
+   copy + fp32 gradient landing buffer (pinned).  threads: worker threads for Adam (<=0: all cores). */
+int   eps_create(int n_blocks, const size_t* elems, int ship_dtype, int threads, eps_store** out);
+int   eps_destroy(eps_store*);
+float* eps_master(eps_store*, int block);      /* fp32 master weights (host) */
+void*  eps_ship(eps_store*, int block);        /* pinned shipping copy in ship_dtype */
+float* eps_grad(eps_store*, int block);        /* pinned fp32 gradient landing buffer */
+float* eps_moment(eps_store*, int block, int which); /* Adam m (0) or v (1) */
+/* master -> shipping copy (round to nearest even for bf16) for blocks [first, last]. */
+int   eps_refresh_ship(eps_store*, int first, int last);
+/* One bias-corrected Adam step (no weight decay) on blocks [first, last] from their landing
+   buffers, then refreshes their shipping copies.  t >= 1 is the step number. */
+int   eps_adam_step(eps_store*, int first, int last, int t, double lr, double beta1, double beta2, double eps_a);
+size_t eps_host_bytes(const eps_store*);
+/* 1 if the shipping and landing buffers are pinned (a GPU was visible at eps_create), else 0: without
+   a GPU the store still works as host logic on ordinary memory. */
+int   eps_is_pinned(const eps_store*);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* L2L_H */

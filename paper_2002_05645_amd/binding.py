@@ -1,0 +1,291 @@
+"""ctypes binding of libl2l.so: argument marshalling only, same names as include/l2l.h.
+
+Every step of the path runs inside the library's HIP kernels; this module fails loudly if the
+library has not been built (python -m paper_2002_05645_amd.build)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libl2l.so")
+
+L2L_OK, L2L_E_ARG, L2L_E_STATE, L2L_E_HIP, L2L_E_NOMEM = 0, -1, -2, -3, -4
+L2L_F32, L2L_BF16 = 0, 1
+PROF_GEMM, PROF_ATTN, PROF_ROWWISE, PROF_COLSUM, PROF_OTHER = range(5)
+PROF_NAMES = ("gemm", "attn", "rowwise", "colsum", "other")
+
+
+class l2l_config(C.Structure):
+    _fields_ = [("hidden", C.c_int), ("heads", C.c_int), ("ffn", C.c_int), ("seq", C.c_int),
+                ("ubatch", C.c_int), ("num_ubatches", C.c_int), ("dtype", C.c_int),
+                ("ln_eps", C.c_float), ("vocab", C.c_int), ("ubatch_group", C.c_int)]
+
+
+class L2LError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"l2l error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+_P = C.c_void_p
+_CFGP = C.POINTER(l2l_config)
+_SIGS = {
+    "l2l_layer_tensor_count": (C.c_int, []),
+    "l2l_embed_tensor_count": (C.c_int, []),
+    "l2l_layer_tensor_offset": (C.c_longlong, [_CFGP, C.c_int]),
+    "l2l_layer_tensor_size": (C.c_longlong, [_CFGP, C.c_int]),
+    "l2l_layer_tensor_name": (C.c_char_p, [C.c_int]),
+    "l2l_embed_tensor_offset": (C.c_longlong, [_CFGP, C.c_int]),
+    "l2l_embed_tensor_size": (C.c_longlong, [_CFGP, C.c_int]),
+    "l2l_embed_tensor_name": (C.c_char_p, [C.c_int]),
+    "l2l_layer_param_count": (C.c_size_t, [_CFGP]),
+    "l2l_layer_packed_elems": (C.c_size_t, [_CFGP]),
+    "l2l_layer_param_bytes": (C.c_size_t, [_CFGP]),
+    "l2l_layer_grad_bytes": (C.c_size_t, [_CFGP]),
+    "l2l_embed_packed_elems": (C.c_size_t, [_CFGP]),
+    "l2l_embed_param_bytes": (C.c_size_t, [_CFGP]),
+    "l2l_embed_grad_bytes": (C.c_size_t, [_CFGP]),
+    "l2l_config_check": (C.c_int, [_CFGP]),
+    "l2l_create": (C.c_int, [_CFGP, _P, _P, C.POINTER(_P)]),
+    "l2l_destroy": (C.c_int, [_P]),
+    "l2l_device_bytes": (C.c_size_t, [_P]),
+    "l2l_last_error": (C.c_char_p, [_P]),
+    "l2l_sync": (C.c_int, [_P]),
+    "l2l_param_stage": (C.c_int, [_P, C.c_int, _P, C.c_int]),
+    "l2l_layer_fwd": (C.c_int, [_P, C.c_int, C.c_int, _P, _P]),
+    "l2l_layer_bwd": (C.c_int, [_P, C.c_int, C.c_int, _P, _P]),
+    "l2l_grad_drain": (C.c_int, [_P, C.c_int, _P]),
+    "l2l_drain_wait": (C.c_int, [_P, C.c_int]),
+    "l2l_embed_stage": (C.c_int, [_P, _P]),
+    "l2l_embed_fwd": (C.c_int, [_P, _P, _P]),
+    "l2l_head_loss": (C.c_int, [_P, _P, _P, _P, _P]),
+    "l2l_embed_bwd": (C.c_int, [_P, _P, _P]),
+    "l2l_embed_grad_drain": (C.c_int, [_P, _P]),
+    "l2l_embed_drain_wait": (C.c_int, [_P]),
+    "l2l_profile": (C.c_int, [_P, C.c_int]),
+    "l2l_profile_read": (C.c_int, [_P, C.c_int, C.POINTER(C.c_longlong), C.POINTER(C.c_double),
+                                   C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+    "l2l_op_gemm": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _P, C.c_longlong,
+                              _P, C.c_longlong, _P, C.c_longlong, C.c_float, _P, _P, C.c_int, C.c_int, C.c_int]),
+    "l2l_op_layernorm": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, _P, _P, _P, C.c_float, _P, _P, _P]),
+    "eps_create": (C.c_int, [C.c_int, C.POINTER(C.c_size_t), C.c_int, C.c_int, C.POINTER(_P)]),
+    "eps_destroy": (C.c_int, [_P]),
+    "eps_master": (C.POINTER(C.c_float), [_P, C.c_int]),
+    "eps_ship": (_P, [_P, C.c_int]),
+    "eps_grad": (C.POINTER(C.c_float), [_P, C.c_int]),
+    "eps_moment": (C.POINTER(C.c_float), [_P, C.c_int, C.c_int]),
+    "eps_refresh_ship": (C.c_int, [_P, C.c_int, C.c_int]),
+    "eps_adam_step": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_double, C.c_double, C.c_double, C.c_double]),
+    "eps_host_bytes": (C.c_size_t, [_P]),
+    "eps_is_pinned": (C.c_int, [_P]),
+}
+EXPORTS = tuple(_SIGS)
+
+
+def lib():
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2002_05645_amd.build` "
+                              "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGS.items():
+            f = getattr(L, name)
+            f.restype, f.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+def make_config(hidden, heads, ffn, seq, ubatch, num_ubatches, dtype, ln_eps=1e-12, vocab=0, ubatch_group=0):
+    d = {"fp32": L2L_F32, "bf16": L2L_BF16}.get(dtype, dtype)
+    return l2l_config(hidden, heads, ffn, seq, ubatch, num_ubatches, d, ln_eps, vocab, ubatch_group)
+
+
+def layer_layout(cfg):
+    """{name: (element offset, element count)} of the packed layer block."""
+    L = lib()
+    return {L.l2l_layer_tensor_name(i).decode(): (L.l2l_layer_tensor_offset(C.byref(cfg), i),
+                                                   L.l2l_layer_tensor_size(C.byref(cfg), i))
+            for i in range(L.l2l_layer_tensor_count())}
+
+
+def embed_layout(cfg):
+    L = lib()
+    return {L.l2l_embed_tensor_name(i).decode(): (L.l2l_embed_tensor_offset(C.byref(cfg), i),
+                                                   L.l2l_embed_tensor_size(C.byref(cfg), i))
+            for i in range(L.l2l_embed_tensor_count())}
+
+
+def _ptr(x):
+    """Address of a torch tensor, a numpy array, an int, or None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    if isinstance(x, np.ndarray):
+        return x.ctypes.data
+    return C.cast(x, C.c_void_p).value
+
+
+class Context:
+    """Owner of one l2l_ctx.  Methods mirror the C entry points one to one."""
+
+    def __init__(self, cfg, compute_stream=0, copy_stream=0):
+        self.cfg = cfg
+        self._h = _P()
+        rc = lib().l2l_create(C.byref(cfg), compute_stream or None, copy_stream or None, C.byref(self._h))
+        if rc != L2L_OK:
+            msg = lib().l2l_last_error(self._h).decode() if self._h else "l2l_create failed (bad config or no GPU)"
+            if self._h:
+                lib().l2l_destroy(self._h)
+                self._h = _P()
+            raise L2LError(rc, msg)
+
+    def close(self):
+        if self._h:
+            lib().l2l_destroy(self._h)
+            self._h = _P()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _ck(self, rc):
+        if rc != L2L_OK:
+            raise L2LError(rc, lib().l2l_last_error(self._h).decode())
+
+    def device_bytes(self):
+        return lib().l2l_device_bytes(self._h)
+
+    def sync(self):
+        self._ck(lib().l2l_sync(self._h))
+
+    def param_stage(self, layer, host_params, slot):
+        self._ck(lib().l2l_param_stage(self._h, layer, _ptr(host_params), slot))
+
+    def layer_fwd(self, layer, slot, x_stash, y_out):
+        self._ck(lib().l2l_layer_fwd(self._h, layer, slot, _ptr(x_stash), _ptr(y_out)))
+
+    def layer_bwd(self, layer, slot, x_stash, dy_dx):
+        self._ck(lib().l2l_layer_bwd(self._h, layer, slot, _ptr(x_stash), _ptr(dy_dx)))
+
+    def grad_drain(self, layer, host_grads):
+        self._ck(lib().l2l_grad_drain(self._h, layer, _ptr(host_grads)))
+
+    def drain_wait(self, layer):
+        self._ck(lib().l2l_drain_wait(self._h, layer))
+
+    def embed_stage(self, host_embed):
+        self._ck(lib().l2l_embed_stage(self._h, _ptr(host_embed)))
+
+    def embed_fwd(self, tokens, x_out):
+        self._ck(lib().l2l_embed_fwd(self._h, _ptr(tokens), _ptr(x_out)))
+
+    def head_loss(self, x_last, labels, dy_out, loss_out):
+        self._ck(lib().l2l_head_loss(self._h, _ptr(x_last), _ptr(labels), _ptr(dy_out), _ptr(loss_out)))
+
+    def embed_bwd(self, tokens, dy):
+        self._ck(lib().l2l_embed_bwd(self._h, _ptr(tokens), _ptr(dy)))
+
+    def embed_grad_drain(self, host_grads):
+        self._ck(lib().l2l_embed_grad_drain(self._h, _ptr(host_grads)))
+
+    def embed_drain_wait(self):
+        self._ck(lib().l2l_embed_drain_wait(self._h))
+
+    def profile(self, on):
+        self._ck(lib().l2l_profile(self._h, int(on)))
+
+    def profile_read(self):
+        """{class name: dict(launches, ms, flops, bytes)}"""
+        out = {}
+        for i, name in enumerate(PROF_NAMES):
+            n, ms, fl, by = C.c_longlong(), C.c_double(), C.c_double(), C.c_double()
+            self._ck(lib().l2l_profile_read(self._h, i, C.byref(n), C.byref(ms), C.byref(fl), C.byref(by)))
+            out[name] = dict(launches=n.value, ms=ms.value, flops=fl.value, bytes=by.value)
+        return out
+
+    def op_gemm(self, in_dtype, out_f32, a_kc, b_kc, M, N, K, A, lda, B, ldb, Cm, ldc, alpha=1.0, bias=None,
+                resid=None, gelu=False, accumulate=False, impl=0):
+        self._ck(lib().l2l_op_gemm(self._h, in_dtype, int(out_f32), int(a_kc), int(b_kc), M, N, K, _ptr(A), lda,
+                                   _ptr(B), ldb, _ptr(Cm), ldc, alpha, _ptr(bias), _ptr(resid), int(gelu),
+                                   int(accumulate), impl))
+
+    def op_layernorm(self, dtype, rows, n, x, gamma, beta, eps, y, mean=None, rstd=None):
+        self._ck(lib().l2l_op_layernorm(self._h, dtype, rows, n, _ptr(x), _ptr(gamma), _ptr(beta), eps, _ptr(y),
+                                        _ptr(mean), _ptr(rstd)))
+
+
+class EPS:
+    """Host eager param-server store: numpy views over the library's host buffers."""
+
+    def __init__(self, elems, ship_dtype, threads=0):
+        self.elems = [int(e) for e in elems]
+        self.ship_dtype = {"fp32": L2L_F32, "bf16": L2L_BF16}.get(ship_dtype, ship_dtype)
+        arr = (C.c_size_t * len(self.elems))(*self.elems)
+        self._h = _P()
+        rc = lib().eps_create(len(self.elems), arr, self.ship_dtype, threads, C.byref(self._h))
+        if rc != L2L_OK:
+            raise L2LError(rc, "eps_create failed")
+
+    def close(self):
+        if self._h:
+            lib().eps_destroy(self._h)
+            self._h = _P()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _f32(self, p, n):
+        return np.ctypeslib.as_array(p, shape=(n,))
+
+    def master(self, i):
+        return self._f32(lib().eps_master(self._h, i), self.elems[i])
+
+    def grad(self, i):
+        return self._f32(lib().eps_grad(self._h, i), self.elems[i])
+
+    def moment(self, i, which):
+        return self._f32(lib().eps_moment(self._h, i, which), self.elems[i])
+
+    def ship_ptr(self, i):
+        return lib().eps_ship(self._h, i)
+
+    def grad_ptr(self, i):
+        return C.cast(lib().eps_grad(self._h, i), C.c_void_p).value
+
+    def ship(self, i):
+        p = lib().eps_ship(self._h, i)
+        if self.ship_dtype == L2L_BF16:
+            return np.ctypeslib.as_array(C.cast(p, C.POINTER(C.c_uint16)), shape=(self.elems[i],))
+        return np.ctypeslib.as_array(C.cast(p, C.POINTER(C.c_float)), shape=(self.elems[i],))
+
+    def refresh_ship(self, first=0, last=None):
+        last = len(self.elems) - 1 if last is None else last
+        rc = lib().eps_refresh_ship(self._h, first, last)
+        if rc != L2L_OK:
+            raise L2LError(rc, "eps_refresh_ship")
+
+    def adam_step(self, first, last, t, lr=1e-4, beta1=0.9, beta2=0.999, eps_a=1e-8):
+        rc = lib().eps_adam_step(self._h, first, last, t, lr, beta1, beta2, eps_a)
+        if rc != L2L_OK:
+            raise L2LError(rc, "eps_adam_step")
+
+    def host_bytes(self):
+        return lib().eps_host_bytes(self._h)
+
+    def is_pinned(self):
+        return bool(lib().eps_is_pinned(self._h))

@@ -1,0 +1,240 @@
+// Host eager param-server (EPS): the model and the optimizer live in host DRAM (Section 2.1); the
+// device only ever sees one layer's shipping copy.  fp32 master weights and Adam moments stay on the
+// host, the optimizer runs on host cores, and a reduced-precision copy is what gets shipped
+// (cross mixed precision, Section 2.3, with bf16 in place of FP16).
+#include <hip/hip_runtime_api.h>
+
+#include <atomic>
+#include <cmath>
+#include <condition_variable>
+#include <cstdlib>
+#include <cstring>
+#include <functional>
+#include <mutex>
+#include <thread>
+#include <vector>
+
+#include "../../include/l2l.h"
+
+namespace {
+
+// Persistent worker pool: run(n, f) calls f(begin, end) on disjoint chunks of [0, n).
+class Pool {
+ public:
+  explicit Pool(int threads) : n_(threads) {
+    for (int i = 1; i < n_; ++i) workers_.emplace_back([this, i] { loop(i); });
+  }
+  ~Pool() {
+    {
+      std::lock_guard<std::mutex> l(mu_);
+      stop_ = true;
+      ++epoch_;
+    }
+    cv_.notify_all();
+    for (auto& t : workers_) t.join();
+  }
+  int size() const { return n_; }
+  void run(size_t n, const std::function<void(size_t, size_t)>& f) {
+    if (n_ == 1 || n < 65536) { f(0, n); return; }
+    {
+      std::lock_guard<std::mutex> l(mu_);
+      fn_ = &f;
+      total_ = n;
+      pending_ = n_ - 1;
+      ++epoch_;
+    }
+    cv_.notify_all();
+    chunk(0);
+    std::unique_lock<std::mutex> l(mu_);
+    done_.wait(l, [this] { return pending_ == 0; });
+    fn_ = nullptr;
+  }
+
+ private:
+  void chunk(int i) {
+    // chunk boundaries on multiples of 16 elements so that vector loops stay aligned
+    const size_t per = ((total_ + n_ - 1) / n_ + 15) / 16 * 16;
+    const size_t b = std::min(total_, per * i), e = std::min(total_, b + per);
+    if (b < e) (*fn_)(b, e);
+  }
+  void loop(int i) {
+    unsigned seen = 0;
+    for (;;) {
+      {
+        std::unique_lock<std::mutex> l(mu_);
+        cv_.wait(l, [&] { return epoch_ != seen; });
+        seen = epoch_;
+        if (stop_) return;
+      }
+      chunk(i);
+      std::lock_guard<std::mutex> l(mu_);
+      if (--pending_ == 0) done_.notify_one();
+    }
+  }
+  int n_;
+  std::vector<std::thread> workers_;
+  std::mutex mu_;
+  std::condition_variable cv_, done_;
+  const std::function<void(size_t, size_t)>* fn_ = nullptr;
+  size_t total_ = 0;
+  int pending_ = 0;
+  unsigned epoch_ = 0;
+  bool stop_ = false;
+};
+
+struct Block {
+  size_t n = 0;
+  bool pinned = false;
+  float *w = nullptr, *m = nullptr, *v = nullptr;  // pageable
+  void* ship = nullptr;                             // pinned
+  float* grad = nullptr;                            // pinned
+};
+
+inline uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u;
+  std::memcpy(&u, &f, 4);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // quiet NaN
+  return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+
+}  // namespace
+
+struct eps_store {
+  std::vector<Block> blocks;
+  int ship_dtype = L2L_BF16;
+  Pool* pool = nullptr;
+  size_t host_bytes = 0;
+  bool pinned = false;
+};
+
+static void ship_range(const eps_store* e, const Block& b, size_t lo, size_t hi) {
+  if (e->ship_dtype == L2L_BF16) {
+    uint16_t* d = (uint16_t*)b.ship;
+    for (size_t i = lo; i < hi; ++i) d[i] = f32_to_bf16_rne(b.w[i]);
+  } else {
+    std::memcpy((float*)b.ship + lo, b.w + lo, (hi - lo) * sizeof(float));
+  }
+}
+
+extern "C" {
+
+int eps_create(int n_blocks, const size_t* elems, int ship_dtype, int threads, eps_store** out) {
+  if (!out || !elems || n_blocks <= 0 || (ship_dtype != L2L_F32 && ship_dtype != L2L_BF16)) return L2L_E_ARG;
+  *out = nullptr;
+  if (threads <= 0) threads = (int)std::thread::hardware_concurrency();
+  if (threads <= 0) threads = 1;
+  eps_store* e = new eps_store;
+  e->ship_dtype = ship_dtype;
+  e->blocks.resize(n_blocks);
+  {
+    int ndev = 0;
+    e->pinned = hipGetDeviceCount(&ndev) == hipSuccess && ndev > 0;
+    if (!e->pinned) (void)hipGetLastError();
+  }
+  const size_t se = ship_dtype == L2L_BF16 ? 2 : 4;
+  for (int i = 0; i < n_blocks; ++i) {
+    Block& b = e->blocks[i];
+    b.n = elems[i];
+    const size_t fb = (b.n * 4 + 63) / 64 * 64;
+    b.w = (float*)aligned_alloc(64, fb);
+    b.m = (float*)aligned_alloc(64, fb);
+    b.v = (float*)aligned_alloc(64, fb);
+    bool ok = b.w && b.m && b.v;
+    if (ok && e->pinned) {
+      ok = hipHostMalloc(&b.ship, b.n * se, hipHostMallocDefault) == hipSuccess;
+      if (ok) ok = hipHostMalloc((void**)&b.grad, b.n * 4, hipHostMallocDefault) == hipSuccess;
+      b.pinned = true;
+    } else if (ok) {  // no GPU in this process: plain host memory (host-side logic still works)
+      b.ship = aligned_alloc(64, (b.n * se + 63) / 64 * 64);
+      b.grad = (float*)aligned_alloc(64, fb);
+      ok = b.ship && b.grad;
+    }
+    if (!ok) {
+      (void)hipGetLastError();
+      eps_destroy(e);
+      return L2L_E_NOMEM;
+    }
+    std::memset(b.w, 0, b.n * 4);
+    std::memset(b.m, 0, b.n * 4);
+    std::memset(b.v, 0, b.n * 4);
+    std::memset(b.ship, 0, b.n * se);
+    std::memset(b.grad, 0, b.n * 4);
+    e->host_bytes += 3 * fb + b.n * se + b.n * 4;
+  }
+  e->pool = new Pool(threads);
+  *out = e;
+  return L2L_OK;
+}
+
+int eps_destroy(eps_store* e) {
+  if (!e) return L2L_E_ARG;
+  delete e->pool;
+  for (Block& b : e->blocks) {
+    free(b.w);
+    free(b.m);
+    free(b.v);
+    if (b.pinned) {
+      if (b.ship) (void)hipHostFree(b.ship);
+      if (b.grad) (void)hipHostFree(b.grad);
+    } else {
+      free(b.ship);
+      free(b.grad);
+    }
+  }
+  delete e;
+  return L2L_OK;
+}
+
+static Block* blk(eps_store* e, int i) {
+  if (!e || i < 0 || i >= (int)e->blocks.size()) return nullptr;
+  return &e->blocks[i];
+}
+float* eps_master(eps_store* e, int i) { Block* b = blk(e, i); return b ? b->w : nullptr; }
+void* eps_ship(eps_store* e, int i) { Block* b = blk(e, i); return b ? b->ship : nullptr; }
+float* eps_grad(eps_store* e, int i) { Block* b = blk(e, i); return b ? b->grad : nullptr; }
+float* eps_moment(eps_store* e, int i, int which) {
+  Block* b = blk(e, i);
+  if (!b || (which != 0 && which != 1)) return nullptr;
+  return which == 0 ? b->m : b->v;
+}
+size_t eps_host_bytes(const eps_store* e) { return e ? e->host_bytes : 0; }
+int eps_is_pinned(const eps_store* e) { return e && e->pinned ? 1 : 0; }
+
+int eps_refresh_ship(eps_store* e, int first, int last) {
+  if (!e || first < 0 || last >= (int)e->blocks.size() || first > last) return L2L_E_ARG;
+  for (int i = first; i <= last; ++i) {
+    const Block& b = e->blocks[i];
+    e->pool->run(b.n, [&](size_t lo, size_t hi) { ship_range(e, b, lo, hi); });
+  }
+  return L2L_OK;
+}
+
+int eps_adam_step(eps_store* e, int first, int last, int t, double lr_d, double beta1_d, double beta2_d, double eps_a_d) {
+  if (!e || first < 0 || last >= (int)e->blocks.size() || first > last || t < 1) return L2L_E_ARG;
+  // hyper-parameters arrive in double so that 1 - beta is rounded once, not computed in fp32
+  const float lr = (float)lr_d, beta1 = (float)beta1_d, beta2 = (float)beta2_d, eps_a = (float)eps_a_d;
+  const float omb1 = (float)(1.0 - beta1_d), omb2 = (float)(1.0 - beta2_d);
+  const float c1 = (float)(1.0 / (1.0 - std::pow(beta1_d, t)));
+  const float c2 = (float)(1.0 / (1.0 - std::pow(beta2_d, t)));
+  for (int i = first; i <= last; ++i) {
+    const Block& b = e->blocks[i];
+    e->pool->run(b.n, [&](size_t lo, size_t hi) {
+      float* __restrict w = b.w;
+      float* __restrict m = b.m;
+      float* __restrict v = b.v;
+      const float* __restrict g = b.grad;
+      for (size_t k = lo; k < hi; ++k) {
+        const float gk = g[k];
+        const float mk = beta1 * m[k] + omb1 * gk;
+        const float vk = beta2 * v[k] + omb2 * gk * gk;
+        m[k] = mk;
+        v[k] = vk;
+        w[k] -= lr * (mk * c1) / (std::sqrt(vk * c2) + eps_a);
+      }
+      ship_range(e, b, lo, hi);
+    });
+  }
+  return L2L_OK;
+}
+
+}  // extern "C"

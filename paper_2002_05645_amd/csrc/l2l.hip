@@ -1,0 +1,908 @@
+// C ABI of the L2L relay-execution library (see include/l2l.h): context, param stage / grad drain
+// pipeline, and the per-layer forward / backward schedules over all U micro-batches (Algorithm 2).
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+#include "../../include/l2l.h"
+#include "gemm.h"
+#include "rowwise.h"
+
+// ================================================================================================
+// packed layouts (host only)
+// ================================================================================================
+namespace {
+
+constexpr long long ALIGN = 128;  // elements
+inline long long up(long long x, long long a) { return (x + a - 1) / a * a; }
+
+enum { T_WQKV, T_BQKV, T_WO, T_BO, T_G1, T_BE1, T_W1, T_B1, T_W2, T_B2, T_G2, T_BE2, N_LAYER_T };
+enum { E_E, E_P, E_GE, E_BE, E_BV, N_EMBED_T };
+const char* kLayerNames[N_LAYER_T] = {"Wqkv", "bqkv", "Wo", "bo", "g1", "be1", "W1", "b1", "W2", "b2", "g2", "be2"};
+const char* kEmbedNames[N_EMBED_T] = {"E", "P", "ge", "be", "bv"};
+
+struct Layout {
+  long long size[N_LAYER_T], off[N_LAYER_T], total;
+  long long esize[N_EMBED_T], eoff[N_EMBED_T], etotal;
+};
+
+bool config_ok(const l2l_config* c) {
+  if (!c) return false;
+  if (c->hidden <= 0 || c->heads <= 0 || c->ffn <= 0 || c->seq <= 0 || c->ubatch <= 0 || c->num_ubatches <= 0) return false;
+  if (c->hidden % 8 || c->ffn % 8 || c->seq % 8) return false;
+  if (c->hidden % c->heads || (c->hidden / c->heads) % 8) return false;
+  if (c->dtype != L2L_F32 && c->dtype != L2L_BF16) return false;
+  if (c->vocab < 0 || c->vocab % 2) return false;
+  if (c->ubatch_group < 0 || c->ubatch_group > c->num_ubatches) return false;
+  if (!(c->ln_eps >= 0.f)) return false;
+  if ((long long)c->ubatch * c->seq * c->num_ubatches > (1LL << 30)) return false;
+  return true;
+}
+
+Layout make_layout(const l2l_config* c) {
+  Layout L;
+  const long long H = c->hidden, F = c->ffn, V = c->vocab, S = c->seq;
+  const long long s[N_LAYER_T] = {H * 3 * H, 3 * H, H * H, H, H, H, H * F, F, F * H, H, H, H};
+  long long o = 0;
+  for (int i = 0; i < N_LAYER_T; ++i) { L.size[i] = s[i]; L.off[i] = o; o = up(o + s[i], ALIGN); }
+  L.total = o;
+  const long long es[N_EMBED_T] = {V * H, S * H, H, H, V};
+  o = 0;
+  for (int i = 0; i < N_EMBED_T; ++i) { L.esize[i] = es[i]; L.eoff[i] = o; o = up(o + es[i], ALIGN); }
+  L.etotal = o;
+  return L;
+}
+
+inline size_t esize(int dtype) { return dtype == L2L_BF16 ? 2 : 4; }
+
+}  // namespace
+
+extern "C" {
+int l2l_layer_tensor_count(void) { return N_LAYER_T; }
+int l2l_embed_tensor_count(void) { return N_EMBED_T; }
+long long l2l_layer_tensor_offset(const l2l_config* c, int i) {
+  return (!config_ok(c) || i < 0 || i >= N_LAYER_T) ? -1 : make_layout(c).off[i];
+}
+long long l2l_layer_tensor_size(const l2l_config* c, int i) {
+  return (!config_ok(c) || i < 0 || i >= N_LAYER_T) ? -1 : make_layout(c).size[i];
+}
+const char* l2l_layer_tensor_name(int i) { return (i < 0 || i >= N_LAYER_T) ? nullptr : kLayerNames[i]; }
+long long l2l_embed_tensor_offset(const l2l_config* c, int i) {
+  return (!config_ok(c) || i < 0 || i >= N_EMBED_T) ? -1 : make_layout(c).eoff[i];
+}
+long long l2l_embed_tensor_size(const l2l_config* c, int i) {
+  return (!config_ok(c) || i < 0 || i >= N_EMBED_T) ? -1 : make_layout(c).esize[i];
+}
+const char* l2l_embed_tensor_name(int i) { return (i < 0 || i >= N_EMBED_T) ? nullptr : kEmbedNames[i]; }
+size_t l2l_layer_param_count(const l2l_config* c) {
+  if (!config_ok(c)) return 0;
+  const size_t H = c->hidden, F = c->ffn;
+  return 4 * H * H + 2 * H * F + 9 * H + F;
+}
+size_t l2l_layer_packed_elems(const l2l_config* c) { return config_ok(c) ? (size_t)make_layout(c).total : 0; }
+size_t l2l_layer_param_bytes(const l2l_config* c) { return config_ok(c) ? (size_t)make_layout(c).total * esize(c->dtype) : 0; }
+size_t l2l_layer_grad_bytes(const l2l_config* c) { return config_ok(c) ? (size_t)make_layout(c).total * 4 : 0; }
+size_t l2l_embed_packed_elems(const l2l_config* c) { return config_ok(c) ? (size_t)make_layout(c).etotal : 0; }
+size_t l2l_embed_param_bytes(const l2l_config* c) { return config_ok(c) ? (size_t)make_layout(c).etotal * esize(c->dtype) : 0; }
+size_t l2l_embed_grad_bytes(const l2l_config* c) { return config_ok(c) ? (size_t)make_layout(c).etotal * 4 : 0; }
+int l2l_config_check(const l2l_config* c) { return config_ok(c) ? L2L_OK : L2L_E_ARG; }
+}
+
+// ================================================================================================
+// context
+// ================================================================================================
+struct ProfRec {
+  hipEvent_t a, b;
+  int cls;
+  double flops, bytes;
+};
+
+struct l2l_ctx {
+  l2l_config cfg;
+  Layout lay;
+  hipStream_t cs = nullptr, xs = nullptr;  // compute, copy
+  int group = 1;                            // micro-batches per launch
+  long long T = 0, Mg = 0;                  // tokens per micro-batch, rows per launch group
+  size_t dev_bytes = 0;
+  std::vector<void*> allocs;
+
+  // parameter slots
+  void* slot[2] = {nullptr, nullptr};
+  int slot_layer[2] = {-1, -1};
+  hipEvent_t slot_staged[2] = {}, slot_released[2] = {};
+  // gradient accumulators
+  float* gacc[2] = {nullptr, nullptr};
+  int gacc_layer[2] = {-1, -1};
+  int gacc_state[2] = {0, 0};  // 0 free, 1 holds un-drained grads, 2 drain enqueued
+  hipEvent_t gacc_ready[2] = {}, gacc_drained[2] = {};
+  int gacc_next = 0;
+
+  // workspace (group-sized)
+  void *qkv, *p, *c, *r1, *y1, *u1, *ga, *r2, *dr2, *du1, *dy1, *dr1, *dc, *dp, *dqkv, *ytmp;
+  float *mean1, *rstd1, *mean2, *rstd2;
+
+  // embedding / head
+  void* emb = nullptr;
+  float* egacc = nullptr;
+  int emb_staged = 0, egacc_state = 0;
+  hipEvent_t emb_staged_ev = nullptr, emb_released_ev = nullptr, egacc_ready = nullptr, egacc_drained = nullptr;
+  float *emean = nullptr, *erstd = nullptr;
+  int32_t *lab_idx = nullptr, *lab_cnt = nullptr, *lab_total = nullptr;
+  void *xl = nullptr, *dz = nullptr, *dxl = nullptr;
+  float* logits = nullptr;
+  long long Vp = 0;
+
+  // profiling
+  int prof_on = 0;
+  std::vector<ProfRec> prof;
+  std::vector<hipEvent_t> ev_pool;
+  long long prof_n[L2L_PROF_CLASSES] = {};
+  double prof_ms[L2L_PROF_CLASSES] = {}, prof_fl[L2L_PROF_CLASSES] = {}, prof_by[L2L_PROF_CLASSES] = {};
+
+  char err[512] = {0};
+};
+
+namespace {
+
+int fail(l2l_ctx* c, int code, const char* fmt, ...) {
+  if (c) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(c->err, sizeof(c->err), fmt, ap);
+    va_end(ap);
+  }
+  return code;
+}
+
+#define HIP_TRY(ctx, call)                                                                       \
+  do {                                                                                           \
+    hipError_t e_ = (call);                                                                      \
+    if (e_ != hipSuccess) return fail(ctx, L2L_E_HIP, "%s: %s", #call, hipGetErrorString(e_)); \
+  } while (0)
+
+#define L2L_TRY(call)        \
+  do {                       \
+    int r_ = (call);         \
+    if (r_ != L2L_OK) return r_; \
+  } while (0)
+
+int dev_alloc(l2l_ctx* c, void** p, size_t bytes) {
+  bytes = (bytes + 255) / 256 * 256;
+  if (bytes == 0) bytes = 256;
+  hipError_t e = hipMalloc(p, bytes);
+  if (e != hipSuccess) return fail(c, L2L_E_NOMEM, "hipMalloc(%zu): %s", bytes, hipGetErrorString(e));
+  c->allocs.push_back(*p);
+  c->dev_bytes += bytes;
+  return L2L_OK;
+}
+
+hipEvent_t take_event(l2l_ctx* c) {
+  if (!c->ev_pool.empty()) {
+    hipEvent_t e = c->ev_pool.back();
+    c->ev_pool.pop_back();
+    return e;
+  }
+  hipEvent_t e;
+  (void)hipEventCreate(&e);
+  return e;
+}
+
+template <typename F>
+int timed(l2l_ctx* c, int cls, double flops, double bytes, F&& f) {
+  if (!c->prof_on) {
+    f();
+  } else {
+    hipEvent_t a = take_event(c), b = take_event(c);
+    (void)hipEventRecord(a, c->cs);
+    f();
+    (void)hipEventRecord(b, c->cs);
+    c->prof.push_back({a, b, cls, flops, bytes});
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(c, L2L_E_HIP, "kernel launch: %s", hipGetErrorString(e));
+  return L2L_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// GEMM dispatch
+// ------------------------------------------------------------------------------------------------
+GemmArgs gemm_args(int M, int N, int K, const void* A, long long lda, int a_kc, const void* B, long long ldb, int b_kc,
+                   void* C, long long ldc) {
+  GemmArgs g;
+  memset(&g, 0, sizeof(g));
+  g.A = A; g.B = B; g.C = C;
+  g.M = M; g.N = N; g.K = K;
+  g.a_kc = a_kc; g.b_kc = b_kc;
+  g.lda = lda; g.ldb = ldb; g.ldc = ldc;
+  g.nbatch = 1; g.zdiv = 1;
+  g.alpha = 1.0f;
+  return g;
+}
+
+bool mfma_ok(const GemmArgs& g) {
+  auto al16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
+  if (!al16(g.A) || !al16(g.B)) return false;
+  if (g.lda % 8 || g.ldb % 8) return false;
+  if (g.a_zo % 8 || g.a_zi % 8 || g.b_zo % 8 || g.b_zi % 8) return false;
+  // a chunk is loaded when its first element is in range: pitches must cover the rounded-up extent
+  const long long m8 = up(g.M, 8), n8 = up(g.N, 8), k8 = up(g.K, 8);
+  if (g.a_kc ? g.lda < k8 : g.lda < m8) return false;
+  if (g.b_kc ? g.ldb < k8 : g.ldb < n8) return false;
+  if (g.a_kc && g.b_kc && g.K % 8) return false;  // nobody guarantees zero padding in both
+  return true;
+}
+
+template <int BM, int BN, int BK, int WM, int WN, typename TC>
+void launch_mfma_cfg(const GemmArgs& g, hipStream_t s) {
+  const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+  dim3 grid(tiles, 1, g.nbatch), block((BM / WM) * (BN / WN) * 64);
+  if (g.a_kc && g.b_kc) hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, BK, WM, WN, true, true, TC>), grid, block, 0, s, g);
+  else if (g.a_kc && !g.b_kc) hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, BK, WM, WN, true, false, TC>), grid, block, 0, s, g);
+  else if (!g.a_kc && g.b_kc) hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, BK, WM, WN, false, true, TC>), grid, block, 0, s, g);
+  else hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, BK, WM, WN, false, false, TC>), grid, block, 0, s, g);
+}
+
+template <typename T, typename TC>
+void launch_plain(const GemmArgs& g, hipStream_t s) {
+  dim3 grid((g.N + 63) / 64, (g.M + 63) / 64, g.nbatch);
+  hipLaunchKernelGGL((gemm_plain_kernel<T, TC>), grid, dim3(256), 0, s, g);
+}
+
+// impl: 0 auto, 1 plain, 2 mfma
+int gemm(l2l_ctx* c, int dtype, bool out_f32, const GemmArgs& g, int impl = 0) {
+  if (g.M <= 0 || g.N <= 0 || g.nbatch <= 0) return L2L_OK;
+  if (g.nbatch > 65535 || (g.M + 63) / 64 > 65535) return fail(c, L2L_E_ARG, "gemm: grid too large");
+  const bool can_mfma = dtype == L2L_BF16 && mfma_ok(g);
+  if (impl == 2 && !can_mfma) return fail(c, L2L_E_ARG, "gemm: shape/alignment not supported by the MFMA kernel");
+  const bool use_mfma = impl == 2 || (impl == 0 && can_mfma);
+  const double flops = 2.0 * g.M * g.N * (double)g.K * g.nbatch;
+  const double es = esize(dtype);
+  const double bytes = ((double)g.M * g.K + (double)g.K * g.N) * es * g.nbatch + (double)g.M * g.N * (out_f32 ? 4 : es) * g.nbatch;
+  return timed(c, L2L_PROF_GEMM, flops, bytes, [&] {
+    if (use_mfma) {
+      if (out_f32) launch_mfma_cfg<128, 128, 32, 64, 64, float>(g, c->cs);
+      else launch_mfma_cfg<128, 128, 32, 64, 64, bf16>(g, c->cs);
+    } else if (dtype == L2L_BF16) {
+      if (out_f32) launch_plain<bf16, float>(g, c->cs);
+      else launch_plain<bf16, bf16>(g, c->cs);
+    } else {
+      launch_plain<float, float>(g, c->cs);
+    }
+  });
+}
+
+// ------------------------------------------------------------------------------------------------
+// typed launch helpers for the row-wise kernels
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+int ln_fwd(l2l_ctx* c, const void* x, const void* gamma, const void* beta, void* y, float* mean, float* rstd, long long rows,
+           int n, float eps) {
+  if (rows <= 0) return L2L_OK;
+  return timed(c, L2L_PROF_ROWWISE, 0, 2.0 * rows * n * sizeof(T), [&] {
+    hipLaunchKernelGGL(ln_fwd_kernel<T>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, c->cs, (const T*)x, (const T*)gamma,
+                       (const T*)beta, (T*)y, mean, rstd, (int)rows, n, eps);
+  });
+}
+
+template <typename T>
+int ln_bwd(l2l_ctx* c, const void* dy, const void* x, const float* mean, const float* rstd, const void* gamma, void* dx,
+           float* dgamma, float* dbeta, long long rows, int n) {
+  if (rows <= 0) return L2L_OK;
+  L2L_TRY(timed(c, L2L_PROF_ROWWISE, 0, 3.0 * rows * n * sizeof(T), [&] {
+    hipLaunchKernelGGL(ln_bwd_dx_kernel<T>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, c->cs, (const T*)dy, (const T*)x,
+                       mean, rstd, (const T*)gamma, (T*)dx, (int)rows, n);
+  }));
+  return timed(c, L2L_PROF_COLSUM, 0, 2.0 * rows * n * sizeof(T), [&] {
+    dim3 grid((n + 127) / 128, (unsigned)((rows + COLSUM_ROWS - 1) / COLSUM_ROWS));
+    hipLaunchKernelGGL((colsum_kernel<T, 1>), grid, dim3(256), 0, c->cs, (const T*)dy, (long long)n, (const T*)x, mean, rstd,
+                       (const int32_t*)nullptr, (const T*)nullptr, (const T*)nullptr, 0, dgamma, dbeta, (int)rows, n,
+                       (const int*)nullptr);
+  });
+}
+
+template <typename T>
+int bias_grad(l2l_ctx* c, const void* a, long long lda, float* out, long long rows, int n, const int* rows_dev = nullptr) {
+  if (rows <= 0) return L2L_OK;
+  return timed(c, L2L_PROF_COLSUM, 0, 1.0 * rows * n * sizeof(T), [&] {
+    dim3 grid((n + 127) / 128, (unsigned)((rows + COLSUM_ROWS - 1) / COLSUM_ROWS));
+    hipLaunchKernelGGL((colsum_kernel<T, 0>), grid, dim3(256), 0, c->cs, (const T*)a, lda, (const T*)nullptr,
+                       (const float*)nullptr, (const float*)nullptr, (const int32_t*)nullptr, (const T*)nullptr,
+                       (const T*)nullptr, 0, (float*)nullptr, out, (int)rows, n, rows_dev);
+  });
+}
+
+int fill_zero(l2l_ctx* c, void* p, size_t bytes) {
+  const long long n = (long long)(bytes / 4);
+  if (n <= 0) return L2L_OK;
+  const unsigned blocks = (unsigned)std::min<long long>((n + 255) / 256, 4096);
+  return timed(c, L2L_PROF_OTHER, 0, (double)bytes, [&] {
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks), dim3(256), 0, c->cs, (uint32_t*)p, 0u, n);
+  });
+}
+
+// ------------------------------------------------------------------------------------------------
+// one encoder layer, forward, on `ng` micro-batches starting at row block x (rows = ng * T)
+// keep: also keep the GELU pre-activation and both LayerNorm statistics (backward recompute)
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+int layer_forward_group(l2l_ctx* c, const void* params, const void* x, void* y, int ng, bool keep) {
+  const l2l_config& f = c->cfg;
+  const int H = f.hidden, A = f.heads, F = f.ffn, S = f.seq, d = H / A;
+  const long long M = (long long)ng * c->T;
+  const int nseq = ng * f.ubatch;
+  const int dt = f.dtype;
+  const T* P = (const T*)params;
+  const long long* off = c->lay.off;
+  T* qkv = (T*)c->qkv;
+
+  // QKV projection with bias
+  {
+    GemmArgs g = gemm_args((int)M, 3 * H, H, x, H, 1, P + off[T_WQKV], 3 * H, 0, qkv, 3 * H);
+    g.epi = EPI_BIAS; g.bias = P + off[T_BQKV];
+    L2L_TRY(gemm(c, dt, false, g));
+  }
+  // scores = Q K^T / sqrt(d) per (sequence, head), softmax over keys, context = P V
+  {
+    GemmArgs g = gemm_args(S, S, d, qkv, 3 * H, 1, qkv + H, 3 * H, 1, c->p, S);
+    g.nbatch = nseq * A; g.zdiv = A;
+    g.a_zo = (long long)S * 3 * H; g.a_zi = d; g.b_zo = g.a_zo; g.b_zi = d;
+    g.c_zo = (long long)A * S * S; g.c_zi = (long long)S * S;
+    g.alpha = 1.0f / sqrtf((float)d);
+    L2L_TRY(gemm(c, dt, false, g));
+    const long long rows = (long long)nseq * A * S;
+    L2L_TRY(timed(c, L2L_PROF_ATTN, 0, 2.0 * rows * S * sizeof(T), [&] {
+      hipLaunchKernelGGL(softmax_fwd_kernel<T>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, c->cs, (T*)c->p, rows, S);
+    }));
+    GemmArgs h = gemm_args(S, d, S, c->p, S, 1, qkv + 2 * H, 3 * H, 0, c->c, H);
+    h.nbatch = nseq * A; h.zdiv = A;
+    h.a_zo = (long long)A * S * S; h.a_zi = (long long)S * S;
+    h.b_zo = (long long)S * 3 * H; h.b_zi = d;
+    h.c_zo = (long long)S * H; h.c_zi = d;
+    L2L_TRY(gemm(c, dt, false, h));
+  }
+  // output projection + bias + residual, LayerNorm 1
+  {
+    GemmArgs g = gemm_args((int)M, H, H, c->c, H, 1, P + off[T_WO], H, 0, c->r1, H);
+    g.epi = EPI_BIAS | EPI_RESID; g.bias = P + off[T_BO]; g.resid = x; g.ldr = H;
+    L2L_TRY(gemm(c, dt, false, g));
+    L2L_TRY(ln_fwd<T>(c, c->r1, P + off[T_G1], P + off[T_BE1], c->y1, keep ? c->mean1 : nullptr, keep ? c->rstd1 : nullptr, M, H,
+                      f.ln_eps));
+  }
+  // FFN1 + bias + GELU, FFN2 + bias + residual, LayerNorm 2
+  {
+    GemmArgs g = gemm_args((int)M, F, H, c->y1, H, 1, P + off[T_W1], F, 0, c->ga, F);
+    g.epi = EPI_BIAS | EPI_GELU; g.bias = P + off[T_B1]; g.aux_out = keep ? c->u1 : nullptr; g.ldaux = F;
+    L2L_TRY(gemm(c, dt, false, g));
+    GemmArgs h = gemm_args((int)M, H, F, c->ga, F, 1, P + off[T_W2], H, 0, c->r2, H);
+    h.epi = EPI_BIAS | EPI_RESID; h.bias = P + off[T_B2]; h.resid = c->y1; h.ldr = H;
+    L2L_TRY(gemm(c, dt, false, h));
+    if (keep) {
+      // backward needs only the statistics of LN2; y itself was stashed by the forward pass
+      L2L_TRY(ln_fwd<T>(c, c->r2, P + off[T_G2], P + off[T_BE2], c->ytmp, c->mean2, c->rstd2, M, H, f.ln_eps));
+    } else {
+      L2L_TRY(ln_fwd<T>(c, c->r2, P + off[T_G2], P + off[T_BE2], y, nullptr, nullptr, M, H, f.ln_eps));
+    }
+  }
+  return L2L_OK;
+}
+
+// backward of the group whose forward intermediates are in the workspace; dy -> dx in place
+template <typename T>
+int layer_backward_group(l2l_ctx* c, const void* params, const void* x, void* dydx, float* G, int ng) {
+  const l2l_config& f = c->cfg;
+  const int H = f.hidden, A = f.heads, F = f.ffn, S = f.seq, d = H / A;
+  const long long M = (long long)ng * c->T;
+  const int nseq = ng * f.ubatch;
+  const int dt = f.dtype;
+  const T* P = (const T*)params;
+  const long long* off = c->lay.off;
+  T* qkv = (T*)c->qkv;
+  T* dqkv = (T*)c->dqkv;
+  const float alpha = 1.0f / sqrtf((float)d);
+
+  // LN2 backward
+  L2L_TRY(ln_bwd<T>(c, dydx, c->r2, c->mean2, c->rstd2, P + off[T_G2], c->dr2, G + off[T_G2], G + off[T_BE2], M, H));
+  // FFN2 backward: dU1 = (dR2 W2^T) * gelu'(U1); dW2 += G^T dR2; db2 += colsum(dR2)
+  {
+    GemmArgs g = gemm_args((int)M, F, H, c->dr2, H, 1, P + off[T_W2], H, 1, c->du1, F);
+    g.epi = EPI_GELUGRAD; g.aux = c->u1; g.ldaux = F;
+    L2L_TRY(gemm(c, dt, false, g));
+    GemmArgs w = gemm_args(F, H, (int)M, c->ga, F, 0, c->dr2, H, 0, G + off[T_W2], H);
+    w.epi = EPI_ACCUM;
+    L2L_TRY(gemm(c, dt, true, w));
+    L2L_TRY(bias_grad<T>(c, c->dr2, H, G + off[T_B2], M, H));
+  }
+  // FFN1 backward: dY1 = dR2 + dU1 W1^T; dW1 += Y1^T dU1; db1 += colsum(dU1)
+  {
+    GemmArgs g = gemm_args((int)M, H, F, c->du1, F, 1, P + off[T_W1], F, 1, c->dy1, H);
+    g.epi = EPI_RESID; g.resid = c->dr2; g.ldr = H;
+    L2L_TRY(gemm(c, dt, false, g));
+    GemmArgs w = gemm_args(H, F, (int)M, c->y1, H, 0, c->du1, F, 0, G + off[T_W1], F);
+    w.epi = EPI_ACCUM;
+    L2L_TRY(gemm(c, dt, true, w));
+    L2L_TRY(bias_grad<T>(c, c->du1, F, G + off[T_B1], M, F));
+  }
+  // LN1 backward
+  L2L_TRY(ln_bwd<T>(c, c->dy1, c->r1, c->mean1, c->rstd1, P + off[T_G1], c->dr1, G + off[T_G1], G + off[T_BE1], M, H));
+  // output projection backward
+  {
+    GemmArgs g = gemm_args((int)M, H, H, c->dr1, H, 1, P + off[T_WO], H, 1, c->dc, H);
+    L2L_TRY(gemm(c, dt, false, g));
+    GemmArgs w = gemm_args(H, H, (int)M, c->c, H, 0, c->dr1, H, 0, G + off[T_WO], H);
+    w.epi = EPI_ACCUM;
+    L2L_TRY(gemm(c, dt, true, w));
+    L2L_TRY(bias_grad<T>(c, c->dr1, H, G + off[T_BO], M, H));
+  }
+  // attention backward per (sequence, head)
+  {
+    const long long zq = (long long)S * 3 * H, zp = (long long)A * S * S, zc = (long long)S * H;
+    auto batch = [&](GemmArgs& g, long long azo, long long azi, long long bzo, long long bzi, long long czo, long long czi) {
+      g.nbatch = nseq * A; g.zdiv = A;
+      g.a_zo = azo; g.a_zi = azi; g.b_zo = bzo; g.b_zi = bzi; g.c_zo = czo; g.c_zi = czi;
+    };
+    // dV = P^T dC
+    GemmArgs g1 = gemm_args(S, d, S, c->p, S, 0, c->dc, H, 0, dqkv + 2 * H, 3 * H);
+    batch(g1, zp, (long long)S * S, zc, d, zq, d);
+    L2L_TRY(gemm(c, dt, false, g1));
+    // dP = dC V^T
+    GemmArgs g2 = gemm_args(S, S, d, c->dc, H, 1, qkv + 2 * H, 3 * H, 1, c->dp, S);
+    batch(g2, zc, d, zq, d, zp, (long long)S * S);
+    L2L_TRY(gemm(c, dt, false, g2));
+    // dS = P * (dP - rowsum(dP * P)), in place
+    const long long rows = (long long)nseq * A * S;
+    L2L_TRY(timed(c, L2L_PROF_ATTN, 0, 3.0 * rows * S * sizeof(T), [&] {
+      hipLaunchKernelGGL(softmax_bwd_kernel<T>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, c->cs, (const T*)c->p, (T*)c->dp,
+                         rows, S);
+    }));
+    // dQ = dS K / sqrt(d)
+    GemmArgs g3 = gemm_args(S, d, S, c->dp, S, 1, qkv + H, 3 * H, 0, dqkv, 3 * H);
+    batch(g3, zp, (long long)S * S, zq, d, zq, d);
+    g3.alpha = alpha;
+    L2L_TRY(gemm(c, dt, false, g3));
+    // dK = dS^T Q / sqrt(d)
+    GemmArgs g4 = gemm_args(S, d, S, c->dp, S, 0, qkv, 3 * H, 0, dqkv + H, 3 * H);
+    batch(g4, zp, (long long)S * S, zq, d, zq, d);
+    g4.alpha = alpha;
+    L2L_TRY(gemm(c, dt, false, g4));
+  }
+  // QKV projection backward: dX = dR1 + dQKV Wqkv^T (over dY in place); dWqkv += X^T dQKV
+  {
+    GemmArgs g = gemm_args((int)M, H, 3 * H, dqkv, 3 * H, 1, P + off[T_WQKV], 3 * H, 1, dydx, H);
+    g.epi = EPI_RESID; g.resid = c->dr1; g.ldr = H;
+    L2L_TRY(gemm(c, dt, false, g));
+    GemmArgs w = gemm_args(H, 3 * H, (int)M, x, H, 0, dqkv, 3 * H, 0, G + off[T_WQKV], 3 * H);
+    w.epi = EPI_ACCUM;
+    L2L_TRY(gemm(c, dt, true, w));
+    L2L_TRY(bias_grad<T>(c, dqkv, 3 * H, G + off[T_BQKV], M, 3 * H));
+  }
+  return L2L_OK;
+}
+
+template <typename T>
+int embed_fwd_t(l2l_ctx* c, const int32_t* tokens, void* x_out) {
+  const long long rows = c->T * c->cfg.num_ubatches;
+  const T* E = (const T*)c->emb;
+  const long long* eo = c->lay.eoff;
+  const int H = c->cfg.hidden;
+  return timed(c, L2L_PROF_ROWWISE, 0, 2.0 * rows * H * sizeof(T), [&] {
+    hipLaunchKernelGGL(embed_fwd_kernel<T>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, c->cs, tokens, E + eo[E_E],
+                       E + eo[E_P], E + eo[E_GE], E + eo[E_BE], (T*)x_out, c->emean, c->erstd, (int)rows, c->cfg.seq, H,
+                       c->cfg.ln_eps);
+  });
+}
+
+template <typename T>
+int head_loss_t(l2l_ctx* c, const void* x_last, const int32_t* labels, void* dy_out, float* loss_out) {
+  const l2l_config& f = c->cfg;
+  const int H = f.hidden, V = f.vocab, U = f.num_ubatches, dt = f.dtype;
+  const int Tn = (int)c->T;
+  const long long Vp = c->Vp;
+  const T* E = (const T*)c->emb;
+  const long long* eo = c->lay.eoff;
+  L2L_TRY(fill_zero(c, c->lab_cnt, (U + 1) * 4));
+  L2L_TRY(fill_zero(c, loss_out, 4));
+  L2L_TRY(fill_zero(c, dy_out, (size_t)U * Tn * H * sizeof(T)));
+  L2L_TRY(timed(c, L2L_PROF_OTHER, 0, 4.0 * U * Tn, [&] {
+    hipLaunchKernelGGL(label_compact_kernel, dim3(U), dim3(256), 0, c->cs, labels, Tn, c->lab_idx, c->lab_cnt, c->lab_total);
+  }));
+  for (int u = 0; u < U; ++u) {
+    const T* x = (const T*)x_last + (long long)u * Tn * H;
+    T* dy = (T*)dy_out + (long long)u * Tn * H;
+    const int32_t* idx = c->lab_idx + (long long)u * Tn;
+    const int32_t* cnt = c->lab_cnt + u;
+    L2L_TRY(timed(c, L2L_PROF_OTHER, 0, 0, [&] {
+      hipLaunchKernelGGL((rows_by_index_kernel<T, false>), dim3((Tn + 3) / 4), dim3(256), 0, c->cs, x, (T*)c->xl, idx, cnt, H);
+    }));
+    // logits = Xl E^T + bv
+    GemmArgs g = gemm_args(Tn, V, H, c->xl, H, 1, E + eo[E_E], H, 1, c->logits, Vp);
+    g.epi = EPI_BIAS; g.bias = E + eo[E_BV]; g.m_dev = cnt;
+    L2L_TRY(gemm(c, dt, true, g));
+    L2L_TRY(timed(c, L2L_PROF_OTHER, 0, 0, [&] {
+      hipLaunchKernelGGL(ce_kernel<T>, dim3(Tn), dim3(256), 0, c->cs, c->logits, Vp, labels + (long long)u * Tn, idx, cnt,
+                         c->lab_total, (T*)c->dz, loss_out, V, (int)Vp);
+    }));
+    // dXl = dz E
+    GemmArgs h = gemm_args(Tn, H, V, c->dz, Vp, 1, E + eo[E_E], H, 0, c->dxl, H);
+    h.m_dev = cnt;
+    L2L_TRY(gemm(c, dt, false, h));
+    L2L_TRY(timed(c, L2L_PROF_OTHER, 0, 0, [&] {
+      hipLaunchKernelGGL((rows_by_index_kernel<T, true>), dim3((Tn + 3) / 4), dim3(256), 0, c->cs, (const T*)c->dxl, dy, idx, cnt, H);
+    }));
+    // dE += dz^T Xl ; dbv += colsum(dz)
+    GemmArgs w = gemm_args(V, H, Tn, c->dz, Vp, 0, c->xl, H, 0, c->egacc + eo[E_E], H);
+    w.epi = EPI_ACCUM; w.k_dev = cnt;
+    L2L_TRY(gemm(c, dt, true, w));
+    L2L_TRY(bias_grad<T>(c, c->dz, Vp, c->egacc + eo[E_BV], Tn, V, cnt));
+  }
+  return L2L_OK;
+}
+
+template <typename T>
+int embed_bwd_t(l2l_ctx* c, const int32_t* tokens, const void* dy) {
+  const long long rows = c->T * c->cfg.num_ubatches;
+  const T* E = (const T*)c->emb;
+  const long long* eo = c->lay.eoff;
+  const int H = c->cfg.hidden, S = c->cfg.seq;
+  L2L_TRY(timed(c, L2L_PROF_ROWWISE, 0, 0, [&] {
+    hipLaunchKernelGGL(embed_bwd_kernel<T>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, c->cs, tokens, E + eo[E_E], E + eo[E_P],
+                       E + eo[E_GE], (const T*)dy, c->emean, c->erstd, c->egacc + eo[E_E], c->egacc + eo[E_P], (int)rows, S, H);
+  }));
+  return timed(c, L2L_PROF_COLSUM, 0, 0, [&] {
+    dim3 grid((H + 127) / 128, (unsigned)((rows + COLSUM_ROWS - 1) / COLSUM_ROWS));
+    hipLaunchKernelGGL((colsum_kernel<T, 2>), grid, dim3(256), 0, c->cs, (const T*)dy, (long long)H, (const T*)nullptr, c->emean,
+                       c->erstd, tokens, E + eo[E_E], E + eo[E_P], S, c->egacc + eo[E_GE], c->egacc + eo[E_BE], (int)rows, H,
+                       (const int*)nullptr);
+  });
+}
+
+int check_slot_call(l2l_ctx* c, int layer, int slot, const void* a, const void* b, const char* who) {
+  if (!c) return L2L_E_ARG;
+  if (!a || !b) return fail(c, L2L_E_ARG, "%s: null pointer", who);
+  if (layer < 0) return fail(c, L2L_E_ARG, "%s: layer %d < 0", who, layer);
+  if (slot != 0 && slot != 1) return fail(c, L2L_E_ARG, "%s: slot %d not 0 or 1", who, slot);
+  if (c->slot_layer[slot] != layer)
+    return fail(c, L2L_E_STATE, "%s: slot %d holds layer %d, not layer %d (stage it first)", who, slot, c->slot_layer[slot], layer);
+  return L2L_OK;
+}
+
+}  // namespace
+
+// ================================================================================================
+// public API
+// ================================================================================================
+extern "C" {
+
+int l2l_create(const l2l_config* cfg, void* compute_stream, void* copy_stream, l2l_ctx** out) {
+  if (!out) return L2L_E_ARG;
+  *out = nullptr;
+  if (!config_ok(cfg)) return L2L_E_ARG;
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) {
+    (void)hipGetLastError();
+    return L2L_E_HIP;
+  }
+  l2l_ctx* c = new l2l_ctx;
+  c->cfg = *cfg;
+  c->lay = make_layout(cfg);
+  c->cs = (hipStream_t)compute_stream;
+  c->xs = (hipStream_t)copy_stream;
+  c->T = (long long)cfg->ubatch * cfg->seq;
+  int g = cfg->ubatch_group;
+  if (g == 0) {  // default: as many micro-batches per launch as keep a launch within 32768 rows
+    g = 1;
+    for (int k = 1; k <= cfg->num_ubatches; ++k)
+      if (cfg->num_ubatches % k == 0 && k * c->T <= 32768) g = k;
+  }
+  // attention launches batch (sequence, head) pairs along grid z
+  while (g > 1 && (long long)g * cfg->ubatch * cfg->heads > 65535) --g;
+  if ((long long)cfg->ubatch * cfg->heads > 65535) {
+    delete c;
+    return L2L_E_ARG;
+  }
+  c->group = g;
+  c->Mg = g * c->T;
+  *out = c;  // from here on the caller can read l2l_last_error and must l2l_destroy
+
+  const size_t es = esize(cfg->dtype);
+  const long long H = cfg->hidden, F = cfg->ffn, S = cfg->seq, A = cfg->heads, Mg = c->Mg;
+  const long long pe = (long long)g * cfg->ubatch * A * S * S;
+  for (int i = 0; i < 2; ++i) {
+    L2L_TRY(dev_alloc(c, &c->slot[i], c->lay.total * es));
+    L2L_TRY(dev_alloc(c, (void**)&c->gacc[i], c->lay.total * 4));
+    HIP_TRY(c, hipEventCreateWithFlags(&c->slot_staged[i], hipEventDisableTiming));
+    HIP_TRY(c, hipEventCreateWithFlags(&c->slot_released[i], hipEventDisableTiming));
+    HIP_TRY(c, hipEventCreateWithFlags(&c->gacc_ready[i], hipEventDisableTiming));
+    HIP_TRY(c, hipEventCreateWithFlags(&c->gacc_drained[i], hipEventDisableTiming));
+  }
+  struct { void** p; long long n; } bufs[] = {
+      {&c->qkv, Mg * 3 * H}, {&c->p, pe}, {&c->c, Mg * H}, {&c->r1, Mg * H}, {&c->y1, Mg * H}, {&c->u1, Mg * F},
+      {&c->ga, Mg * F}, {&c->r2, Mg * H}, {&c->dr2, Mg * H}, {&c->du1, Mg * F}, {&c->dy1, Mg * H}, {&c->dr1, Mg * H},
+      {&c->dc, Mg * H}, {&c->dp, pe}, {&c->dqkv, Mg * 3 * H}, {&c->ytmp, Mg * H}};
+  for (auto& b : bufs) L2L_TRY(dev_alloc(c, b.p, b.n * es));
+  float** stats[] = {&c->mean1, &c->rstd1, &c->mean2, &c->rstd2};
+  for (auto s : stats) L2L_TRY(dev_alloc(c, (void**)s, Mg * 4));
+
+  if (cfg->vocab > 0) {
+    const long long V = cfg->vocab, UT = c->T * cfg->num_ubatches;
+    c->Vp = up(V, 64);
+    L2L_TRY(dev_alloc(c, &c->emb, c->lay.etotal * es));
+    L2L_TRY(dev_alloc(c, (void**)&c->egacc, c->lay.etotal * 4));
+    L2L_TRY(dev_alloc(c, (void**)&c->emean, UT * 4));
+    L2L_TRY(dev_alloc(c, (void**)&c->erstd, UT * 4));
+    L2L_TRY(dev_alloc(c, (void**)&c->lab_idx, UT * 4));
+    L2L_TRY(dev_alloc(c, (void**)&c->lab_cnt, (cfg->num_ubatches + 1) * 4));
+    c->lab_total = c->lab_cnt + cfg->num_ubatches;
+    L2L_TRY(dev_alloc(c, &c->xl, c->T * H * es));
+    L2L_TRY(dev_alloc(c, &c->dxl, c->T * H * es));
+    L2L_TRY(dev_alloc(c, (void**)&c->logits, c->T * c->Vp * 4));
+    L2L_TRY(dev_alloc(c, &c->dz, c->T * c->Vp * es));
+    HIP_TRY(c, hipEventCreateWithFlags(&c->emb_staged_ev, hipEventDisableTiming));
+    HIP_TRY(c, hipEventCreateWithFlags(&c->emb_released_ev, hipEventDisableTiming));
+    HIP_TRY(c, hipEventCreateWithFlags(&c->egacc_ready, hipEventDisableTiming));
+    HIP_TRY(c, hipEventCreateWithFlags(&c->egacc_drained, hipEventDisableTiming));
+  }
+  return L2L_OK;
+}
+
+int l2l_destroy(l2l_ctx* c) {
+  if (!c) return L2L_E_ARG;
+  (void)hipDeviceSynchronize();
+  for (void* p : c->allocs) (void)hipFree(p);
+  for (auto& r : c->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+  for (auto e : c->ev_pool) (void)hipEventDestroy(e);
+  hipEvent_t evs[] = {c->slot_staged[0], c->slot_staged[1], c->slot_released[0], c->slot_released[1], c->gacc_ready[0],
+                      c->gacc_ready[1], c->gacc_drained[0], c->gacc_drained[1], c->emb_staged_ev, c->emb_released_ev,
+                      c->egacc_ready, c->egacc_drained};
+  for (hipEvent_t e : evs)
+    if (e) (void)hipEventDestroy(e);
+  delete c;
+  return L2L_OK;
+}
+
+size_t l2l_device_bytes(const l2l_ctx* c) { return c ? c->dev_bytes : 0; }
+const char* l2l_last_error(const l2l_ctx* c) { return c ? c->err : "null context"; }
+
+int l2l_sync(l2l_ctx* c) {
+  if (!c) return L2L_E_ARG;
+  HIP_TRY(c, hipStreamSynchronize(c->cs));
+  HIP_TRY(c, hipStreamSynchronize(c->xs));
+  return L2L_OK;
+}
+
+int l2l_param_stage(l2l_ctx* c, int layer, const void* host_params, int slot) {
+  if (!c) return L2L_E_ARG;
+  if (!host_params) return fail(c, L2L_E_ARG, "l2l_param_stage: null host pointer");
+  if (layer < 0) return fail(c, L2L_E_ARG, "l2l_param_stage: layer %d < 0", layer);
+  if (slot != 0 && slot != 1) return fail(c, L2L_E_ARG, "l2l_param_stage: slot %d not 0 or 1", slot);
+  // the copy may start only when every kernel that reads the slot's previous contents is done
+  if (c->slot_layer[slot] >= 0) HIP_TRY(c, hipStreamWaitEvent(c->xs, c->slot_released[slot], 0));
+  HIP_TRY(c, hipMemcpyAsync(c->slot[slot], host_params, c->lay.total * esize(c->cfg.dtype), hipMemcpyHostToDevice, c->xs));
+  HIP_TRY(c, hipEventRecord(c->slot_staged[slot], c->xs));
+  c->slot_layer[slot] = layer;
+  return L2L_OK;
+}
+
+int l2l_layer_fwd(l2l_ctx* c, int layer, int slot, const void* x_stash, void* y_out) {
+  L2L_TRY(check_slot_call(c, layer, slot, x_stash, y_out, "l2l_layer_fwd"));
+  HIP_TRY(c, hipStreamWaitEvent(c->cs, c->slot_staged[slot], 0));
+  const size_t es = esize(c->cfg.dtype);
+  const int U = c->cfg.num_ubatches;
+  for (int u0 = 0; u0 < U; u0 += c->group) {
+    const int ng = std::min(c->group, U - u0);
+    const size_t o = (size_t)u0 * c->T * c->cfg.hidden * es;
+    const void* x = (const char*)x_stash + o;
+    void* y = (char*)y_out + o;
+    if (c->cfg.dtype == L2L_BF16) L2L_TRY(layer_forward_group<bf16>(c, c->slot[slot], x, y, ng, false));
+    else L2L_TRY(layer_forward_group<float>(c, c->slot[slot], x, y, ng, false));
+  }
+  HIP_TRY(c, hipEventRecord(c->slot_released[slot], c->cs));
+  return L2L_OK;
+}
+
+int l2l_layer_bwd(l2l_ctx* c, int layer, int slot, const void* x_stash, void* dy_dx) {
+  L2L_TRY(check_slot_call(c, layer, slot, x_stash, dy_dx, "l2l_layer_bwd"));
+  const int a = c->gacc_next;
+  if (c->gacc_state[a] == 1)
+    return fail(c, L2L_E_STATE, "l2l_layer_bwd: gradients of layer %d were never drained", c->gacc_layer[a]);
+  HIP_TRY(c, hipStreamWaitEvent(c->cs, c->slot_staged[slot], 0));
+  if (c->gacc_state[a] == 2) HIP_TRY(c, hipStreamWaitEvent(c->cs, c->gacc_drained[a], 0));
+  float* G = c->gacc[a];
+  L2L_TRY(fill_zero(c, G, c->lay.total * 4));
+  const size_t es = esize(c->cfg.dtype);
+  const int U = c->cfg.num_ubatches;
+  for (int u0 = 0; u0 < U; u0 += c->group) {
+    const int ng = std::min(c->group, U - u0);
+    const size_t o = (size_t)u0 * c->T * c->cfg.hidden * es;
+    const void* x = (const char*)x_stash + o;
+    void* dy = (char*)dy_dx + o;
+    if (c->cfg.dtype == L2L_BF16) {
+      L2L_TRY(layer_forward_group<bf16>(c, c->slot[slot], x, nullptr, ng, true));  // recompute
+      L2L_TRY(layer_backward_group<bf16>(c, c->slot[slot], x, dy, G, ng));
+    } else {
+      L2L_TRY(layer_forward_group<float>(c, c->slot[slot], x, nullptr, ng, true));
+      L2L_TRY(layer_backward_group<float>(c, c->slot[slot], x, dy, G, ng));
+    }
+  }
+  HIP_TRY(c, hipEventRecord(c->slot_released[slot], c->cs));
+  HIP_TRY(c, hipEventRecord(c->gacc_ready[a], c->cs));
+  c->gacc_layer[a] = layer;
+  c->gacc_state[a] = 1;
+  c->gacc_next = a ^ 1;
+  return L2L_OK;
+}
+
+int l2l_grad_drain(l2l_ctx* c, int layer, void* host_grads) {
+  if (!c) return L2L_E_ARG;
+  if (!host_grads) return fail(c, L2L_E_ARG, "l2l_grad_drain: null host pointer");
+  for (int a = 0; a < 2; ++a) {
+    if (c->gacc_state[a] == 1 && c->gacc_layer[a] == layer) {
+      HIP_TRY(c, hipStreamWaitEvent(c->xs, c->gacc_ready[a], 0));
+      HIP_TRY(c, hipMemcpyAsync(host_grads, c->gacc[a], c->lay.total * 4, hipMemcpyDeviceToHost, c->xs));
+      HIP_TRY(c, hipEventRecord(c->gacc_drained[a], c->xs));
+      c->gacc_state[a] = 2;
+      return L2L_OK;
+    }
+  }
+  return fail(c, L2L_E_STATE, "l2l_grad_drain: no un-drained gradients for layer %d", layer);
+}
+
+int l2l_drain_wait(l2l_ctx* c, int layer) {
+  if (!c) return L2L_E_ARG;
+  for (int a = 0; a < 2; ++a) {
+    if (c->gacc_state[a] == 2 && c->gacc_layer[a] == layer) {
+      HIP_TRY(c, hipEventSynchronize(c->gacc_drained[a]));
+      return L2L_OK;
+    }
+  }
+  return fail(c, L2L_E_STATE, "l2l_drain_wait: no drain in flight for layer %d", layer);
+}
+
+// ---- embedding and head ----------------------------------------------------------------------------
+static int need_vocab(l2l_ctx* c, const char* who) {
+  if (!c) return L2L_E_ARG;
+  if (c->cfg.vocab <= 0) return fail(c, L2L_E_STATE, "%s: context was created with vocab = 0", who);
+  return L2L_OK;
+}
+
+int l2l_embed_stage(l2l_ctx* c, const void* host) {
+  L2L_TRY(need_vocab(c, "l2l_embed_stage"));
+  if (!host) return fail(c, L2L_E_ARG, "l2l_embed_stage: null host pointer");
+  if (c->emb_staged) HIP_TRY(c, hipStreamWaitEvent(c->xs, c->emb_released_ev, 0));
+  HIP_TRY(c, hipMemcpyAsync(c->emb, host, c->lay.etotal * esize(c->cfg.dtype), hipMemcpyHostToDevice, c->xs));
+  HIP_TRY(c, hipEventRecord(c->emb_staged_ev, c->xs));
+  c->emb_staged = 1;
+  return L2L_OK;
+}
+
+
+int l2l_embed_fwd(l2l_ctx* c, const int32_t* tokens, void* x_out) {
+  L2L_TRY(need_vocab(c, "l2l_embed_fwd"));
+  if (!tokens || !x_out) return fail(c, L2L_E_ARG, "l2l_embed_fwd: null pointer");
+  if (!c->emb_staged) return fail(c, L2L_E_STATE, "l2l_embed_fwd: embedding block never staged");
+  if (c->egacc_state == 1) return fail(c, L2L_E_STATE, "l2l_embed_fwd: embedding gradients of the previous step were never drained");
+  HIP_TRY(c, hipStreamWaitEvent(c->cs, c->emb_staged_ev, 0));
+  if (c->egacc_state == 2) HIP_TRY(c, hipStreamWaitEvent(c->cs, c->egacc_drained, 0));
+  L2L_TRY(fill_zero(c, c->egacc, c->lay.etotal * 4));
+  c->egacc_state = 0;
+  if (c->cfg.dtype == L2L_BF16) L2L_TRY(embed_fwd_t<bf16>(c, tokens, x_out));
+  else L2L_TRY(embed_fwd_t<float>(c, tokens, x_out));
+  HIP_TRY(c, hipEventRecord(c->emb_released_ev, c->cs));
+  return L2L_OK;
+}
+
+
+int l2l_head_loss(l2l_ctx* c, const void* x_last, const int32_t* labels, void* dy_out, float* loss_out) {
+  L2L_TRY(need_vocab(c, "l2l_head_loss"));
+  if (!x_last || !labels || !dy_out || !loss_out) return fail(c, L2L_E_ARG, "l2l_head_loss: null pointer");
+  if (!c->emb_staged) return fail(c, L2L_E_STATE, "l2l_head_loss: embedding block never staged");
+  HIP_TRY(c, hipStreamWaitEvent(c->cs, c->emb_staged_ev, 0));
+  if (c->cfg.dtype == L2L_BF16) L2L_TRY(head_loss_t<bf16>(c, x_last, labels, dy_out, loss_out));
+  else L2L_TRY(head_loss_t<float>(c, x_last, labels, dy_out, loss_out));
+  HIP_TRY(c, hipEventRecord(c->emb_released_ev, c->cs));
+  return L2L_OK;
+}
+
+
+int l2l_embed_bwd(l2l_ctx* c, const int32_t* tokens, const void* dy) {
+  L2L_TRY(need_vocab(c, "l2l_embed_bwd"));
+  if (!tokens || !dy) return fail(c, L2L_E_ARG, "l2l_embed_bwd: null pointer");
+  if (!c->emb_staged) return fail(c, L2L_E_STATE, "l2l_embed_bwd: embedding block never staged");
+  if (c->cfg.dtype == L2L_BF16) L2L_TRY(embed_bwd_t<bf16>(c, tokens, dy));
+  else L2L_TRY(embed_bwd_t<float>(c, tokens, dy));
+  HIP_TRY(c, hipEventRecord(c->emb_released_ev, c->cs));
+  HIP_TRY(c, hipEventRecord(c->egacc_ready, c->cs));
+  c->egacc_state = 1;
+  return L2L_OK;
+}
+
+int l2l_embed_grad_drain(l2l_ctx* c, void* host_grads) {
+  L2L_TRY(need_vocab(c, "l2l_embed_grad_drain"));
+  if (!host_grads) return fail(c, L2L_E_ARG, "l2l_embed_grad_drain: null host pointer");
+  if (c->egacc_state != 1) return fail(c, L2L_E_STATE, "l2l_embed_grad_drain: no un-drained embedding gradients");
+  HIP_TRY(c, hipStreamWaitEvent(c->xs, c->egacc_ready, 0));
+  HIP_TRY(c, hipMemcpyAsync(host_grads, c->egacc, c->lay.etotal * 4, hipMemcpyDeviceToHost, c->xs));
+  HIP_TRY(c, hipEventRecord(c->egacc_drained, c->xs));
+  c->egacc_state = 2;
+  return L2L_OK;
+}
+
+int l2l_embed_drain_wait(l2l_ctx* c) {
+  L2L_TRY(need_vocab(c, "l2l_embed_drain_wait"));
+  if (c->egacc_state != 2) return fail(c, L2L_E_STATE, "l2l_embed_drain_wait: no drain in flight");
+  HIP_TRY(c, hipEventSynchronize(c->egacc_drained));
+  return L2L_OK;
+}
+
+// ---- profiling -----------------------------------------------------------------------------------
+static void prof_resolve(l2l_ctx* c) {
+  for (auto& r : c->prof) {
+    (void)hipEventSynchronize(r.b);
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) {
+      c->prof_n[r.cls] += 1;
+      c->prof_ms[r.cls] += ms;
+      c->prof_fl[r.cls] += r.flops;
+      c->prof_by[r.cls] += r.bytes;
+    }
+    c->ev_pool.push_back(r.a);
+    c->ev_pool.push_back(r.b);
+  }
+  c->prof.clear();
+  (void)hipGetLastError();
+}
+
+int l2l_profile(l2l_ctx* c, int on) {
+  if (!c) return L2L_E_ARG;
+  prof_resolve(c);
+  for (int i = 0; i < L2L_PROF_CLASSES; ++i) { c->prof_n[i] = 0; c->prof_ms[i] = c->prof_fl[i] = c->prof_by[i] = 0; }
+  c->prof_on = on != 0;
+  return L2L_OK;
+}
+
+int l2l_profile_read(l2l_ctx* c, int cls, long long* launches, double* ms, double* flops, double* bytes) {
+  if (!c) return L2L_E_ARG;
+  if (cls < 0 || cls >= L2L_PROF_CLASSES) return fail(c, L2L_E_ARG, "l2l_profile_read: class %d", cls);
+  prof_resolve(c);
+  if (launches) *launches = c->prof_n[cls];
+  if (ms) *ms = c->prof_ms[cls];
+  if (flops) *flops = c->prof_fl[cls];
+  if (bytes) *bytes = c->prof_by[cls];
+  return L2L_OK;
+}
+
+// ---- single operations ---------------------------------------------------------------------------
+int l2l_op_gemm(l2l_ctx* c, int in_dtype, int out_f32, int a_kc, int b_kc, int M, int N, int K, const void* A, long long lda,
+                const void* B, long long ldb, void* C, long long ldc, float alpha, const void* bias, const void* resid, int gelu,
+                int accumulate, int impl) {
+  if (!c) return L2L_E_ARG;
+  if (!A || !B || !C) return fail(c, L2L_E_ARG, "l2l_op_gemm: null pointer");
+  if (M < 0 || N < 0 || K < 0 || lda <= 0 || ldb <= 0 || ldc < N) return fail(c, L2L_E_ARG, "l2l_op_gemm: bad shape");
+  if (in_dtype != L2L_F32 && in_dtype != L2L_BF16) return fail(c, L2L_E_ARG, "l2l_op_gemm: bad dtype");
+  if (in_dtype == L2L_F32) out_f32 = 1;
+  if (accumulate && !out_f32) return fail(c, L2L_E_ARG, "l2l_op_gemm: accumulate needs an fp32 output");
+  if (impl < 0 || impl > 2) return fail(c, L2L_E_ARG, "l2l_op_gemm: impl %d", impl);
+  GemmArgs g = gemm_args(M, N, K, A, lda, a_kc != 0, B, ldb, b_kc != 0, C, ldc);
+  g.alpha = alpha;
+  if (bias) { g.epi |= EPI_BIAS; g.bias = bias; }
+  if (gelu) g.epi |= EPI_GELU;
+  if (resid) { g.epi |= EPI_RESID; g.resid = resid; g.ldr = ldc; }
+  if (accumulate) g.epi |= EPI_ACCUM;
+  return gemm(c, in_dtype, out_f32 != 0, g, impl);
+}
+
+int l2l_op_layernorm(l2l_ctx* c, int dtype, int rows, int n, const void* x, const void* gamma, const void* beta, float eps, void* y,
+                     float* mean, float* rstd) {
+  if (!c) return L2L_E_ARG;
+  if (!x || !gamma || !beta || !y) return fail(c, L2L_E_ARG, "l2l_op_layernorm: null pointer");
+  if (rows < 0 || n <= 0 || n % 8) return fail(c, L2L_E_ARG, "l2l_op_layernorm: n must be a positive multiple of 8");
+  if ((mean == nullptr) != (rstd == nullptr)) return fail(c, L2L_E_ARG, "l2l_op_layernorm: mean and rstd go together");
+  if (dtype == L2L_BF16) return ln_fwd<bf16>(c, x, gamma, beta, y, mean, rstd, rows, n, eps);
+  if (dtype == L2L_F32) return ln_fwd<float>(c, x, gamma, beta, y, mean, rstd, rows, n, eps);
+  return fail(c, L2L_E_ARG, "l2l_op_layernorm: bad dtype");
+}
+
+}  // extern "C"

@@ -1,0 +1,342 @@
+// Memory-bound kernels of the L2L layer: LayerNorm forward/backward, row softmax forward/backward,
+// column sums (bias / gain gradients), embedding gather / scatter, cross-entropy.
+// One wavefront owns one row; reductions use wavefront shuffles; statistics are fp32.
+#pragma once
+#include "common.h"
+
+// ---- 8-wide vector access ------------------------------------------------------------------------
+__device__ __forceinline__ void load8(const float* p, float v[8]) {
+  const f32x4 a = *(const f32x4*)p, b = *(const f32x4*)(p + 4);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ __forceinline__ void load8(const bf16* p, float v[8]) {
+  const bf16x8 a = *(const bf16x8*)p;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v[i] = (float)a[i];
+}
+__device__ __forceinline__ void store8(float* p, const float v[8]) {
+  *(f32x4*)p = f32x4{v[0], v[1], v[2], v[3]};
+  *(f32x4*)(p + 4) = f32x4{v[4], v[5], v[6], v[7]};
+}
+__device__ __forceinline__ void store8(bf16* p, const float v[8]) {
+  bf16x8 a;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a[i] = (bf16)v[i];
+  *(bf16x8*)p = a;
+}
+
+// Row sources: a plain row, or the embedding sum E[tok] + Ppos[s] formed on the fly.
+template <typename T>
+struct PlainRow {
+  const T* p;
+  __device__ __forceinline__ void operator()(int j, float v[8]) const { load8(p + j, v); }
+};
+template <typename T>
+struct EmbedRow {
+  const T* e;
+  const T* pos;
+  __device__ __forceinline__ void operator()(int j, float v[8]) const {
+    float a[8], b[8];
+    load8(e + j, a);
+    load8(pos + j, b);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = a[i] + b[i];
+  }
+};
+
+// mean and 1/sqrt(biased variance + eps) of one row, two passes (the second re-reads through cache).
+template <typename Row>
+__device__ __forceinline__ void row_stats(const Row& row, int n, float eps, int lane, float& mean, float& rstd) {
+  float s = 0.f;
+  for (int j = lane * 8; j < n; j += WAVE * 8) {
+    float v[8];
+    row(j, v);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s += v[i];
+  }
+  mean = wave_sum(s) / n;
+  float q = 0.f;
+  for (int j = lane * 8; j < n; j += WAVE * 8) {
+    float v[8];
+    row(j, v);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) q += (v[i] - mean) * (v[i] - mean);
+  }
+  rstd = rsqrtf(wave_sum(q) / n + eps);
+}
+
+template <typename T, typename Row>
+__device__ __forceinline__ void ln_write(const Row& row, int n, int lane, float mean, float rstd, const T* gamma,
+                                         const T* beta, T* y) {
+  for (int j = lane * 8; j < n; j += WAVE * 8) {
+    float v[8], g[8], b[8];
+    row(j, v);
+    load8(gamma + j, g);
+    load8(beta + j, b);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = g[i] * ((v[i] - mean) * rstd) + b[i];
+    store8(y + j, v);
+  }
+}
+
+// y = LN(x); optionally keeps mean / rstd per row.
+template <typename T>
+__global__ __launch_bounds__(256) void ln_fwd_kernel(const T* x, const T* gamma, const T* beta, T* y, float* mean_out,
+                                                     float* rstd_out, int rows, int n, float eps) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  PlainRow<T> row{x + (long long)r * n};
+  float mean, rstd;
+  row_stats(row, n, eps, lane, mean, rstd);
+  ln_write<T>(row, n, lane, mean, rstd, gamma, beta, y + (long long)r * n);
+  if (lane == 0 && mean_out) { mean_out[r] = mean; rstd_out[r] = rstd; }
+}
+
+// x0 = LN_e(E[tok] + Ppos[s]) per token row; keeps mean / rstd for the backward pass.
+template <typename T>
+__global__ __launch_bounds__(256) void embed_fwd_kernel(const int32_t* tokens, const T* E, const T* pos, const T* gamma,
+                                                        const T* beta, T* y, float* mean_out, float* rstd_out, int rows,
+                                                        int S, int n, float eps) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  EmbedRow<T> row{E + (long long)tokens[r] * n, pos + (long long)(r % S) * n};
+  float mean, rstd;
+  row_stats(row, n, eps, lane, mean, rstd);
+  ln_write<T>(row, n, lane, mean, rstd, gamma, beta, y + (long long)r * n);
+  if (lane == 0) { mean_out[r] = mean; rstd_out[r] = rstd; }
+}
+
+// dr = rstd * (g - mean(g) - xhat * mean(g * xhat)), g = dy * gamma.
+template <typename T, typename Row, typename Sink>
+__device__ __forceinline__ void ln_bwd_row(const Row& row, int n, int lane, float mean, float rstd, const T* gamma,
+                                           const T* dy, Sink sink) {
+  float c1 = 0.f, c2 = 0.f;
+  for (int j = lane * 8; j < n; j += WAVE * 8) {
+    float v[8], g[8], d[8];
+    row(j, v);
+    load8(gamma + j, g);
+    load8(dy + j, d);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float gg = d[i] * g[i];
+      c1 += gg;
+      c2 += gg * ((v[i] - mean) * rstd);
+    }
+  }
+  c1 = wave_sum(c1) / n;
+  c2 = wave_sum(c2) / n;
+  for (int j = lane * 8; j < n; j += WAVE * 8) {
+    float v[8], g[8], d[8];
+    row(j, v);
+    load8(gamma + j, g);
+    load8(dy + j, d);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = rstd * (d[i] * g[i] - c1 - ((v[i] - mean) * rstd) * c2);
+    sink(j, v);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void ln_bwd_dx_kernel(const T* dy, const T* x, const float* mean, const float* rstd,
+                                                        const T* gamma, T* dx, int rows, int n) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  PlainRow<T> row{x + (long long)r * n};
+  T* out = dx + (long long)r * n;
+  ln_bwd_row<T>(row, n, lane, mean[r], rstd[r], gamma, dy + (long long)r * n,
+             [out](int j, const float v[8]) { store8(out + j, v); });
+}
+
+// Embedding backward: dr through LN_e, scatter-added (fp32 atomics) into dE[tok] and dPpos[s].
+template <typename T>
+__global__ __launch_bounds__(256) void embed_bwd_kernel(const int32_t* tokens, const T* E, const T* pos, const T* gamma,
+                                                        const T* dy, const float* mean, const float* rstd, float* dE,
+                                                        float* dpos, int rows, int S, int n) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  const long long tok = tokens[r];
+  const int s = r % S;
+  EmbedRow<T> row{E + tok * n, pos + (long long)s * n};
+  float* de = dE + tok * n;
+  float* dp = dpos + (long long)s * n;
+  ln_bwd_row<T>(row, n, lane, mean[r], rstd[r], gamma, dy + (long long)r * n, [de, dp](int j, const float v[8]) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      atomicAdd(de + j + i, v[i]);
+      atomicAdd(dp + j + i, v[i]);
+    }
+  });
+}
+
+// ---- column reductions -----------------------------------------------------------------------------
+// out_a[j] += sum_t a[t,j] * w(t,j), out_b[j] += sum_t a[t,j], with w = xhat of a LayerNorm input
+// (MODE 1: plain rows x; MODE 2: embedding rows) or out_b only (MODE 0: bias gradient).
+// Block: 128 columns x ROWS_PER_BLOCK rows; lanes own column pairs; waves stride rows; LDS combine;
+// one fp32 atomic per column per block.
+constexpr int COLSUM_ROWS = 128;
+template <typename T, int MODE>
+__global__ __launch_bounds__(256) void colsum_kernel(const T* a, long long lda, const T* x, const float* mean,
+                                                     const float* rstd, const int32_t* tokens, const T* E, const T* pos,
+                                                     int S, float* out_a, float* out_b, int rows, int n,
+                                                     const int* rows_dev) {
+  __shared__ float red[4][2][128];
+  if (rows_dev) rows = min(rows, *rows_dev);
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int j = blockIdx.x * 128 + lane * 2;
+  const int r0 = blockIdx.y * COLSUM_ROWS;
+  if (r0 >= rows) return;
+  const int r1 = min(rows, r0 + COLSUM_ROWS);
+  float sa0 = 0.f, sa1 = 0.f, sb0 = 0.f, sb1 = 0.f;
+  if (j < n) {
+    for (int r = r0 + w; r < r1; r += 4) {
+      const float d0 = to_f32(a[(long long)r * lda + j]), d1 = to_f32(a[(long long)r * lda + j + 1]);
+      sb0 += d0;
+      sb1 += d1;
+      if (MODE != 0) {
+        float x0, x1;
+        if (MODE == 1) {
+          x0 = to_f32(x[(long long)r * n + j]);
+          x1 = to_f32(x[(long long)r * n + j + 1]);
+        } else {
+          const long long tok = tokens[r];
+          const int s = r % S;
+          x0 = to_f32(E[tok * n + j]) + to_f32(pos[(long long)s * n + j]);
+          x1 = to_f32(E[tok * n + j + 1]) + to_f32(pos[(long long)s * n + j + 1]);
+        }
+        const float mu = mean[r], rs = rstd[r];
+        sa0 += d0 * ((x0 - mu) * rs);
+        sa1 += d1 * ((x1 - mu) * rs);
+      }
+    }
+  }
+  red[w][0][lane * 2] = sa0; red[w][0][lane * 2 + 1] = sa1;
+  red[w][1][lane * 2] = sb0; red[w][1][lane * 2 + 1] = sb1;
+  __syncthreads();
+  const int t = threadIdx.x;  // 256 threads: 2 outputs x 128 columns
+  const int which = t >> 7, c = t & 127;
+  const int col = blockIdx.x * 128 + c;
+  if (col < n && (MODE != 0 || which == 1)) {
+    const float s = red[0][which][c] + red[1][which][c] + red[2][which][c] + red[3][which][c];
+    atomicAdd((which == 0 ? out_a : out_b) + col, s);
+  }
+}
+
+// ---- softmax ---------------------------------------------------------------------------------------
+// In place: p[r,:] = softmax(p[r,:]) for rows of length n.
+template <typename T>
+__global__ __launch_bounds__(256) void softmax_fwd_kernel(T* p, long long rows, int n) {
+  const int lane = threadIdx.x & 63;
+  const long long r = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  T* row = p + r * n;
+  float mx = -INFINITY;
+  for (int j = lane; j < n; j += WAVE) mx = fmaxf(mx, to_f32(row[j]));
+  mx = wave_max(mx);
+  float s = 0.f;
+  for (int j = lane; j < n; j += WAVE) s += __expf(to_f32(row[j]) - mx);
+  s = 1.0f / wave_sum(s);
+  for (int j = lane; j < n; j += WAVE) row[j] = from_f32<T>(__expf(to_f32(row[j]) - mx) * s);
+}
+
+// In place on dp: ds = p * (dp - sum_j dp*p).
+template <typename T>
+__global__ __launch_bounds__(256) void softmax_bwd_kernel(const T* p, T* dp, long long rows, int n) {
+  const int lane = threadIdx.x & 63;
+  const long long r = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  const T* pr = p + r * n;
+  T* dr = dp + r * n;
+  float s = 0.f;
+  for (int j = lane; j < n; j += WAVE) s += to_f32(pr[j]) * to_f32(dr[j]);
+  s = wave_sum(s);
+  for (int j = lane; j < n; j += WAVE) dr[j] = from_f32<T>(to_f32(pr[j]) * (to_f32(dr[j]) - s));
+}
+
+// ---- head: label compaction, row gather / scatter, cross-entropy -----------------------------------
+// One block per micro-batch: idx[u*T + i] = position of the i-th labelled token (ascending),
+// cnt[u] = how many; total[0] += cnt[u].
+__global__ __launch_bounds__(256) void label_compact_kernel(const int32_t* labels, int T, int32_t* idx, int32_t* cnt,
+                                                            int32_t* total) {
+  __shared__ int part[256];
+  const int u = blockIdx.x, t = threadIdx.x;
+  const int32_t* lab = labels + (long long)u * T;
+  const int per = (T + 255) / 256;
+  const int b = t * per, e = min(T, b + per);
+  int c = 0;
+  for (int i = b; i < e; ++i) c += lab[i] >= 0;
+  part[t] = c;
+  __syncthreads();
+  if (t == 0) {
+    int run = 0;
+    for (int i = 0; i < 256; ++i) { const int v = part[i]; part[i] = run; run += v; }
+    cnt[u] = run;
+    atomicAdd(total, run);
+  }
+  __syncthreads();
+  int o = part[t];
+  for (int i = b; i < e; ++i)
+    if (lab[i] >= 0) idx[(long long)u * T + o++] = i;
+}
+
+// dst[i,:] = src[idx[i],:] (gather) or dst[idx[i],:] = src[i,:] (SCATTER) for i < *cnt; wave per row.
+template <typename T, bool SCATTER>
+__global__ __launch_bounds__(256) void rows_by_index_kernel(const T* src, T* dst, const int32_t* idx, const int32_t* cnt,
+                                                            int n) {
+  const int lane = threadIdx.x & 63;
+  const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (i >= *cnt) return;
+  const long long a = SCATTER ? i : idx[i], b = SCATTER ? idx[i] : i;
+  for (int j = lane * 8; j < n; j += WAVE * 8) {
+    float v[8];
+    load8(src + a * n + j, v);
+    store8(dst + b * n + j, v);
+  }
+}
+
+// Cross-entropy over one row of logits z[Vp] (first V valid): adds (lse - z[label]) / N to *loss and
+// writes dz = (softmax(z) - onehot) / N in T, zero in the padding columns.  One block per row.
+template <typename T>
+__global__ __launch_bounds__(256) void ce_kernel(const float* z, long long ldz, const int32_t* labels,
+                                                 const int32_t* idx, const int32_t* cnt, const int32_t* total, T* dz,
+                                                 float* loss, int V, int Vp) {
+  __shared__ float red[4];
+  const int i = blockIdx.x;
+  if (i >= *cnt) return;
+  const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+  const float* row = z + (long long)i * ldz;
+  float mx = -INFINITY;
+  for (int j = t; j < V; j += 256) mx = fmaxf(mx, row[j]);
+  mx = wave_max(mx);
+  if (lane == 0) red[w] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  __syncthreads();
+  float s = 0.f;
+  for (int j = t; j < V; j += 256) s += __expf(row[j] - mx);
+  s = wave_sum(s);
+  if (lane == 0) red[w] = s;
+  __syncthreads();
+  s = red[0] + red[1] + red[2] + red[3];
+  const float inv_n = 1.0f / (float)(*total);
+  const int label = labels[idx[i]];
+  const float lse = mx + __logf(s);
+  if (t == 0) atomicAdd(loss, (lse - row[label]) * inv_n);
+  T* d = dz + (long long)i * Vp;
+  const float inv_s = 1.0f / s;
+  for (int j = t; j < Vp; j += 256) {
+    float v = 0.f;
+    if (j < V) v = (__expf(row[j] - mx) * inv_s - (j == label ? 1.0f : 0.0f)) * inv_n;
+    d[j] = from_f32<T>(v);
+  }
+}
+
+// p[i] = v for i < n (graph-capturable replacement for a memset).
+__global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t* p, uint32_t v, long long n) {
+  long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  const long long stride = (long long)gridDim.x * 256;
+  for (; i < n; i += stride) p[i] = v;
+}

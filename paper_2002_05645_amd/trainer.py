@@ -1,0 +1,160 @@
+"""Step driver of L2L relay execution (Algorithm 2) above the C ABI.
+
+PyTorch supplies device memory and the two streams; every arithmetic step runs inside libl2l.so.
+The host EPS (block 0 = embedding/head block, block 1 + l = encoder layer l) keeps fp32 master
+weights and Adam state, ships the configured dtype, and receives fp32 gradients (Section 2.1, 2.3).
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def pack(layout, total, tensors) -> np.ndarray:
+    """dict of arrays -> flat fp32 packed block (padding zero)."""
+    flat = np.zeros(total, np.float32)
+    for k, (off, n) in layout.items():
+        a = np.asarray(tensors[k], np.float32).reshape(-1)
+        assert a.size == n, (k, a.size, n)
+        flat[off:off + n] = a
+    return flat
+
+
+def unpack(layout, shapes, flat) -> dict:
+    return {k: np.array(flat[off:off + n]).reshape(shapes[k]) for k, (off, n) in layout.items()}
+
+
+class L2LTrainer:
+    def __init__(self, *, layers, hidden, heads, ffn, seq, vocab, ubatch, num_ubatches, dtype="bf16",
+                 ln_eps=1e-12, lr=1e-4, beta1=0.9, beta2=0.999, eps_a=1e-8, ubatch_group=0,
+                 eps_threads=0, stash="device", device="cuda:0"):
+        assert stash in ("device", "host")
+        self.L, self.H, self.S, self.V = layers, hidden, seq, vocab
+        self.U, self.ub = num_ubatches, ubatch
+        self.dtype = dtype
+        self.hp = dict(lr=lr, beta1=beta1, beta2=beta2, eps_a=eps_a)
+        self.stash_mode = stash
+        self.device = torch.device(device)
+        self.cfg = B.make_config(hidden, heads, ffn, seq, ubatch, num_ubatches, dtype, ln_eps, vocab, ubatch_group)
+        if B.lib().l2l_config_check(self.cfg) != B.L2L_OK:
+            raise ValueError("unsupported L2L configuration")
+        self.layer_layout = B.layer_layout(self.cfg)
+        self.embed_layout = B.embed_layout(self.cfg)
+        self.layer_elems = B.lib().l2l_layer_packed_elems(self.cfg)
+        self.embed_elems = B.lib().l2l_embed_packed_elems(self.cfg)
+        self.eps = B.EPS([self.embed_elems] + [self.layer_elems] * layers, dtype, eps_threads)
+        torch.cuda.set_device(self.device)
+        self.compute = torch.cuda.Stream(device=self.device)
+        self.copy = torch.cuda.Stream(device=self.device)
+        self.ctx = B.Context(self.cfg, self.compute.cuda_stream, self.copy.cuda_stream)
+        tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+        shape = (num_ubatches, ubatch, seq, hidden)
+        n_stash = layers + 1 if stash == "device" else 2
+        self.stash = [torch.empty(shape, dtype=tdt, device=self.device) for _ in range(n_stash)]
+        if stash == "host":
+            self.host_stash = [torch.empty(shape, dtype=tdt, pin_memory=True) for _ in range(layers + 1)]
+            self.stash_ev = [torch.cuda.Event() for _ in range(2)]
+            self.stash_free = [torch.cuda.Event() for _ in range(2)]
+        self.dy = torch.empty(shape, dtype=tdt, device=self.device)
+        self.loss_dev = torch.zeros(1, dtype=torch.float32, device=self.device)
+        self.t = 0
+
+    # ---- parameters -------------------------------------------------------------------------------
+    def load_params(self, emb: dict, layers: list):
+        self.eps.master(0)[:] = pack(self.embed_layout, self.embed_elems, emb)
+        for l, p in enumerate(layers):
+            self.eps.master(1 + l)[:] = pack(self.layer_layout, self.layer_elems, p)
+        self.eps.refresh_ship()
+
+    def layer_shapes(self):
+        H, F = self.cfg.hidden, self.cfg.ffn
+        return {"Wqkv": (H, 3 * H), "bqkv": (3 * H,), "Wo": (H, H), "bo": (H,), "g1": (H,), "be1": (H,),
+                "W1": (H, F), "b1": (F,), "W2": (F, H), "b2": (H,), "g2": (H,), "be2": (H,)}
+
+    def embed_shapes(self):
+        return {"E": (self.V, self.H), "P": (self.S, self.H), "ge": (self.H,), "be": (self.H,), "bv": (self.V,)}
+
+    def grads(self):
+        """(embedding-block grads, per-layer grads) as dicts, from the EPS landing buffers."""
+        ge = unpack(self.embed_layout, self.embed_shapes(), self.eps.grad(0))
+        gl = [unpack(self.layer_layout, self.layer_shapes(), self.eps.grad(1 + l)) for l in range(self.L)]
+        return ge, gl
+
+    def master_params(self):
+        e = unpack(self.embed_layout, self.embed_shapes(), self.eps.master(0))
+        ls = [unpack(self.layer_layout, self.layer_shapes(), self.eps.master(1 + l)) for l in range(self.L)]
+        return e, ls
+
+    # ---- one step -----------------------------------------------------------------------------------
+    def _stash_slot(self, l):
+        return self.stash[l] if self.stash_mode == "device" else self.stash[l % 2]
+
+    def device_pipeline(self, tokens: torch.Tensor, labels: torch.Tensor):
+        """Stage -> forward over layers -> head -> backward over layers -> drain.  Asynchronous:
+        call finish() (or read the loss) to wait.  tokens / labels: int32 device tensors [U, ub, S]."""
+        c, e, L = self.ctx, self.eps, self.L
+        host_mode = self.stash_mode == "host"
+        c.embed_stage(e.ship_ptr(0))
+        c.param_stage(0, e.ship_ptr(1), 0)
+        c.embed_fwd(tokens, self._stash_slot(0))
+        if host_mode:
+            self._offload(0)
+        for l in range(L):
+            if l + 1 < L:
+                c.param_stage(l + 1, e.ship_ptr(2 + l), (l + 1) % 2)
+            if host_mode:
+                self.compute.wait_event(self.stash_free[(l + 1) % 2])
+            c.layer_fwd(l, l % 2, self._stash_slot(l), self._stash_slot(l + 1))
+            if host_mode:
+                self._offload(l + 1)
+        c.head_loss(self._stash_slot(L), labels, self.dy, self.loss_dev)
+        for l in reversed(range(L)):
+            if l - 1 >= 0:
+                c.param_stage(l - 1, e.ship_ptr(l), (l - 1) % 2)
+            if host_mode:
+                self._reload(l)
+            c.layer_bwd(l, l % 2, self._stash_slot(l), self.dy)
+            if host_mode:
+                self.stash_free[l % 2].record(self.compute)
+            c.grad_drain(l, e.grad_ptr(1 + l))
+        c.embed_bwd(tokens, self.dy)
+        c.embed_grad_drain(e.grad_ptr(0))
+
+    def _offload(self, l):
+        """device stash slot -> pinned host, on the copy stream, after the producing kernels."""
+        ev = self.stash_ev[l % 2]
+        ev.record(self.compute)
+        self.copy.wait_event(ev)
+        with torch.cuda.stream(self.copy):
+            self.host_stash[l].copy_(self.stash[l % 2], non_blocking=True)
+            self.stash_free[l % 2].record(self.copy)
+
+    def _reload(self, l):
+        """pinned host -> device stash slot before layer l's backward (layer L's input is not needed)."""
+        self.copy.wait_event(self.stash_free[l % 2])
+        with torch.cuda.stream(self.copy):
+            self.stash[l % 2].copy_(self.host_stash[l], non_blocking=True)
+            ev = self.stash_ev[l % 2]
+            ev.record(self.copy)
+        self.compute.wait_event(ev)
+
+    def finish(self) -> float:
+        self.ctx.sync()
+        return float(self.loss_dev.item())
+
+    def optimizer_step(self):
+        """EPS Adam over every block, after all gradients have landed (Algorithm 2's tail loop)."""
+        self.t += 1
+        self.eps.adam_step(0, self.L, self.t, **self.hp)
+
+    def step(self, tokens, labels) -> float:
+        self.device_pipeline(tokens, labels)
+        loss = self.finish()
+        self.optimizer_step()
+        return loss
+
+    def close(self):
+        self.ctx.close()
+        self.eps.close()

@@ -1,0 +1,329 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Tolerances: fp32 mode 1e-4 relative (rel-L2 per tensor), bf16 mode 2e-2 relative on
+gradients and loss; kernel-level cases are tighter where the arithmetic allows."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import l2l_synth as S
+import paper_2002_05645_amd as P
+from paper_2002_05645_amd import binding as B
+from paper_2002_05645_amd.trainer import L2LTrainer, pack, unpack
+from oracle import l2l_oracle as O
+from gpu_util import to_dev, to_host, rounded, pinned
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"fp32": 1e-4, "bf16": 2e-2}
+DT = {"fp32": P.L2L_F32, "bf16": P.L2L_BF16}
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    cfg = P.make_config(64, 2, 128, 16, 2, 2, "bf16", 1e-5, 0)
+    c = P.Context(cfg)
+    yield c
+    c.close()
+
+
+# ------------------------------------------------------------------------------------- GEMM kernel
+def _gemm_case(ctx, dtype, impl, a_kc, b_kc, M, N, K, bias=False, resid=False, gelu=False, accumulate=False,
+               out_f32=False, alpha=1.0, seed=0):
+    rng = np.random.default_rng(seed)
+    A = rng.normal(size=(M, K)).astype(np.float32)
+    Bm = rng.normal(size=(K, N)).astype(np.float32)
+    lda = ((K if a_kc else M) + 7) // 8 * 8 + 8
+    ldb = ((K if b_kc else N) + 7) // 8 * 8 + 8
+    ldc = N + 3
+    Ah = np.zeros((M, lda) if a_kc else (K, lda), np.float32)
+    Bh = np.zeros((N, ldb) if b_kc else (K, ldb), np.float32)
+    if a_kc:
+        Ah[:, :K] = A
+    else:
+        Ah[:, :M] = A.T
+    if b_kc:
+        Bh[:, :K] = Bm.T
+    else:
+        Bh[:, :N] = Bm
+    f32out = out_f32 or dtype == "fp32"
+    C0 = rng.normal(size=(M, ldc)).astype(np.float32)
+    Cd = torch.from_numpy(C0).cuda() if f32out else to_dev(C0, dtype)
+    C0v = to_host(Cd)
+    bias_h = rng.normal(size=N).astype(np.float32) if bias else None
+    res_h = rng.normal(size=(M, ldc)).astype(np.float32) if resid else None
+    Ad, Bd = to_dev(Ah, dtype), to_dev(Bh, dtype)
+    bd = to_dev(bias_h, dtype) if bias else None
+    rd = to_dev(res_h, dtype) if resid else None
+    ctx.op_gemm(DT[dtype], f32out, a_kc, b_kc, M, N, K, Ad, lda, Bd, ldb, Cd, ldc, alpha, bd, rd, gelu, accumulate,
+                impl)
+    torch.cuda.synchronize()
+    ref = alpha * (rounded(A, dtype) @ rounded(Bm, dtype))
+    if bias:
+        ref = ref + rounded(bias_h, dtype)
+    if gelu:
+        ref = O.gelu(ref)
+    if resid:
+        ref = ref + rounded(res_h, dtype)[:, :N]
+    if accumulate:
+        ref = ref + C0v[:, :N]
+    got = to_host(Cd)
+    assert np.array_equal(got[:, N:], C0v[:, N:]), "wrote outside the N columns"
+    return O.rel_l2(got[:, :N], ref)
+
+
+@pytest.mark.parametrize("a_kc,b_kc", [(1, 0), (1, 1), (0, 0), (0, 1)])
+@pytest.mark.parametrize("dtype,impl", [("fp32", 1), ("bf16", 1), ("bf16", 2)])
+def test_gemm_layouts_ragged(ctx, dtype, impl, a_kc, b_kc):
+    for (M, N, K) in [(200, 136, 96), (128, 128, 32), (1, 8, 8), (300, 72, 264), (130, 258, 40)]:
+        err = _gemm_case(ctx, dtype, impl, a_kc, b_kc, M, N, K, out_f32=True, seed=M + N)
+        assert err < 2e-6, (M, N, K, err)
+        err = _gemm_case(ctx, dtype, impl, a_kc, b_kc, M, N, K, bias=True, resid=True, seed=M)
+        assert err < (2e-6 if dtype == "fp32" else 3e-3), (M, N, K, err)
+
+
+@pytest.mark.parametrize("dtype,impl", [("fp32", 1), ("bf16", 1), ("bf16", 2)])
+def test_gemm_epilogues(ctx, dtype, impl):
+    lim = 2e-6 if dtype == "fp32" else 3e-3
+    assert _gemm_case(ctx, dtype, impl, 1, 0, 256, 192, 128, bias=True, gelu=True, alpha=0.1) < lim
+    assert _gemm_case(ctx, dtype, impl, 0, 0, 192, 256, 520, accumulate=True, out_f32=True) < 2e-6
+    assert _gemm_case(ctx, dtype, impl, 1, 1, 264, 136, 64, alpha=0.125, out_f32=True) < 2e-6
+    # ragged K (not a multiple of 8) on the strided-K layout
+    assert _gemm_case(ctx, dtype, impl, 0, 0, 136, 72, 613, accumulate=True, out_f32=True) < 2e-6
+
+
+def test_gemm_large_tile_sweep(ctx):
+    # several tiles in every direction plus tails, MFMA kernel
+    assert _gemm_case(ctx, "bf16", 2, 1, 0, 1000, 520, 264, bias=True, out_f32=True) < 2e-6
+    assert _gemm_case(ctx, "bf16", 2, 1, 1, 520, 1000, 136, out_f32=True) < 2e-6
+    assert _gemm_case(ctx, "bf16", 2, 0, 0, 520, 392, 1000, out_f32=True) < 2e-6
+
+
+def test_gemm_rejects_bad_arguments(ctx):
+    x = torch.zeros(64, 64, device="cuda")
+    with pytest.raises(P.L2LError) as e:
+        ctx.op_gemm(P.L2L_BF16, False, 1, 0, 8, 8, 8, x, 8, x, 8, x, 8, accumulate=True)
+    assert e.value.code == P.L2L_E_ARG
+    with pytest.raises(P.L2LError):
+        ctx.op_gemm(P.L2L_F32, True, 1, 0, 8, 8, 8, None, 8, x, 8, x, 8)
+    with pytest.raises(P.L2LError):
+        ctx.op_gemm(P.L2L_BF16, True, 1, 0, 8, 8, 8, x, 7, x, 8, x, 8, impl=2)     # lda not a multiple of 8
+
+
+# ------------------------------------------------------------------------------------- LayerNorm kernel
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("rows,n", [(1, 8), (37, 1024), (5, 200), (130, 6144)])
+def test_layernorm(ctx, dtype, rows, n):
+    rng = np.random.default_rng(rows)
+    x = (rng.normal(size=(rows, n)) * 2 + 0.5).astype(np.float32)
+    g = (1 + 0.1 * rng.normal(size=n)).astype(np.float32)
+    b = (0.1 * rng.normal(size=n)).astype(np.float32)
+    xd, gd, bd = to_dev(x, dtype), to_dev(g, dtype), to_dev(b, dtype)
+    yd = torch.empty_like(xd)
+    mean = torch.empty(rows, device="cuda")
+    rstd = torch.empty(rows, device="cuda")
+    ctx.op_layernorm(DT[dtype], rows, n, xd, gd, bd, 1e-12, yd, mean, rstd)
+    torch.cuda.synchronize()
+    ref, (xhat, rs) = O.layer_norm_fwd(rounded(x, dtype), rounded(g, dtype), rounded(b, dtype), 1e-12)
+    assert O.rel_l2(to_host(yd), ref) < (2e-6 if dtype == "fp32" else 3e-3)
+    assert O.rel_l2(to_host(rstd), rs[:, 0]) < 1e-5
+    assert O.rel_l2(to_host(mean), rounded(x, dtype).mean(-1)) < 1e-5
+
+
+# ------------------------------------------------------------------------------------- one layer, all micro-batches
+def _layer_case(w: S.Workload, group=0, x_scale=1.0, check_fwd_only=False):
+    dtype = w.dtype
+    cfg = P.make_config(w.hidden, w.heads, w.ffn, w.seq, w.ubatch, w.num_ubatches, dtype, 1e-12, 0, group)
+    c = P.Context(cfg)
+    try:
+        lay = P.layer_layout(cfg)
+        total = P.lib().l2l_layer_packed_elems(cfg)
+        p32 = S.layer_params(w, 0)
+        flat = pack(lay, total, p32)
+        host = pinned(O.bf16_bits(flat).view(np.int16) if dtype == "bf16" else flat)
+        pr = {k: rounded(v, dtype) for k, v in p32.items()}
+        X = S.activations(w) * x_scale
+        dY = S.output_grads(w)
+        Xd, dYd = to_dev(X, dtype), to_dev(dY, dtype)
+        Yd = torch.empty_like(Xd)
+        c.param_stage(0, host, 0)
+        c.layer_fwd(0, 0, Xd, Yd)
+        c.sync()
+        Xr, dYr = rounded(X, dtype), rounded(dY, dtype)
+        Yref = O.layer_l2l_fwd(Xr, pr, w.heads, 1e-12)
+        errs = {"Y": O.rel_l2(to_host(Yd), Yref)}
+        if not check_fwd_only:
+            c.layer_bwd(0, 0, Xd, dYd)
+            gh = torch.empty(total, dtype=torch.float32).pin_memory()
+            c.grad_drain(0, gh)
+            c.drain_wait(0)
+            c.sync()
+            dXref, gref = O.layer_l2l_bwd(Xr, dYr, pr, w.heads, 1e-12)
+            errs["dX"] = O.rel_l2(to_host(dYd), dXref)
+            got = unpack(lay, S.layer_shapes(w), gh.numpy())
+            for k in gref:
+                errs["d" + k] = O.rel_l2(got[k], gref[k])
+            # padding of the gradient block stays zero
+            mask = np.ones(total, bool)
+            for off, n in lay.values():
+                mask[off:off + n] = False
+            assert not gh.numpy()[mask].any()
+        return errs
+    finally:
+        c.close()
+
+
+def _assert_errs(errs, tol):
+    bad = {k: v for k, v in errs.items() if not (v < tol)}
+    assert not bad, f"over tolerance {tol}: {bad}; all: {errs}"
+
+
+def test_layer_tiny_fp32():
+    w = S.WORKLOADS[0]
+    _assert_errs(_layer_case(w), TOL["fp32"])
+
+
+def test_layer_tiny_fp32_ungrouped_equals_grouped():
+    w = S.WORKLOADS[0]
+    _assert_errs(_layer_case(w, group=1), TOL["fp32"])
+    _assert_errs(_layer_case(w.scaled(num_ubatches=3), group=2), TOL["fp32"])     # ragged last group
+
+
+def test_layer_ragged_bf16():
+    # nothing is a multiple of a tile: H=96 (3 heads of 32), F=200, S=24, ub=3, U=3 in groups of 2
+    w = S.Workload("ragged", 1, 96, 3, 200, 24, 50, 3, 3, "bf16", 1.0, 77)
+    _assert_errs(_layer_case(w, group=2), TOL["bf16"])
+    w32 = w.scaled(dtype="fp32")
+    _assert_errs(_layer_case(w32, group=2), TOL["fp32"])
+
+
+def test_layer_single_sequence_single_ubatch():
+    w = S.Workload("one", 1, 64, 1, 64, 8, 50, 1, 1, "bf16", 1.0, 78)
+    _assert_errs(_layer_case(w), TOL["bf16"])
+
+
+def test_layer_bert_base_shape_bf16():
+    w = S.WORKLOADS[1].scaled(num_ubatches=2, ubatch=4)          # real widths, fewer rows: oracle in seconds
+    _assert_errs(_layer_case(w), TOL["bf16"])
+
+
+@pytest.mark.slow
+def test_layer_bert_large_full_shape_bf16():
+    # the benchmark's launch configuration: U = 8 micro-batches of 32 sequences, S = 128
+    w = S.WORKLOADS[2]
+    _assert_errs(_layer_case(w), TOL["bf16"])
+
+
+def test_layer_seq512_bf16():
+    w = S.WORKLOADS[3].scaled(num_ubatches=2, ubatch=1)
+    _assert_errs(_layer_case(w), TOL["bf16"])
+
+
+# ------------------------------------------------------------------------------------- whole step
+def _step_case(w: S.Workload, stash="device", group=0, lr=1e-4):
+    dtype = w.dtype
+    tr = L2LTrainer(layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, vocab=w.vocab,
+                    ubatch=w.ubatch, num_ubatches=w.num_ubatches, dtype=dtype, lr=lr, stash=stash, ubatch_group=group,
+                    eps_threads=8)
+    try:
+        assert tr.eps.is_pinned()
+        emb = S.embed_params(w)
+        layers = [S.layer_params(w, l) for l in range(w.layers)]
+        tr.load_params(emb, layers)
+        tok, lab = S.tokens_and_labels(w)
+        tokd, labd = torch.from_numpy(tok).cuda(), torch.from_numpy(lab).cuda()
+        e_r = {k: rounded(v, dtype) for k, v in emb.items()}
+        l_r = [{k: rounded(v, dtype) for k, v in p.items()} for p in layers]
+        loss_ref, gemb_ref, gl_ref = O.run_l2l(e_r, l_r, tok, lab, w.heads, 1e-12)
+        loss = tr.step(tokd, labd)
+        errs = {"loss": abs(loss - loss_ref) / abs(loss_ref)}
+        ge, gl = tr.grads()
+        for k in gemb_ref:
+            errs["emb.d" + k] = O.rel_l2(ge[k], gemb_ref[k])
+        for l in range(w.layers):
+            for k in gl_ref[l]:
+                errs[f"l{l}.d{k}"] = O.rel_l2(gl[l][k], gl_ref[l][k])
+        # optimizer: the EPS's fp32 master after one Adam step, from ITS OWN gradients, against the oracle's Adam
+        me, ml = tr.master_params()
+        for k in emb:
+            wref, _, _ = O.adam_step(emb[k].astype(np.float64), ge[k].astype(np.float64), 0.0, 0.0, 1, lr=lr)
+            errs["adam.emb." + k] = O.rel_l2(me[k] - emb[k], wref - emb[k]) if np.any(ge[k]) else 0.0
+        for k in layers[0]:
+            wref, _, _ = O.adam_step(layers[0][k].astype(np.float64), gl[0][k].astype(np.float64), 0.0, 0.0, 1, lr=lr)
+            errs["adam.l0." + k] = O.rel_l2(ml[0][k] - layers[0][k], wref - layers[0][k])
+        return errs, loss, loss_ref
+    finally:
+        tr.close()
+
+
+def test_step_tiny_fp32_matches_oracle():
+    w = S.WORKLOADS[0]
+    errs, loss, loss_ref = _step_case(w)
+    adam = {k: v for k, v in errs.items() if k.startswith("adam.")}
+    rest = {k: v for k, v in errs.items() if not k.startswith("adam.")}
+    _assert_errs(rest, TOL["fp32"])
+    _assert_errs(adam, 1e-3)      # w - w0 is a difference of fp32 numbers of size 1: ~1e-7 / 1e-4
+    assert abs(loss_ref - math.log(w.vocab)) < 0.05        # random init: loss sits at ln V
+
+
+def test_step_tiny_fp32_host_stash():
+    errs, _, _ = _step_case(S.WORKLOADS[0], stash="host")
+    _assert_errs({k: v for k, v in errs.items() if not k.startswith("adam.")}, TOL["fp32"])
+
+
+def test_step_bf16_small_depth():
+    # BERT-Base widths, 3 layers, fewer rows; 15% random labels
+    w = S.WORKLOADS[1].scaled(layers=3, ubatch=2, num_ubatches=3, vocab=3000)
+    errs, loss, loss_ref = _step_case(w, group=2)
+    _assert_errs({k: v for k, v in errs.items() if not k.startswith("adam.")}, TOL["bf16"])
+
+
+@pytest.mark.slow
+def test_step_bert_base_bf16_full():
+    w = S.WORKLOADS[1]
+    errs, loss, loss_ref = _step_case(w)
+    _assert_errs({k: v for k, v in errs.items() if not k.startswith("adam.")}, TOL["bf16"])
+    assert abs(loss_ref - math.log(w.vocab)) < 0.05
+
+
+# ------------------------------------------------------------------------------------- call-order errors
+def test_call_order_errors():
+    cfg = P.make_config(64, 2, 128, 16, 2, 2, "fp32", 1e-5, 0)
+    c = P.Context(cfg)
+    x = torch.zeros(2, 2, 16, 64, device="cuda")
+    y = torch.zeros_like(x)
+    try:
+        with pytest.raises(P.L2LError) as e:
+            c.layer_fwd(0, 0, x, y)                       # never staged
+        assert e.value.code == P.L2L_E_STATE
+        with pytest.raises(P.L2LError) as e:
+            c.layer_fwd(0, 2, x, y)
+        assert e.value.code == P.L2L_E_ARG
+        with pytest.raises(P.L2LError) as e:
+            c.grad_drain(0, pinned(np.zeros(4, np.float32)))
+        assert e.value.code == P.L2L_E_STATE
+        with pytest.raises(P.L2LError) as e:
+            c.embed_fwd(x, y)                             # vocab = 0
+        assert e.value.code == P.L2L_E_STATE
+        n = P.lib().l2l_layer_packed_elems(cfg)
+        host = pinned(np.zeros(n, np.float32))
+        c.param_stage(3, host, 1)
+        with pytest.raises(P.L2LError) as e:
+            c.layer_fwd(2, 1, x, y)                       # slot holds another layer
+        assert e.value.code == P.L2L_E_STATE
+        with pytest.raises(P.L2LError):
+            c.layer_fwd(3, 1, None, y)
+        c.layer_bwd(3, 1, x, y)
+        c.param_stage(4, host, 0)
+        c.layer_bwd(4, 0, x, y)
+        with pytest.raises(P.L2LError) as e:
+            c.layer_bwd(3, 1, x, y)                       # both accumulators hold un-drained gradients
+        assert e.value.code == P.L2L_E_STATE
+        g = torch.empty(n, dtype=torch.float32).pin_memory()
+        c.grad_drain(3, g)
+        c.drain_wait(3)
+        c.layer_bwd(3, 1, x, y)
+        c.sync()
+    finally:
+        c.close()

@@ -1,0 +1,129 @@
+"""CPU-only tests: the C-ABI library loads and exports what the header declares; packed layouts;
+config checking; the host EPS (Adam, bf16 shipping copy) against the oracle."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2002_05645_amd as P
+from paper_2002_05645_amd import binding as B
+from oracle import l2l_oracle as O
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    src = open(os.path.join(ROOT, "include", "l2l.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b((?:l2l|eps)_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert len(names) > 40
+    lib = C.CDLL(P.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(names) == set(B.EXPORTS), set(names) ^ set(B.EXPORTS)
+
+
+def test_layout_and_counts():
+    cfg = P.make_config(1024, 16, 4096, 128, 32, 8, "bf16", 1e-12, 30522)
+    L = P.lib()
+    assert L.l2l_layer_param_count(cfg) == O.layer_param_count(1024, 4096) == 12596224
+    lay = P.layer_layout(cfg)
+    assert list(lay) == list(O.LAYER_KEYS)
+    end = 0
+    for k, (off, n) in lay.items():
+        assert off % 128 == 0 and off >= end
+        end = off + n
+    assert L.l2l_layer_packed_elems(cfg) >= end
+    assert L.l2l_layer_param_bytes(cfg) == 2 * L.l2l_layer_packed_elems(cfg)
+    assert L.l2l_layer_grad_bytes(cfg) == 4 * L.l2l_layer_packed_elems(cfg)
+    assert sum(n for _, n in lay.values()) == 12596224
+    el = P.embed_layout(cfg)
+    assert list(el) == list(O.EMBED_KEYS)
+    assert el["E"][1] == 30522 * 1024 and el["bv"][1] == 30522
+    # ragged sizes get padded sub-blocks
+    cfg2 = P.make_config(72, 3, 200, 24, 3, 3, "fp32", 1e-5, 50)
+    lay2 = P.layer_layout(cfg2)
+    assert all(off % 128 == 0 for off, _ in lay2.values())
+    assert L.l2l_layer_param_bytes(cfg2) == 4 * L.l2l_layer_packed_elems(cfg2)
+
+
+@pytest.mark.parametrize("bad", [dict(hidden=100), dict(heads=3), dict(ffn=130), dict(seq=12), dict(dtype=7),
+                                 dict(vocab=31), dict(ubatch=0), dict(num_ubatches=0), dict(ubatch_group=9),
+                                 dict(ln_eps=-1.0)])
+def test_config_check_rejects(bad):
+    kw = dict(hidden=128, heads=2, ffn=512, seq=64, ubatch=4, num_ubatches=4, dtype=0, ln_eps=1e-12, vocab=1000,
+              ubatch_group=0)
+    assert P.lib().l2l_config_check(B.l2l_config(**kw)) == P.L2L_OK
+    kw.update(bad)
+    cfg = B.l2l_config(**kw)
+    assert P.lib().l2l_config_check(cfg) == P.L2L_E_ARG
+    assert P.lib().l2l_layer_packed_elems(cfg) == 0
+    assert P.lib().l2l_layer_tensor_offset(cfg, 0) == -1
+
+
+def test_null_arguments_are_errors_not_crashes():
+    L = P.lib()
+    assert L.l2l_config_check(None) == P.L2L_E_ARG
+    assert L.l2l_param_stage(None, 0, None, 0) == P.L2L_E_ARG
+    assert L.l2l_layer_fwd(None, 0, 0, None, None) == P.L2L_E_ARG
+    assert L.l2l_layer_bwd(None, 0, 0, None, None) == P.L2L_E_ARG
+    assert L.l2l_grad_drain(None, 0, None) == P.L2L_E_ARG
+    assert L.l2l_drain_wait(None, 0) == P.L2L_E_ARG
+    assert L.l2l_sync(None) == P.L2L_E_ARG
+    assert L.l2l_destroy(None) == P.L2L_E_ARG
+    assert L.l2l_layer_tensor_name(99) is None
+    assert L.eps_destroy(None) == P.L2L_E_ARG
+    assert L.eps_adam_step(None, 0, 0, 1, 1e-4, 0.9, 0.999, 1e-8) == P.L2L_E_ARG
+    out = C.c_void_p()
+    assert L.eps_create(0, None, 1, 1, C.byref(out)) == P.L2L_E_ARG
+    assert L.l2l_create(None, None, None, C.byref(out)) == P.L2L_E_ARG
+
+
+def test_eps_bf16_ship_is_round_to_nearest_even_bit_exact():
+    n = 1 << 18
+    rng = np.random.default_rng(0)
+    w = (rng.normal(size=n) * np.exp(rng.normal(size=n) * 4)).astype(np.float32)
+    w[:8] = np.array([0x3F808000, 0x3F818000, 0x3F808001, 0x3F807FFF, 0x7F7FFFFF, 0x00000001, 0x80000000, 0x7F800000],
+                     np.uint32).view(np.float32)
+    e = P.EPS([n], "bf16", 4)
+    e.master(0)[:] = w
+    e.refresh_ship()
+    assert np.array_equal(e.ship(0), O.bf16_bits(w))
+    e.close()
+
+
+@pytest.mark.parametrize("threads", [1, 5])
+def test_eps_adam_matches_oracle(threads):
+    n = 300001
+    rng = np.random.default_rng(1)
+    w0 = rng.normal(size=n).astype(np.float32)
+    e = P.EPS([7, n], "bf16", threads)
+    e.master(1)[:] = w0
+    w, m, v = w0.astype(np.float64), np.zeros(n), np.zeros(n)
+    for t in range(1, 4):
+        g = (rng.normal(size=n) * 10.0 ** rng.integers(-6, 1, size=n)).astype(np.float32)
+        g[::17] = 0
+        e.grad(1)[:] = g
+        e.adam_step(1, 1, t, lr=1e-3)
+        w, m, v = O.adam_step(w, g.astype(np.float64), m, v, t, lr=1e-3)
+        np.testing.assert_allclose(e.master(1), w, rtol=2e-6, atol=1e-9)
+        np.testing.assert_allclose(e.moment(1, 0), m, rtol=1e-5, atol=1e-7)      # fp32 cancellation when m crosses zero
+        np.testing.assert_allclose(e.moment(1, 1), v, rtol=1e-5, atol=1e-30)
+        assert np.array_equal(e.ship(1), O.bf16_bits(e.master(1)))
+    assert np.all(e.master(0) == 0)          # untouched block
+    # first step of Adam moves every weight with a non-zero gradient by about lr
+    e2 = P.EPS([n], "fp32", threads)
+    e2.master(0)[:] = w0
+    g = rng.normal(size=n).astype(np.float32)
+    e2.grad(0)[:] = g
+    e2.adam_step(0, 0, 1, lr=1e-3)
+    np.testing.assert_allclose(e2.master(0) - w0, -1e-3 * g / (np.abs(g) + 1e-8), atol=5e-7)
+    assert np.array_equal(e2.ship(0), e2.master(0))
+    e.close()
+    e2.close()
