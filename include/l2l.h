@@ -165,7 +165,8 @@ int l2l_profile_read(l2l_ctx*, int cls, long long* launches, double* ms, double*
    in_dtype: dtype of A, B, bias, resid;  out_f32: 1 = C is fp32, else in_dtype.
    bias: [N] or NULL; resid: [M,N] with row stride ldc or NULL; accumulate: C += result (needs out_f32).
    gelu: apply GELU after the bias.  impl: 0 = library's choice, 1 = force the plain kernel,
-   2 = force the MFMA kernel (L2L_E_ARG if the shape does not allow it). */
+   2 = force the MFMA kernel (L2L_E_ARG if the shape does not allow it); 100 + v = MFMA tile variant v
+   (for tuning). */
 int l2l_op_gemm(l2l_ctx*, int in_dtype, int out_f32, int a_kc, int b_kc, int M, int N, int K,
                 const void* A, long long lda, const void* B, long long ldb, void* C, long long ldc,
                 float alpha, const void* bias, const void* resid, int gelu, int accumulate, int impl);

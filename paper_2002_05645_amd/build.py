@@ -1,7 +1,9 @@
 """Builds libl2l.so (HIP kernels + C ABI + host EPS) for gfx950, in-tree."""
 from __future__ import annotations
 
+import concurrent.futures
 import os
+import re
 import subprocess
 import sys
 
@@ -13,7 +15,10 @@ HIPCC = os.path.join(ROCM, "bin", "hipcc")
 
 HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 instructions
+             "-munsafe-fp-atomics",      # fp32 atomics on device memory go to the hardware atomic units
              "-Wno-unused-result"]
+with open(os.path.join(CSRC, "gemm_variants.h")) as _f:
+    NUM_GEMM_VARIANTS = int(re.search(r"kNumGemmVariants\s*=\s*(\d+)", _f.read()).group(1))
 HOST_FLAGS = ["-O3", "-std=c++17", "-fPIC", "-mavx2", "-mfma", "-D__HIP_PLATFORM_AMD__", f"-I{ROCM}/include", "-pthread"]
 
 
@@ -31,9 +36,16 @@ def build(verbose: bool = False) -> str:
     os.makedirs(obj_dir, exist_ok=True)
     o_hip = os.path.join(obj_dir, "l2l.o")
     o_eps = os.path.join(obj_dir, "eps.o")
-    _run([HIPCC, *HIP_FLAGS, "-c", os.path.join(CSRC, "l2l.hip"), "-o", o_hip])
-    _run(["g++", *HOST_FLAGS, "-c", os.path.join(CSRC, "eps.cpp"), "-o", o_eps])
-    _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", o_hip, o_eps, "-o", LIB, "-pthread"])
+    jobs = [[HIPCC, *HIP_FLAGS, "-c", os.path.join(CSRC, "l2l.hip"), "-o", o_hip],
+            ["g++", *HOST_FLAGS, "-c", os.path.join(CSRC, "eps.cpp"), "-o", o_eps]]
+    objs = [o_hip, o_eps]
+    for v in range(NUM_GEMM_VARIANTS):        # one translation unit per MFMA tile variant
+        o = os.path.join(obj_dir, f"gemm_v{v}.o")
+        jobs.append([HIPCC, *HIP_FLAGS, f"-DL2L_VARIANT={v}", "-c", os.path.join(CSRC, "gemm_variant.hip"), "-o", o])
+        objs.append(o)
+    with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
+        list(ex.map(_run, jobs))
+    _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB, "-pthread"])
     if verbose:
         print("built", LIB)
     return LIB

@@ -3,6 +3,16 @@
 // bias / GELU / GELU-gradient / residual / accumulate epilogues.
 #pragma once
 #include "common.h"
+#include <type_traits>
+
+// compile-time loop: f(integral_constant<int, I>) for I in [0, N) -- keeps register arrays indexed by constants
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
+}
 
 // ------------------------------------------------------------------------------------------------
 // Epilogue shared by both kernels.  v = alpha * acc already applied by the caller.
@@ -87,110 +97,184 @@ __global__ __launch_bounds__(256) void gemm_plain_kernel(GemmArgs g) {
 // as (WM/32) x (WN/32) accumulators of v_mfma_f32_32x32x16_bf16.  An operand whose K index is
 // contiguous in memory is kept in LDS as [row][BK+8] bf16 and read back as one 16-byte fragment
 // (8 consecutive k).  An operand whose K index is the strided one ([K,M] or [K,N] in memory) is
-// loaded as two 16-byte row chunks for k and k+1, interleaved into (k,k+1) pairs per column and
-// kept as [BK/2][cols+8] dwords; a fragment is then four dword reads.  Both give the same k order,
-// so every combination of layouts feeds the same MFMA -- no transposed copies of weights or
-// activations exist in memory.  LDS is double buffered; the next tile's global loads are issued
+// loaded as 8 x 8 blocks (eight 16-byte row chunks per thread), transposed in registers and stored
+// in that same LDS image, so every combination of layouts feeds the same MFMA from 16-byte LDS
+// reads (the only LDS read width that reaches 256 B/clk on this chip) -- no transposed copies of
+// weights or activations exist in memory.  LDS is double buffered; the next tile's global loads are issued
 // before the current tile's MFMAs.
 //
-// Bounds: a 16-byte chunk is loaded iff its first element is inside the operand's extent, so row
-// pitches must cover the extent rounded up to 8 elements and ragged K needs zero padding in the
-// K-contiguous operand.  Stores are masked exactly.
-template <int ROWS, int BK, bool KC>
+// Global loads are buffer loads: the descriptor's byte range ends where the operand's valid rows end,
+// so rows past M / N / K come back as zeros from the hardware without a branch; a 16-byte chunk of a
+// K-contiguous operand whose first element is past K is sent out of range explicitly.  Row pitches
+// must therefore cover the extent rounded up to 8 elements, and ragged K needs zero padding in the
+// K-contiguous operand.  Columns past M / N only feed outputs that are never stored.
+//
+// Epilogue: each wave parks one 32-row strip of its accumulators in LDS (fp32), reads it back row
+// major and applies bias / GELU / residual on 8 consecutive columns at a time with 16-byte global
+// accesses; a scalar path covers unaligned outputs.  Stores are masked exactly.
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+constexpr uint32_t BUF_OOB = 0x80000000u;  // beyond any descriptor range used here (operands are < 2 GiB)
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ u32x4 buf_load16(__amdgpu_buffer_rsrc_t r, uint32_t byte_off) {
+  return __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0);
+}
+
+// LDS image of one operand tile, the same for both memory layouts: [row][BK + 8] bf16 (row = output
+// row for A, output column for B), so a fragment is always one 16-byte read.
+template <int ROWS, int BK>
 struct TileLds {
-  // bytes of one stage
-  static constexpr int PITCH = KC ? (BK + 8) : (ROWS + 8);            // bf16 elems (KC) or dwords (!KC)
-  static constexpr int BYTES = KC ? ROWS * PITCH * 2 : (BK / 2) * PITCH * 4;
+  static constexpr int PITCH = BK + 8;              // bf16 elements; 16 bytes of padding per row
+  static constexpr int BYTES = ROWS * PITCH * 2;    // one stage
 };
 
+// Byte range of an operand tile seen from its first element: rows_left rows (KC) or K rows (!KC).
+template <bool KC>
+__device__ __forceinline__ uint32_t tile_bytes(long long ld, int rows_left, int K) {
+  const long long k8 = (K + 7) & ~7, r8 = (rows_left + 7) & ~7;
+  const long long e = KC ? (long long)(rows_left - 1) * ld + k8 : (long long)(K - 1) * ld + r8;
+  return (uint32_t)(e * 2);
+}
+
+// Global -> registers -> LDS for one operand tile.
+//  KC  (memory [rows, K]):   a unit is one 16-byte chunk (8 k of one row), copied as is.
+//  !KC (memory [K, rows]):   a unit is an 8(k) x 8(rows) block: eight 16-byte loads (one per k), transposed
+//                            in registers with byte permutes, stored as eight 16-byte chunks (one per row).
+//                            Lanes of a wave take 8 row-blocks x 8 k-blocks, so that each load instruction
+//                            reads 128-byte row segments and each store instruction covers all LDS banks.
 template <int ROWS, int BK, bool KC, int NT>
 struct TileLoader {
-  static constexpr int UNITS = KC ? ROWS * (BK / 8) : (BK / 2) * (ROWS / 8);
+  static constexpr int PITCH = TileLds<ROWS, BK>::PITCH;
+  static constexpr int UNITS = KC ? ROWS * (BK / 8) : (ROWS / 8) * (BK / 8);
   static constexpr int PER = (UNITS + NT - 1) / NT;
-  static constexpr int REGS = KC ? PER : 2 * PER;
+  static constexpr int REGS = KC ? PER : 8 * PER;
+  static_assert(KC || (BK / 8 == 8 && (ROWS / 8) % 8 == 0), "transposing loader wants BK = 64 and rows in blocks of 64");
   u32x4 r[REGS];
 
-  // base: operand pointer already offset to (row0, k = 0); ld: row stride; rows_left: extent - row0
-  __device__ __forceinline__ void load(const bf16* base, long long ld, int rows_left, int k0, int K, int tid) {
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
+  // unit -> (row block, k block) for the transposing loader
+  static __device__ __forceinline__ void unit_pos(int u, int& rb, int& kb) {
+    const int w = u >> 6, l = u & 63;          // 64 units per wave: 8 row blocks x 8 k blocks
+    rb = w * 8 + (l >> 3);   // 16 consecutive lanes = 2 row blocks x 8 k blocks: their 16-byte stores hit all banks
+    kb = l & 7;
+  }
+
+  __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rs, uint32_t ld, int k0, int K, int tid) {
+    static_for<0, PER>([&](auto ic) {
+      constexpr int i = decltype(ic)::value;
       const int u = tid + i * NT;
-      if (KC) {
+      const bool live = UNITS % NT == 0 || u < UNITS;
+      if constexpr (KC) {
         const int row = u / (BK / 8), kc = u % (BK / 8);
         const int k = k0 + kc * 8;
-        u32x4 v = {0, 0, 0, 0};
-        if ((UNITS % NT == 0 || u < UNITS) && row < rows_left && k < K)
-          v = *(const u32x4*)(base + (long long)row * ld + k);
-        r[i] = v;
+        uint32_t off = ((uint32_t)row * ld + (uint32_t)k) * 2u;
+        if (k >= K || !live) off = BUF_OOB;
+        r[i] = buf_load16(rs, off);
       } else {
-        const int kp = u / (ROWS / 8), cc = u % (ROWS / 8);
-        const int k = k0 + 2 * kp, col = cc * 8;
-        u32x4 lo = {0, 0, 0, 0}, hi = {0, 0, 0, 0};
-        if ((UNITS % NT == 0 || u < UNITS) && col < rows_left) {
-          if (k < K) lo = *(const u32x4*)(base + (long long)k * ld + col);
-          if (k + 1 < K) hi = *(const u32x4*)(base + (long long)(k + 1) * ld + col);
-        }
-        r[2 * i] = lo;
-        r[2 * i + 1] = hi;
+        int rb, kb;
+        unit_pos(u, rb, kb);
+        // rows k >= K fall past the descriptor's range and read as zero
+        uint32_t off = ((uint32_t)(k0 + kb * 8) * ld + (uint32_t)(rb * 8)) * 2u;
+        static_for<0, 8>([&](auto kc) {
+          constexpr int kq = decltype(kc)::value;
+          r[8 * i + kq] = buf_load16(rs, live ? off + (uint32_t)kq * ld * 2u : BUF_OOB);
+        });
       }
-    }
+    });
   }
 
   __device__ __forceinline__ void store(char* lds, int tid) const {
-    constexpr int PITCH = TileLds<ROWS, BK, KC>::PITCH;
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
+    static_for<0, PER>([&](auto ic) {
+      constexpr int i = decltype(ic)::value;
       const int u = tid + i * NT;
-      if (UNITS % NT != 0 && u >= UNITS) continue;
-      if (KC) {
-        const int row = u / (BK / 8), kc = u % (BK / 8);
-        *(u32x4*)(lds + (row * PITCH + kc * 8) * 2) = r[i];
-      } else {
-        const int kp = u / (ROWS / 8), cc = u % (ROWS / 8);
-        const u32x4 lo = r[2 * i], hi = r[2 * i + 1];
-        u32x4 p0, p1;  // dword j = (k element j, k+1 element j)
-        p0.x = __builtin_amdgcn_perm(hi.x, lo.x, 0x05040100u);
-        p0.y = __builtin_amdgcn_perm(hi.x, lo.x, 0x07060302u);
-        p0.z = __builtin_amdgcn_perm(hi.y, lo.y, 0x05040100u);
-        p0.w = __builtin_amdgcn_perm(hi.y, lo.y, 0x07060302u);
-        p1.x = __builtin_amdgcn_perm(hi.z, lo.z, 0x05040100u);
-        p1.y = __builtin_amdgcn_perm(hi.z, lo.z, 0x07060302u);
-        p1.z = __builtin_amdgcn_perm(hi.w, lo.w, 0x05040100u);
-        p1.w = __builtin_amdgcn_perm(hi.w, lo.w, 0x07060302u);
-        char* p = lds + (kp * PITCH + cc * 8) * 4;
-        *(u32x4*)p = p0;
-        *(u32x4*)(p + 16) = p1;
+      if (UNITS % NT == 0 || u < UNITS) {
+        if constexpr (KC) {
+          const int row = u / (BK / 8), kc = u % (BK / 8);
+          *(u32x4*)(lds + (row * PITCH + kc * 8) * 2) = r[i];
+        } else {
+          int rb, kb;
+          unit_pos(u, rb, kb);
+          char* p = lds + ((rb * 8) * PITCH + kb * 8) * 2;
+          // out row j, dword d = (k = 2d, k = 2d + 1) of input column j: halves of dword j/2 of r[2d], r[2d+1]
+          static_for<0, 8>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            constexpr uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
+            u32x4 o;
+            o.x = __builtin_amdgcn_perm(r[8 * i + 1][j >> 1], r[8 * i + 0][j >> 1], sel);
+            o.y = __builtin_amdgcn_perm(r[8 * i + 3][j >> 1], r[8 * i + 2][j >> 1], sel);
+            o.z = __builtin_amdgcn_perm(r[8 * i + 5][j >> 1], r[8 * i + 4][j >> 1], sel);
+            o.w = __builtin_amdgcn_perm(r[8 * i + 7][j >> 1], r[8 * i + 6][j >> 1], sel);
+            *(u32x4*)(p + j * PITCH * 2) = o;
+          });
+        }
       }
-    }
+    });
   }
 };
 
-// Fragment (8 k-values for one row/column) of k16-step kk out of a staged tile.
-template <int ROWS, int BK, bool KC>
+// Fragment (8 consecutive k of one row / column) of k16-step kk out of a staged tile.
+template <int ROWS, int BK>
 __device__ __forceinline__ bf16x8 read_frag(const char* lds, int row, int kk, int lane) {
-  constexpr int PITCH = TileLds<ROWS, BK, KC>::PITCH;
-  const int g = lane >> 5;
-  if (KC) {
-    return *(const bf16x8*)(lds + (row * PITCH + kk * 16 + g * 8) * 2);
-  } else {
-    const uint32_t* p = (const uint32_t*)lds + (kk * 8 + g * 4) * PITCH + row;
-    u32x4 v;
-    v.x = p[0];
-    v.y = p[PITCH];
-    v.z = p[2 * PITCH];
-    v.w = p[3 * PITCH];
-    return __builtin_bit_cast(bf16x8, v);
+  return *(const bf16x8*)(lds + (row * TileLds<ROWS, BK>::PITCH + kk * 16 + (lane >> 5) * 8) * 2);
+}
+
+// Split-K partial sums go into the (pre-zeroed or already accumulating) fp32 output with hardware atomics.
+__device__ __forceinline__ void gemm_epilogue_atomic(const GemmArgs& g, float* C, long long m, long long n, float v) {
+  unsafeAtomicAdd(C + m * g.ldc + n, v);
+}
+
+// 8 consecutive outputs of one row: v[] = alpha * acc on entry.
+template <typename TC>
+__device__ __forceinline__ void epilogue8(const GemmArgs& g, TC* C, long long m, long long n, float v[8], bool atomic) {
+  float t[8];
+  if (g.epi & EPI_BIAS) {
+    load8((const bf16*)g.bias + n, t);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] += t[i];
   }
+  if (g.epi & EPI_GELU) {
+    if (g.aux_out) store8((bf16*)g.aux_out + m * g.ldaux + n, v);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = gelu_fast_f(v[i]);
+  }
+  if (g.epi & EPI_GELUGRAD) {
+    load8((const bf16*)g.aux + m * g.ldaux + n, t);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] *= gelu_grad_fast_f(t[i]);
+  }
+  if (g.epi & EPI_RESID) {
+    load8((const bf16*)g.resid + m * g.ldr + n, t);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] += t[i];
+  }
+  TC* c = C + m * g.ldc + n;
+  if constexpr (sizeof(TC) == 4) {
+    if (atomic) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) unsafeAtomicAdd((float*)c + i, v[i]);
+      return;
+    }
+  }
+  if (g.epi & EPI_ACCUM) {
+    load8(c, t);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] += t[i];
+  }
+  store8(c, v);
 }
 
 template <int BM, int BN, int BK, int WM, int WN, bool AKC, bool BKC, typename TC>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_kernel(GemmArgs g) {
   constexpr int NWM = BM / WM, NWN = BN / WN, NT = NWM * NWN * 64;
-  constexpr int FM = WM / 32, FN = WN / 32;
-  using LA = TileLds<BM, BK, AKC>;
-  using LB = TileLds<BN, BK, BKC>;
+  constexpr int FM = WM / 32, FN = WN / 32, KK = BK / 16;
+  using LA = TileLds<BM, BK>;
+  using LB = TileLds<BN, BK>;
   constexpr int STAGE = LA::BYTES + LB::BYTES;
-  __shared__ __attribute__((aligned(16))) char lds[2 * STAGE];
+  constexpr int EP_PITCH = WN + 4;                       // floats
+  constexpr int EP_BYTES = 32 * EP_PITCH * 4;            // one wave's strip
+  static_assert(NWM * NWN * EP_BYTES <= 2 * STAGE, "epilogue strips must fit the staging buffers");
+  extern __shared__ __attribute__((aligned(16))) char lds[];  // 2 * STAGE bytes
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / NWN, wn = wave % NWN;
@@ -213,50 +297,62 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_kernel(G
   const int m0 = tm * BM, n0 = tn * BN;
   if (m0 >= M) return;
 
+  // split-K: blockIdx.y owns k-tiles [kt0, kt1)
+  const int nk_all = (K + BK - 1) / BK;
+  const int per_split = (nk_all + gridDim.y - 1) / gridDim.y;
+  const int kt0 = blockIdx.y * per_split, kt1 = min(nk_all, kt0 + per_split);
+  if (kt0 >= kt1) return;
+
   const int z = blockIdx.z, zo = z / g.zdiv, zi = z % g.zdiv;
   const bf16* A = (const bf16*)g.A + zo * g.a_zo + zi * g.a_zi + (AKC ? (long long)m0 * g.lda : (long long)m0);
   const bf16* B = (const bf16*)g.B + zo * g.b_zo + zi * g.b_zi + (BKC ? (long long)n0 * g.ldb : (long long)n0);
   TC* C = (TC*)g.C + zo * g.c_zo + zi * g.c_zi;
+  const __amdgpu_buffer_rsrc_t ra = make_rsrc(A, tile_bytes<AKC>(g.lda, M - m0, K));
+  const __amdgpu_buffer_rsrc_t rb = make_rsrc(B, tile_bytes<BKC>(g.ldb, N - n0, K));
+  const uint32_t lda = (uint32_t)g.lda, ldb = (uint32_t)g.ldb;
 
   TileLoader<BM, BK, AKC, NT> la;
   TileLoader<BN, BK, BKC, NT> lb;
-  f32x16 acc[FM][FN];
-#pragma unroll
-  for (int i = 0; i < FM; ++i)
-#pragma unroll
-    for (int j = 0; j < FN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  f32x16 acc[FM * FN];
+  static_for<0, FM * FN>([&](auto t) {
+    constexpr int T = decltype(t)::value;
+    acc[T] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  });
 
-  const int nk = (K + BK - 1) / BK;
-  la.load(A, g.lda, M - m0, 0, K, tid);
-  lb.load(B, g.ldb, N - n0, 0, K, tid);
+  la.load(ra, lda, kt0 * BK, K, tid);
+  lb.load(rb, ldb, kt0 * BK, K, tid);
   la.store(lds, tid);
   lb.store(lds + LA::BYTES, tid);
   __syncthreads();
 
-  for (int kt = 0; kt < nk; ++kt) {
-    const char* cur = lds + (kt & 1) * STAGE;
-    char* nxt = lds + ((kt + 1) & 1) * STAGE;
-    const bool more = kt + 1 < nk;
+  const int arow = wm * WM + (lane & 31), brow = wn * WN + (lane & 31);
+  for (int kt = kt0; kt < kt1; ++kt) {
+    const char* cur = lds + ((kt - kt0) & 1) * STAGE;
+    char* nxt = lds + ((kt - kt0 + 1) & 1) * STAGE;
+    const bool more = kt + 1 < kt1;
     if (more) {
-      la.load(A, g.lda, M - m0, (kt + 1) * BK, K, tid);
-      lb.load(B, g.ldb, N - n0, (kt + 1) * BK, K, tid);
+      la.load(ra, lda, (kt + 1) * BK, K, tid);
+      lb.load(rb, ldb, (kt + 1) * BK, K, tid);
     }
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 af[FM], bfr[FN];
-#pragma unroll
-      for (int i = 0; i < FM; ++i) af[i] = read_frag<BM, BK, AKC>(cur, wm * WM + i * 32 + (lane & 31), kk, lane);
-#pragma unroll
-      for (int j = 0; j < FN; ++j)
-        bfr[j] = read_frag<BN, BK, BKC>(cur + LA::BYTES, wn * WN + j * 32 + (lane & 31), kk, lane);
-#pragma unroll
-      for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-    }
+    // fragments of step kk+1 are fetched from LDS while the MFMAs of step kk run
+    bf16x8 af[2 * FM], bfr[2 * FN];
+    static_for<0, FM>([&](auto i) { af[i] = read_frag<BM, BK>(cur, arow + i * 32, 0, lane); });
+    static_for<0, FN>([&](auto j) { bfr[j] = read_frag<BN, BK>(cur + LA::BYTES, brow + j * 32, 0, lane); });
+    static_for<0, KK>([&](auto kkc) {
+      constexpr int kk = decltype(kkc)::value;
+      constexpr int cs = (kk & 1), ns = ((kk + 1) & 1);
+      if constexpr (kk + 1 < KK) {
+        static_for<0, FM>([&](auto i) { af[ns * FM + i] = read_frag<BM, BK>(cur, arow + i * 32, kk + 1, lane); });
+        static_for<0, FN>(
+            [&](auto j) { bfr[ns * FN + j] = read_frag<BN, BK>(cur + LA::BYTES, brow + j * 32, kk + 1, lane); });
+      }
+      static_for<0, FM * FN>([&](auto t) {
+        constexpr int T = decltype(t)::value;
+        constexpr int i = T / FN, j = T % FN;
+        acc[T] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cs * FM + i], bfr[cs * FN + j], acc[T], 0, 0, 0);
+      });
+      __builtin_amdgcn_sched_barrier(0);  // keep at most two fragment sets live
+    });
     if (more) {
       la.store(nxt, tid);
       lb.store(nxt + LA::BYTES, tid);
@@ -264,18 +360,58 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_kernel(G
     __syncthreads();
   }
 
+  // ---- epilogue ---------------------------------------------------------------------------------
   // accumulator layout of the 32x32 MFMA: lane -> column (lane % 32); register r -> row
-  // 8*(r/4) + 4*(lane/32) + r%4.
-#pragma unroll
-  for (int i = 0; i < FM; ++i)
-#pragma unroll
-    for (int j = 0; j < FN; ++j) {
-      const int n = n0 + wn * WN + j * 32 + (lane & 31);
-      if (n >= N) continue;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * WM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (m < M) gemm_epilogue<bf16, TC>(g, C, m, n, g.alpha * acc[i][j][r]);
+  // 8*(r/4) + 4*(lane/32) + r%4.  One 32 x WN strip at a time goes through this wave's LDS region.
+  const bool atomic = gridDim.y > 1;
+  float* strip = (float*)(lds + wave * EP_BYTES);
+  const auto al16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
+  const bool vec_ok = (N % 8 == 0) && (g.ldc % 8 == 0) && al16(C) &&
+                      (!(g.epi & EPI_BIAS) || al16(g.bias)) &&
+                      (!(g.epi & EPI_RESID) || (g.ldr % 8 == 0 && al16(g.resid))) &&
+                      (!(g.epi & EPI_GELUGRAD) || (g.ldaux % 8 == 0 && al16(g.aux))) &&
+                      (!((g.epi & EPI_GELU) && g.aux_out) || (g.ldaux % 8 == 0 && al16(g.aux_out)));
+  static_for<0, FM>([&](auto ic) {
+    constexpr int i = decltype(ic)::value;
+    __builtin_amdgcn_sched_barrier(0);  // one strip's accumulators at a time leave the accumulation registers
+    static_for<0, FN>([&](auto jc) {
+      constexpr int j = decltype(jc)::value;
+      static_for<0, 16>([&](auto rc) {
+        constexpr int r = decltype(rc)::value;
+        strip[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * EP_PITCH + j * 32 + (lane & 31)] = g.alpha * acc[i * FN + j][r];
+      });
+    });
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const int mrow0 = m0 + wm * WM + i * 32, ncol0 = n0 + wn * WN;
+    if (vec_ok && !atomic) {   // atomics go lane-per-column so that one instruction touches two cache lines
+#pragma unroll 1
+      for (int u = lane; u < 32 * (WN / 8); u += 64) {
+        const int row = u / (WN / 8), c8 = (u % (WN / 8)) * 8;
+        const int m = mrow0 + row, n = ncol0 + c8;
+        if (m < M && n < N) {
+          float v[8];
+          load8(strip + row * EP_PITCH + c8, v);
+          epilogue8<TC>(g, C, m, n, v, atomic);
+        }
+      }
+    } else {
+#pragma unroll 1
+      for (int u = lane; u < 32 * WN; u += 64) {
+        const int row = u / WN, col = u % WN;
+        const int m = mrow0 + row, n = ncol0 + col;
+        if (m < M && n < N) {
+          const float v = strip[row * EP_PITCH + col];
+          if constexpr (sizeof(TC) == 4) {
+            if (atomic) { gemm_epilogue_atomic(g, (float*)C, m, n, v); continue; }
+          }
+          gemm_epilogue<bf16, TC>(g, C, m, n, v);
+        }
       }
     }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  });
 }

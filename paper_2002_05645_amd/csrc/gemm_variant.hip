@@ -1,0 +1,48 @@
+// One tile variant of the bf16 MFMA GEMM (selected with -DL2L_VARIANT=<index>): all four operand
+// layouts, bf16 and fp32 outputs.
+#include "gemm.h"
+#include "gemm_variants.h"
+
+#ifndef L2L_VARIANT
+#error "compile with -DL2L_VARIANT=<index>"
+#endif
+
+namespace {
+
+template <int BM, int BN, int BK, int WM, int WN, bool AKC, bool BKC, typename TC>
+void launch_one(const GemmArgs& g, hipStream_t s, int splits) {
+  constexpr int LDS = 2 * (TileLds<BM, BK>::BYTES + TileLds<BN, BK>::BYTES);
+  static_assert(LDS <= 160 * 1024, "tile does not fit the 160 KB LDS");
+  auto kern = gemm_mfma_kernel<BM, BN, BK, WM, WN, AKC, BKC, TC>;
+  static const bool once = [&] {
+    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    return true;
+  }();
+  (void)once;
+  const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+  dim3 grid(tiles, splits, g.nbatch), block((BM / WM) * (BN / WN) * 64);
+  hipLaunchKernelGGL(kern, grid, block, LDS, s, g);
+}
+
+template <int BM, int BN, int BK, int WM, int WN, typename TC>
+void launch_layout(const GemmArgs& g, hipStream_t s, int splits) {
+  if (g.a_kc && g.b_kc) launch_one<BM, BN, BK, WM, WN, true, true, TC>(g, s, splits);
+  else if (g.a_kc && !g.b_kc) launch_one<BM, BN, BK, WM, WN, true, false, TC>(g, s, splits);
+  else if (!g.a_kc && g.b_kc) launch_one<BM, BN, BK, WM, WN, false, true, TC>(g, s, splits);
+  else launch_one<BM, BN, BK, WM, WN, false, false, TC>(g, s, splits);
+}
+
+}  // namespace
+
+struct TileCfg { int bm, bn, bk, wm, wn; };
+#define L2L_ROW(i, bm, bn, bk, wm, wn) {bm, bn, bk, wm, wn},
+constexpr TileCfg kCfg[] = {L2L_GEMM_VARIANTS(L2L_ROW)};
+#undef L2L_ROW
+constexpr TileCfg kThis = kCfg[L2L_VARIANT];
+
+#define L2L_CAT2(a, b) a##b
+#define L2L_CAT(a, b) L2L_CAT2(a, b)
+void L2L_CAT(l2l_launch_mfma_v, L2L_VARIANT)(const GemmArgs& g, hipStream_t s, int splits, bool out_f32) {
+  if (out_f32) launch_layout<kThis.bm, kThis.bn, kThis.bk, kThis.wm, kThis.wn, float>(g, s, splits);
+  else launch_layout<kThis.bm, kThis.bn, kThis.bk, kThis.wm, kThis.wn, bf16>(g, s, 1);
+}

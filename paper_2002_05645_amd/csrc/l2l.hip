@@ -10,6 +10,7 @@
 
 #include "../../include/l2l.h"
 #include "gemm.h"
+#include "gemm_variants.h"
 #include "rowwise.h"
 
 // ================================================================================================
@@ -236,14 +237,20 @@ bool mfma_ok(const GemmArgs& g) {
   return true;
 }
 
-template <int BM, int BN, int BK, int WM, int WN, typename TC>
-void launch_mfma_cfg(const GemmArgs& g, hipStream_t s) {
-  const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
-  dim3 grid(tiles, 1, g.nbatch), block((BM / WM) * (BN / WN) * 64);
-  if (g.a_kc && g.b_kc) hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, BK, WM, WN, true, true, TC>), grid, block, 0, s, g);
-  else if (g.a_kc && !g.b_kc) hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, BK, WM, WN, true, false, TC>), grid, block, 0, s, g);
-  else if (!g.a_kc && g.b_kc) hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, BK, WM, WN, false, true, TC>), grid, block, 0, s, g);
-  else hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, BK, WM, WN, false, false, TC>), grid, block, 0, s, g);
+// tile variants of the MFMA kernel live in their own translation units (gemm_variant.hip)
+struct TileCfg { int bm, bn, bk, wm, wn; };
+#define L2L_ROW(i, bm, bn, bk, wm, wn) {bm, bn, bk, wm, wn},
+constexpr TileCfg kTiles[] = {L2L_GEMM_VARIANTS(L2L_ROW)};
+#undef L2L_ROW
+constexpr int kNumTiles = kNumGemmVariants;
+
+void launch_mfma_variant(int v, const GemmArgs& g, hipStream_t s, int splits, bool out_f32) {
+  switch (v) {
+#define L2L_CASE(i, bm, bn, bk, wm, wn) case i: l2l_launch_mfma_v##i(g, s, splits, out_f32); break;
+    L2L_GEMM_VARIANTS(L2L_CASE)
+#undef L2L_CASE
+    default: break;
+  }
 }
 
 template <typename T, typename TC>
@@ -252,20 +259,46 @@ void launch_plain(const GemmArgs& g, hipStream_t s) {
   hipLaunchKernelGGL((gemm_plain_kernel<T, TC>), grid, dim3(256), 0, s, g);
 }
 
-// impl: 0 auto, 1 plain, 2 mfma
+int g_force_splits = 0;  // tuning override
+
+// tile variant and split-K factor for one launch
+void pick_tile(const GemmArgs& g, bool out_f32, int* variant, int* splits) {
+  int v = 0;
+  *splits = 1;
+  const long long small = std::min(g.M, g.N);
+  if (small >= 256 && g.K >= 256) v = 3;
+  else if (g.M >= 256 && g.N >= 128) v = 2;
+  else if (g.N <= 64) v = 1;
+  const TileCfg t = kTiles[v];
+  // split K when an accumulating fp32 GEMM has too few tiles to fill 256 CUs
+  if (out_f32 && (g.epi == EPI_ACCUM) && !g.k_dev) {
+    const long long tiles = (long long)((g.M + t.bm - 1) / t.bm) * ((g.N + t.bn - 1) / t.bn) * g.nbatch;
+    const int nk = (g.K + t.bk - 1) / t.bk;
+    long long want = (512 + tiles - 1) / tiles;
+    want = std::min<long long>(want, std::max(1, nk / 8));
+    *splits = (int)std::max<long long>(1, std::min<long long>(want, 64));
+  }
+  *variant = v;
+}
+
+// impl: 0 auto, 1 plain, 2 mfma (auto tile), 100 + v: mfma tile variant v (tuning)
 int gemm(l2l_ctx* c, int dtype, bool out_f32, const GemmArgs& g, int impl = 0) {
   if (g.M <= 0 || g.N <= 0 || g.nbatch <= 0) return L2L_OK;
   if (g.nbatch > 65535 || (g.M + 63) / 64 > 65535) return fail(c, L2L_E_ARG, "gemm: grid too large");
   const bool can_mfma = dtype == L2L_BF16 && mfma_ok(g);
-  if (impl == 2 && !can_mfma) return fail(c, L2L_E_ARG, "gemm: shape/alignment not supported by the MFMA kernel");
-  const bool use_mfma = impl == 2 || (impl == 0 && can_mfma);
+  if (impl >= 2 && !can_mfma) return fail(c, L2L_E_ARG, "gemm: shape/alignment not supported by the MFMA kernel");
+  if (impl >= 100 + kNumTiles) return fail(c, L2L_E_ARG, "gemm: no such tile variant");
+  const bool use_mfma = impl >= 2 || (impl == 0 && can_mfma);
   const double flops = 2.0 * g.M * g.N * (double)g.K * g.nbatch;
   const double es = esize(dtype);
   const double bytes = ((double)g.M * g.K + (double)g.K * g.N) * es * g.nbatch + (double)g.M * g.N * (out_f32 ? 4 : es) * g.nbatch;
   return timed(c, L2L_PROF_GEMM, flops, bytes, [&] {
     if (use_mfma) {
-      if (out_f32) launch_mfma_cfg<128, 128, 32, 64, 64, float>(g, c->cs);
-      else launch_mfma_cfg<128, 128, 32, 64, 64, bf16>(g, c->cs);
+      int v, splits;
+      pick_tile(g, out_f32, &v, &splits);
+      if (impl >= 100) v = impl - 100;
+      if (g_force_splits > 0 && out_f32 && g.epi == EPI_ACCUM) splits = g_force_splits;
+      launch_mfma_variant(v, g, c->cs, splits, out_f32);
     } else if (dtype == L2L_BF16) {
       if (out_f32) launch_plain<bf16, float>(g, c->cs);
       else launch_plain<bf16, bf16>(g, c->cs);
@@ -318,7 +351,7 @@ int bias_grad(l2l_ctx* c, const void* a, long long lda, float* out, long long ro
 int fill_zero(l2l_ctx* c, void* p, size_t bytes) {
   const long long n = (long long)(bytes / 4);
   if (n <= 0) return L2L_OK;
-  const unsigned blocks = (unsigned)std::min<long long>((n + 255) / 256, 4096);
+  const unsigned blocks = (unsigned)std::min<long long>((n / 4 + 255) / 256 + 1, 2048);
   return timed(c, L2L_PROF_OTHER, 0, (double)bytes, [&] {
     hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks), dim3(256), 0, c->cs, (uint32_t*)p, 0u, n);
   });
@@ -884,7 +917,7 @@ int l2l_op_gemm(l2l_ctx* c, int in_dtype, int out_f32, int a_kc, int b_kc, int M
   if (in_dtype != L2L_F32 && in_dtype != L2L_BF16) return fail(c, L2L_E_ARG, "l2l_op_gemm: bad dtype");
   if (in_dtype == L2L_F32) out_f32 = 1;
   if (accumulate && !out_f32) return fail(c, L2L_E_ARG, "l2l_op_gemm: accumulate needs an fp32 output");
-  if (impl < 0 || impl > 2) return fail(c, L2L_E_ARG, "l2l_op_gemm: impl %d", impl);
+  if (impl < 0 || (impl > 2 && impl < 100)) return fail(c, L2L_E_ARG, "l2l_op_gemm: impl %d", impl);
   GemmArgs g = gemm_args(M, N, K, A, lda, a_kc != 0, B, ldb, b_kc != 0, C, ldc);
   g.alpha = alpha;
   if (bias) { g.epi |= EPI_BIAS; g.bias = bias; }

@@ -4,27 +4,6 @@
 #pragma once
 #include "common.h"
 
-// ---- 8-wide vector access ------------------------------------------------------------------------
-__device__ __forceinline__ void load8(const float* p, float v[8]) {
-  const f32x4 a = *(const f32x4*)p, b = *(const f32x4*)(p + 4);
-  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-}
-__device__ __forceinline__ void load8(const bf16* p, float v[8]) {
-  const bf16x8 a = *(const bf16x8*)p;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) v[i] = (float)a[i];
-}
-__device__ __forceinline__ void store8(float* p, const float v[8]) {
-  *(f32x4*)p = f32x4{v[0], v[1], v[2], v[3]};
-  *(f32x4*)(p + 4) = f32x4{v[4], v[5], v[6], v[7]};
-}
-__device__ __forceinline__ void store8(bf16* p, const float v[8]) {
-  bf16x8 a;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) a[i] = (bf16)v[i];
-  *(bf16x8*)p = a;
-}
-
 // Row sources: a plain row, or the embedding sum E[tok] + Ppos[s] formed on the fly.
 template <typename T>
 struct PlainRow {
@@ -334,9 +313,12 @@ __global__ __launch_bounds__(256) void ce_kernel(const float* z, long long ldz, 
   }
 }
 
-// p[i] = v for i < n (graph-capturable replacement for a memset).
+// p[i] = v for i < n (a kernel rather than a memset so that callers can capture it in a graph).
+// 16-byte stores over the aligned body, dwords for the tail.
 __global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t* p, uint32_t v, long long n) {
-  long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  const long long n4 = n / 4;
   const long long stride = (long long)gridDim.x * 256;
-  for (; i < n; i += stride) p[i] = v;
+  u32x4* p4 = (u32x4*)p;
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) p4[i] = u32x4{v, v, v, v};
+  for (long long i = n4 * 4 + (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) p[i] = v;
 }
