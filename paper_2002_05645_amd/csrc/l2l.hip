@@ -119,7 +119,7 @@ struct l2l_ctx {
   float* gacc[2] = {nullptr, nullptr};
   int gacc_layer[2] = {-1, -1};
   int gacc_state[2] = {0, 0};  // 0 free, 1 holds un-drained grads, 2 drain enqueued
-  hipEvent_t gacc_ready[2] = {}, gacc_drained[2] = {};
+  hipEvent_t gacc_ready[2] = {}, gacc_landed[2] = {}, gacc_drained[2] = {};  // bwd done / D2H landed / cleared again
   int gacc_next = 0;
 
   // workspace (group-sized)
@@ -130,7 +130,7 @@ struct l2l_ctx {
   void* emb = nullptr;
   float* egacc = nullptr;
   int emb_staged = 0, egacc_state = 0;
-  hipEvent_t emb_staged_ev = nullptr, emb_released_ev = nullptr, egacc_ready = nullptr, egacc_drained = nullptr;
+  hipEvent_t emb_staged_ev = nullptr, emb_released_ev = nullptr, egacc_ready = nullptr, egacc_landed = nullptr, egacc_drained = nullptr;
   float *emean = nullptr, *erstd = nullptr;
   int32_t *lab_idx = nullptr, *lab_cnt = nullptr, *lab_total = nullptr;
   void *xl = nullptr, *dz = nullptr, *dxl = nullptr;
@@ -346,6 +346,17 @@ int bias_grad(l2l_ctx* c, const void* a, long long lda, float* out, long long ro
                        (const float*)nullptr, (const float*)nullptr, (const int32_t*)nullptr, (const T*)nullptr,
                        (const T*)nullptr, 0, (float*)nullptr, out, (int)rows, n, rows_dev);
   });
+}
+
+// zero on the copy stream: keeps the clearing of a drained accumulator off the compute stream
+int fill_zero_copy_stream(l2l_ctx* c, void* p, size_t bytes) {
+  const long long n = (long long)(bytes / 4);
+  if (n <= 0) return L2L_OK;
+  const unsigned blocks = (unsigned)std::min<long long>((n / 4 + 255) / 256 + 1, 2048);
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks), dim3(256), 0, c->xs, (uint32_t*)p, 0u, n);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(c, L2L_E_HIP, "fill launch: %s", hipGetErrorString(e));
+  return L2L_OK;
 }
 
 int fill_zero(l2l_ctx* c, void* p, size_t bytes) {
@@ -646,10 +657,12 @@ int l2l_create(const l2l_config* cfg, void* compute_stream, void* copy_stream, l
   for (int i = 0; i < 2; ++i) {
     L2L_TRY(dev_alloc(c, &c->slot[i], c->lay.total * es));
     L2L_TRY(dev_alloc(c, (void**)&c->gacc[i], c->lay.total * 4));
+    HIP_TRY(c, hipMemset(c->gacc[i], 0, c->lay.total * 4));
     HIP_TRY(c, hipEventCreateWithFlags(&c->slot_staged[i], hipEventDisableTiming));
     HIP_TRY(c, hipEventCreateWithFlags(&c->slot_released[i], hipEventDisableTiming));
     HIP_TRY(c, hipEventCreateWithFlags(&c->gacc_ready[i], hipEventDisableTiming));
     HIP_TRY(c, hipEventCreateWithFlags(&c->gacc_drained[i], hipEventDisableTiming));
+    HIP_TRY(c, hipEventCreateWithFlags(&c->gacc_landed[i], hipEventDisableTiming));
   }
   struct { void** p; long long n; } bufs[] = {
       {&c->qkv, Mg * 3 * H}, {&c->p, pe}, {&c->c, Mg * H}, {&c->r1, Mg * H}, {&c->y1, Mg * H}, {&c->u1, Mg * F},
@@ -664,6 +677,7 @@ int l2l_create(const l2l_config* cfg, void* compute_stream, void* copy_stream, l
     c->Vp = up(V, 64);
     L2L_TRY(dev_alloc(c, &c->emb, c->lay.etotal * es));
     L2L_TRY(dev_alloc(c, (void**)&c->egacc, c->lay.etotal * 4));
+    HIP_TRY(c, hipMemset(c->egacc, 0, c->lay.etotal * 4));
     L2L_TRY(dev_alloc(c, (void**)&c->emean, UT * 4));
     L2L_TRY(dev_alloc(c, (void**)&c->erstd, UT * 4));
     L2L_TRY(dev_alloc(c, (void**)&c->lab_idx, UT * 4));
@@ -677,6 +691,7 @@ int l2l_create(const l2l_config* cfg, void* compute_stream, void* copy_stream, l
     HIP_TRY(c, hipEventCreateWithFlags(&c->emb_released_ev, hipEventDisableTiming));
     HIP_TRY(c, hipEventCreateWithFlags(&c->egacc_ready, hipEventDisableTiming));
     HIP_TRY(c, hipEventCreateWithFlags(&c->egacc_drained, hipEventDisableTiming));
+    HIP_TRY(c, hipEventCreateWithFlags(&c->egacc_landed, hipEventDisableTiming));
   }
   return L2L_OK;
 }
@@ -688,7 +703,7 @@ int l2l_destroy(l2l_ctx* c) {
   for (auto& r : c->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
   for (auto e : c->ev_pool) (void)hipEventDestroy(e);
   hipEvent_t evs[] = {c->slot_staged[0], c->slot_staged[1], c->slot_released[0], c->slot_released[1], c->gacc_ready[0],
-                      c->gacc_ready[1], c->gacc_drained[0], c->gacc_drained[1], c->emb_staged_ev, c->emb_released_ev,
+                      c->gacc_ready[1], c->gacc_drained[0], c->gacc_drained[1], c->gacc_landed[0], c->gacc_landed[1], c->egacc_landed, c->emb_staged_ev, c->emb_released_ev,
                       c->egacc_ready, c->egacc_drained};
   for (hipEvent_t e : evs)
     if (e) (void)hipEventDestroy(e);
@@ -743,8 +758,7 @@ int l2l_layer_bwd(l2l_ctx* c, int layer, int slot, const void* x_stash, void* dy
     return fail(c, L2L_E_STATE, "l2l_layer_bwd: gradients of layer %d were never drained", c->gacc_layer[a]);
   HIP_TRY(c, hipStreamWaitEvent(c->cs, c->slot_staged[slot], 0));
   if (c->gacc_state[a] == 2) HIP_TRY(c, hipStreamWaitEvent(c->cs, c->gacc_drained[a], 0));
-  float* G = c->gacc[a];
-  L2L_TRY(fill_zero(c, G, c->lay.total * 4));
+  float* G = c->gacc[a];   // zero: cleared at creation and again, on the copy stream, after every drain
   const size_t es = esize(c->cfg.dtype);
   const int U = c->cfg.num_ubatches;
   for (int u0 = 0; u0 < U; u0 += c->group) {
@@ -775,6 +789,8 @@ int l2l_grad_drain(l2l_ctx* c, int layer, void* host_grads) {
     if (c->gacc_state[a] == 1 && c->gacc_layer[a] == layer) {
       HIP_TRY(c, hipStreamWaitEvent(c->xs, c->gacc_ready[a], 0));
       HIP_TRY(c, hipMemcpyAsync(host_grads, c->gacc[a], c->lay.total * 4, hipMemcpyDeviceToHost, c->xs));
+      HIP_TRY(c, hipEventRecord(c->gacc_landed[a], c->xs));
+      L2L_TRY(fill_zero_copy_stream(c, c->gacc[a], c->lay.total * 4));   // "erased from the device" (Section 2.1)
       HIP_TRY(c, hipEventRecord(c->gacc_drained[a], c->xs));
       c->gacc_state[a] = 2;
       return L2L_OK;
@@ -787,7 +803,7 @@ int l2l_drain_wait(l2l_ctx* c, int layer) {
   if (!c) return L2L_E_ARG;
   for (int a = 0; a < 2; ++a) {
     if (c->gacc_state[a] == 2 && c->gacc_layer[a] == layer) {
-      HIP_TRY(c, hipEventSynchronize(c->gacc_drained[a]));
+      HIP_TRY(c, hipEventSynchronize(c->gacc_landed[a]));
       return L2L_OK;
     }
   }
@@ -819,8 +835,7 @@ int l2l_embed_fwd(l2l_ctx* c, const int32_t* tokens, void* x_out) {
   if (c->egacc_state == 1) return fail(c, L2L_E_STATE, "l2l_embed_fwd: embedding gradients of the previous step were never drained");
   HIP_TRY(c, hipStreamWaitEvent(c->cs, c->emb_staged_ev, 0));
   if (c->egacc_state == 2) HIP_TRY(c, hipStreamWaitEvent(c->cs, c->egacc_drained, 0));
-  L2L_TRY(fill_zero(c, c->egacc, c->lay.etotal * 4));
-  c->egacc_state = 0;
+  c->egacc_state = 0;   // the accumulator is zero: cleared at creation and after every drain
   if (c->cfg.dtype == L2L_BF16) L2L_TRY(embed_fwd_t<bf16>(c, tokens, x_out));
   else L2L_TRY(embed_fwd_t<float>(c, tokens, x_out));
   HIP_TRY(c, hipEventRecord(c->emb_released_ev, c->cs));
@@ -858,6 +873,8 @@ int l2l_embed_grad_drain(l2l_ctx* c, void* host_grads) {
   if (c->egacc_state != 1) return fail(c, L2L_E_STATE, "l2l_embed_grad_drain: no un-drained embedding gradients");
   HIP_TRY(c, hipStreamWaitEvent(c->xs, c->egacc_ready, 0));
   HIP_TRY(c, hipMemcpyAsync(host_grads, c->egacc, c->lay.etotal * 4, hipMemcpyDeviceToHost, c->xs));
+  HIP_TRY(c, hipEventRecord(c->egacc_landed, c->xs));
+  L2L_TRY(fill_zero_copy_stream(c, c->egacc, c->lay.etotal * 4));
   HIP_TRY(c, hipEventRecord(c->egacc_drained, c->xs));
   c->egacc_state = 2;
   return L2L_OK;
@@ -866,7 +883,7 @@ int l2l_embed_grad_drain(l2l_ctx* c, void* host_grads) {
 int l2l_embed_drain_wait(l2l_ctx* c) {
   L2L_TRY(need_vocab(c, "l2l_embed_drain_wait"));
   if (c->egacc_state != 2) return fail(c, L2L_E_STATE, "l2l_embed_drain_wait: no drain in flight");
-  HIP_TRY(c, hipEventSynchronize(c->egacc_drained));
+  HIP_TRY(c, hipEventSynchronize(c->egacc_landed));
   return L2L_OK;
 }
 

@@ -6,6 +6,9 @@ weights and Adam state, ships the configured dtype, and receives fp32 gradients 
 """
 from __future__ import annotations
 
+import queue
+import threading
+
 import numpy as np
 import torch
 
@@ -29,7 +32,7 @@ def unpack(layout, shapes, flat) -> dict:
 class L2LTrainer:
     def __init__(self, *, layers, hidden, heads, ffn, seq, vocab, ubatch, num_ubatches, dtype="bf16",
                  ln_eps=1e-12, lr=1e-4, beta1=0.9, beta2=0.999, eps_a=1e-8, ubatch_group=0,
-                 eps_threads=0, stash="device", device="cuda:0"):
+                 eps_threads=0, stash="device", device="cuda:0", eager=False):
         assert stash in ("device", "host")
         self.L, self.H, self.S, self.V = layers, hidden, seq, vocab
         self.U, self.ub = num_ubatches, ubatch
@@ -60,6 +63,16 @@ class L2LTrainer:
         self.dy = torch.empty(shape, dtype=tdt, device=self.device)
         self.loss_dev = torch.zeros(1, dtype=torch.float32, device=self.device)
         self.t = 0
+        # eager EPS (Section 2.1 "reduces ... eagerly", Section 4.1): a host thread runs Adam on a block as
+        # soon as its gradients have landed, while the device is still busy with the layers below it
+        self.eager = eager
+        self._landed = [torch.cuda.Event() for _ in range(layers + 1)]
+        self._work = queue.Queue()
+        self._worker_error = None
+        self._worker = None
+        if eager:
+            self._worker = threading.Thread(target=self._eager_loop, daemon=True)
+            self._worker.start()
 
     # ---- parameters -------------------------------------------------------------------------------
     def load_params(self, emb: dict, layers: list):
@@ -119,8 +132,29 @@ class L2LTrainer:
             if host_mode:
                 self.stash_free[l % 2].record(self.compute)
             c.grad_drain(l, e.grad_ptr(1 + l))
+            self._after_drain(1 + l)
         c.embed_bwd(tokens, self.dy)
         c.embed_grad_drain(e.grad_ptr(0))
+        self._after_drain(0)
+
+    def _after_drain(self, block):
+        if self.eager:
+            self._landed[block].record(self.copy)
+            self._work.put((block, self.t + 1))
+
+    def _eager_loop(self):
+        while True:
+            item = self._work.get()
+            if item is None:
+                return
+            block, t = item
+            try:
+                self._landed[block].synchronize()
+                self.eps.adam_step(block, block, t, **self.hp)
+            except Exception as ex:       # surfaced by optimizer_step
+                self._worker_error = ex
+            finally:
+                self._work.task_done()
 
     def _offload(self, l):
         """device stash slot -> pinned host, on the copy stream, after the producing kernels."""
@@ -146,6 +180,12 @@ class L2LTrainer:
 
     def optimizer_step(self):
         """EPS Adam over every block, after all gradients have landed (Algorithm 2's tail loop)."""
+        if self.eager:
+            self._work.join()             # every block was queued by device_pipeline; wait for the stragglers
+            if self._worker_error is not None:
+                raise self._worker_error
+            self.t += 1
+            return
         self.t += 1
         self.eps.adam_step(0, self.L, self.t, **self.hp)
 
@@ -156,5 +196,9 @@ class L2LTrainer:
         return loss
 
     def close(self):
+        if self._worker is not None:
+            self._work.put(None)
+            self._worker.join()
+            self._worker = None
         self.ctx.close()
         self.eps.close()
