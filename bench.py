@@ -125,7 +125,7 @@ def main():
                    "kernel_launches_per_step": {k: v["launches"] / a.steps for k, v in prof.items()}},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
-                     "kernel": "gemm_mfma_kernel (all layer GEMMs of the step)",
+                     "kernel": "gemm_mfma_dlds_kernel / gemm_mfma_kernel: the layer's dense GEMMs (QKV, out-proj, FFN1, FFN2; forward, recompute, dX, dW)",
                      "avg_launch_us": 1e3 * g["ms"] / max(g["launches"], 1),
                      "flops_per_launch": g["flops"] / max(g["launches"], 1)},
     }

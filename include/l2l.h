@@ -149,7 +149,10 @@ int l2l_embed_bwd(l2l_ctx*, const int32_t* tokens, const void* dy);
 int l2l_embed_grad_drain(l2l_ctx*, void* host_grads);
 int l2l_embed_drain_wait(l2l_ctx*);
 
-/* ---- profiling: HIP-event timing of kernel classes on the compute stream ---------------------- */
+/* ---- profiling: HIP-event timing of kernel classes on the compute stream ----------------------
+   GEMM = the layer's dense projections (QKV, out-proj, FFN1, FFN2 and their dX / dW GEMMs);
+   ATTN = the per-(sequence, head) score/context products and softmax; ROWWISE = LayerNorm, embedding;
+   COLSUM = bias / gain gradient reductions; OTHER = head, cross-entropy, fills. */
 enum { L2L_PROF_GEMM = 0, L2L_PROF_ATTN = 1, L2L_PROF_ROWWISE = 2, L2L_PROF_COLSUM = 3, L2L_PROF_OTHER = 4,
        L2L_PROF_CLASSES = 5 };
 /* on != 0: every launch is bracketed by events (slows the host side); counters are reset. */

@@ -329,11 +329,11 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_kernel(G
   for (int kt = kt0; kt < kt1; ++kt) {
     const char* cur = lds + ((kt - kt0) & 1) * STAGE;
     char* nxt = lds + ((kt - kt0 + 1) & 1) * STAGE;
-    const bool more = kt + 1 < kt1;
-    if (more) {
-      la.load(ra, lda, (kt + 1) * BK, K, tid);
-      lb.load(rb, ldb, (kt + 1) * BK, K, tid);
-    }
+    // next tile into registers while this one is multiplied; unconditional, so that the loop has no
+    // branch: past the last tile this fetches rows beyond K (zeros) or the next split's tile, unused.
+    // (Keeping two tiles in flight was measured and bought nothing: load latency is not the limiter.)
+    la.load(ra, lda, (kt + 1) * BK, K, tid);
+    lb.load(rb, ldb, (kt + 1) * BK, K, tid);
     // fragments of step kk+1 are fetched from LDS while the MFMAs of step kk run
     bf16x8 af[2 * FM], bfr[2 * FN];
     static_for<0, FM>([&](auto i) { af[i] = read_frag<BM, BK>(cur, arow + i * 32, 0, lane); });
@@ -353,10 +353,8 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_kernel(G
       });
       __builtin_amdgcn_sched_barrier(0);  // keep at most two fragment sets live
     });
-    if (more) {
-      la.store(nxt, tid);
-      lb.store(nxt + LA::BYTES, tid);
-    }
+    la.store(nxt, tid);
+    lb.store(nxt + LA::BYTES, tid);
     __syncthreads();
   }
 
@@ -386,6 +384,189 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_kernel(G
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     const int mrow0 = m0 + wm * WM + i * 32, ncol0 = n0 + wn * WN;
     if (vec_ok && !atomic) {   // atomics go lane-per-column so that one instruction touches two cache lines
+#pragma unroll 1
+      for (int u = lane; u < 32 * (WN / 8); u += 64) {
+        const int row = u / (WN / 8), c8 = (u % (WN / 8)) * 8;
+        const int m = mrow0 + row, n = ncol0 + c8;
+        if (m < M && n < N) {
+          float v[8];
+          load8(strip + row * EP_PITCH + c8, v);
+          epilogue8<TC>(g, C, m, n, v, atomic);
+        }
+      }
+    } else {
+#pragma unroll 1
+      for (int u = lane; u < 32 * WN; u += 64) {
+        const int row = u / WN, col = u % WN;
+        const int m = mrow0 + row, n = ncol0 + col;
+        if (m < M && n < N) {
+          const float v = strip[row * EP_PITCH + col];
+          if constexpr (sizeof(TC) == 4) {
+            if (atomic) { gemm_epilogue_atomic(g, (float*)C, m, n, v); continue; }
+          }
+          gemm_epilogue<bf16, TC>(g, C, m, n, v);
+        }
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  });
+}
+
+// ------------------------------------------------------------------------------------------------
+// bf16 MFMA kernel, both operands K-contiguous, global loads written straight into LDS.
+//
+// Same tiling and epilogue as gemm_mfma_kernel, but the tiles never pass through registers: each
+// wave issues buffer loads with the LDS modifier, one instruction filling 1 KiB (8 rows x 128 bytes) of
+// the stage; no staging registers, no LDS store instructions, no byte permutes.  The LDS image is
+// [row][64] bf16 without padding; the 16-byte chunk c of row r sits at chunk slot c ^ ((r >> 1) & 7),
+// which makes the 16 rows that a quarter-wave reads for one fragment land on 16 different bank groups.
+// The swizzle is applied on the global side (which chunk a lane fetches), since the LDS side of such
+// a load is fixed: lane l writes bytes [16 l, 16 l + 16) of the instruction's 1 KiB.
+template <int ROWS, int BK, int NT>
+struct DirectLoader {
+  static_assert(BK == 64, "one LDS row = 128 bytes = 8 chunks");
+  static constexpr int BYTES = ROWS * 128;       // one stage
+  static constexpr int PER = ROWS / 8 / (NT / 64);  // 1 KiB blocks per wave
+  static_assert(PER * (NT / 64) * 8 == ROWS, "rows must split evenly over the waves");
+
+  // row_local = lane / 8, slot = lane % 8; block b covers rows 8 b .. 8 b + 7
+  __device__ __forceinline__ static void load(__amdgpu_buffer_rsrc_t rs, uint32_t ld, int k0, int K, char* stage, int wave,
+                                              int lane) {
+    static_for<0, PER>([&](auto ic) {
+      constexpr int i = decltype(ic)::value;
+      const int blk = i * (NT / 64) + wave;
+      const int row = blk * 8 + (lane >> 3);
+      const int c = (lane & 7) ^ ((row >> 1) & 7);
+      const int k = k0 + c * 8;
+      uint32_t off = ((uint32_t)row * ld + (uint32_t)k) * 2u;
+      if (k >= K) off = BUF_OOB;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void*)(stage + blk * 1024), 16, (int)off, 0, 0,
+                                           0);
+    });
+  }
+};
+
+// wait until this wave's LDS-directed loads have landed (vmcnt(0); other counters untouched)
+__device__ __forceinline__ void wait_vm0() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
+template <int BM, int BN, int WM, int WN, typename TC>
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_kernel(GemmArgs g) {
+  constexpr int BK = 64;
+  constexpr int NWM = BM / WM, NWN = BN / WN, NT = NWM * NWN * 64;
+  constexpr int FM = WM / 32, FN = WN / 32, KK = BK / 16;
+  using DA = DirectLoader<BM, BK, NT>;
+  using DB = DirectLoader<BN, BK, NT>;
+  constexpr int STAGE = DA::BYTES + DB::BYTES;
+  constexpr int EP_PITCH = WN + 4;
+  constexpr int EP_BYTES = 32 * EP_PITCH * 4;
+  static_assert(NWM * NWN * EP_BYTES <= 2 * STAGE, "epilogue strips must fit the staging buffers");
+  extern __shared__ __attribute__((aligned(1024))) char lds[];  // 2 * STAGE bytes
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / NWN, wn = wave % NWN;
+
+  int M = g.M, K = g.K;
+  if (g.m_dev) M = min(M, *g.m_dev);
+  if (g.k_dev) K = min(K, *g.k_dev);
+  const int N = g.N;
+
+  const int tiles_n = (N + BN - 1) / BN, tiles_m = (g.M + BM - 1) / BM;
+  const int total = tiles_m * tiles_n;
+  int id = blockIdx.x;
+  {
+    const int per = total / 8, rem_start = per * 8;
+    if (id < rem_start) id = (id % 8) * per + id / 8;
+  }
+  const int tm = id / tiles_n, tn = id % tiles_n;
+  const int m0 = tm * BM, n0 = tn * BN;
+  if (m0 >= M) return;
+
+  const int nk_all = (K + BK - 1) / BK;
+  const int per_split = (nk_all + gridDim.y - 1) / gridDim.y;
+  const int kt0 = blockIdx.y * per_split, kt1 = min(nk_all, kt0 + per_split);
+  if (kt0 >= kt1) return;
+
+  const int z = blockIdx.z, zo = z / g.zdiv, zi = z % g.zdiv;
+  const bf16* A = (const bf16*)g.A + zo * g.a_zo + zi * g.a_zi + (long long)m0 * g.lda;
+  const bf16* B = (const bf16*)g.B + zo * g.b_zo + zi * g.b_zi + (long long)n0 * g.ldb;
+  TC* C = (TC*)g.C + zo * g.c_zo + zi * g.c_zi;
+  const __amdgpu_buffer_rsrc_t ra = make_rsrc(A, tile_bytes<true>(g.lda, M - m0, K));
+  const __amdgpu_buffer_rsrc_t rb = make_rsrc(B, tile_bytes<true>(g.ldb, N - n0, K));
+  const uint32_t lda = (uint32_t)g.lda, ldb = (uint32_t)g.ldb;
+
+  f32x16 acc[FM * FN];
+  static_for<0, FM * FN>([&](auto t) {
+    constexpr int T = decltype(t)::value;
+    acc[T] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  });
+
+  DA::load(ra, lda, kt0 * BK, K, lds, wave, lane);
+  DB::load(rb, ldb, kt0 * BK, K, lds + DA::BYTES, wave, lane);
+  wait_vm0();
+  __syncthreads();
+
+  // fragment addresses: row r of a tile lives at r * 128; chunk c = 2 kk + (lane / 32) at slot c ^ ((r >> 1) & 7);
+  // rows of one lane differ by multiples of 32, so the swizzle term depends on the lane only
+  const int r = lane & 31, gsel = lane >> 5, sw = (r >> 1) & 7;
+  const int abase = (wm * WM + r) * 128, bbase = DA::BYTES + (wn * WN + r) * 128;
+  int koff[KK];
+  static_for<0, KK>([&](auto kc) { koff[kc] = (((decltype(kc)::value * 2) | gsel) ^ sw) * 16; });
+
+  for (int kt = kt0; kt < kt1; ++kt) {
+    const char* cur = lds + ((kt - kt0) & 1) * STAGE;
+    char* nxt = lds + ((kt - kt0 + 1) & 1) * STAGE;
+    // next tile straight into the other stage (every wave left it at the previous barrier); past the
+    // last tile this fetches rows beyond K (zeros) or the next split's tile, neither of which is read
+    DA::load(ra, lda, (kt + 1) * BK, K, nxt, wave, lane);
+    DB::load(rb, ldb, (kt + 1) * BK, K, nxt + DA::BYTES, wave, lane);
+    bf16x8 af[2 * FM], bfr[2 * FN];
+    static_for<0, FM>([&](auto i) { af[i] = *(const bf16x8*)(cur + abase + i * 4096 + koff[0]); });
+    static_for<0, FN>([&](auto j) { bfr[j] = *(const bf16x8*)(cur + bbase + j * 4096 + koff[0]); });
+    static_for<0, KK>([&](auto kkc) {
+      constexpr int kk = decltype(kkc)::value;
+      constexpr int cs = (kk & 1), ns = ((kk + 1) & 1);
+      if constexpr (kk + 1 < KK) {
+        static_for<0, FM>([&](auto i) { af[ns * FM + i] = *(const bf16x8*)(cur + abase + i * 4096 + koff[kk + 1]); });
+        static_for<0, FN>([&](auto j) { bfr[ns * FN + j] = *(const bf16x8*)(cur + bbase + j * 4096 + koff[kk + 1]); });
+      }
+      static_for<0, FM * FN>([&](auto t) {
+        constexpr int T = decltype(t)::value;
+        constexpr int i = T / FN, j = T % FN;
+        acc[T] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cs * FM + i], bfr[cs * FN + j], acc[T], 0, 0, 0);
+      });
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    wait_vm0();
+    __syncthreads();
+  }
+
+  // ---- epilogue (as in gemm_mfma_kernel) ----------------------------------------------------------
+  const bool atomic = gridDim.y > 1;
+  float* strip = (float*)(lds + wave * EP_BYTES);
+  const auto al16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
+  const bool vec_ok = (N % 8 == 0) && (g.ldc % 8 == 0) && al16(C) &&
+                      (!(g.epi & EPI_BIAS) || al16(g.bias)) &&
+                      (!(g.epi & EPI_RESID) || (g.ldr % 8 == 0 && al16(g.resid))) &&
+                      (!(g.epi & EPI_GELUGRAD) || (g.ldaux % 8 == 0 && al16(g.aux))) &&
+                      (!((g.epi & EPI_GELU) && g.aux_out) || (g.ldaux % 8 == 0 && al16(g.aux_out)));
+  static_for<0, FM>([&](auto ic) {
+    constexpr int i = decltype(ic)::value;
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<0, FN>([&](auto jc) {
+      constexpr int j = decltype(jc)::value;
+      static_for<0, 16>([&](auto rc) {
+        constexpr int rr = decltype(rc)::value;
+        strip[(8 * (rr >> 2) + 4 * (lane >> 5) + (rr & 3)) * EP_PITCH + j * 32 + (lane & 31)] = g.alpha * acc[i * FN + j][rr];
+      });
+    });
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const int mrow0 = m0 + wm * WM + i * 32, ncol0 = n0 + wn * WN;
+    if (vec_ok && !atomic) {
 #pragma unroll 1
       for (int u = lane; u < 32 * (WN / 8); u += 64) {
         const int row = u / (WN / 8), c8 = (u % (WN / 8)) * 8;

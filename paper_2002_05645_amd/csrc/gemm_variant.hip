@@ -34,8 +34,23 @@ void launch_layout(const GemmArgs& g, hipStream_t s, int splits) {
 
 }  // namespace
 
-struct TileCfg { int bm, bn, bk, wm, wn; };
-#define L2L_ROW(i, bm, bn, bk, wm, wn) {bm, bn, bk, wm, wn},
+template <int BM, int BN, int WM, int WN, typename TC>
+void launch_direct(const GemmArgs& g, hipStream_t s, int splits) {
+  constexpr int LDS = 2 * (BM + BN) * 128;
+  static_assert(LDS <= 160 * 1024, "tile does not fit the 160 KB LDS");
+  auto kern = gemm_mfma_dlds_kernel<BM, BN, WM, WN, TC>;
+  static const bool once = [&] {
+    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    return true;
+  }();
+  (void)once;
+  const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+  dim3 grid(tiles, splits, g.nbatch), block((BM / WM) * (BN / WN) * 64);
+  hipLaunchKernelGGL(kern, grid, block, LDS, s, g);
+}
+
+struct TileCfg { int bm, bn, bk, wm, wn, direct; };
+#define L2L_ROW(i, bm, bn, bk, wm, wn, d) {bm, bn, bk, wm, wn, d},
 constexpr TileCfg kCfg[] = {L2L_GEMM_VARIANTS(L2L_ROW)};
 #undef L2L_ROW
 constexpr TileCfg kThis = kCfg[L2L_VARIANT];
@@ -43,6 +58,11 @@ constexpr TileCfg kThis = kCfg[L2L_VARIANT];
 #define L2L_CAT2(a, b) a##b
 #define L2L_CAT(a, b) L2L_CAT2(a, b)
 void L2L_CAT(l2l_launch_mfma_v, L2L_VARIANT)(const GemmArgs& g, hipStream_t s, int splits, bool out_f32) {
-  if (out_f32) launch_layout<kThis.bm, kThis.bn, kThis.bk, kThis.wm, kThis.wn, float>(g, s, splits);
-  else launch_layout<kThis.bm, kThis.bn, kThis.bk, kThis.wm, kThis.wn, bf16>(g, s, 1);
+  if constexpr (kThis.direct) {   // callers pick these variants only for K-contiguous operand pairs
+    if (out_f32) launch_direct<kThis.bm, kThis.bn, kThis.wm, kThis.wn, float>(g, s, splits);
+    else launch_direct<kThis.bm, kThis.bn, kThis.wm, kThis.wn, bf16>(g, s, 1);
+  } else {
+    if (out_f32) launch_layout<kThis.bm, kThis.bn, kThis.bk, kThis.wm, kThis.wn, float>(g, s, splits);
+    else launch_layout<kThis.bm, kThis.bn, kThis.bk, kThis.wm, kThis.wn, bf16>(g, s, 1);
+  }
 }

@@ -125,6 +125,7 @@ struct l2l_ctx {
   // workspace (group-sized)
   void *qkv, *p, *c, *r1, *y1, *u1, *ga, *r2, *dr2, *du1, *dy1, *dr1, *dc, *dp, *dqkv, *ytmp;
   float *mean1, *rstd1, *mean2, *rstd2;
+  void* wt[2] = {nullptr, nullptr};  // bf16 mode: per slot, [out, in] copies of the four weight matrices (packed offsets)
 
   // embedding / head
   void* emb = nullptr;
@@ -238,15 +239,15 @@ bool mfma_ok(const GemmArgs& g) {
 }
 
 // tile variants of the MFMA kernel live in their own translation units (gemm_variant.hip)
-struct TileCfg { int bm, bn, bk, wm, wn; };
-#define L2L_ROW(i, bm, bn, bk, wm, wn) {bm, bn, bk, wm, wn},
+struct TileCfg { int bm, bn, bk, wm, wn, direct; };
+#define L2L_ROW(i, bm, bn, bk, wm, wn, d) {bm, bn, bk, wm, wn, d},
 constexpr TileCfg kTiles[] = {L2L_GEMM_VARIANTS(L2L_ROW)};
 #undef L2L_ROW
 constexpr int kNumTiles = kNumGemmVariants;
 
 void launch_mfma_variant(int v, const GemmArgs& g, hipStream_t s, int splits, bool out_f32) {
   switch (v) {
-#define L2L_CASE(i, bm, bn, bk, wm, wn) case i: l2l_launch_mfma_v##i(g, s, splits, out_f32); break;
+#define L2L_CASE(i, bm, bn, bk, wm, wn, d) case i: l2l_launch_mfma_v##i(g, s, splits, out_f32); break;
     L2L_GEMM_VARIANTS(L2L_CASE)
 #undef L2L_CASE
     default: break;
@@ -266,9 +267,11 @@ void pick_tile(const GemmArgs& g, bool out_f32, int* variant, int* splits) {
   int v = 0;
   *splits = 1;
   const long long small = std::min(g.M, g.N);
-  if (small >= 256 && g.K >= 256) v = 3;
-  else if (g.M >= 256 && g.N >= 128) v = 2;
+  const bool kc = g.a_kc && g.b_kc;   // both operands K-contiguous: loads can go straight into LDS
+  if (small >= 256 && g.K >= 256) v = kc ? 6 : 3;
+  else if (g.M >= 256 && g.N >= 128) v = kc ? 8 : 2;
   else if (g.N <= 64) v = 1;
+  else v = kc ? 7 : 0;
   const TileCfg t = kTiles[v];
   // split K when an accumulating fp32 GEMM has too few tiles to fill 256 CUs
   if (out_f32 && (g.epi == EPI_ACCUM) && !g.k_dev) {
@@ -282,7 +285,7 @@ void pick_tile(const GemmArgs& g, bool out_f32, int* variant, int* splits) {
 }
 
 // impl: 0 auto, 1 plain, 2 mfma (auto tile), 100 + v: mfma tile variant v (tuning)
-int gemm(l2l_ctx* c, int dtype, bool out_f32, const GemmArgs& g, int impl = 0) {
+int gemm(l2l_ctx* c, int dtype, bool out_f32, const GemmArgs& g, int impl = 0, int cls = L2L_PROF_GEMM) {
   if (g.M <= 0 || g.N <= 0 || g.nbatch <= 0) return L2L_OK;
   if (g.nbatch > 65535 || (g.M + 63) / 64 > 65535) return fail(c, L2L_E_ARG, "gemm: grid too large");
   const bool can_mfma = dtype == L2L_BF16 && mfma_ok(g);
@@ -292,11 +295,12 @@ int gemm(l2l_ctx* c, int dtype, bool out_f32, const GemmArgs& g, int impl = 0) {
   const double flops = 2.0 * g.M * g.N * (double)g.K * g.nbatch;
   const double es = esize(dtype);
   const double bytes = ((double)g.M * g.K + (double)g.K * g.N) * es * g.nbatch + (double)g.M * g.N * (out_f32 ? 4 : es) * g.nbatch;
-  return timed(c, L2L_PROF_GEMM, flops, bytes, [&] {
+  return timed(c, cls, flops, bytes, [&] {
     if (use_mfma) {
       int v, splits;
       pick_tile(g, out_f32, &v, &splits);
       if (impl >= 100) v = impl - 100;
+      if (kTiles[v].direct && !(g.a_kc && g.b_kc)) v = 3;   // direct-to-LDS variants take K-contiguous operands only
       if (g_force_splits > 0 && out_f32 && g.epi == EPI_ACCUM) splits = g_force_splits;
       launch_mfma_variant(v, g, c->cs, splits, out_f32);
     } else if (dtype == L2L_BF16) {
@@ -368,12 +372,31 @@ int fill_zero(l2l_ctx* c, void* p, size_t bytes) {
   });
 }
 
+// bf16 mode: the forward GEMMs X W want W with its input index contiguous, like every other operand
+// of the MFMA kernel's fastest path; the four matrices of a staged layer (25 MB at BERT-Large) are
+// transposed once, on the copy stream right behind the stage's DMA, so that the work overlaps the
+// previous layer's compute and all micro-batches share the result.
+int transpose_weights(l2l_ctx* c, int slot) {
+  if (c->cfg.dtype != L2L_BF16) return L2L_OK;
+  const int H = c->cfg.hidden, F = c->cfg.ffn;
+  const long long* off = c->lay.off;
+  const struct { int t, rows, cols; } m[4] = {{T_WQKV, H, 3 * H}, {T_WO, H, H}, {T_W1, H, F}, {T_W2, F, H}};
+  for (const auto& w : m) {
+    hipLaunchKernelGGL(transpose_bf16_kernel, dim3((w.cols + 127) / 128, (w.rows + 127) / 128), dim3(256), 0, c->xs,
+                       (const bf16*)c->slot[slot] + off[w.t], (bf16*)c->wt[slot] + off[w.t], w.rows, w.cols);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(c, L2L_E_HIP, "transpose launch: %s", hipGetErrorString(e));
+  return L2L_OK;
+}
+
 // ------------------------------------------------------------------------------------------------
 // one encoder layer, forward, on `ng` micro-batches starting at row block x (rows = ng * T)
 // keep: also keep the GELU pre-activation and both LayerNorm statistics (backward recompute)
 // ------------------------------------------------------------------------------------------------
 template <typename T>
-int layer_forward_group(l2l_ctx* c, const void* params, const void* x, void* y, int ng, bool keep) {
+int layer_forward_group(l2l_ctx* c, int slot, const void* x, void* y, int ng, bool keep) {
+  const void* params = c->slot[slot];
   const l2l_config& f = c->cfg;
   const int H = f.hidden, A = f.heads, F = f.ffn, S = f.seq, d = H / A;
   const long long M = (long long)ng * c->T;
@@ -382,10 +405,14 @@ int layer_forward_group(l2l_ctx* c, const void* params, const void* x, void* y, 
   const T* P = (const T*)params;
   const long long* off = c->lay.off;
   T* qkv = (T*)c->qkv;
+  // weight operand of a forward GEMM: [out, in] copy (bf16) or the packed [in, out] matrix (fp32)
+  const bool tw = dt == L2L_BF16;
+  const T* W = tw ? (const T*)c->wt[slot] : P;
+  auto wld = [&](int in, int out) { return (long long)(tw ? in : out); };
 
   // QKV projection with bias
   {
-    GemmArgs g = gemm_args((int)M, 3 * H, H, x, H, 1, P + off[T_WQKV], 3 * H, 0, qkv, 3 * H);
+    GemmArgs g = gemm_args((int)M, 3 * H, H, x, H, 1, W + off[T_WQKV], wld(H, 3 * H), tw, qkv, 3 * H);
     g.epi = EPI_BIAS; g.bias = P + off[T_BQKV];
     L2L_TRY(gemm(c, dt, false, g));
   }
@@ -396,7 +423,7 @@ int layer_forward_group(l2l_ctx* c, const void* params, const void* x, void* y, 
     g.a_zo = (long long)S * 3 * H; g.a_zi = d; g.b_zo = g.a_zo; g.b_zi = d;
     g.c_zo = (long long)A * S * S; g.c_zi = (long long)S * S;
     g.alpha = 1.0f / sqrtf((float)d);
-    L2L_TRY(gemm(c, dt, false, g));
+    L2L_TRY(gemm(c, dt, false, g, 0, L2L_PROF_ATTN));
     const long long rows = (long long)nseq * A * S;
     L2L_TRY(timed(c, L2L_PROF_ATTN, 0, 2.0 * rows * S * sizeof(T), [&] {
       hipLaunchKernelGGL(softmax_fwd_kernel<T>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, c->cs, (T*)c->p, rows, S);
@@ -406,11 +433,11 @@ int layer_forward_group(l2l_ctx* c, const void* params, const void* x, void* y, 
     h.a_zo = (long long)A * S * S; h.a_zi = (long long)S * S;
     h.b_zo = (long long)S * 3 * H; h.b_zi = d;
     h.c_zo = (long long)S * H; h.c_zi = d;
-    L2L_TRY(gemm(c, dt, false, h));
+    L2L_TRY(gemm(c, dt, false, h, 0, L2L_PROF_ATTN));
   }
   // output projection + bias + residual, LayerNorm 1
   {
-    GemmArgs g = gemm_args((int)M, H, H, c->c, H, 1, P + off[T_WO], H, 0, c->r1, H);
+    GemmArgs g = gemm_args((int)M, H, H, c->c, H, 1, W + off[T_WO], wld(H, H), tw, c->r1, H);
     g.epi = EPI_BIAS | EPI_RESID; g.bias = P + off[T_BO]; g.resid = x; g.ldr = H;
     L2L_TRY(gemm(c, dt, false, g));
     L2L_TRY(ln_fwd<T>(c, c->r1, P + off[T_G1], P + off[T_BE1], c->y1, keep ? c->mean1 : nullptr, keep ? c->rstd1 : nullptr, M, H,
@@ -418,10 +445,10 @@ int layer_forward_group(l2l_ctx* c, const void* params, const void* x, void* y, 
   }
   // FFN1 + bias + GELU, FFN2 + bias + residual, LayerNorm 2
   {
-    GemmArgs g = gemm_args((int)M, F, H, c->y1, H, 1, P + off[T_W1], F, 0, c->ga, F);
+    GemmArgs g = gemm_args((int)M, F, H, c->y1, H, 1, W + off[T_W1], wld(H, F), tw, c->ga, F);
     g.epi = EPI_BIAS | EPI_GELU; g.bias = P + off[T_B1]; g.aux_out = keep ? c->u1 : nullptr; g.ldaux = F;
     L2L_TRY(gemm(c, dt, false, g));
-    GemmArgs h = gemm_args((int)M, H, F, c->ga, F, 1, P + off[T_W2], H, 0, c->r2, H);
+    GemmArgs h = gemm_args((int)M, H, F, c->ga, F, 1, W + off[T_W2], wld(F, H), tw, c->r2, H);
     h.epi = EPI_BIAS | EPI_RESID; h.bias = P + off[T_B2]; h.resid = c->y1; h.ldr = H;
     L2L_TRY(gemm(c, dt, false, h));
     if (keep) {
@@ -491,11 +518,11 @@ int layer_backward_group(l2l_ctx* c, const void* params, const void* x, void* dy
     // dV = P^T dC
     GemmArgs g1 = gemm_args(S, d, S, c->p, S, 0, c->dc, H, 0, dqkv + 2 * H, 3 * H);
     batch(g1, zp, (long long)S * S, zc, d, zq, d);
-    L2L_TRY(gemm(c, dt, false, g1));
+    L2L_TRY(gemm(c, dt, false, g1, 0, L2L_PROF_ATTN));
     // dP = dC V^T
     GemmArgs g2 = gemm_args(S, S, d, c->dc, H, 1, qkv + 2 * H, 3 * H, 1, c->dp, S);
     batch(g2, zc, d, zq, d, zp, (long long)S * S);
-    L2L_TRY(gemm(c, dt, false, g2));
+    L2L_TRY(gemm(c, dt, false, g2, 0, L2L_PROF_ATTN));
     // dS = P * (dP - rowsum(dP * P)), in place
     const long long rows = (long long)nseq * A * S;
     L2L_TRY(timed(c, L2L_PROF_ATTN, 0, 3.0 * rows * S * sizeof(T), [&] {
@@ -506,12 +533,12 @@ int layer_backward_group(l2l_ctx* c, const void* params, const void* x, void* dy
     GemmArgs g3 = gemm_args(S, d, S, c->dp, S, 1, qkv + H, 3 * H, 0, dqkv, 3 * H);
     batch(g3, zp, (long long)S * S, zq, d, zq, d);
     g3.alpha = alpha;
-    L2L_TRY(gemm(c, dt, false, g3));
+    L2L_TRY(gemm(c, dt, false, g3, 0, L2L_PROF_ATTN));
     // dK = dS^T Q / sqrt(d)
     GemmArgs g4 = gemm_args(S, d, S, c->dp, S, 0, qkv, 3 * H, 0, dqkv + H, 3 * H);
     batch(g4, zp, (long long)S * S, zq, d, zq, d);
     g4.alpha = alpha;
-    L2L_TRY(gemm(c, dt, false, g4));
+    L2L_TRY(gemm(c, dt, false, g4, 0, L2L_PROF_ATTN));
   }
   // QKV projection backward: dX = dR1 + dQKV Wqkv^T (over dY in place); dWqkv += X^T dQKV
   {
@@ -564,7 +591,7 @@ int head_loss_t(l2l_ctx* c, const void* x_last, const int32_t* labels, void* dy_
     // logits = Xl E^T + bv
     GemmArgs g = gemm_args(Tn, V, H, c->xl, H, 1, E + eo[E_E], H, 1, c->logits, Vp);
     g.epi = EPI_BIAS; g.bias = E + eo[E_BV]; g.m_dev = cnt;
-    L2L_TRY(gemm(c, dt, true, g));
+    L2L_TRY(gemm(c, dt, true, g, 0, L2L_PROF_OTHER));
     L2L_TRY(timed(c, L2L_PROF_OTHER, 0, 0, [&] {
       hipLaunchKernelGGL(ce_kernel<T>, dim3(Tn), dim3(256), 0, c->cs, c->logits, Vp, labels + (long long)u * Tn, idx, cnt,
                          c->lab_total, (T*)c->dz, loss_out, V, (int)Vp);
@@ -572,14 +599,14 @@ int head_loss_t(l2l_ctx* c, const void* x_last, const int32_t* labels, void* dy_
     // dXl = dz E
     GemmArgs h = gemm_args(Tn, H, V, c->dz, Vp, 1, E + eo[E_E], H, 0, c->dxl, H);
     h.m_dev = cnt;
-    L2L_TRY(gemm(c, dt, false, h));
+    L2L_TRY(gemm(c, dt, false, h, 0, L2L_PROF_OTHER));
     L2L_TRY(timed(c, L2L_PROF_OTHER, 0, 0, [&] {
       hipLaunchKernelGGL((rows_by_index_kernel<T, true>), dim3((Tn + 3) / 4), dim3(256), 0, c->cs, (const T*)c->dxl, dy, idx, cnt, H);
     }));
     // dE += dz^T Xl ; dbv += colsum(dz)
     GemmArgs w = gemm_args(V, H, Tn, c->dz, Vp, 0, c->xl, H, 0, c->egacc + eo[E_E], H);
     w.epi = EPI_ACCUM; w.k_dev = cnt;
-    L2L_TRY(gemm(c, dt, true, w));
+    L2L_TRY(gemm(c, dt, true, w, 0, L2L_PROF_OTHER));
     L2L_TRY(bias_grad<T>(c, c->dz, Vp, c->egacc + eo[E_BV], Tn, V, cnt));
   }
   return L2L_OK;
@@ -669,6 +696,8 @@ int l2l_create(const l2l_config* cfg, void* compute_stream, void* copy_stream, l
       {&c->ga, Mg * F}, {&c->r2, Mg * H}, {&c->dr2, Mg * H}, {&c->du1, Mg * F}, {&c->dy1, Mg * H}, {&c->dr1, Mg * H},
       {&c->dc, Mg * H}, {&c->dp, pe}, {&c->dqkv, Mg * 3 * H}, {&c->ytmp, Mg * H}};
   for (auto& b : bufs) L2L_TRY(dev_alloc(c, b.p, b.n * es));
+  if (cfg->dtype == L2L_BF16)
+    for (int i = 0; i < 2; ++i) L2L_TRY(dev_alloc(c, &c->wt[i], c->lay.total * es));
   float** stats[] = {&c->mean1, &c->rstd1, &c->mean2, &c->rstd2};
   for (auto s : stats) L2L_TRY(dev_alloc(c, (void**)s, Mg * 4));
 
@@ -729,6 +758,7 @@ int l2l_param_stage(l2l_ctx* c, int layer, const void* host_params, int slot) {
   // the copy may start only when every kernel that reads the slot's previous contents is done
   if (c->slot_layer[slot] >= 0) HIP_TRY(c, hipStreamWaitEvent(c->xs, c->slot_released[slot], 0));
   HIP_TRY(c, hipMemcpyAsync(c->slot[slot], host_params, c->lay.total * esize(c->cfg.dtype), hipMemcpyHostToDevice, c->xs));
+  L2L_TRY(transpose_weights(c, slot));
   HIP_TRY(c, hipEventRecord(c->slot_staged[slot], c->xs));
   c->slot_layer[slot] = layer;
   return L2L_OK;
@@ -744,8 +774,8 @@ int l2l_layer_fwd(l2l_ctx* c, int layer, int slot, const void* x_stash, void* y_
     const size_t o = (size_t)u0 * c->T * c->cfg.hidden * es;
     const void* x = (const char*)x_stash + o;
     void* y = (char*)y_out + o;
-    if (c->cfg.dtype == L2L_BF16) L2L_TRY(layer_forward_group<bf16>(c, c->slot[slot], x, y, ng, false));
-    else L2L_TRY(layer_forward_group<float>(c, c->slot[slot], x, y, ng, false));
+    if (c->cfg.dtype == L2L_BF16) L2L_TRY(layer_forward_group<bf16>(c, slot, x, y, ng, false));
+    else L2L_TRY(layer_forward_group<float>(c, slot, x, y, ng, false));
   }
   HIP_TRY(c, hipEventRecord(c->slot_released[slot], c->cs));
   return L2L_OK;
@@ -767,10 +797,10 @@ int l2l_layer_bwd(l2l_ctx* c, int layer, int slot, const void* x_stash, void* dy
     const void* x = (const char*)x_stash + o;
     void* dy = (char*)dy_dx + o;
     if (c->cfg.dtype == L2L_BF16) {
-      L2L_TRY(layer_forward_group<bf16>(c, c->slot[slot], x, nullptr, ng, true));  // recompute
+      L2L_TRY(layer_forward_group<bf16>(c, slot, x, nullptr, ng, true));  // recompute
       L2L_TRY(layer_backward_group<bf16>(c, c->slot[slot], x, dy, G, ng));
     } else {
-      L2L_TRY(layer_forward_group<float>(c, c->slot[slot], x, nullptr, ng, true));
+      L2L_TRY(layer_forward_group<float>(c, slot, x, nullptr, ng, true));
       L2L_TRY(layer_backward_group<float>(c, c->slot[slot], x, dy, G, ng));
     }
   }

@@ -313,6 +313,44 @@ __global__ __launch_bounds__(256) void ce_kernel(const float* z, long long ldz, 
   }
 }
 
+// out[c, r] = in[r, c] for a bf16 matrix [R, C] (both multiples of 8): 128 x 128 tiles through LDS, so that
+// both the reads and the writes are 256-byte row segments moved with 16-byte accesses.  The LDS tile is
+// kept as dwords holding (row 2i, row 2i+1) pairs of one column: a 16-byte output chunk (8 consecutive
+// rows of one column) is then four dword reads, and the pair packing is done with byte permutes on the way in.
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16* in, bf16* out, int R, int C) {
+  __shared__ uint32_t tile[64][128 + 1];   // [row pair][column]
+  const int r0 = blockIdx.y * 128, c0 = blockIdx.x * 128, t = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int u = t + i * 256;            // 64 row pairs x 16 column chunks
+    const int rp = u >> 4, cc = (u & 15) * 8;
+    u32x4 lo = {0, 0, 0, 0}, hi = {0, 0, 0, 0};
+    if (c0 + cc < C) {
+      if (r0 + 2 * rp < R) lo = *(const u32x4*)(in + (long long)(r0 + 2 * rp) * C + c0 + cc);
+      if (r0 + 2 * rp + 1 < R) hi = *(const u32x4*)(in + (long long)(r0 + 2 * rp + 1) * C + c0 + cc);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      tile[rp][cc + 2 * j] = __builtin_amdgcn_perm(hi[j], lo[j], 0x05040100u);
+      tile[rp][cc + 2 * j + 1] = __builtin_amdgcn_perm(hi[j], lo[j], 0x07060302u);
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int u = t + i * 256;            // 128 output rows (columns of in) x 16 chunks of 8 input rows
+    const int col = u >> 4, rq = u & 15;
+    if (c0 + col < C && r0 + rq * 8 < R) {
+      u32x4 v;
+      v.x = tile[rq * 4 + 0][col];
+      v.y = tile[rq * 4 + 1][col];
+      v.z = tile[rq * 4 + 2][col];
+      v.w = tile[rq * 4 + 3][col];
+      *(u32x4*)(out + (long long)(c0 + col) * R + r0 + rq * 8) = v;
+    }
+  }
+}
+
 // p[i] = v for i < n (a kernel rather than a memset so that callers can capture it in a graph).
 // 16-byte stores over the aligned body, dwords for the tail.
 __global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t* p, uint32_t v, long long n) {
