@@ -155,7 +155,8 @@ int l2l_embed_drain_wait(l2l_ctx*);
    COLSUM = bias / gain gradient reductions; OTHER = head, cross-entropy, fills. */
 enum { L2L_PROF_GEMM = 0, L2L_PROF_ATTN = 1, L2L_PROF_ROWWISE = 2, L2L_PROF_COLSUM = 3, L2L_PROF_OTHER = 4,
        L2L_PROF_CLASSES = 5 };
-/* on != 0: every launch is bracketed by events (slows the host side); counters are reset. */
+/* on = 1: every launch is bracketed by events; on = 2: only the GEMM class (less perturbation);
+   on = 0: off.  Counters are reset by every call. */
 int l2l_profile(l2l_ctx*, int on);
 /* Resolves pending events and returns, for one class: launches, total milliseconds, total
    algorithmic flops and bytes of those launches. */

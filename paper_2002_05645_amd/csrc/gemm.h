@@ -415,49 +415,105 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_kernel(G
 }
 
 // ------------------------------------------------------------------------------------------------
-// bf16 MFMA kernel, both operands K-contiguous, global loads written straight into LDS.
+// bf16 MFMA kernel whose global loads are written straight into LDS.
 //
 // Same tiling and epilogue as gemm_mfma_kernel, but the tiles never pass through registers: each
-// wave issues buffer loads with the LDS modifier, one instruction filling 1 KiB (8 rows x 128 bytes) of
-// the stage; no staging registers, no LDS store instructions, no byte permutes.  The LDS image is
-// [row][64] bf16 without padding; the 16-byte chunk c of row r sits at chunk slot c ^ ((r >> 1) & 7),
-// which makes the 16 rows that a quarter-wave reads for one fragment land on 16 different bank groups.
-// The swizzle is applied on the global side (which chunk a lane fetches), since the LDS side of such
-// a load is fixed: lane l writes bytes [16 l, 16 l + 16) of the instruction's 1 KiB.
-template <int ROWS, int BK, int NT>
+// wave issues buffer loads with the LDS modifier, one instruction filling 1 KiB of the stage; no
+// staging registers, no LDS store instructions, no byte permutes.  The LDS side of such a load is
+// fixed (lane l writes bytes [16 l, 16 l + 16) of the instruction's 1 KiB), so the bank-conflict
+// avoiding swizzle is applied on the global side: which 16-byte chunk a lane fetches.
+//
+//  K-contiguous operand (memory [rows, K]): LDS image [row][64] bf16, 128 bytes per row, no padding;
+//    chunk c of row r sits at chunk slot c ^ ((r >> 1) & 7); a fragment is one 16-byte read and the 16
+//    rows a quarter-wave reads land on 16 different bank groups.
+//  K-strided operand (memory [K, rows]): LDS image [k][rows] as in memory; chunk c of k-row k sits at
+//    slot c ^ ((k & 3) << 1).  A fragment (8 consecutive k of one column) is two ds_read_b64_tr_b16:
+//    within 16 lanes, lane 4 R + Q supplies the address of 4 consecutive columns of k-row R, and
+//    lane i receives column i of those 4 k-rows; the swizzle puts the 4 k-rows on different banks.
+template <int ROWS, int NT, bool KC>
 struct DirectLoader {
-  static_assert(BK == 64, "one LDS row = 128 bytes = 8 chunks");
-  static constexpr int BYTES = ROWS * 128;       // one stage
-  static constexpr int PER = ROWS / 8 / (NT / 64);  // 1 KiB blocks per wave
-  static_assert(PER * (NT / 64) * 8 == ROWS, "rows must split evenly over the waves");
+  static constexpr int BK = 64;
+  static constexpr int BYTES = ROWS * BK * 2;              // one stage
+  static constexpr int NBLK = BYTES / 1024;                // 1 KiB blocks, one load instruction each
+  static constexpr int PER = NBLK / (NT / 64);
+  static_assert(PER * (NT / 64) == NBLK, "blocks must split evenly over the waves");
+  static constexpr int ROWB = ROWS * 2;                    // !KC: bytes per k-row
+  static constexpr int CPR = ROWS / 8;                     // !KC: chunks per k-row
+  static_assert(KC || (CPR <= 64 && 64 % CPR == 0), "a k-row must fit one load instruction");
 
-  // row_local = lane / 8, slot = lane % 8; block b covers rows 8 b .. 8 b + 7
   __device__ __forceinline__ static void load(__amdgpu_buffer_rsrc_t rs, uint32_t ld, int k0, int K, char* stage, int wave,
                                               int lane) {
     static_for<0, PER>([&](auto ic) {
       constexpr int i = decltype(ic)::value;
       const int blk = i * (NT / 64) + wave;
-      const int row = blk * 8 + (lane >> 3);
-      const int c = (lane & 7) ^ ((row >> 1) & 7);
-      const int k = k0 + c * 8;
-      uint32_t off = ((uint32_t)row * ld + (uint32_t)k) * 2u;
-      if (k >= K) off = BUF_OOB;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void*)(stage + blk * 1024), 16, (int)off, 0, 0,
-                                           0);
+      uint32_t off;
+      if constexpr (KC) {
+        const int row = blk * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ ((row >> 1) & 7);
+        const int k = k0 + c * 8;
+        off = ((uint32_t)row * ld + (uint32_t)k) * 2u;
+        if (k >= K) off = BUF_OOB;
+      } else {
+        const int k = blk * (64 / CPR) + lane / CPR;        // k-row inside the tile
+        const int c = (lane % CPR) ^ ((k & 3) << 1);
+        off = ((uint32_t)(k0 + k) * ld + (uint32_t)(c * 8)) * 2u;   // k0 + k >= K is past the descriptor: zeros
+      }
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void*)(stage + blk * 1024), 16, (int)off,
+                                               0, 0, 0);
     });
+  }
+};
+
+// Per-lane part of a fragment's LDS address; the k16-step and the 32-row fragment index add constants.
+template <int ROWS, bool KC>
+struct FragAddr {
+  int base[2];   // KC: [0] only.  !KC: even / odd 32-column fragment
+  int koff[4];   // KC: chunk offset of each k16-step (swizzled)
+  __device__ __forceinline__ void init(int row0, int lane) {   // row0: first row / column of this wave's tile
+    if constexpr (KC) {
+      const int r = lane & 31, gsel = lane >> 5, sw = (r >> 1) & 7;
+      base[0] = (row0 + r) * 128;
+      base[1] = 0;
+      static_for<0, 4>([&](auto kc) { koff[kc] = (((decltype(kc)::value * 2) | gsel) ^ sw) * 16; });
+    } else {
+      const int i16 = lane & 15, q16 = lane >> 4;
+      const int R = i16 >> 2, Q = i16 & 3, colhalf = q16 & 1, gsel = q16 >> 1;
+      const int common = (gsel * 8 + R) * (ROWS * 2) + (row0 / 64) * 128 + (Q >> 1) * 16 + (Q & 1) * 8;
+      base[0] = common + ((colhalf ^ R) * 32);
+      base[1] = common + (((2 | colhalf) ^ R) * 32);
+      static_for<0, 4>([&](auto kc) { koff[kc] = decltype(kc)::value * 16 * (ROWS * 2); });
+    }
+  }
+  // fragment f (32 rows / columns each) of k16-step kk
+  template <int F, int KKI>
+  __device__ __forceinline__ bf16x8 read(const char* tile) const {
+    if constexpr (KC) {
+      return *(const bf16x8*)(tile + base[0] + F * 4096 + koff[KKI]);
+    } else {
+      typedef __attribute__((ext_vector_type(4))) short s16x4;
+      typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+      const char* p = tile + base[F & 1] + (F >> 1) * 128 + koff[KKI];
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(__attribute__((address_space(3))) char*)p);
+      const s16x4 hi =
+          __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(__attribute__((address_space(3))) char*)(p + 4 * (ROWS * 2)));
+      typedef __attribute__((ext_vector_type(8))) short s16x8;
+      const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      return __builtin_bit_cast(bf16x8, v);
+    }
   }
 };
 
 // wait until this wave's LDS-directed loads have landed (vmcnt(0); other counters untouched)
 __device__ __forceinline__ void wait_vm0() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
-template <int BM, int BN, int WM, int WN, typename TC>
+template <int BM, int BN, int WM, int WN, bool AKC, bool BKC, typename TC>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_kernel(GemmArgs g) {
   constexpr int BK = 64;
   constexpr int NWM = BM / WM, NWN = BN / WN, NT = NWM * NWN * 64;
   constexpr int FM = WM / 32, FN = WN / 32, KK = BK / 16;
-  using DA = DirectLoader<BM, BK, NT>;
-  using DB = DirectLoader<BN, BK, NT>;
+  static_assert(WM % 64 == 0 && WN % 64 == 0, "wave tiles start on multiples of 64 rows / columns");
+  using DA = DirectLoader<BM, NT, AKC>;
+  using DB = DirectLoader<BN, NT, BKC>;
   constexpr int STAGE = DA::BYTES + DB::BYTES;
   constexpr int EP_PITCH = WN + 4;
   constexpr int EP_BYTES = 32 * EP_PITCH * 4;
@@ -490,11 +546,11 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
   if (kt0 >= kt1) return;
 
   const int z = blockIdx.z, zo = z / g.zdiv, zi = z % g.zdiv;
-  const bf16* A = (const bf16*)g.A + zo * g.a_zo + zi * g.a_zi + (long long)m0 * g.lda;
-  const bf16* B = (const bf16*)g.B + zo * g.b_zo + zi * g.b_zi + (long long)n0 * g.ldb;
+  const bf16* A = (const bf16*)g.A + zo * g.a_zo + zi * g.a_zi + (AKC ? (long long)m0 * g.lda : (long long)m0);
+  const bf16* B = (const bf16*)g.B + zo * g.b_zo + zi * g.b_zi + (BKC ? (long long)n0 * g.ldb : (long long)n0);
   TC* C = (TC*)g.C + zo * g.c_zo + zi * g.c_zi;
-  const __amdgpu_buffer_rsrc_t ra = make_rsrc(A, tile_bytes<true>(g.lda, M - m0, K));
-  const __amdgpu_buffer_rsrc_t rb = make_rsrc(B, tile_bytes<true>(g.ldb, N - n0, K));
+  const __amdgpu_buffer_rsrc_t ra = make_rsrc(A, tile_bytes<AKC>(g.lda, M - m0, K));
+  const __amdgpu_buffer_rsrc_t rb = make_rsrc(B, tile_bytes<BKC>(g.ldb, N - n0, K));
   const uint32_t lda = (uint32_t)g.lda, ldb = (uint32_t)g.ldb;
 
   f32x16 acc[FM * FN];
@@ -508,12 +564,10 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
   wait_vm0();
   __syncthreads();
 
-  // fragment addresses: row r of a tile lives at r * 128; chunk c = 2 kk + (lane / 32) at slot c ^ ((r >> 1) & 7);
-  // rows of one lane differ by multiples of 32, so the swizzle term depends on the lane only
-  const int r = lane & 31, gsel = lane >> 5, sw = (r >> 1) & 7;
-  const int abase = (wm * WM + r) * 128, bbase = DA::BYTES + (wn * WN + r) * 128;
-  int koff[KK];
-  static_for<0, KK>([&](auto kc) { koff[kc] = (((decltype(kc)::value * 2) | gsel) ^ sw) * 16; });
+  FragAddr<BM, AKC> fa;
+  FragAddr<BN, BKC> fb;
+  fa.init(wm * WM, lane);
+  fb.init(wn * WN, lane);
 
   for (int kt = kt0; kt < kt1; ++kt) {
     const char* cur = lds + ((kt - kt0) & 1) * STAGE;
@@ -522,15 +576,17 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
     // last tile this fetches rows beyond K (zeros) or the next split's tile, neither of which is read
     DA::load(ra, lda, (kt + 1) * BK, K, nxt, wave, lane);
     DB::load(rb, ldb, (kt + 1) * BK, K, nxt + DA::BYTES, wave, lane);
+    const char* ta = cur;
+    const char* tb = cur + DA::BYTES;
     bf16x8 af[2 * FM], bfr[2 * FN];
-    static_for<0, FM>([&](auto i) { af[i] = *(const bf16x8*)(cur + abase + i * 4096 + koff[0]); });
-    static_for<0, FN>([&](auto j) { bfr[j] = *(const bf16x8*)(cur + bbase + j * 4096 + koff[0]); });
+    static_for<0, FM>([&](auto i) { af[i] = fa.template read<decltype(i)::value, 0>(ta); });
+    static_for<0, FN>([&](auto j) { bfr[j] = fb.template read<decltype(j)::value, 0>(tb); });
     static_for<0, KK>([&](auto kkc) {
       constexpr int kk = decltype(kkc)::value;
       constexpr int cs = (kk & 1), ns = ((kk + 1) & 1);
       if constexpr (kk + 1 < KK) {
-        static_for<0, FM>([&](auto i) { af[ns * FM + i] = *(const bf16x8*)(cur + abase + i * 4096 + koff[kk + 1]); });
-        static_for<0, FN>([&](auto j) { bfr[ns * FN + j] = *(const bf16x8*)(cur + bbase + j * 4096 + koff[kk + 1]); });
+        static_for<0, FM>([&](auto i) { af[ns * FM + i] = fa.template read<decltype(i)::value, kk + 1>(ta); });
+        static_for<0, FN>([&](auto j) { bfr[ns * FN + j] = fb.template read<decltype(j)::value, kk + 1>(tb); });
       }
       static_for<0, FM * FN>([&](auto t) {
         constexpr int T = decltype(t)::value;

@@ -34,11 +34,11 @@ void launch_layout(const GemmArgs& g, hipStream_t s, int splits) {
 
 }  // namespace
 
-template <int BM, int BN, int WM, int WN, typename TC>
-void launch_direct(const GemmArgs& g, hipStream_t s, int splits) {
+template <int BM, int BN, int WM, int WN, bool AKC, bool BKC, typename TC>
+void launch_direct_one(const GemmArgs& g, hipStream_t s, int splits) {
   constexpr int LDS = 2 * (BM + BN) * 128;
   static_assert(LDS <= 160 * 1024, "tile does not fit the 160 KB LDS");
-  auto kern = gemm_mfma_dlds_kernel<BM, BN, WM, WN, TC>;
+  auto kern = gemm_mfma_dlds_kernel<BM, BN, WM, WN, AKC, BKC, TC>;
   static const bool once = [&] {
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     return true;
@@ -47,6 +47,14 @@ void launch_direct(const GemmArgs& g, hipStream_t s, int splits) {
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
   dim3 grid(tiles, splits, g.nbatch), block((BM / WM) * (BN / WN) * 64);
   hipLaunchKernelGGL(kern, grid, block, LDS, s, g);
+}
+
+// the direct-to-LDS kernel is built for the two layout pairs that carry the layer's work: both operands
+// K-contiguous (forward with transposed weights, dX) and both K-strided (dW)
+template <int BM, int BN, int WM, int WN, typename TC>
+void launch_direct(const GemmArgs& g, hipStream_t s, int splits) {
+  if (g.a_kc && g.b_kc) launch_direct_one<BM, BN, WM, WN, true, true, TC>(g, s, splits);
+  else launch_direct_one<BM, BN, WM, WN, false, false, TC>(g, s, splits);
 }
 
 struct TileCfg { int bm, bn, bk, wm, wn, direct; };

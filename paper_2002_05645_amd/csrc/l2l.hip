@@ -195,7 +195,7 @@ hipEvent_t take_event(l2l_ctx* c) {
 
 template <typename F>
 int timed(l2l_ctx* c, int cls, double flops, double bytes, F&& f) {
-  if (!c->prof_on) {
+  if (!c->prof_on || (c->prof_on == 2 && cls != L2L_PROF_GEMM)) {
     f();
   } else {
     hipEvent_t a = take_event(c), b = take_event(c);
@@ -267,7 +267,7 @@ void pick_tile(const GemmArgs& g, bool out_f32, int* variant, int* splits) {
   int v = 0;
   *splits = 1;
   const long long small = std::min(g.M, g.N);
-  const bool kc = g.a_kc && g.b_kc;   // both operands K-contiguous: loads can go straight into LDS
+  const bool kc = g.a_kc == g.b_kc;   // both operands K-contiguous or both K-strided: loads go straight into LDS
   if (small >= 256 && g.K >= 256) v = kc ? 6 : 3;
   else if (g.M >= 256 && g.N >= 128) v = kc ? 8 : 2;
   else if (g.N <= 64) v = 1;
@@ -300,7 +300,7 @@ int gemm(l2l_ctx* c, int dtype, bool out_f32, const GemmArgs& g, int impl = 0, i
       int v, splits;
       pick_tile(g, out_f32, &v, &splits);
       if (impl >= 100) v = impl - 100;
-      if (kTiles[v].direct && !(g.a_kc && g.b_kc)) v = 3;   // direct-to-LDS variants take K-contiguous operands only
+      if (kTiles[v].direct && g.a_kc != g.b_kc) v = 3;   // direct-to-LDS variants exist for like layouts only
       if (g_force_splits > 0 && out_f32 && g.epi == EPI_ACCUM) splits = g_force_splits;
       launch_mfma_variant(v, g, c->cs, splits, out_f32);
     } else if (dtype == L2L_BF16) {
@@ -939,7 +939,7 @@ int l2l_profile(l2l_ctx* c, int on) {
   if (!c) return L2L_E_ARG;
   prof_resolve(c);
   for (int i = 0; i < L2L_PROF_CLASSES; ++i) { c->prof_n[i] = 0; c->prof_ms[i] = c->prof_fl[i] = c->prof_by[i] = 0; }
-  c->prof_on = on != 0;
+  c->prof_on = on;
   return L2L_OK;
 }
 
