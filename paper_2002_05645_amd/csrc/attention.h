@@ -1,0 +1,303 @@
+// Fused attention for the bf16 path, head width d = 64, sequence length a multiple of 32 up to 128:
+// scores, softmax and context (forward) and all five attention gradients (backward) of one
+// (sequence, head) pair in one workgroup, without the S x S matrices ever leaving the chip.
+//
+// Everything is computed "transposed": the MFMA tiles are S^T = K Q^T (keys along the accumulator's
+// register axis, queries along its lane axis), so that a softmax row lives in the registers of one
+// lane pair and row reductions are register adds plus one cross-lane exchange.  The 32x32x16 MFMA's
+// accumulator gives lane l the column l % 32 and, per register r, the row 8 (r / 4) + 4 (l / 32) + r % 4;
+// eight consecutive registers therefore hold, for one query, exactly the eight keys that the same
+// lane must supply as the B operand of the next product over keys (the contraction index may be
+// permuted freely as long as both operands agree), so P and dS feed O^T = V^T P^T and
+// dQ^T = K^T dS^T straight from registers.  Operands that are needed with the contraction index
+// strided in memory (V^T, K^T, and everything contracted over queries) come out of their natural
+// [row][64] LDS image through ds_read_b64_tr_b16.
+//
+// LDS images are [row][64] bf16 (128-byte rows) with the 16-byte chunk c of row r at slot
+// c ^ ((r >> 1) & 7): conflict-free for 16-byte fragment reads, two-way for the transpose reads.
+#pragma once
+#include "gemm.h"
+
+namespace attn {
+
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+
+__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
+
+// rows [0, S) of a [S][64] slice with row pitch `ld` elements, straight into LDS (1 KiB = 8 rows per instruction)
+__device__ __forceinline__ void load_rows(__amdgpu_buffer_rsrc_t rs, uint32_t ld, int S, char* dst, int wave, int nwaves, int lane) {
+  for (int blk = wave; blk < S / 8; blk += nwaves) {
+    const int row = blk * 8 + (lane >> 3);
+    const int c = swz(row, lane & 7);
+    const uint32_t off = ((uint32_t)row * ld + (uint32_t)c * 8) * 2u;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void*)(dst + blk * 1024), 16, (int)off, 0, 0, 0);
+  }
+}
+
+// fragment with rows as the M/N index: 8 consecutive columns (k = 16 step + 8 (lane / 32) ..) of row `row`
+__device__ __forceinline__ bf16x8 frag_rows(const char* img, int row, int step, int lane) {
+  return *(const bf16x8*)(img + row * 128 + swz(row, step * 2 + (lane >> 5)) * 16);
+}
+
+// four consecutive rows (the contraction index) of column col0 + 16 ((lane / 16) & 1) + lane % 16
+__device__ __forceinline__ s16x4 tr_read(const char* img, int row0, int col0, int lane) {
+  typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+  const int i16 = lane & 15, R = i16 >> 2, Q = i16 & 3;
+  const int row = row0 + R, col = col0 + 16 * ((lane >> 4) & 1) + Q * 4;
+  const char* p = img + row * 128 + swz(row, col >> 3) * 16 + (col & 7) * 2;
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(__attribute__((address_space(3))) char*)p);
+}
+
+// A-operand fragment for a product over keys whose B operand comes from accumulator registers 8 s .. 8 s + 7 of
+// key block kb: the keys are kb*32 + 16 s + 4 (lane / 32) + {0..3} and those + 8; column tile = 32 t
+__device__ __forceinline__ bf16x8 frag_keys_T(const char* img, int kb, int s, int t, int lane) {
+  const int base = kb * 32 + 16 * s + 4 * (lane >> 5);
+  const s16x4 lo = tr_read(img, base, t * 32, lane), hi = tr_read(img, base + 8, t * 32, lane);
+  const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+__device__ __forceinline__ bf16x8 pack8(const f32x16& a, int r0) {
+  bf16x8 v;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v[i] = (bf16)a[r0 + i];
+  return v;
+}
+
+__device__ __forceinline__ float xor32_max(float v) { return fmaxf(v, __shfl_xor(v, 32, 64)); }
+__device__ __forceinline__ float xor32_sum(float v) { return v + __shfl_xor(v, 32, 64); }
+
+// store a transposed 2 x (32 x 32) accumulator pair (rows = 64 columns of the output, lane = output row) as
+// out[(row0 + lane % 32) * ld + 8 blk + 4 (lane / 32) + {0..3} (+32 for the second tile)], scaled
+__device__ __forceinline__ void store_T(const f32x16 (&acc)[2], bf16* out, long long ld, int lane, float scale) {
+  bf16* p = out + (long long)(lane & 31) * ld + 4 * (lane >> 5);
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk) {
+      typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+      bf16x4 v;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) v[i] = (bf16)(acc[t][blk * 4 + i] * scale);
+      *(bf16x4*)(p + t * 32 + blk * 8) = v;
+    }
+}
+
+constexpr int SMAX = 128;   // longest sequence the fused kernels take
+constexpr int NKB = SMAX / 32;
+
+// Forward: out[b*S + q, h*64 ..] = softmax_rows(Q K^T * alpha) V for one (b, h) per workgroup; wave w owns queries
+// 32 w .. 32 w + 31.  qkv: [rows, 3H] with Q | K | V column groups.
+__global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16* qkv, bf16* out, int S, int H, int A, float alpha) {
+  __shared__ __attribute__((aligned(1024))) char lds[2 * SMAX * 128];
+  char* Ks = lds;
+  char* Vs = lds + SMAX * 128;
+  const int b = blockIdx.x / A, h = blockIdx.x % A;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const long long ld = 3LL * H;
+  const bf16* base = qkv + (long long)b * S * ld + h * 64;
+  const uint32_t bytes = (uint32_t)(((long long)(S - 1) * ld + 64) * 2);
+  load_rows(make_rsrc(base + H, bytes), (uint32_t)ld, S, Ks, wave, 4, lane);
+  load_rows(make_rsrc(base + 2 * H, bytes), (uint32_t)ld, S, Vs, wave, 4, lane);
+  const int nkb = S / 32;
+  const bool active = wave < nkb;
+  // this wave's queries as B-operand fragments, straight from memory
+  bf16x8 qf[4];
+  if (active) {
+    const bf16* qrow = base + (long long)(wave * 32 + (lane & 31)) * ld + (lane >> 5) * 8;
+#pragma unroll
+    for (int st = 0; st < 4; ++st) qf[st] = *(const bf16x8*)(qrow + st * 16);
+  }
+  wait_vm0();
+  __syncthreads();
+  if (!active) return;
+
+  f32x16 st_[NKB];
+  float m = -INFINITY;
+#pragma unroll
+  for (int kb = 0; kb < NKB; ++kb) {
+    if (kb < nkb) {
+      f32x16 a = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s4 = 0; s4 < 4; ++s4)
+        a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Ks, kb * 32 + (lane & 31), s4, lane), qf[s4], a, 0, 0, 0);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { a[r] *= alpha; m = fmaxf(m, a[r]); }
+      st_[kb] = a;
+    }
+  }
+  m = xor32_max(m);
+  float sum = 0.f;
+#pragma unroll
+  for (int kb = 0; kb < NKB; ++kb)
+    if (kb < nkb) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { st_[kb][r] = __expf(st_[kb][r] - m); sum += st_[kb][r]; }
+    }
+  sum = xor32_sum(sum);
+  const float inv = 1.0f / sum;
+
+  f32x16 o[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) o[t] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int kb = 0; kb < NKB; ++kb)
+    if (kb < nkb) {
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const bf16x8 pf = pack8(st_[kb], 8 * s2);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_keys_T(Vs, kb, s2, t, lane), pf, o[t], 0, 0, 0);
+      }
+    }
+  store_T(o, out + ((long long)b * S + wave * 32) * H + h * 64, H, lane, inv);
+}
+
+
+// ---- backward ------------------------------------------------------------------------------------------
+// image of P or dS for products over queries: [q][SMAX] bf16, 256-byte rows, the 32-byte group holding keys
+// 16 p .. 16 p + 15 of row q at group slot p ^ (q & 3) (so that four consecutive query rows hit different banks)
+__device__ __forceinline__ int pq_addr(int q, int key) { return q * 256 + (((key >> 4) ^ (q & 3)) * 32) + (key & 15) * 2; }
+
+__device__ __forceinline__ void pq_store(char* img, const f32x16& a, int q, int kb, int lane) {
+  typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+#pragma unroll
+  for (int blk = 0; blk < 4; ++blk) {
+    bf16x4 v;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = (bf16)a[blk * 4 + i];
+    *(bf16x4*)(img + pq_addr(q, kb * 32 + 8 * blk + 4 * (lane >> 5))) = v;
+  }
+}
+
+// B-operand fragment over queries 16 s + 8 (lane / 32) .. + 7 for key column 32 w + lane % 32
+__device__ __forceinline__ bf16x8 pq_frag(const char* img, int s, int w, int lane) {
+  typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+  const int i16 = lane & 15, R = i16 >> 2, Q = i16 & 3;
+  const int q0 = 16 * s + 8 * (lane >> 5) + R, key = 32 * w + 16 * ((lane >> 4) & 1) + Q * 4;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(__attribute__((address_space(3))) char*)(img + pq_addr(q0, key)));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(__attribute__((address_space(3))) char*)(img + pq_addr(q0 + 4, key)));
+  const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// A-operand fragment over queries 16 s + 8 (lane / 32) .. + 7 for column 32 t + lane % 32 of a [q][64] image
+__device__ __forceinline__ bf16x8 frag_queries_T(const char* img, int s, int t, int lane) {
+  const int q0 = 16 * s + 8 * (lane >> 5);
+  const s16x4 lo = tr_read(img, q0, t * 32, lane), hi = tr_read(img, q0 + 4, t * 32, lane);
+  const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+constexpr int BWD_LDS = 4 * SMAX * 128 + 2 * SMAX * 256;
+
+// Backward for one (b, h) per workgroup.  dout: [rows, H] gradient of the context; dqkv: [rows, 3H] receives
+// dQ | dK | dV.  Phase 1 (wave w = queries 32 w ..): recompute P, dP = dO V^T, dS = P (dP - rowsum(P dP)),
+// dQ = alpha dS K, and park P and dS in LDS.  Phase 2 (wave w = keys 32 w ..): dV = P^T dO, dK = alpha dS^T Q.
+__global__ __launch_bounds__(256) void attn_bwd_kernel(const bf16* qkv, const bf16* dout, bf16* dqkv, int S, int H, int A,
+                                                       float alpha) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  char* Ks = lds;
+  char* Vs = lds + SMAX * 128;
+  char* Qs = lds + 2 * SMAX * 128;
+  char* Os = lds + 3 * SMAX * 128;
+  char* Ps = lds + 4 * SMAX * 128;
+  char* Ds = Ps + SMAX * 256;
+  const int b = blockIdx.x / A, h = blockIdx.x % A;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const long long ld = 3LL * H;
+  const bf16* base = qkv + (long long)b * S * ld + h * 64;
+  const uint32_t bytes = (uint32_t)(((long long)(S - 1) * ld + 64) * 2);
+  load_rows(make_rsrc(base, bytes), (uint32_t)ld, S, Qs, wave, 4, lane);
+  load_rows(make_rsrc(base + H, bytes), (uint32_t)ld, S, Ks, wave, 4, lane);
+  load_rows(make_rsrc(base + 2 * H, bytes), (uint32_t)ld, S, Vs, wave, 4, lane);
+  const bf16* dob = dout + (long long)b * S * H + h * 64;
+  load_rows(make_rsrc(dob, (uint32_t)(((long long)(S - 1) * H + 64) * 2)), (uint32_t)H, S, Os, wave, 4, lane);
+  const int nkb = S / 32;
+  const bool active = wave < nkb;
+  wait_vm0();
+  __syncthreads();
+
+  bf16* dq_out = dqkv + ((long long)b * S + wave * 32) * ld + h * 64;
+  if (active) {
+    const int qrow = wave * 32 + (lane & 31);
+    bf16x8 qf[4], of[4];
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) { qf[s4] = frag_rows(Qs, qrow, s4, lane); of[s4] = frag_rows(Os, qrow, s4, lane); }
+    f32x16 p_[NKB], dp_[NKB];
+    float m = -INFINITY;
+#pragma unroll
+    for (int kb = 0; kb < NKB; ++kb)
+      if (kb < nkb) {
+        f32x16 a = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        f32x16 d = a;
+        const int krow = kb * 32 + (lane & 31);
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4) {
+          a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Ks, krow, s4, lane), qf[s4], a, 0, 0, 0);
+          d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Vs, krow, s4, lane), of[s4], d, 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { a[r] *= alpha; m = fmaxf(m, a[r]); }
+        p_[kb] = a;
+        dp_[kb] = d;
+      }
+    m = xor32_max(m);
+    float sum = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < NKB; ++kb)
+      if (kb < nkb) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { p_[kb][r] = __expf(p_[kb][r] - m); sum += p_[kb][r]; }
+      }
+    const float inv = 1.0f / xor32_sum(sum);
+    float dsum = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < NKB; ++kb)
+      if (kb < nkb) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { p_[kb][r] *= inv; dsum += p_[kb][r] * dp_[kb][r]; }
+      }
+    dsum = xor32_sum(dsum);
+    f32x16 dq[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) dq[t] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kb = 0; kb < NKB; ++kb)
+      if (kb < nkb) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) dp_[kb][r] = p_[kb][r] * (dp_[kb][r] - dsum);   // dS
+        pq_store(Ps, p_[kb], qrow, kb, lane);
+        pq_store(Ds, dp_[kb], qrow, kb, lane);
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          const bf16x8 df = pack8(dp_[kb], 8 * s2);
+#pragma unroll
+          for (int t = 0; t < 2; ++t) dq[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_keys_T(Ks, kb, s2, t, lane), df, dq[t], 0, 0, 0);
+        }
+      }
+    store_T(dq, dq_out, ld, lane, alpha);
+  }
+  __syncthreads();
+  if (active) {
+    f32x16 dv[2], dk[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      dv[t] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      dk[t] = dv[t];
+    }
+    for (int s = 0; s < S / 16; ++s) {
+      const bf16x8 pf = pq_frag(Ps, s, wave, lane), df = pq_frag(Ds, s, wave, lane);
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        dv[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_queries_T(Os, s, t, lane), pf, dv[t], 0, 0, 0);
+        dk[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_queries_T(Qs, s, t, lane), df, dk[t], 0, 0, 0);
+      }
+    }
+    store_T(dv, dq_out + 2 * H, ld, lane, 1.0f);
+    store_T(dk, dq_out + H, ld, lane, alpha);
+  }
+}
+
+}  // namespace attn

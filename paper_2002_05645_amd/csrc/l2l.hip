@@ -5,12 +5,14 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <vector>
 
 #include "../../include/l2l.h"
 #include "gemm.h"
 #include "gemm_variants.h"
+#include "attention.h"
 #include "rowwise.h"
 
 // ================================================================================================
@@ -107,6 +109,7 @@ struct l2l_ctx {
   Layout lay;
   hipStream_t cs = nullptr, xs = nullptr;  // compute, copy
   int group = 1;                            // micro-batches per launch
+  int no_fused_attention = 0;               // L2L_NO_FUSED_ATTENTION=1: use the batched-GEMM attention path
   long long T = 0, Mg = 0;                  // tokens per micro-batch, rows per launch group
   size_t dev_bytes = 0;
   std::vector<void*> allocs;
@@ -363,6 +366,12 @@ int fill_zero_copy_stream(l2l_ctx* c, void* p, size_t bytes) {
   return L2L_OK;
 }
 
+// the fused attention kernels take bf16, head width 64 and sequences of 32, 64, 96 or 128 tokens
+bool fused_attention_ok(const l2l_ctx* c) {
+  const l2l_config& f = c->cfg;
+  return f.dtype == L2L_BF16 && f.hidden / f.heads == 64 && f.seq % 32 == 0 && f.seq <= attn::SMAX && !c->no_fused_attention;
+}
+
 int fill_zero(l2l_ctx* c, void* p, size_t bytes) {
   const long long n = (long long)(bytes / 4);
   if (n <= 0) return L2L_OK;
@@ -417,6 +426,13 @@ int layer_forward_group(l2l_ctx* c, int slot, const void* x, void* y, int ng, bo
     L2L_TRY(gemm(c, dt, false, g));
   }
   // scores = Q K^T / sqrt(d) per (sequence, head), softmax over keys, context = P V
+  if (fused_attention_ok(c)) {
+    const double fl = 4.0 * S * S * d * nseq * A;
+    L2L_TRY(timed(c, L2L_PROF_ATTN, fl, (3.0 + 1.0) * M * H * sizeof(T), [&] {
+      hipLaunchKernelGGL(attn::attn_fwd_kernel, dim3(nseq * A), dim3(256), 0, c->cs, (const bf16*)qkv, (bf16*)c->c, S, H, A,
+                         1.0f / sqrtf((float)d));
+    }));
+  } else
   {
     GemmArgs g = gemm_args(S, S, d, qkv, 3 * H, 1, qkv + H, 3 * H, 1, c->p, S);
     g.nbatch = nseq * A; g.zdiv = A;
@@ -509,6 +525,13 @@ int layer_backward_group(l2l_ctx* c, const void* params, const void* x, void* dy
     L2L_TRY(bias_grad<T>(c, c->dr1, H, G + off[T_BO], M, H));
   }
   // attention backward per (sequence, head)
+  if (fused_attention_ok(c)) {
+    const double fl = 10.0 * S * S * d * nseq * A;
+    L2L_TRY(timed(c, L2L_PROF_ATTN, fl, (3.0 + 1.0 + 3.0) * M * H * sizeof(T), [&] {
+      hipLaunchKernelGGL(attn::attn_bwd_kernel, dim3(nseq * A), dim3(256), attn::BWD_LDS, c->cs, (const bf16*)qkv,
+                         (const bf16*)c->dc, (bf16*)dqkv, S, H, A, alpha);
+    }));
+  } else
   {
     const long long zq = (long long)S * 3 * H, zp = (long long)A * S * S, zc = (long long)S * H;
     auto batch = [&](GemmArgs& g, long long azo, long long azi, long long bzo, long long bzi, long long czo, long long czi) {
@@ -676,6 +699,8 @@ int l2l_create(const l2l_config* cfg, void* compute_stream, void* copy_stream, l
   }
   c->group = g;
   c->Mg = g * c->T;
+  if (const char* e = getenv("L2L_NO_FUSED_ATTENTION")) c->no_fused_attention = atoi(e) != 0;
+  (void)hipFuncSetAttribute((const void*)attn::attn_bwd_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, attn::BWD_LDS);
   *out = c;  // from here on the caller can read l2l_last_error and must l2l_destroy
 
   const size_t es = esize(cfg->dtype);
