@@ -58,6 +58,8 @@ def main():
     ap.add_argument("--stash", default="device", choices=["device", "host"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", type=int, default=0, help="override depth (memory-vs-depth sweeps)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (a known-size dispatch for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--tail-adam", action="store_true",
                     help="run the host Adam after all gradients arrived instead of eagerly per layer during backward")
     a = ap.parse_args()
@@ -130,12 +132,21 @@ def main():
                    "peak_device_bytes": int(peak_mem), "ctx_device_bytes": int(tr.ctx.device_bytes()),
                    "instrumented_ms_per_step": 1e3 * prof_total_s / a.steps},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": achieved / PEAK_BF16_TFLOPS,
+                     # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (profiles/bench_bert_large_gemm_hbm_traffic.md);
+                     # measured on the headline workload only
+                     "traffic": 680.5e6 if (a.config == 2 and not a.layers and not a.group) else None,
                      "kernel": "gemm_mfma_dlds_kernel / gemm_mfma_kernel: the layer's dense GEMMs (QKV, out-proj, FFN1, FFN2; forward, recompute, dX, dW)",
                      "gemm_ms_per_step": g["ms"] / a.steps, "launches_per_step": g["launches"] / a.steps,
                      "avg_launch_us": 1e3 * g["ms"] / max(g["launches"], 1),
                      "flops_per_launch": g["flops"] / max(g["launches"], 1)},
     }
+    if a.calibrate_copy:
+        src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                   # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
     tr.close()
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
