@@ -112,6 +112,21 @@ __global__ __launch_bounds__(256) void gemm_plain_kernel(GemmArgs g) {
 // Epilogue: each wave parks one 32-row strip of its accumulators in LDS (fp32), reads it back row
 // major and applies bias / GELU / residual on 8 consecutive columns at a time with 16-byte global
 // accesses; a scalar path covers unaligned outputs.  Stores are masked exactly.
+// Workgroup -> tile.  Consecutive workgroup ids land on different XCDs (id % 8), each with its own 4 MB
+// L2, so an XCD is given a contiguous range of the tile order; the order itself walks strips of up to 8
+// tile rows, M fastest, so that the ~32 tiles an XCD works on at a time are a near-square patch: few
+// A panels and few B panels, each shared by many resident tiles.
+__device__ __forceinline__ void tile_of_block(int id, int tiles_m, int tiles_n, int& tm, int& tn) {
+  const int total = tiles_m * tiles_n;
+  const int per = total / 8;
+  if (id < per * 8) id = (id % 8) * per + id / 8;
+  const int GM = min(8, tiles_m);
+  const int group = GM * tiles_n, grp = id / group, first = grp * GM;
+  const int gm = min(GM, tiles_m - first), in = id - grp * group;
+  tm = first + in % gm;
+  tn = in / gm;
+}
+
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 constexpr uint32_t BUF_OOB = 0x80000000u;  // beyond any descriptor range used here (operands are < 2 GiB)
 
@@ -284,16 +299,9 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_kernel(G
   if (g.k_dev) K = min(K, *g.k_dev);
   const int N = g.N;
 
-  // tile mapping: consecutive workgroups go to different XCDs, so give each XCD (id % 8) a
-  // contiguous range of tiles, N fastest, so that one XCD's L2 sees the same A panel repeatedly.
   const int tiles_n = (N + BN - 1) / BN, tiles_m = (g.M + BM - 1) / BM;
-  const int total = tiles_m * tiles_n;
-  int id = blockIdx.x;
-  {
-    const int per = total / 8, rem_start = per * 8;
-    if (id < rem_start) id = (id % 8) * per + id / 8;
-  }
-  const int tm = id / tiles_n, tn = id % tiles_n;
+  int tm, tn;
+  tile_of_block(blockIdx.x, tiles_m, tiles_n, tm, tn);
   const int m0 = tm * BM, n0 = tn * BN;
   if (m0 >= M) return;
 
@@ -530,13 +538,8 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
   const int N = g.N;
 
   const int tiles_n = (N + BN - 1) / BN, tiles_m = (g.M + BM - 1) / BM;
-  const int total = tiles_m * tiles_n;
-  int id = blockIdx.x;
-  {
-    const int per = total / 8, rem_start = per * 8;
-    if (id < rem_start) id = (id % 8) * per + id / 8;
-  }
-  const int tm = id / tiles_n, tn = id % tiles_n;
+  int tm, tn;
+  tile_of_block(blockIdx.x, tiles_m, tiles_n, tm, tn);
   const int m0 = tm * BM, n0 = tn * BN;
   if (m0 >= M) return;
 
@@ -574,8 +577,10 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
     char* nxt = lds + ((kt - kt0 + 1) & 1) * STAGE;
     // next tile straight into the other stage (every wave left it at the previous barrier); past the
     // last tile this fetches rows beyond K (zeros) or the next split's tile, neither of which is read
+#ifndef L2L_DBG_NOLOAD
     DA::load(ra, lda, (kt + 1) * BK, K, nxt, wave, lane);
     DB::load(rb, ldb, (kt + 1) * BK, K, nxt + DA::BYTES, wave, lane);
+#endif
     const char* ta = cur;
     const char* tb = cur + DA::BYTES;
     bf16x8 af[2 * FM], bfr[2 * FN];
