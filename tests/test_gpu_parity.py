@@ -289,6 +289,40 @@ def test_step_tiny_fp32_eager_eps():
     _assert_errs(adam, 1e-3)
 
 
+def test_three_training_steps_match_oracle_fp32():
+    # the whole loop, three times: stage -> forward -> head -> backward -> drain -> EPS Adam -> ship -> stage ...
+    w = S.WORKLOADS[0]
+    lr = 1e-3
+    tr = L2LTrainer(layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, vocab=w.vocab, ubatch=w.ubatch,
+                    num_ubatches=w.num_ubatches, dtype="fp32", lr=lr, eager=True, eps_threads=4)
+    try:
+        emb = {k: v.astype(np.float64) for k, v in S.embed_params(w).items()}
+        layers = [{k: v.astype(np.float64) for k, v in S.layer_params(w, l).items()} for l in range(w.layers)]
+        tr.load_params(emb, layers)
+        tok, lab = S.tokens_and_labels(w)
+        tokd, labd = torch.from_numpy(tok).cuda(), torch.from_numpy(lab).cuda()
+        blocks = [emb] + layers
+        m = [{k: np.zeros_like(v) for k, v in b.items()} for b in blocks]
+        v2 = [{k: np.zeros_like(v) for k, v in b.items()} for b in blocks]
+        for t in range(1, 4):
+            loss = tr.step(tokd, labd)
+            loss_ref, gemb, gl = O.run_l2l(emb, layers, tok, lab, w.heads, 1e-12)
+            assert abs(loss - loss_ref) / abs(loss_ref) < 1e-4, (t, loss, loss_ref)
+            for b, g, mm, vv in zip(blocks, [gemb] + gl, m, v2):
+                for k in b:
+                    b[k], mm[k], vv[k] = O.adam_step(b[k], g[k], mm[k], vv[k], t, lr=lr)
+        me, ml = tr.master_params()
+        ref0 = {k: v.astype(np.float64) for k, v in S.embed_params(w).items()}
+        for k in emb:       # compare the accumulated update, not the weights (which are dominated by their initial value)
+            if np.any(emb[k] != ref0[k]):
+                assert O.rel_l2(me[k] - ref0[k], emb[k] - ref0[k]) < 2e-3, k
+        l0 = S.layer_params(w, 0)
+        for k in layers[0]:
+            assert O.rel_l2(ml[0][k] - l0[k], layers[0][k] - l0[k]) < 2e-3, k
+    finally:
+        tr.close()
+
+
 def test_step_tiny_fp32_host_stash():
     errs, _, _ = _step_case(S.WORKLOADS[0], stash="host")
     _assert_errs({k: v for k, v in errs.items() if not k.startswith("adam.")}, TOL["fp32"])
