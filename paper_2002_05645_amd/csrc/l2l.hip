@@ -280,7 +280,9 @@ void pick_tile(const GemmArgs& g, bool out_f32, int* variant, int* splits) {
   if (out_f32 && (g.epi == EPI_ACCUM) && !g.k_dev) {
     const long long tiles = (long long)((g.M + t.bm - 1) / t.bm) * ((g.N + t.bn - 1) / t.bn) * g.nbatch;
     const int nk = (g.K + t.bk - 1) / t.bk;
-    long long want = (512 + tiles - 1) / tiles;
+    // one resident workgroup per CU: tiles x splits as close to the 256 CUs as it gets without exceeding
+    // them (measured best for the dW shapes: 64 x 4, 48 x 5, 16 x 16)
+    long long want = tiles < 256 ? 256 / tiles : 1;
     want = std::min<long long>(want, std::max(1, nk / 8));
     *splits = (int)std::max<long long>(1, std::min<long long>(want, 64));
   }
@@ -304,6 +306,7 @@ int gemm(l2l_ctx* c, int dtype, bool out_f32, const GemmArgs& g, int impl = 0, i
       pick_tile(g, out_f32, &v, &splits);
       if (impl >= 100) v = impl - 100;
       if (kTiles[v].direct && g.a_kc != g.b_kc) v = 3;   // direct-to-LDS variants exist for like layouts only
+      if (const char* e = getenv("L2L_FORCE_SPLITS")) g_force_splits = atoi(e);
       if (g_force_splits > 0 && out_f32 && g.epi == EPI_ACCUM) splits = g_force_splits;
       launch_mfma_variant(v, g, c->cs, splits, out_f32);
     } else if (dtype == L2L_BF16) {
