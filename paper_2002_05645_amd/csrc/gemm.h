@@ -435,9 +435,12 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_kernel(G
 //    chunk c of row r sits at chunk slot c ^ ((r >> 1) & 7); a fragment is one 16-byte read and the 16
 //    rows a quarter-wave reads land on 16 different bank groups.
 //  K-strided operand (memory [K, rows]): LDS image [k][rows] as in memory; chunk c of k-row k sits at
-//    slot c ^ ((k & 3) << 1).  A fragment (8 consecutive k of one column) is two ds_read_b64_tr_b16:
-//    within 16 lanes, lane 4 R + Q supplies the address of 4 consecutive columns of k-row R, and
-//    lane i receives column i of those 4 k-rows; the swizzle puts the 4 k-rows on different banks.
+//    slot c ^ ((k & 3) << 2), i.e. the 64-byte blocks of a k-row are permuted within groups of four.
+//    A fragment (8 consecutive k of one column) is two ds_read_b64_tr_b16: within 16 lanes, lane
+//    4 R + Q supplies the address of 4 consecutive columns of k-row R, and lane i receives column i of
+//    those 4 k-rows.  A k-row is a multiple of 256 bytes, so unswizzled the 4 k-rows of a read would sit
+//    on the same banks; with the swizzle the 32 lanes of a half-wave (4 k-rows x 64 bytes) cover all
+//    64 banks once.
 template <int ROWS, int NT, bool KC>
 struct DirectLoader {
   static constexpr int BK = 64;
@@ -463,7 +466,7 @@ struct DirectLoader {
         if (k >= K) off = BUF_OOB;
       } else {
         const int k = blk * (64 / CPR) + lane / CPR;        // k-row inside the tile
-        const int c = (lane % CPR) ^ ((k & 3) << 1);
+        const int c = (lane % CPR) ^ ((k & 3) << 2);
         off = ((uint32_t)(k0 + k) * ld + (uint32_t)(c * 8)) * 2u;   // k0 + k >= K is past the descriptor: zeros
       }
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void*)(stage + blk * 1024), 16, (int)off,
@@ -475,20 +478,20 @@ struct DirectLoader {
 // Per-lane part of a fragment's LDS address; the k16-step and the 32-row fragment index add constants.
 template <int ROWS, bool KC>
 struct FragAddr {
-  int base[2];   // KC: [0] only.  !KC: even / odd 32-column fragment
+  int base[4];   // KC: [0] only.  !KC: one per 32-column fragment of the wave's tile
   int koff[4];   // KC: chunk offset of each k16-step (swizzled)
   __device__ __forceinline__ void init(int row0, int lane) {   // row0: first row / column of this wave's tile
     if constexpr (KC) {
       const int r = lane & 31, gsel = lane >> 5, sw = (r >> 1) & 7;
       base[0] = (row0 + r) * 128;
-      base[1] = 0;
+      base[1] = base[2] = base[3] = 0;
       static_for<0, 4>([&](auto kc) { koff[kc] = (((decltype(kc)::value * 2) | gsel) ^ sw) * 16; });
     } else {
       const int i16 = lane & 15, q16 = lane >> 4;
       const int R = i16 >> 2, Q = i16 & 3, colhalf = q16 & 1, gsel = q16 >> 1;
-      const int common = (gsel * 8 + R) * (ROWS * 2) + (row0 / 64) * 128 + (Q >> 1) * 16 + (Q & 1) * 8;
-      base[0] = common + ((colhalf ^ R) * 32);
-      base[1] = common + (((2 | colhalf) ^ R) * 32);
+      // fragment f starts at 64-byte block (row0 / 32 + f) of the k-row; the swizzle XORs the block index with R
+      const int common = (gsel * 8 + R) * (ROWS * 2) + colhalf * 32 + Q * 8;
+      static_for<0, 4>([&](auto f) { base[f] = common + (((row0 / 32 + decltype(f)::value) ^ R) * 64); });
       static_for<0, 4>([&](auto kc) { koff[kc] = decltype(kc)::value * 16 * (ROWS * 2); });
     }
   }
@@ -500,7 +503,8 @@ struct FragAddr {
     } else {
       typedef __attribute__((ext_vector_type(4))) short s16x4;
       typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
-      const char* p = tile + base[F & 1] + (F >> 1) * 128 + koff[KKI];
+      static_assert(F < 4, "a wave's tile holds at most four fragments per operand");
+      const char* p = tile + base[F] + koff[KKI];
       const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(__attribute__((address_space(3))) char*)p);
       const s16x4 hi =
           __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(__attribute__((address_space(3))) char*)(p + 4 * (ROWS * 2)));
@@ -513,6 +517,12 @@ struct FragAddr {
 
 // wait until this wave's LDS-directed loads have landed (vmcnt(0); other counters untouched)
 __device__ __forceinline__ void wait_vm0() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+// ... and until every LDS read this wave issued has returned (vmcnt(0) lgkmcnt(0))
+__device__ __forceinline__ void wait_vm0_lds0() { __builtin_amdgcn_s_waitcnt(0x0070); }
+
+// dynamic LDS of gemm_mfma_dlds_kernel: two stages
+template <int BM, int BN, int WM, int WN>
+constexpr int dlds_lds_bytes() { return 2 * (BM + BN) * 128; }
 
 template <int BM, int BN, int WM, int WN, bool AKC, bool BKC, typename TC>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_kernel(GemmArgs g) {
@@ -526,7 +536,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
   constexpr int EP_PITCH = WN + 4;
   constexpr int EP_BYTES = 32 * EP_PITCH * 4;
   static_assert(NWM * NWN * EP_BYTES <= 2 * STAGE, "epilogue strips must fit the staging buffers");
-  extern __shared__ __attribute__((aligned(1024))) char lds[];  // 2 * STAGE bytes
+  extern __shared__ __attribute__((aligned(1024))) char lds[];  // dlds_lds_bytes<BM, BN, WM, WN>()
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -562,37 +572,45 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
     acc[T] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   });
 
-  DA::load(ra, lda, kt0 * BK, K, lds, wave, lane);
-  DB::load(rb, ldb, kt0 * BK, K, lds + DA::BYTES, wave, lane);
-  wait_vm0();
-  __syncthreads();
-
   FragAddr<BM, AKC> fa;
   FragAddr<BN, BKC> fb;
   fa.init(wm * WM, lane);
   fb.init(wn * WN, lane);
 
+  // Two LDS stages.  The loads of tile t + 1 are issued once every wave has read the last fragments
+  // of tile t - 1 out of that stage, which is at the barrier before the last k16-step of tile t - 1;
+  // that same barrier publishes tile t.  The barrier therefore sits between MFMA groups, and the
+  // first fragments of the next tile are read while the last MFMAs of this one run.  Past the last
+  // tile the loads fetch rows beyond K (zeros) or the next split's tile, neither of which is used.
+  DA::load(ra, lda, kt0 * BK, K, lds, wave, lane);
+  DB::load(rb, ldb, kt0 * BK, K, lds + DA::BYTES, wave, lane);
+  wait_vm0();
+  __syncthreads();
+  DA::load(ra, lda, (kt0 + 1) * BK, K, lds + STAGE, wave, lane);
+  DB::load(rb, ldb, (kt0 + 1) * BK, K, lds + STAGE + DA::BYTES, wave, lane);
+
+  bf16x8 af[2 * FM], bfr[2 * FN];
+  static_for<0, FM>([&](auto i) { af[i] = fa.template read<decltype(i)::value, 0>(lds); });
+  static_for<0, FN>([&](auto j) { bfr[j] = fb.template read<decltype(j)::value, 0>(lds + DA::BYTES); });
+
   for (int kt = kt0; kt < kt1; ++kt) {
-    const char* cur = lds + ((kt - kt0) & 1) * STAGE;
-    char* nxt = lds + ((kt - kt0 + 1) & 1) * STAGE;
-    // next tile straight into the other stage (every wave left it at the previous barrier); past the
-    // last tile this fetches rows beyond K (zeros) or the next split's tile, neither of which is read
-#ifndef L2L_DBG_NOLOAD
-    DA::load(ra, lda, (kt + 1) * BK, K, nxt, wave, lane);
-    DB::load(rb, ldb, (kt + 1) * BK, K, nxt + DA::BYTES, wave, lane);
-#endif
-    const char* ta = cur;
-    const char* tb = cur + DA::BYTES;
-    bf16x8 af[2 * FM], bfr[2 * FN];
-    static_for<0, FM>([&](auto i) { af[i] = fa.template read<decltype(i)::value, 0>(ta); });
-    static_for<0, FN>([&](auto j) { bfr[j] = fb.template read<decltype(j)::value, 0>(tb); });
+    char* cur = lds + ((kt - kt0) & 1) * STAGE;
+    const char* nxt = lds + ((kt - kt0 + 1) & 1) * STAGE;
     static_for<0, KK>([&](auto kkc) {
       constexpr int kk = decltype(kkc)::value;
       constexpr int cs = (kk & 1), ns = ((kk + 1) & 1);
       if constexpr (kk + 1 < KK) {
-        static_for<0, FM>([&](auto i) { af[ns * FM + i] = fa.template read<decltype(i)::value, kk + 1>(ta); });
-        static_for<0, FN>([&](auto j) { bfr[ns * FN + j] = fb.template read<decltype(j)::value, kk + 1>(tb); });
+        static_for<0, FM>([&](auto i) { af[ns * FM + i] = fa.template read<decltype(i)::value, kk + 1>(cur); });
+        static_for<0, FN>([&](auto j) { bfr[ns * FN + j] = fb.template read<decltype(j)::value, kk + 1>(cur + DA::BYTES); });
+      } else {
+        // every fragment of this tile is in registers and this wave's part of the next tile has landed
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        DA::load(ra, lda, (kt + 2) * BK, K, cur, wave, lane);
+        DB::load(rb, ldb, (kt + 2) * BK, K, cur + DA::BYTES, wave, lane);
+        static_for<0, FM>([&](auto i) { af[ns * FM + i] = fa.template read<decltype(i)::value, 0>(nxt); });
+        static_for<0, FN>([&](auto j) { bfr[ns * FN + j] = fb.template read<decltype(j)::value, 0>(nxt + DA::BYTES); });
       }
+      __builtin_amdgcn_sched_barrier(0);   // fragment reads first: the MFMAs below cover their latency
       static_for<0, FM * FN>([&](auto t) {
         constexpr int T = decltype(t)::value;
         constexpr int i = T / FN, j = T % FN;
@@ -600,9 +618,10 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
       });
       __builtin_amdgcn_sched_barrier(0);
     });
-    wait_vm0();
-    __syncthreads();
   }
+  // the loads still in flight target the staging buffers the epilogue is about to reuse
+  wait_vm0();
+  __syncthreads();
 
   // ---- epilogue (as in gemm_mfma_kernel) ----------------------------------------------------------
   const bool atomic = gridDim.y > 1;

@@ -36,7 +36,7 @@ void launch_layout(const GemmArgs& g, hipStream_t s, int splits) {
 
 template <int BM, int BN, int WM, int WN, bool AKC, bool BKC, typename TC>
 void launch_direct_one(const GemmArgs& g, hipStream_t s, int splits) {
-  constexpr int LDS = 2 * (BM + BN) * 128;
+  constexpr int LDS = dlds_lds_bytes<BM, BN, WM, WN>();
   static_assert(LDS <= 160 * 1024, "tile does not fit the 160 KB LDS");
   auto kern = gemm_mfma_dlds_kernel<BM, BN, WM, WN, AKC, BKC, TC>;
   static const bool once = [&] {
