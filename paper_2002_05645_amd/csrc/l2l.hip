@@ -136,7 +136,8 @@ struct l2l_ctx {
   int emb_staged = 0, egacc_state = 0;
   hipEvent_t emb_staged_ev = nullptr, emb_released_ev = nullptr, egacc_ready = nullptr, egacc_landed = nullptr, egacc_drained = nullptr;
   float *emean = nullptr, *erstd = nullptr;
-  int32_t *lab_idx = nullptr, *lab_cnt = nullptr, *lab_total = nullptr;
+  int32_t *lab_idx = nullptr, *lab_cnt = nullptr, *lab_total = nullptr, *lab_gidx = nullptr, *chunk_cnt = nullptr;
+  long long head_rows = 0;   // labelled rows per pass of the head
   void *xl = nullptr, *dz = nullptr, *dxl = nullptr;
   float* logits = nullptr;
   long long Vp = 0;
@@ -600,40 +601,50 @@ int head_loss_t(l2l_ctx* c, const void* x_last, const int32_t* labels, void* dy_
   const long long Vp = c->Vp;
   const T* E = (const T*)c->emb;
   const long long* eo = c->lay.eoff;
+  const long long UT = (long long)U * Tn, RC = c->head_rows;
+  const int nchunks = (int)((UT + RC - 1) / RC);
   L2L_TRY(fill_zero(c, c->lab_cnt, (U + 1) * 4));
   L2L_TRY(fill_zero(c, loss_out, 4));
-  L2L_TRY(fill_zero(c, dy_out, (size_t)U * Tn * H * sizeof(T)));
-  L2L_TRY(timed(c, L2L_PROF_OTHER, 0, 4.0 * U * Tn, [&] {
+  L2L_TRY(fill_zero(c, dy_out, (size_t)UT * H * sizeof(T)));
+  L2L_TRY(timed(c, L2L_PROF_OTHER, 0, 4.0 * UT, [&] {
     hipLaunchKernelGGL(label_compact_kernel, dim3(U), dim3(256), 0, c->cs, labels, Tn, c->lab_idx, c->lab_cnt, c->lab_total);
   }));
-  for (int u = 0; u < U; ++u) {
-    const T* x = (const T*)x_last + (long long)u * Tn * H;
-    T* dy = (T*)dy_out + (long long)u * Tn * H;
-    const int32_t* idx = c->lab_idx + (long long)u * Tn;
-    const int32_t* cnt = c->lab_cnt + u;
+  L2L_TRY(timed(c, L2L_PROF_OTHER, 0, 0, [&] {
+    hipLaunchKernelGGL(label_merge_kernel, dim3(U), dim3(256), 0, c->cs, c->lab_idx, c->lab_cnt, Tn, c->lab_gidx, c->chunk_cnt,
+                       (int)RC, nchunks);
+  }));
+  // The labelled rows of the whole mini-batch, RC at a time (one pass at the usual masking rates): the
+  // vocabulary GEMMs then have enough rows to fill the chip, and E is read once per pass, not once per
+  // micro-batch.  Passes beyond the labelled count find a zero in chunk_cnt and do nothing.
+  for (int ch = 0; ch < nchunks; ++ch) {
+    const int32_t* idx = c->lab_gidx + (long long)ch * RC;
+    const int32_t* cnt = c->chunk_cnt + ch;
+    const int rows = (int)std::min<long long>(RC, UT - (long long)ch * RC);
     L2L_TRY(timed(c, L2L_PROF_OTHER, 0, 0, [&] {
-      hipLaunchKernelGGL((rows_by_index_kernel<T, false>), dim3((Tn + 3) / 4), dim3(256), 0, c->cs, x, (T*)c->xl, idx, cnt, H);
+      hipLaunchKernelGGL((rows_by_index_kernel<T, false>), dim3((rows + 3) / 4), dim3(256), 0, c->cs, (const T*)x_last, (T*)c->xl,
+                         idx, cnt, H);
     }));
     // logits = Xl E^T + bv
-    GemmArgs g = gemm_args(Tn, V, H, c->xl, H, 1, E + eo[E_E], H, 1, c->logits, Vp);
+    GemmArgs g = gemm_args(rows, V, H, c->xl, H, 1, E + eo[E_E], H, 1, c->logits, Vp);
     g.epi = EPI_BIAS; g.bias = E + eo[E_BV]; g.m_dev = cnt;
     L2L_TRY(gemm(c, dt, true, g, 0, L2L_PROF_OTHER));
     L2L_TRY(timed(c, L2L_PROF_OTHER, 0, 0, [&] {
-      hipLaunchKernelGGL(ce_kernel<T>, dim3(Tn), dim3(256), 0, c->cs, c->logits, Vp, labels + (long long)u * Tn, idx, cnt,
-                         c->lab_total, (T*)c->dz, loss_out, V, (int)Vp);
+      hipLaunchKernelGGL(ce_kernel<T>, dim3(rows), dim3(256), 0, c->cs, c->logits, Vp, labels, idx, cnt, c->lab_total, (T*)c->dz,
+                         loss_out, V, (int)Vp);
     }));
     // dXl = dz E
-    GemmArgs h = gemm_args(Tn, H, V, c->dz, Vp, 1, E + eo[E_E], H, 0, c->dxl, H);
+    GemmArgs h = gemm_args(rows, H, V, c->dz, Vp, 1, E + eo[E_E], H, 0, c->dxl, H);
     h.m_dev = cnt;
     L2L_TRY(gemm(c, dt, false, h, 0, L2L_PROF_OTHER));
     L2L_TRY(timed(c, L2L_PROF_OTHER, 0, 0, [&] {
-      hipLaunchKernelGGL((rows_by_index_kernel<T, true>), dim3((Tn + 3) / 4), dim3(256), 0, c->cs, (const T*)c->dxl, dy, idx, cnt, H);
+      hipLaunchKernelGGL((rows_by_index_kernel<T, true>), dim3((rows + 3) / 4), dim3(256), 0, c->cs, (const T*)c->dxl, (T*)dy_out,
+                         idx, cnt, H);
     }));
     // dE += dz^T Xl ; dbv += colsum(dz)
-    GemmArgs w = gemm_args(V, H, Tn, c->dz, Vp, 0, c->xl, H, 0, c->egacc + eo[E_E], H);
+    GemmArgs w = gemm_args(V, H, rows, c->dz, Vp, 0, c->xl, H, 0, c->egacc + eo[E_E], H);
     w.epi = EPI_ACCUM; w.k_dev = cnt;
     L2L_TRY(gemm(c, dt, true, w, 0, L2L_PROF_OTHER));
-    L2L_TRY(bias_grad<T>(c, c->dz, Vp, c->egacc + eo[E_BV], Tn, V, cnt));
+    L2L_TRY(bias_grad<T>(c, c->dz, Vp, c->egacc + eo[E_BV], rows, V, cnt));
   }
   return L2L_OK;
 }
@@ -740,10 +751,15 @@ int l2l_create(const l2l_config* cfg, void* compute_stream, void* copy_stream, l
     L2L_TRY(dev_alloc(c, (void**)&c->lab_idx, UT * 4));
     L2L_TRY(dev_alloc(c, (void**)&c->lab_cnt, (cfg->num_ubatches + 1) * 4));
     c->lab_total = c->lab_cnt + cfg->num_ubatches;
-    L2L_TRY(dev_alloc(c, &c->xl, c->T * H * es));
-    L2L_TRY(dev_alloc(c, &c->dxl, c->T * H * es));
-    L2L_TRY(dev_alloc(c, (void**)&c->logits, c->T * c->Vp * 4));
-    L2L_TRY(dev_alloc(c, &c->dz, c->T * c->Vp * es));
+    c->head_rows = std::min<long long>(UT, 8192);
+    if (const char* e = getenv("L2L_HEAD_ROWS"))   // smaller passes, for tests of the multi-pass path
+      if (atoll(e) > 0) c->head_rows = std::min<long long>(UT, atoll(e));
+    L2L_TRY(dev_alloc(c, (void**)&c->lab_gidx, UT * 4));
+    L2L_TRY(dev_alloc(c, (void**)&c->chunk_cnt, ((UT + c->head_rows - 1) / c->head_rows) * 4));
+    L2L_TRY(dev_alloc(c, &c->xl, c->head_rows * H * es));
+    L2L_TRY(dev_alloc(c, &c->dxl, c->head_rows * H * es));
+    L2L_TRY(dev_alloc(c, (void**)&c->logits, c->head_rows * c->Vp * 4));
+    L2L_TRY(dev_alloc(c, &c->dz, c->head_rows * c->Vp * es));
     HIP_TRY(c, hipEventCreateWithFlags(&c->emb_staged_ev, hipEventDisableTiming));
     HIP_TRY(c, hipEventCreateWithFlags(&c->emb_released_ev, hipEventDisableTiming));
     HIP_TRY(c, hipEventCreateWithFlags(&c->egacc_ready, hipEventDisableTiming));

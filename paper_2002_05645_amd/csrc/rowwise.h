@@ -261,6 +261,24 @@ __global__ __launch_bounds__(256) void label_compact_kernel(const int32_t* label
     if (lab[i] >= 0) idx[(long long)u * T + o++] = i;
 }
 
+// Joins the per-micro-batch lists into one list over the whole mini-batch: gidx[prefix(u) + i] =
+// u * T + idx[u * T + i], and chunk_cnt[c] = how many entries of that list fall into rows
+// [c * chunk, (c + 1) * chunk).  One block per micro-batch.
+__global__ __launch_bounds__(256) void label_merge_kernel(const int32_t* idx, const int32_t* cnt, int T, int32_t* gidx,
+                                                          int32_t* chunk_cnt, int chunk, int nchunks) {
+  const int u = blockIdx.x, t = threadIdx.x;
+  int before = 0, total = 0;
+  for (int v = 0; v < (int)gridDim.x; ++v) {
+    const int n = cnt[v];
+    if (v < u) before += n;
+    total += n;
+  }
+  const int mine = cnt[u];
+  for (int i = t; i < mine; i += 256) gidx[before + i] = u * T + idx[(long long)u * T + i];
+  if (u == 0)
+    for (int c = t; c < nchunks; c += 256) chunk_cnt[c] = max(0, min(chunk, total - c * chunk));
+}
+
 // dst[i,:] = src[idx[i],:] (gather) or dst[idx[i],:] = src[i,:] (SCATTER) for i < *cnt; wave per row.
 template <typename T, bool SCATTER>
 __global__ __launch_bounds__(256) void rows_by_index_kernel(const T* src, T* dst, const int32_t* idx, const int32_t* cnt,

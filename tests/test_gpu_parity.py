@@ -328,6 +328,15 @@ def test_step_tiny_fp32_host_stash():
     _assert_errs({k: v for k, v in errs.items() if not k.startswith("adam.")}, TOL["fp32"])
 
 
+@pytest.mark.parametrize("head_rows,label_prob", [(5, 1.0), (64, 1.0), (64, 0.3)])
+def test_step_head_in_several_passes(monkeypatch, head_rows, label_prob):
+    # the head takes the labelled rows of the mini-batch head_rows at a time: full passes, a ragged last
+    # one, and (label_prob < 1) passes past the labelled count that must do nothing
+    monkeypatch.setenv("L2L_HEAD_ROWS", str(head_rows))
+    errs, _, _ = _step_case(S.WORKLOADS[0].scaled(label_prob=label_prob))
+    _assert_errs({k: v for k, v in errs.items() if not k.startswith("adam.")}, TOL["fp32"])
+
+
 def test_step_bf16_small_depth():
     # BERT-Base widths, 3 layers, fewer rows; 15% random labels
     w = S.WORKLOADS[1].scaled(layers=3, ubatch=2, num_ubatches=3, vocab=3000)
