@@ -56,28 +56,40 @@ __device__ __forceinline__ float gelu_grad_f(float u) {
   return 0.5f * (1.0f + erff(u * 0.70710678118654752f)) + u * __expf(-0.5f * u * u) * 0.39894228040143268f;
 }
 
-// Cheaper forms for the bf16 path, whose results are rounded to bf16 anyway: erf by the rational
-// approximation erf(x) = 1 - (a1 t + ... + a5 t^5) exp(-x^2), t = 1 / (1 + p x), x >= 0 (Abramowitz and
-// Stegun 7.1.26, absolute error below 1.5e-7).  phi_out receives exp(-u^2 / 2), which the derivative needs.
-__device__ __forceinline__ float erf_as(float x, float& e) {
-  const float ax = fabsf(x);
-  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.0f));
-  float p = fmaf(1.061405429f, t, -1.453152027f);
-  p = fmaf(p, t, 1.421413741f);
-  p = fmaf(p, t, -0.284496736f);
-  p = fmaf(p, t, 0.254829592f);
-  e = __expf(-ax * ax);
-  const float r = 1.0f - p * t * e;
-  return copysignf(r, x);
-}
+// Cheaper forms for the bf16 path, whose results are rounded to bf16 (relative step 2^-8) anyway: no
+// transcendental instructions, one odd polynomial each, fitted (minimax, in s = u / a) to the exact
+// functions on [-a, a] with the value at s = 1 pinned to the limit (P(1) = Q(1) = 1/2); outside, u is
+// clamped to the interval, so the tails are 0 and 1 to fp32 rounding (the true functions are within the
+// fit's error of those limits there).
+//   Phi(u) = 1/2 (1 + erf(u / sqrt 2)) = 1/2 + s P(s^2),  a = 4,   |error| < 4e-5
+//   gelu'(u) = Phi(u) + u phi(u)      = 1/2 + s Q(s^2),  a = 4.5, |error| < 2e-4 (fp32 rounding of Q included)
 __device__ __forceinline__ float gelu_fast_f(float u) {
-  float e;
-  return 0.5f * u * (1.0f + erf_as(u * 0.70710678118654752f, e));
+  const float s = __builtin_amdgcn_fmed3f(u, -4.0f, 4.0f) * 0.25f;
+  const float t = s * s;
+  float p = -1.372012435e+00f;
+  p = fmaf(p, t, 7.008298544e+00f);
+  p = fmaf(p, t, -1.555825966e+01f);
+  p = fmaf(p, t, 1.997211423e+01f);
+  p = fmaf(p, t, -1.672855746e+01f);
+  p = fmaf(p, t, 9.811292493e+00f);
+  p = fmaf(p, t, -4.228097766e+00f);
+  p = fmaf(p, t, 1.595222051e+00f);
+  return u * fmaf(p, s, 0.5f);
 }
 __device__ __forceinline__ float gelu_grad_fast_f(float u) {
-  float e;
-  const float cdf = 0.5f * (1.0f + erf_as(u * 0.70710678118654752f, e));
-  return fmaf(u * e, 0.39894228040143268f, cdf);
+  const float s = __builtin_amdgcn_fmed3f(u, -4.5f, 4.5f) * (1.0f / 4.5f);
+  const float t = s * s;
+  float p = -6.218507148e+01f;
+  p = fmaf(p, t, 3.462898774e+02f);
+  p = fmaf(p, t, -8.493878126e+02f);
+  p = fmaf(p, t, 1.214708786e+03f);
+  p = fmaf(p, t, -1.132123153e+03f);
+  p = fmaf(p, t, 7.287199075e+02f);
+  p = fmaf(p, t, -3.336748434e+02f);
+  p = fmaf(p, t, 1.087429044e+02f);
+  p = fmaf(p, t, -2.418076579e+01f);
+  p = fmaf(p, t, 3.590171402e+00f);
+  return fmaf(p, s, 0.5f);
 }
 
 // Epilogue flags of the GEMM kernels.

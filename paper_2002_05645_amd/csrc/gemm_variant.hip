@@ -54,6 +54,7 @@ void launch_direct_one(const GemmArgs& g, hipStream_t s, int splits) {
 template <int BM, int BN, int WM, int WN, typename TC>
 void launch_direct(const GemmArgs& g, hipStream_t s, int splits) {
   if (g.a_kc && g.b_kc) launch_direct_one<BM, BN, WM, WN, true, true, TC>(g, s, splits);
+  else if (g.a_kc) launch_direct_one<BM, BN, WM, WN, true, false, TC>(g, s, splits);
   else launch_direct_one<BM, BN, WM, WN, false, false, TC>(g, s, splits);
 }
 

@@ -271,7 +271,7 @@ void pick_tile(const GemmArgs& g, bool out_f32, int* variant, int* splits) {
   int v = 0;
   *splits = 1;
   const long long small = std::min(g.M, g.N);
-  const bool kc = g.a_kc == g.b_kc;   // both operands K-contiguous or both K-strided: loads go straight into LDS
+  const bool kc = g.a_kc || !g.b_kc;   // the direct-to-LDS kernel covers every layout pair but (A K-strided, B K-contiguous)
   if (small >= 256 && g.K >= 256) v = kc ? 6 : 3;
   else if (g.M >= 256 && g.N >= 128) v = kc ? 8 : 2;
   else if (g.N <= 64) v = 1;
@@ -306,7 +306,7 @@ int gemm(l2l_ctx* c, int dtype, bool out_f32, const GemmArgs& g, int impl = 0, i
       int v, splits;
       pick_tile(g, out_f32, &v, &splits);
       if (impl >= 100) v = impl - 100;
-      if (kTiles[v].direct && g.a_kc != g.b_kc) v = 3;   // direct-to-LDS variants exist for like layouts only
+      if (kTiles[v].direct && !g.a_kc && g.b_kc) v = 3;   // no direct-to-LDS kernel for A K-strided with B K-contiguous
       if (const char* e = getenv("L2L_FORCE_SPLITS")) g_force_splits = atoi(e);
       if (g_force_splits > 0 && out_f32 && g.epi == EPI_ACCUM) splits = g_force_splits;
       launch_mfma_variant(v, g, c->cs, splits, out_f32);

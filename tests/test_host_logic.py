@@ -127,3 +127,37 @@ def test_eps_adam_matches_oracle(threads):
     assert np.array_equal(e2.ship(0), e2.master(0))
     e.close()
     e2.close()
+
+
+# ------------------------------------------------------------------ polynomial GELU of the bf16 epilogues
+def _fast_form(name, a):
+    """Evaluates, in fp32 and in the kernel's order, the odd polynomial `name` of csrc/common.h on clamped u / a."""
+    import re
+    src = open(os.path.join(os.path.dirname(B.__file__), "csrc", "common.h")).read()
+    body = src[src.index("float " + name):]
+    body = body[:body.index("return")]
+    c = [np.float32(x) for x in re.findall(r"(-?\d\.\d+e[+-]\d+)f", body)]
+    assert len(c) >= 8
+
+    def f(u):
+        s = (np.clip(u, -a, a).astype(np.float32) * np.float32(1.0 / a)).astype(np.float32)
+        t = (s * s).astype(np.float32)
+        p = np.full_like(t, c[0])
+        for k in c[1:]:
+            p = (p * t + k).astype(np.float32)
+        return (p * s + np.float32(0.5)).astype(np.float32)
+    return f
+
+
+def test_fast_gelu_polynomials_match_exact_functions():
+    # the bf16 GEMM epilogues use polynomial forms of Phi and gelu'; their error must stay far below the
+    # bf16 rounding step (2^-8 relative) of the values they produce
+    u = np.linspace(-20.0, 20.0, 800001).astype(np.float32)
+    u64 = u.astype(np.float64)
+    gelu = u * _fast_form("gelu_fast_f", 4.0)(u)
+    dgelu = _fast_form("gelu_grad_fast_f", 4.5)(u)
+    assert np.abs(gelu - O.gelu(u64)).max() < 2e-4
+    assert np.abs(dgelu - O.gelu_grad(u64)).max() < 3e-4
+    big = np.abs(u) > 6                                              # tails: the limits, to fp32 rounding
+    assert np.abs(gelu[big] - np.maximum(u[big], 0)).max() <= 1e-6 * 20
+    assert np.abs(dgelu[big] - (u[big] > 0)).max() <= 1e-5
