@@ -333,23 +333,43 @@ int ln_fwd(l2l_ctx* c, const void* x, const void* gamma, const void* beta, void*
 }
 
 template <typename T>
+int bias_grad(l2l_ctx* c, const void* a, long long lda, float* out, long long rows, int n, const int* rows_dev = nullptr);
+
+// LayerNorm backward: dx, dgamma, dbeta, and dbias = colsum(dx) (the bias in front of the LayerNorm)
+template <typename T>
 int ln_bwd(l2l_ctx* c, const void* dy, const void* x, const float* mean, const float* rstd, const void* gamma, void* dx,
-           float* dgamma, float* dbeta, long long rows, int n) {
+           float* dgamma, float* dbeta, float* dbias, long long rows, int n) {
   if (rows <= 0) return L2L_OK;
+  if (n % 8 == 0 && n <= 2048) {   // one pass, column sums included
+    const int nch = n <= 512 ? 1 : n <= 1024 ? 2 : 4;
+    const size_t lds = (size_t)4 * 3 * nch * 512 * sizeof(float);
+    return timed(c, L2L_PROF_ROWWISE, 0, 3.0 * rows * n * sizeof(T), [&] {
+      const dim3 grid((unsigned)((rows + LNF_ROWS - 1) / LNF_ROWS));
+      auto go = [&](auto kern) {
+        static_cast<void>(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        hipLaunchKernelGGL(kern, grid, dim3(256), lds, c->cs, (const T*)dy, (const T*)x, mean, rstd, (const T*)gamma, (T*)dx,
+                           dgamma, dbeta, dbias, (int)rows, n);
+      };
+      if (nch == 1) go(ln_bwd_fused_kernel<T, 1>);
+      else if (nch == 2) go(ln_bwd_fused_kernel<T, 2>);
+      else go(ln_bwd_fused_kernel<T, 4>);
+    });
+  }
   L2L_TRY(timed(c, L2L_PROF_ROWWISE, 0, 3.0 * rows * n * sizeof(T), [&] {
     hipLaunchKernelGGL(ln_bwd_dx_kernel<T>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, c->cs, (const T*)dy, (const T*)x,
                        mean, rstd, (const T*)gamma, (T*)dx, (int)rows, n);
   }));
-  return timed(c, L2L_PROF_COLSUM, 0, 2.0 * rows * n * sizeof(T), [&] {
+  L2L_TRY(timed(c, L2L_PROF_COLSUM, 0, 2.0 * rows * n * sizeof(T), [&] {
     dim3 grid((n + 127) / 128, (unsigned)((rows + COLSUM_ROWS - 1) / COLSUM_ROWS));
     hipLaunchKernelGGL((colsum_kernel<T, 1>), grid, dim3(256), 0, c->cs, (const T*)dy, (long long)n, (const T*)x, mean, rstd,
                        (const int32_t*)nullptr, (const T*)nullptr, (const T*)nullptr, 0, dgamma, dbeta, (int)rows, n,
                        (const int*)nullptr);
-  });
+  }));
+  return bias_grad<T>(c, dx, n, dbias, rows, n);
 }
 
 template <typename T>
-int bias_grad(l2l_ctx* c, const void* a, long long lda, float* out, long long rows, int n, const int* rows_dev = nullptr) {
+int bias_grad(l2l_ctx* c, const void* a, long long lda, float* out, long long rows, int n, const int* rows_dev) {
   if (rows <= 0) return L2L_OK;
   return timed(c, L2L_PROF_COLSUM, 0, 1.0 * rows * n * sizeof(T), [&] {
     dim3 grid((n + 127) / 128, (unsigned)((rows + COLSUM_ROWS - 1) / COLSUM_ROWS));
@@ -496,8 +516,8 @@ int layer_backward_group(l2l_ctx* c, const void* params, const void* x, void* dy
   const float alpha = 1.0f / sqrtf((float)d);
 
   // LN2 backward
-  L2L_TRY(ln_bwd<T>(c, dydx, c->r2, c->mean2, c->rstd2, P + off[T_G2], c->dr2, G + off[T_G2], G + off[T_BE2], M, H));
-  // FFN2 backward: dU1 = (dR2 W2^T) * gelu'(U1); dW2 += G^T dR2; db2 += colsum(dR2)
+  L2L_TRY(ln_bwd<T>(c, dydx, c->r2, c->mean2, c->rstd2, P + off[T_G2], c->dr2, G + off[T_G2], G + off[T_BE2], G + off[T_B2], M, H));
+  // FFN2 backward: dU1 = (dR2 W2^T) * gelu'(U1); dW2 += G^T dR2 (db2 came with LN2's backward)
   {
     GemmArgs g = gemm_args((int)M, F, H, c->dr2, H, 1, P + off[T_W2], H, 1, c->du1, F);
     g.epi = EPI_GELUGRAD; g.aux = c->u1; g.ldaux = F;
@@ -505,7 +525,6 @@ int layer_backward_group(l2l_ctx* c, const void* params, const void* x, void* dy
     GemmArgs w = gemm_args(F, H, (int)M, c->ga, F, 0, c->dr2, H, 0, G + off[T_W2], H);
     w.epi = EPI_ACCUM;
     L2L_TRY(gemm(c, dt, true, w));
-    L2L_TRY(bias_grad<T>(c, c->dr2, H, G + off[T_B2], M, H));
   }
   // FFN1 backward: dY1 = dR2 + dU1 W1^T; dW1 += Y1^T dU1; db1 += colsum(dU1)
   {
@@ -518,7 +537,7 @@ int layer_backward_group(l2l_ctx* c, const void* params, const void* x, void* dy
     L2L_TRY(bias_grad<T>(c, c->du1, F, G + off[T_B1], M, F));
   }
   // LN1 backward
-  L2L_TRY(ln_bwd<T>(c, c->dy1, c->r1, c->mean1, c->rstd1, P + off[T_G1], c->dr1, G + off[T_G1], G + off[T_BE1], M, H));
+  L2L_TRY(ln_bwd<T>(c, c->dy1, c->r1, c->mean1, c->rstd1, P + off[T_G1], c->dr1, G + off[T_G1], G + off[T_BE1], G + off[T_BO], M, H));
   // output projection backward
   {
     GemmArgs g = gemm_args((int)M, H, H, c->dr1, H, 1, P + off[T_WO], H, 1, c->dc, H);
@@ -526,7 +545,6 @@ int layer_backward_group(l2l_ctx* c, const void* params, const void* x, void* dy
     GemmArgs w = gemm_args(H, H, (int)M, c->c, H, 0, c->dr1, H, 0, G + off[T_WO], H);
     w.epi = EPI_ACCUM;
     L2L_TRY(gemm(c, dt, true, w));
-    L2L_TRY(bias_grad<T>(c, c->dr1, H, G + off[T_BO], M, H));
   }
   // attention backward per (sequence, head)
   if (fused_attention_ok(c)) {

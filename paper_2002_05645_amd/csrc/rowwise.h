@@ -129,6 +129,86 @@ __global__ __launch_bounds__(256) void ln_bwd_dx_kernel(const T* dy, const T* x,
              [out](int j, const float v[8]) { store8(out + j, v); });
 }
 
+// LayerNorm backward with its three column reductions in the same pass: dx as above, and
+//   dgamma[j] += sum_r dy[r,j] xhat[r,j],  dbeta[j] += sum_r dy[r,j],  dbias[j] += sum_r dx[r,j]
+// (dbias: the bias of the linear layer whose output, plus a residual, this LayerNorm normalises).  A block
+// takes LNF_ROWS rows, a wave one row at a time; a lane owns columns lane * 8 + 512 k, k < NCH, keeps
+// the row's values in registers between the two passes and the column sums in registers across rows;
+// the four waves' sums are combined in LDS and leave as one fp32 atomic per column and block.
+constexpr int LNF_ROWS = 64;   // measured best of 16 .. 128 at 32768 x 1024: fewer rows mean more atomics, more mean fewer waves
+template <typename T, int NCH>
+__global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* dy, const T* x, const float* mean, const float* rstd,
+                                                           const T* gamma, T* dx, float* dgamma, float* dbeta,
+                                                           float* dbias, int rows, int n) {
+  extern __shared__ float lnf_red[];   // [4 waves][3][NCH * 512]
+  constexpr int NC = NCH * 512;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  float sg[NCH][8], sb[NCH][8], sx[NCH][8], gam[NCH][8];
+#pragma unroll
+  for (int k = 0; k < NCH; ++k) {
+    const int j = lane * 8 + k * 512;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sg[k][i] = sb[k][i] = sx[k][i] = gam[k][i] = 0.f;
+    if (j < n) load8(gamma + j, gam[k]);
+  }
+  const int r0 = blockIdx.x * LNF_ROWS, r1 = min(rows, r0 + LNF_ROWS);
+  for (int r = r0 + w; r < r1; r += 4) {
+    const float mu = mean[r], rs = rstd[r];
+    float xh[NCH][8], d[NCH][8];
+    float c1 = 0.f, c2 = 0.f;
+#pragma unroll
+    for (int k = 0; k < NCH; ++k) {
+      const int j = lane * 8 + k * 512;
+      if (j < n) {
+        load8(x + (long long)r * n + j, xh[k]);
+        load8(dy + (long long)r * n + j, d[k]);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          xh[k][i] = (xh[k][i] - mu) * rs;
+          const float gg = d[k][i] * gam[k][i];
+          c1 += gg;
+          c2 += gg * xh[k][i];
+        }
+      }
+    }
+    c1 = wave_sum(c1) / n;
+    c2 = wave_sum(c2) / n;
+#pragma unroll
+    for (int k = 0; k < NCH; ++k) {
+      const int j = lane * 8 + k * 512;
+      if (j < n) {
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          v[i] = rs * (d[k][i] * gam[k][i] - c1 - xh[k][i] * c2);
+          sg[k][i] += d[k][i] * xh[k][i];
+          sb[k][i] += d[k][i];
+          sx[k][i] += v[i];
+        }
+        store8(dx + (long long)r * n + j, v);
+      }
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < NCH; ++k) {
+    float* p = lnf_red + (w * 3) * NC + k * 512 + lane * 8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      p[i] = sg[k][i];
+      p[NC + i] = sb[k][i];
+      p[2 * NC + i] = sx[k][i];
+    }
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < 3 * NC; idx += 256) {
+    const int which = idx / NC, col = idx % NC;
+    if (col < n) {
+      const float s = lnf_red[idx] + lnf_red[3 * NC + idx] + lnf_red[6 * NC + idx] + lnf_red[9 * NC + idx];
+      atomicAdd((which == 0 ? dgamma : which == 1 ? dbeta : dbias) + col, s);
+    }
+  }
+}
+
 // Embedding backward: dr through LN_e, scatter-added (fp32 atomics) into dE[tok] and dPpos[s].
 template <typename T>
 __global__ __launch_bounds__(256) void embed_bwd_kernel(const int32_t* tokens, const T* E, const T* pos, const T* gamma,
