@@ -22,8 +22,8 @@ cpu-baseline leg of the benchmark may import it.
 
 Pins (tests/test_oracle_*.py): central finite differences for every backward
 formula, Algorithm 1 == Algorithm 2 == one concatenated minibatch, closed
-forms for softmax / LayerNorm / GELU / cross-entropy / Adam, exhaustive bf16
-round trip.  Unpinned: end-to-end task accuracy against the paper's Table 7
+forms for softmax / LayerNorm / GELU / cross-entropy / Adam / LAMB (plus LAMB's
+step-length and scale invariances), exhaustive bf16 round trip.  Unpinned: end-to-end task accuracy against the paper's Table 7
 (needs the GLUE data and pretrained weights) -- parity unpinned.
 """
 from __future__ import annotations
@@ -307,6 +307,24 @@ def adam_step(w, g, m, v, t, lr=1e-4, beta1=0.9, beta2=0.999, eps_a=1e-8):
     mhat = m / (1.0 - beta1 ** t)
     vhat = v / (1.0 - beta2 ** t)
     return w - lr * mhat / (np.sqrt(vhat) + eps_a), m, v
+
+
+def lamb_step(w, g, m, v, t, lr=1e-3, beta1=0.9, beta2=0.999, eps_a=1e-6, weight_decay=0.0):
+    """One LAMB update of ONE parameter tensor (the optimizer Table 1 names; the update rule is the one of
+    the LAMB publication the paper cites, with bias correction and the identity scaling function):
+        m, v as in Adam;  r = mhat / (sqrt(vhat) + eps);  u = r + weight_decay * w;
+        trust = ||w|| / ||u|| (1 where either norm is zero);  w <- w - lr * trust * u.
+    The norms are over the whole tensor, which is why the host EPS, holding each layer's tensors whole,
+    can apply it layer by layer.  Returns (w, m, v)."""
+    m = beta1 * m + (1.0 - beta1) * g
+    v = beta2 * v + (1.0 - beta2) * g * g
+    mhat = m / (1.0 - beta1 ** t)
+    vhat = v / (1.0 - beta2 ** t)
+    u = mhat / (np.sqrt(vhat) + eps_a) + weight_decay * w
+    wn = float(np.sqrt(np.sum(np.square(w, dtype=np.float64))))
+    un = float(np.sqrt(np.sum(np.square(u, dtype=np.float64))))
+    trust = wn / un if (wn > 0.0 and un > 0.0) else 1.0
+    return w - lr * trust * u, m, v
 
 
 def bf16_bits(x):

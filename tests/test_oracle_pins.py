@@ -290,6 +290,40 @@ def test_adam_closed_forms():
     np.testing.assert_allclose(v2, (1 - 0.999 ** 2) * g * g, rtol=1e-12)
 
 
+def test_lamb_closed_forms_and_invariants():
+    rng = np.random.default_rng(7)
+    n = 257
+    w = rng.normal(size=n)
+    g = rng.normal(size=n)
+    z = np.zeros(n)
+    lr = 2e-3
+    # first step, no decay, eps -> 0: r = sign(g), ||u|| = sqrt(n), so w' = w - lr ||w|| sign(g) / sqrt(n)
+    w1, m1, v1 = O.lamb_step(w, g, z, z, 1, lr=lr, eps_a=1e-30, weight_decay=0.0)
+    np.testing.assert_allclose(w1, w - lr * np.linalg.norm(w) * np.sign(g) / np.sqrt(n), rtol=1e-12, atol=1e-15)
+    # the moments are Adam's
+    _, ma, va = O.adam_step(w, g, z, z, 1)
+    np.testing.assert_array_equal(m1, ma)
+    np.testing.assert_array_equal(v1, va)
+    # without decay every step moves the tensor by exactly lr ||w||, whatever the gradient's scale
+    for scale in (1e-3, 1.0, 1e3):
+        w2, _, _ = O.lamb_step(w1, scale * rng.normal(size=n), m1, v1, 2, lr=lr, eps_a=1e-30)
+        np.testing.assert_allclose(np.linalg.norm(w2 - w1), lr * np.linalg.norm(w1), rtol=1e-10)
+    # scaling the whole gradient history leaves the update unchanged (eps -> 0)
+    wa, _, _ = O.lamb_step(w, g, z, z, 1, lr=lr, eps_a=1e-30, weight_decay=0.01)
+    wb, _, _ = O.lamb_step(w, 50.0 * g, z, z, 1, lr=lr, eps_a=1e-30, weight_decay=0.01)
+    np.testing.assert_allclose(wa, wb, rtol=1e-12)
+    # a zero tensor has trust ratio 1: the step is Adam's
+    wz, _, _ = O.lamb_step(z, g, z, z, 1, lr=lr, eps_a=1e-8)
+    wad, _, _ = O.adam_step(z, g, z, z, 1, lr=lr, eps_a=1e-8)
+    np.testing.assert_allclose(wz, wad, rtol=1e-14)
+    # zero gradient and no decay: nothing moves
+    w0, m0, v0 = O.lamb_step(w, z, z, z, 1, lr=lr)
+    np.testing.assert_array_equal(w0, w)
+    # decay alone (zero gradient): u = lambda w, trust = 1 / lambda, so w' = (1 - lr) w
+    wd, _, _ = O.lamb_step(w, z, z, z, 1, lr=lr, weight_decay=0.1)
+    np.testing.assert_allclose(wd, (1 - lr) * w, rtol=1e-12)
+
+
 def test_bf16_exhaustive_round_trip_and_ties():
     bits = np.arange(65536, dtype=np.uint16)
     f = O.bf16_to_f32(bits)
