@@ -59,6 +59,8 @@ def main():
                     help="also run one plain 256 MiB device copy (a known-size dispatch for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--tail-adam", action="store_true",
                     help="run the host Adam after all gradients arrived instead of eagerly per layer during backward")
+    ap.add_argument("--optimizer", default="adam", choices=["adam", "lamb"],
+                    help="host optimizer (lamb: per-tensor trust ratio, learning rate 1e-3, weight decay 0.01 on matrices)")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -72,7 +74,8 @@ def main():
         w = w.scaled(layers=a.layers)
     tr = L2LTrainer(layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, vocab=w.vocab,
                     ubatch=w.ubatch, num_ubatches=w.num_ubatches, dtype=w.dtype, ubatch_group=a.group, stash=a.stash,
-                    eager=not a.tail_adam)
+                    eager=not a.tail_adam, optimizer=a.optimizer,
+                    **(dict(lr=1e-3, eps_a=1e-6, weight_decay=0.01) if a.optimizer == "lamb" else {}))
     tr.load_params(S.embed_params(w), [S.layer_params(w, l) for l in range(w.layers)])
     tok, lab = S.tokens_and_labels(w)
     tok, lab = torch.from_numpy(tok).cuda(), torch.from_numpy(lab).cuda()
@@ -125,7 +128,7 @@ def main():
         "config": {"workload": f"{w.name}: L={w.layers} H={w.hidden} A={w.heads} F={w.ffn} S={w.seq} V={w.vocab} "
                                f"U={w.num_ubatches} x ub={w.ubatch}", "stash": a.stash, "ubatch_group": tr.ctx.cfg.ubatch_group,
                    "device_pipeline_samples_per_s": samples * a.steps / dev_s, "device_pipeline_ms": 1e3 * dev_s / a.steps,
-                   "host_adam_exposed_ms": 1e3 * adam_s / a.steps, "eps": "tail" if a.tail_adam else "eager", "loss_first": loss0, "loss_last": loss, "losses": [round(x, 4) for x in losses],
+                   "host_adam_exposed_ms": 1e3 * adam_s / a.steps, "eps": "tail" if a.tail_adam else "eager", "optimizer": a.optimizer, "loss_first": loss0, "loss_last": loss, "losses": [round(x, 4) for x in losses],
                    "peak_device_bytes": int(peak_mem), "ctx_device_bytes": int(tr.ctx.device_bytes()),
                    "instrumented_ms_per_step": 1e3 * prof_total_s / a.steps},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",

@@ -194,6 +194,17 @@ int   eps_refresh_ship(eps_store*, int first, int last);
 /* One bias-corrected Adam step (no weight decay) on blocks [first, last] from their landing
    buffers, then refreshes their shipping copies.  t >= 1 is the step number. */
 int   eps_adam_step(eps_store*, int first, int last, int t, double lr, double beta1, double beta2, double eps_a);
+/* One LAMB step (the optimizer of Table 1; update rule of the LAMB publication the paper cites, with
+   bias correction): per tensor, u = mhat / (sqrt(vhat) + eps_a) + weight_decay * w and
+   w -= lr * (||w|| / ||u||) * u, the ratio taken as 1 where either norm is zero.  The tensors of a
+   block are the n_seg element ranges [seg_begin[i], seg_end[i]) (host arrays, the same for every block
+   in [first, last]; elements outside every range, i.e. the packing's padding, are left alone).
+   seg_decay[i] scales weight_decay for range i (null: 1 for all; pass 0 for biases and LayerNorm
+   parameters to exempt them).  Norms are accumulated in double.  Refreshes the shipping copies.
+   L2L_E_ARG on overlapping, unordered or out-of-range segments. */
+int   eps_lamb_step(eps_store*, int first, int last, int t, double lr, double beta1, double beta2, double eps_a,
+                    double weight_decay, int n_seg, const long long* seg_begin, const long long* seg_end,
+                    const double* seg_decay);
 size_t eps_host_bytes(const eps_store*);
 /* 1 if the shipping and landing buffers are pinned (a GPU was visible at eps_create), else 0: without
    a GPU the store still works as host logic on ordinary memory. */

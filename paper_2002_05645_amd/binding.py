@@ -81,6 +81,8 @@ _SIGS = {
     "eps_moment": (C.POINTER(C.c_float), [_P, C.c_int, C.c_int]),
     "eps_refresh_ship": (C.c_int, [_P, C.c_int, C.c_int]),
     "eps_adam_step": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_double, C.c_double, C.c_double, C.c_double]),
+    "eps_lamb_step": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_double, C.c_double, C.c_double, C.c_double, C.c_double,
+                                C.c_int, C.POINTER(C.c_longlong), C.POINTER(C.c_longlong), C.POINTER(C.c_double)]),
     "eps_host_bytes": (C.c_size_t, [_P]),
     "eps_is_pinned": (C.c_int, [_P]),
 }
@@ -283,6 +285,18 @@ class EPS:
         rc = lib().eps_adam_step(self._h, first, last, t, lr, beta1, beta2, eps_a)
         if rc != L2L_OK:
             raise L2LError(rc, "eps_adam_step")
+
+    def lamb_step(self, first, last, t, segments, lr=1e-3, beta1=0.9, beta2=0.999, eps_a=1e-6, weight_decay=0.0,
+                  decay_mask=None):
+        """segments: [(begin, end)] element ranges of the tensors inside each of the blocks [first, last];
+        decay_mask: per-segment factor on weight_decay (None: 1 everywhere)."""
+        n = len(segments)
+        b = (C.c_longlong * n)(*[int(s[0]) for s in segments])
+        e = (C.c_longlong * n)(*[int(s[1]) for s in segments])
+        d = None if decay_mask is None else (C.c_double * n)(*[float(x) for x in decay_mask])
+        rc = lib().eps_lamb_step(self._h, first, last, t, lr, beta1, beta2, eps_a, weight_decay, n, b, e, d)
+        if rc != L2L_OK:
+            raise L2LError(rc, "eps_lamb_step")
 
     def host_bytes(self):
         return lib().eps_host_bytes(self._h)

@@ -237,4 +237,63 @@ int eps_adam_step(eps_store* e, int first, int last, int t, double lr_d, double 
   return L2L_OK;
 }
 
+int eps_lamb_step(eps_store* e, int first, int last, int t, double lr_d, double beta1_d, double beta2_d, double eps_a_d,
+                  double weight_decay, int n_seg, const long long* seg_begin, const long long* seg_end,
+                  const double* seg_decay) {
+  if (!e || first < 0 || last >= (int)e->blocks.size() || first > last || t < 1) return L2L_E_ARG;
+  if (n_seg < 0 || (n_seg > 0 && (!seg_begin || !seg_end))) return L2L_E_ARG;
+  for (int i = first; i <= last; ++i) {
+    long long prev = 0;
+    for (int s = 0; s < n_seg; ++s) {
+      if (seg_begin[s] < prev || seg_end[s] < seg_begin[s] || (size_t)seg_end[s] > e->blocks[i].n) return L2L_E_ARG;
+      prev = seg_end[s];
+    }
+  }
+  const float beta1 = (float)beta1_d, beta2 = (float)beta2_d, eps_a = (float)eps_a_d;
+  const float omb1 = (float)(1.0 - beta1_d), omb2 = (float)(1.0 - beta2_d);
+  const float c1 = (float)(1.0 / (1.0 - std::pow(beta1_d, t)));
+  const float c2 = (float)(1.0 / (1.0 - std::pow(beta2_d, t)));
+  std::mutex sum_mu;
+  for (int i = first; i <= last; ++i) {
+    const Block& b = e->blocks[i];
+    for (int s = 0; s < n_seg; ++s) {
+      const size_t s0 = (size_t)seg_begin[s], len = (size_t)(seg_end[s] - seg_begin[s]);
+      if (len == 0) continue;
+      const float wd = (float)(weight_decay * (seg_decay ? seg_decay[s] : 1.0));
+      float* __restrict w = b.w + s0;
+      float* __restrict m = b.m + s0;
+      float* __restrict v = b.v + s0;
+      const float* __restrict g = b.grad + s0;
+      // pass 1: moments, and the two norms of the tensor (u is formed again in pass 2: w has not moved yet)
+      double wn2 = 0.0, un2 = 0.0;
+      e->pool->run(len, [&](size_t lo, size_t hi) {
+        double a = 0.0, c = 0.0;
+        for (size_t k = lo; k < hi; ++k) {
+          const float gk = g[k];
+          const float mk = beta1 * m[k] + omb1 * gk;
+          const float vk = beta2 * v[k] + omb2 * gk * gk;
+          m[k] = mk;
+          v[k] = vk;
+          const float u = (mk * c1) / (std::sqrt(vk * c2) + eps_a) + wd * w[k];
+          a += (double)w[k] * w[k];
+          c += (double)u * u;
+        }
+        std::lock_guard<std::mutex> l(sum_mu);
+        wn2 += a;
+        un2 += c;
+      });
+      const double trust = (wn2 > 0.0 && un2 > 0.0) ? std::sqrt(wn2) / std::sqrt(un2) : 1.0;
+      const float step = (float)(lr_d * trust);
+      e->pool->run(len, [&](size_t lo, size_t hi) {
+        for (size_t k = lo; k < hi; ++k) {
+          const float u = (m[k] * c1) / (std::sqrt(v[k] * c2) + eps_a) + wd * w[k];
+          w[k] -= step * u;
+        }
+        ship_range(e, b, s0 + lo, s0 + hi);
+      });
+    }
+  }
+  return L2L_OK;
+}
+
 }  // extern "C"

@@ -32,8 +32,10 @@ def unpack(layout, shapes, flat) -> dict:
 class L2LTrainer:
     def __init__(self, *, layers, hidden, heads, ffn, seq, vocab, ubatch, num_ubatches, dtype="bf16",
                  ln_eps=1e-12, lr=1e-4, beta1=0.9, beta2=0.999, eps_a=1e-8, ubatch_group=0,
-                 eps_threads=0, stash="device", device="cuda:0", eager=False):
+                 eps_threads=0, stash="device", device="cuda:0", eager=False, optimizer="adam", weight_decay=0.0):
         assert stash in ("device", "host")
+        assert optimizer in ("adam", "lamb")
+        self.optimizer = optimizer
         self.L, self.H, self.S, self.V = layers, hidden, seq, vocab
         self.U, self.ub = num_ubatches, ubatch
         self.dtype = dtype
@@ -48,6 +50,15 @@ class L2LTrainer:
         self.layer_elems = B.lib().l2l_layer_packed_elems(self.cfg)
         self.embed_elems = B.lib().l2l_embed_packed_elems(self.cfg)
         self.eps = B.EPS([self.embed_elems] + [self.layer_elems] * layers, dtype, eps_threads)
+        if optimizer == "lamb":
+            # LAMB (Table 1's optimizer) works tensor by tensor: the tensors of a block, in packing order, with
+            # biases and LayerNorm parameters (everything that is not a matrix) exempt from weight decay
+            self.hp["weight_decay"] = weight_decay
+            def segs(layout, shapes):
+                names = sorted(layout, key=lambda k: layout[k][0])
+                return ([(layout[k][0], layout[k][0] + layout[k][1]) for k in names],
+                        [1.0 if len(shapes[k]) == 2 else 0.0 for k in names])
+            self._segs = {True: segs(self.embed_layout, self.embed_shapes()), False: segs(self.layer_layout, self.layer_shapes())}
         torch.cuda.set_device(self.device)
         self.compute = torch.cuda.Stream(device=self.device)
         self.copy = torch.cuda.Stream(device=self.device)
@@ -137,6 +148,18 @@ class L2LTrainer:
         c.embed_grad_drain(e.grad_ptr(0))
         self._after_drain(0)
 
+    def _eps_update(self, first, last, t):
+        if self.optimizer == "adam":
+            self.eps.adam_step(first, last, t, **self.hp)
+            return
+        if first == 0:                        # the embedding block has its own tensors
+            seg, mask = self._segs[True]
+            self.eps.lamb_step(0, 0, t, seg, decay_mask=mask, **self.hp)
+            first = 1
+        if first <= last:
+            seg, mask = self._segs[False]
+            self.eps.lamb_step(first, last, t, seg, decay_mask=mask, **self.hp)
+
     def _after_drain(self, block):
         if self.eager:
             self._landed[block].record(self.copy)
@@ -150,7 +173,7 @@ class L2LTrainer:
             block, t = item
             try:
                 self._landed[block].synchronize()
-                self.eps.adam_step(block, block, t, **self.hp)
+                self._eps_update(block, block, t)
             except Exception as ex:       # surfaced by optimizer_step
                 self._worker_error = ex
             finally:
@@ -187,7 +210,7 @@ class L2LTrainer:
             self.t += 1
             return
         self.t += 1
-        self.eps.adam_step(0, self.L, self.t, **self.hp)
+        self._eps_update(0, self.L, self.t)
 
     def step(self, tokens, labels) -> float:
         self.device_pipeline(tokens, labels)

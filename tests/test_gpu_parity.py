@@ -323,6 +323,41 @@ def test_three_training_steps_match_oracle_fp32():
         tr.close()
 
 
+@pytest.mark.parametrize("eager", [False, True])
+def test_two_lamb_steps_match_oracle_fp32(eager):
+    # LAMB on the host EPS, tensor by tensor, matrices decayed and vectors not; tail loop and eager per-layer update
+    w = S.WORKLOADS[0]
+    lr, wd = 2e-3, 0.01
+    tr = L2LTrainer(layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, vocab=w.vocab, ubatch=w.ubatch,
+                    num_ubatches=w.num_ubatches, dtype="fp32", lr=lr, eps_a=1e-6, eager=eager, eps_threads=4,
+                    optimizer="lamb", weight_decay=wd)
+    try:
+        emb = {k: v.astype(np.float64) for k, v in S.embed_params(w).items()}
+        layers = [{k: v.astype(np.float64) for k, v in S.layer_params(w, l).items()} for l in range(w.layers)]
+        start = [dict(b) for b in [emb] + layers]
+        tr.load_params(emb, layers)
+        tok, lab = S.tokens_and_labels(w)
+        tokd, labd = torch.from_numpy(tok).cuda(), torch.from_numpy(lab).cuda()
+        blocks = [emb] + layers
+        m = [{k: np.zeros_like(v) for k, v in b.items()} for b in blocks]
+        v2 = [{k: np.zeros_like(v) for k, v in b.items()} for b in blocks]
+        for t in range(1, 3):
+            loss = tr.step(tokd, labd)
+            loss_ref, gemb, gl = O.run_l2l(emb, layers, tok, lab, w.heads, 1e-12)
+            assert abs(loss - loss_ref) / abs(loss_ref) < 1e-4, (t, loss, loss_ref)
+            for b, g, mm, vv in zip(blocks, [gemb] + gl, m, v2):
+                for k in b:
+                    b[k], mm[k], vv[k] = O.lamb_step(b[k], g[k], mm[k], vv[k], t, lr=lr, eps_a=1e-6,
+                                                     weight_decay=wd if b[k].ndim == 2 else 0.0)
+        me, ml = tr.master_params()
+        for got, ref, s0 in zip([me] + ml, blocks, start):
+            for k in ref:
+                if np.any(ref[k] != s0[k]):
+                    assert O.rel_l2(got[k] - s0[k], ref[k] - s0[k]) < 2e-3, k
+    finally:
+        tr.close()
+
+
 def test_step_tiny_fp32_host_stash():
     errs, _, _ = _step_case(S.WORKLOADS[0], stash="host")
     _assert_errs({k: v for k, v in errs.items() if not k.startswith("adam.")}, TOL["fp32"])

@@ -129,6 +129,51 @@ def test_eps_adam_matches_oracle(threads):
     e2.close()
 
 
+@pytest.mark.parametrize("threads", [1, 5])
+def test_eps_lamb_matches_oracle_per_tensor(threads):
+    # three tensors of different size inside one block, with padding between them that must stay untouched
+    n = 200000
+    segs = [(0, 70001), (70016, 70016 + 999), (80000, 200000)]
+    mask = [1.0, 0.0, 1.0]
+    rng = np.random.default_rng(3)
+    w0 = rng.normal(size=n).astype(np.float32)
+    e = P.EPS([n, n], "bf16", threads)
+    e.master(0)[:] = w0
+    e.master(1)[:] = w0
+    e.refresh_ship()
+    w = w0.astype(np.float64)
+    m, v = np.zeros(n), np.zeros(n)
+    hp = dict(lr=2e-3, beta1=0.9, beta2=0.999, eps_a=1e-6, weight_decay=0.01)
+    for t in range(1, 4):
+        g = (rng.normal(size=n) * 10.0 ** rng.integers(-4, 1, size=n)).astype(np.float32)
+        e.grad(1)[:] = g
+        e.lamb_step(1, 1, t, segs, decay_mask=mask, **hp)
+        for (a, b), dm in zip(segs, mask):
+            w[a:b], m[a:b], v[a:b] = O.lamb_step(w[a:b], g[a:b].astype(np.float64), m[a:b], v[a:b], t, lr=hp["lr"],
+                                                 eps_a=hp["eps_a"], weight_decay=hp["weight_decay"] * dm)
+        np.testing.assert_allclose(e.master(1), w, rtol=3e-6, atol=1e-8)
+        np.testing.assert_allclose(e.moment(1, 1), v, rtol=1e-5, atol=1e-30)
+        assert np.array_equal(e.ship(1), O.bf16_bits(e.master(1)))
+    pad = np.ones(n, bool)
+    for a, b in segs:
+        pad[a:b] = False
+    assert np.array_equal(e.master(1)[pad], w0[pad])          # outside every tensor: untouched
+    assert np.array_equal(e.master(0), w0)                    # other block untouched
+    # without decay a step moves each tensor by lr * ||w||
+    e.master(0)[:] = w0
+    e.grad(0)[:] = rng.normal(size=n).astype(np.float32)
+    e.lamb_step(0, 0, 1, segs, lr=1e-2, weight_decay=0.0)
+    for a, b in segs:
+        np.testing.assert_allclose(np.linalg.norm(e.master(0)[a:b].astype(np.float64) - w0[a:b]),
+                                   1e-2 * np.linalg.norm(w0[a:b].astype(np.float64)), rtol=1e-4)
+    # malformed segment lists are rejected
+    for bad in ([(10, 5)], [(0, 100), (50, 200)], [(0, n + 1)]):
+        with pytest.raises(P.L2LError) as ex:
+            e.lamb_step(0, 0, 1, bad)
+        assert ex.value.code == P.L2L_E_ARG
+    e.close()
+
+
 # ------------------------------------------------------------------ polynomial GELU of the bf16 epilogues
 def _fast_form(name, a):
     """Evaluates, in fp32 and in the kernel's order, the odd polynomial `name` of csrc/common.h on clamped u / a."""
