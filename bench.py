@@ -59,6 +59,7 @@ def main():
                     help="also run one plain 256 MiB device copy (a known-size dispatch for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--tail-adam", action="store_true",
                     help="run the host Adam after all gradients arrived instead of eagerly per layer during backward")
+    ap.add_argument("--ubatches", type=int, default=0, help="override U, the number of micro-batches (sweeps of the paper's Tables 3 and 4)")
     ap.add_argument("--optimizer", default="adam", choices=["adam", "lamb"],
                     help="host optimizer (lamb: per-tensor trust ratio, learning rate 1e-3, weight decay 0.01 on matrices)")
     a = ap.parse_args()
@@ -72,6 +73,8 @@ def main():
     w = S.WORKLOADS[a.config]
     if a.layers:
         w = w.scaled(layers=a.layers)
+    if a.ubatches:
+        w = w.scaled(num_ubatches=a.ubatches)
     tr = L2LTrainer(layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, vocab=w.vocab,
                     ubatch=w.ubatch, num_ubatches=w.num_ubatches, dtype=w.dtype, ubatch_group=a.group, stash=a.stash,
                     eager=not a.tail_adam, optimizer=a.optimizer,

@@ -103,6 +103,16 @@ size_t l2l_device_bytes(const l2l_ctx*);
 const char* l2l_last_error(const l2l_ctx*);
 int  l2l_sync(l2l_ctx*);  /* host blocks until both streams are idle */
 
+/* A HIP stream whose kernels run on a subset of the compute units only: of every 32 consecutive bits of
+   the CU mask the first `cus_per_32` (1..32) are set, which spreads the subset over all XCDs whichever
+   way the runtime enumerates them.  Meant for the copy stream: on systems where the runtime moves
+   host<->device copies with a copy kernel, that kernel otherwise takes workgroup slots on every CU and
+   kernels launched while it runs wait for it (the transfers of Section 2.2 are supposed to hide behind
+   compute, not in front of it).  *out receives a hipStream_t; release it with l2l_stream_destroy.
+   L2L_E_ARG for a bad count or a null pointer, L2L_E_HIP if the runtime refuses. */
+int  l2l_stream_create_cu_masked(int cus_per_32, void** out);
+int  l2l_stream_destroy(void* stream);
+
 /* ---- the four calls of the relay (Algorithm 2; Section 2.1) -------------------------------------- */
 
 /* Param stage: asynchronous host->device copy, on copy_stream, of one layer's packed parameters

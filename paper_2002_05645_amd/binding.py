@@ -80,6 +80,8 @@ _SIGS = {
     "eps_grad": (C.POINTER(C.c_float), [_P, C.c_int]),
     "eps_moment": (C.POINTER(C.c_float), [_P, C.c_int, C.c_int]),
     "eps_refresh_ship": (C.c_int, [_P, C.c_int, C.c_int]),
+    "l2l_stream_create_cu_masked": (C.c_int, [C.c_int, C.POINTER(C.c_void_p)]),
+    "l2l_stream_destroy": (C.c_int, [C.c_void_p]),
     "eps_adam_step": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_double, C.c_double, C.c_double, C.c_double]),
     "eps_lamb_step": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_double, C.c_double, C.c_double, C.c_double, C.c_double,
                                 C.c_int, C.POINTER(C.c_longlong), C.POINTER(C.c_longlong), C.POINTER(C.c_double)]),
@@ -122,6 +124,21 @@ def embed_layout(cfg):
     return {L.l2l_embed_tensor_name(i).decode(): (L.l2l_embed_tensor_offset(C.byref(cfg), i),
                                                    L.l2l_embed_tensor_size(C.byref(cfg), i))
             for i in range(L.l2l_embed_tensor_count())}
+
+
+def stream_create_cu_masked(cus_per_32: int) -> int:
+    """hipStream_t (as an int) restricted to cus_per_32 of every 32 compute units; see include/l2l.h."""
+    out = C.c_void_p()
+    rc = lib().l2l_stream_create_cu_masked(cus_per_32, C.byref(out))
+    if rc != L2L_OK:
+        raise L2LError(rc, "l2l_stream_create_cu_masked")
+    return out.value
+
+
+def stream_destroy(handle: int):
+    rc = lib().l2l_stream_destroy(handle)
+    if rc != L2L_OK:
+        raise L2LError(rc, "l2l_stream_destroy")
 
 
 def _ptr(x):

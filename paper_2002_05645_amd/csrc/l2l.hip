@@ -674,7 +674,8 @@ int embed_bwd_t(l2l_ctx* c, const int32_t* tokens, const void* dy) {
   const long long* eo = c->lay.eoff;
   const int H = c->cfg.hidden, S = c->cfg.seq;
   L2L_TRY(timed(c, L2L_PROF_ROWWISE, 0, 0, [&] {
-    hipLaunchKernelGGL(embed_bwd_kernel<T>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, c->cs, tokens, E + eo[E_E], E + eo[E_P],
+    const unsigned nseq = (unsigned)(rows / S);
+    hipLaunchKernelGGL(embed_bwd_kernel<T>, dim3((unsigned)S * ((nseq + EMB_SEQS - 1) / EMB_SEQS)), dim3(256), (size_t)H * sizeof(float), c->cs, tokens, E + eo[E_E], E + eo[E_P],
                        E + eo[E_GE], (const T*)dy, c->emean, c->erstd, c->egacc + eo[E_E], c->egacc + eo[E_P], (int)rows, S, H);
   }));
   return timed(c, L2L_PROF_COLSUM, 0, 0, [&] {
@@ -976,6 +977,37 @@ int l2l_embed_drain_wait(l2l_ctx* c) {
   L2L_TRY(need_vocab(c, "l2l_embed_drain_wait"));
   if (c->egacc_state != 2) return fail(c, L2L_E_STATE, "l2l_embed_drain_wait: no drain in flight");
   HIP_TRY(c, hipEventSynchronize(c->egacc_landed));
+  return L2L_OK;
+}
+
+int l2l_stream_create_cu_masked(int cus_per_32, void** out) {
+  if (!out || cus_per_32 < 1 || cus_per_32 > 32) return L2L_E_ARG;
+  *out = nullptr;
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return L2L_E_HIP;
+  }
+  const int words = (prop.multiProcessorCount + 31) / 32;
+  std::vector<uint32_t> mask((size_t)words, cus_per_32 == 32 ? 0xFFFFFFFFu : ((1u << cus_per_32) - 1u));
+  hipStream_t s = nullptr;
+  const hipError_t err = hipExtStreamCreateWithCUMask(&s, (uint32_t)words, mask.data());
+  if (err != hipSuccess) {
+    fprintf(stderr, "l2l_stream_create_cu_masked: %s (%d CUs, %d mask words)\n", hipGetErrorString(err), prop.multiProcessorCount, words);
+    (void)hipGetLastError();
+    return L2L_E_HIP;
+  }
+  *out = (void*)s;
+  return L2L_OK;
+}
+
+int l2l_stream_destroy(void* stream) {
+  if (!stream) return L2L_E_ARG;
+  if (hipStreamDestroy((hipStream_t)stream) != hipSuccess) {
+    (void)hipGetLastError();
+    return L2L_E_HIP;
+  }
   return L2L_OK;
 }
 

@@ -210,25 +210,37 @@ __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* dy, const T*
 }
 
 // Embedding backward: dr through LN_e, scatter-added (fp32 atomics) into dE[tok] and dPpos[s].
+// A block takes one position s of EMB_SEQS consecutive sequences (a wave one row at a time), so that the
+// rows' contributions to dPpos[s] meet in LDS first and leave as one global atomic per column and block;
+// the token rows are scattered, their atomics go to memory directly.  Dynamic LDS: n floats.
+constexpr int EMB_SEQS = 16;
 template <typename T>
 __global__ __launch_bounds__(256) void embed_bwd_kernel(const int32_t* tokens, const T* E, const T* pos, const T* gamma,
                                                         const T* dy, const float* mean, const float* rstd, float* dE,
                                                         float* dpos, int rows, int S, int n) {
-  const int lane = threadIdx.x & 63;
-  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (r >= rows) return;
-  const long long tok = tokens[r];
-  const int s = r % S;
-  EmbedRow<T> row{E + tok * n, pos + (long long)s * n};
-  float* de = dE + tok * n;
-  float* dp = dpos + (long long)s * n;
-  ln_bwd_row<T>(row, n, lane, mean[r], rstd[r], gamma, dy + (long long)r * n, [de, dp](int j, const float v[8]) {
+  extern __shared__ float pos_acc[];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int s = blockIdx.x % S, grp = blockIdx.x / S;
+  const int nseq = rows / S;
+  for (int j = threadIdx.x; j < n; j += 256) pos_acc[j] = 0.f;
+  __syncthreads();
+  const int q1 = min(nseq, (grp + 1) * EMB_SEQS);
+  for (int q = grp * EMB_SEQS + w; q < q1; q += 4) {
+    const int r = q * S + s;
+    const long long tok = tokens[r];
+    EmbedRow<T> row{E + tok * n, pos + (long long)s * n};
+    float* de = dE + tok * n;
+    ln_bwd_row<T>(row, n, lane, mean[r], rstd[r], gamma, dy + (long long)r * n, [de](int j, const float v[8]) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      atomicAdd(de + j + i, v[i]);
-      atomicAdd(dp + j + i, v[i]);
-    }
-  });
+      for (int i = 0; i < 8; ++i) {
+        atomicAdd(de + j + i, v[i]);
+        atomicAdd(pos_acc + j + i, v[i]);
+      }
+    });
+  }
+  __syncthreads();
+  float* dp = dpos + (long long)s * n;
+  for (int j = threadIdx.x; j < n; j += 256) atomicAdd(dp + j, pos_acc[j]);
 }
 
 // ---- column reductions -----------------------------------------------------------------------------

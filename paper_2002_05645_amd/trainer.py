@@ -6,6 +6,7 @@ weights and Adam state, ships the configured dtype, and receives fp32 gradients 
 """
 from __future__ import annotations
 
+import os
 import queue
 import threading
 
@@ -32,7 +33,8 @@ def unpack(layout, shapes, flat) -> dict:
 class L2LTrainer:
     def __init__(self, *, layers, hidden, heads, ffn, seq, vocab, ubatch, num_ubatches, dtype="bf16",
                  ln_eps=1e-12, lr=1e-4, beta1=0.9, beta2=0.999, eps_a=1e-8, ubatch_group=0,
-                 eps_threads=0, stash="device", device="cuda:0", eager=False, optimizer="adam", weight_decay=0.0):
+                 eps_threads=0, stash="device", device="cuda:0", eager=False, optimizer="adam", weight_decay=0.0,
+                 copy_cus=0):
         assert stash in ("device", "host")
         assert optimizer in ("adam", "lamb")
         self.optimizer = optimizer
@@ -61,7 +63,14 @@ class L2LTrainer:
             self._segs = {True: segs(self.embed_layout, self.embed_shapes()), False: segs(self.layer_layout, self.layer_shapes())}
         torch.cuda.set_device(self.device)
         self.compute = torch.cuda.Stream(device=self.device)
-        self.copy = torch.cuda.Stream(device=self.device)
+        self._copy_handle = None
+        copy_cus = int(os.environ.get("L2L_COPY_CUS", copy_cus))
+        if copy_cus > 0:
+            # the runtime's copy kernels (stages, drains, stash traffic) confined to copy_cus of every 32 CUs
+            self._copy_handle = B.stream_create_cu_masked(copy_cus)
+            self.copy = torch.cuda.ExternalStream(self._copy_handle, device=self.device)
+        else:
+            self.copy = torch.cuda.Stream(device=self.device)
         self.ctx = B.Context(self.cfg, self.compute.cuda_stream, self.copy.cuda_stream)
         tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
         shape = (num_ubatches, ubatch, seq, hidden)
@@ -225,3 +234,7 @@ class L2LTrainer:
             self._worker = None
         self.ctx.close()
         self.eps.close()
+        if self._copy_handle is not None:
+            torch.cuda.synchronize(self.device)
+            B.stream_destroy(self._copy_handle)
+            self._copy_handle = None
