@@ -117,6 +117,15 @@ def main():
     prof_total_s, _, _ = run_steps(a.steps)
     prof = tr.ctx.profile_read()
     tr.ctx.profile(0)
+    # a few more steps with every kernel and every copy-stream operation bracketed: how much of the step has
+    # a kernel running, and how much of the copy stream's work (stages, drains) runs under those kernels
+    n_ov = min(3, a.steps)
+    tr.ctx.profile(1)
+    run_steps(n_ov)
+    ov = tr.ctx.profile_overlap(merge_gap_ms=0.05)   # kernel-to-kernel launch gaps (<= 50 us) count as busy
+    classes = tr.ctx.profile_read()
+    tr.ctx.profile(0)
+    kernel_ms = sum(v["ms"] for k, v in classes.items() if k != "copy") / n_ov
 
     samples = w.num_ubatches * w.ubatch
     ms_step = 1e3 * total_s / a.steps
@@ -133,7 +142,17 @@ def main():
                    "device_pipeline_samples_per_s": samples * a.steps / dev_s, "device_pipeline_ms": 1e3 * dev_s / a.steps,
                    "host_adam_exposed_ms": 1e3 * adam_s / a.steps, "eps": "tail" if a.tail_adam else "eager", "optimizer": a.optimizer, "loss_first": loss0, "loss_last": loss, "losses": [round(x, 4) for x in losses],
                    "peak_device_bytes": int(peak_mem), "ctx_device_bytes": int(tr.ctx.device_bytes()),
-                   "instrumented_ms_per_step": 1e3 * prof_total_s / a.steps},
+                   "instrumented_ms_per_step": 1e3 * prof_total_s / a.steps,
+                   # sum of kernel durations over the un-instrumented device-pipeline time; and the fraction of the
+                   # copy stream's busy time during which a compute kernel was running
+                   "compute_busy_frac": kernel_ms / (1e3 * dev_s / a.steps),
+                   "hidden_transfer_frac": ov["copy_hidden_ms"] / ov["copy_busy_ms"] if ov["copy_busy_ms"] > 0 else None,
+                   # the brackets slow the host's enqueue, so the instrumented steps have idle gaps the timed steps do not
+                   # have; in the timed steps at most (device pipeline - kernel time) of the copy work can be exposed:
+                   "hidden_transfer_frac_timed_steps_at_least": max(0.0, 1.0 - max(0.0, 1e3 * dev_s / a.steps - kernel_ms)
+                                                                    / (ov["copy_busy_ms"] / n_ov)) if ov["copy_busy_ms"] > 0 else None,
+                   "copy_stream_busy_ms": ov["copy_busy_ms"] / n_ov,
+                   "kernel_ms_by_class": {k: round(v["ms"] / n_ov, 3) for k, v in classes.items()}},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS,
                      # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (profiles/bench_bert_large_gemm_hbm_traffic.md);

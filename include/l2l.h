@@ -164,13 +164,23 @@ int l2l_embed_drain_wait(l2l_ctx*);
    ATTN = the per-(sequence, head) score/context products and softmax; ROWWISE = LayerNorm, embedding;
    COLSUM = bias / gain gradient reductions; OTHER = head, cross-entropy, fills. */
 enum { L2L_PROF_GEMM = 0, L2L_PROF_ATTN = 1, L2L_PROF_ROWWISE = 2, L2L_PROF_COLSUM = 3, L2L_PROF_OTHER = 4,
-       L2L_PROF_CLASSES = 5 };
+       L2L_PROF_COPY = 5,   /* copy stream: stages (with the weight transposes), drains (with the clearing) */
+       L2L_PROF_CLASSES = 6 };
 /* on = 1: every launch is bracketed by events; on = 2: only the GEMM class (less perturbation);
    on = 0: off.  Counters are reset by every call. */
 int l2l_profile(l2l_ctx*, int on);
 /* Resolves pending events and returns, for one class: launches, total milliseconds, total
    algorithmic flops and bytes of those launches. */
 int l2l_profile_read(l2l_ctx*, int cls, long long* launches, double* ms, double* flops, double* bytes);
+/* Overlap of the two streams over everything recorded since l2l_profile(ctx, 1): the time the compute
+   stream had a kernel running (union of the bracketed intervals), the time the copy stream was busy,
+   the part of the latter that fell inside the former (the transfers Section 2.2 wants hidden), and the
+   span from the first start to the last end; all in ms.  Compute intervals closer together than
+   merge_gap_ms are joined first (the launch gap between two back-to-back kernels, which the event
+   brackets themselves widen, is not time the copy stream could have avoided); 0 joins nothing.
+   Any pointer may be null. */
+int l2l_profile_overlap(l2l_ctx*, double merge_gap_ms, double* compute_busy_ms, double* copy_busy_ms, double* copy_hidden_ms,
+                        double* span_ms);
 
 /* ---- single operations, for kernel-level parity tests and micro-benchmarks --------------------- */
 /* C[M,N] = epilogue(alpha * A B), device pointers, on compute_stream.

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_PKG, "libl2l.so")
 L2L_OK, L2L_E_ARG, L2L_E_STATE, L2L_E_HIP, L2L_E_NOMEM = 0, -1, -2, -3, -4
 L2L_F32, L2L_BF16 = 0, 1
 PROF_GEMM, PROF_ATTN, PROF_ROWWISE, PROF_COLSUM, PROF_OTHER = range(5)
-PROF_NAMES = ("gemm", "attn", "rowwise", "colsum", "other")
+PROF_NAMES = ("gemm", "attn", "rowwise", "colsum", "other", "copy")
 
 
 class l2l_config(C.Structure):
@@ -68,6 +68,8 @@ _SIGS = {
     "l2l_embed_grad_drain": (C.c_int, [_P, _P]),
     "l2l_embed_drain_wait": (C.c_int, [_P]),
     "l2l_profile": (C.c_int, [_P, C.c_int]),
+    "l2l_profile_overlap": (C.c_int, [_P, C.c_double, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double),
+                                      C.POINTER(C.c_double)]),
     "l2l_profile_read": (C.c_int, [_P, C.c_int, C.POINTER(C.c_longlong), C.POINTER(C.c_double),
                                    C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "l2l_op_gemm": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _P, C.c_longlong,
@@ -233,6 +235,12 @@ class Context:
             self._ck(lib().l2l_profile_read(self._h, i, C.byref(n), C.byref(ms), C.byref(fl), C.byref(by)))
             out[name] = dict(launches=n.value, ms=ms.value, flops=fl.value, bytes=by.value)
         return out
+
+    def profile_overlap(self, merge_gap_ms=0.0):
+        """dict(compute_busy_ms, copy_busy_ms, copy_hidden_ms, span_ms) since profile(1)"""
+        v = [C.c_double() for _ in range(4)]
+        self._ck(lib().l2l_profile_overlap(self._h, merge_gap_ms, *[C.byref(x) for x in v]))
+        return dict(zip(("compute_busy_ms", "copy_busy_ms", "copy_hidden_ms", "span_ms"), [x.value for x in v]))
 
     def op_gemm(self, in_dtype, out_f32, a_kc, b_kc, M, N, K, A, lda, B, ldb, Cm, ldc, alpha=1.0, bias=None,
                 resid=None, gelu=False, accumulate=False, impl=0):

@@ -2,11 +2,13 @@
 // pipeline, and the per-layer forward / backward schedules over all U micro-batches (Algorithm 2).
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <utility>
 #include <vector>
 
 #include "../../include/l2l.h"
@@ -146,6 +148,8 @@ struct l2l_ctx {
   int prof_on = 0;
   std::vector<ProfRec> prof;
   std::vector<hipEvent_t> ev_pool;
+  hipEvent_t prof_base = nullptr;                          // recorded when profiling is switched on
+  std::vector<std::pair<float, float>> iv_compute, iv_copy;  // resolved intervals, ms after prof_base
   long long prof_n[L2L_PROF_CLASSES] = {};
   double prof_ms[L2L_PROF_CLASSES] = {}, prof_fl[L2L_PROF_CLASSES] = {}, prof_by[L2L_PROF_CLASSES] = {};
 
@@ -195,6 +199,23 @@ hipEvent_t take_event(l2l_ctx* c) {
   hipEvent_t e;
   (void)hipEventCreate(&e);
   return e;
+}
+
+// brackets work on the copy stream (profile mode 1 only); call begin after the stream's waits are queued
+struct CopyMark { hipEvent_t a = nullptr; };
+CopyMark copy_begin(l2l_ctx* c) {
+  CopyMark m;
+  if (c->prof_on == 1) {
+    m.a = take_event(c);
+    (void)hipEventRecord(m.a, c->xs);
+  }
+  return m;
+}
+void copy_end(l2l_ctx* c, const CopyMark& m, double bytes) {
+  if (!m.a) return;
+  hipEvent_t b = take_event(c);
+  (void)hipEventRecord(b, c->xs);
+  c->prof.push_back({m.a, b, L2L_PROF_COPY, 0.0, bytes});
 }
 
 template <typename F>
@@ -820,8 +841,10 @@ int l2l_param_stage(l2l_ctx* c, int layer, const void* host_params, int slot) {
   if (slot != 0 && slot != 1) return fail(c, L2L_E_ARG, "l2l_param_stage: slot %d not 0 or 1", slot);
   // the copy may start only when every kernel that reads the slot's previous contents is done
   if (c->slot_layer[slot] >= 0) HIP_TRY(c, hipStreamWaitEvent(c->xs, c->slot_released[slot], 0));
+  const CopyMark mark = copy_begin(c);
   HIP_TRY(c, hipMemcpyAsync(c->slot[slot], host_params, c->lay.total * esize(c->cfg.dtype), hipMemcpyHostToDevice, c->xs));
   L2L_TRY(transpose_weights(c, slot));
+  copy_end(c, mark, (double)c->lay.total * esize(c->cfg.dtype));
   HIP_TRY(c, hipEventRecord(c->slot_staged[slot], c->xs));
   c->slot_layer[slot] = layer;
   return L2L_OK;
@@ -881,9 +904,11 @@ int l2l_grad_drain(l2l_ctx* c, int layer, void* host_grads) {
   for (int a = 0; a < 2; ++a) {
     if (c->gacc_state[a] == 1 && c->gacc_layer[a] == layer) {
       HIP_TRY(c, hipStreamWaitEvent(c->xs, c->gacc_ready[a], 0));
+      const CopyMark mark = copy_begin(c);
       HIP_TRY(c, hipMemcpyAsync(host_grads, c->gacc[a], c->lay.total * 4, hipMemcpyDeviceToHost, c->xs));
       HIP_TRY(c, hipEventRecord(c->gacc_landed[a], c->xs));
       L2L_TRY(fill_zero_copy_stream(c, c->gacc[a], c->lay.total * 4));   // "erased from the device" (Section 2.1)
+      copy_end(c, mark, (double)c->lay.total * 4);
       HIP_TRY(c, hipEventRecord(c->gacc_drained[a], c->xs));
       c->gacc_state[a] = 2;
       return L2L_OK;
@@ -914,7 +939,9 @@ int l2l_embed_stage(l2l_ctx* c, const void* host) {
   L2L_TRY(need_vocab(c, "l2l_embed_stage"));
   if (!host) return fail(c, L2L_E_ARG, "l2l_embed_stage: null host pointer");
   if (c->emb_staged) HIP_TRY(c, hipStreamWaitEvent(c->xs, c->emb_released_ev, 0));
+  const CopyMark mark = copy_begin(c);
   HIP_TRY(c, hipMemcpyAsync(c->emb, host, c->lay.etotal * esize(c->cfg.dtype), hipMemcpyHostToDevice, c->xs));
+  copy_end(c, mark, (double)c->lay.etotal * esize(c->cfg.dtype));
   HIP_TRY(c, hipEventRecord(c->emb_staged_ev, c->xs));
   c->emb_staged = 1;
   return L2L_OK;
@@ -965,9 +992,11 @@ int l2l_embed_grad_drain(l2l_ctx* c, void* host_grads) {
   if (!host_grads) return fail(c, L2L_E_ARG, "l2l_embed_grad_drain: null host pointer");
   if (c->egacc_state != 1) return fail(c, L2L_E_STATE, "l2l_embed_grad_drain: no un-drained embedding gradients");
   HIP_TRY(c, hipStreamWaitEvent(c->xs, c->egacc_ready, 0));
+  const CopyMark mark = copy_begin(c);
   HIP_TRY(c, hipMemcpyAsync(host_grads, c->egacc, c->lay.etotal * 4, hipMemcpyDeviceToHost, c->xs));
   HIP_TRY(c, hipEventRecord(c->egacc_landed, c->xs));
   L2L_TRY(fill_zero_copy_stream(c, c->egacc, c->lay.etotal * 4));
+  copy_end(c, mark, (double)c->lay.etotal * 4);
   HIP_TRY(c, hipEventRecord(c->egacc_drained, c->xs));
   c->egacc_state = 2;
   return L2L_OK;
@@ -1017,6 +1046,9 @@ static void prof_resolve(l2l_ctx* c) {
     (void)hipEventSynchronize(r.b);
     float ms = 0.f;
     if (hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) {
+      float t0 = 0.f;
+      if (c->prof_base && hipEventElapsedTime(&t0, c->prof_base, r.a) == hipSuccess)
+        (r.cls == L2L_PROF_COPY ? c->iv_copy : c->iv_compute).push_back({t0, t0 + ms});
       c->prof_n[r.cls] += 1;
       c->prof_ms[r.cls] += ms;
       c->prof_fl[r.cls] += r.flops;
@@ -1033,7 +1065,49 @@ int l2l_profile(l2l_ctx* c, int on) {
   if (!c) return L2L_E_ARG;
   prof_resolve(c);
   for (int i = 0; i < L2L_PROF_CLASSES; ++i) { c->prof_n[i] = 0; c->prof_ms[i] = c->prof_fl[i] = c->prof_by[i] = 0; }
+  c->iv_compute.clear();
+  c->iv_copy.clear();
   c->prof_on = on;
+  if (on) {
+    if (!c->prof_base) HIP_TRY(c, hipEventCreate(&c->prof_base));
+    HIP_TRY(c, hipEventRecord(c->prof_base, c->cs));
+  }
+  return L2L_OK;
+}
+
+int l2l_profile_overlap(l2l_ctx* c, double merge_gap_ms, double* compute_busy_ms, double* copy_busy_ms, double* copy_hidden_ms,
+                        double* span_ms) {
+  if (!c || !(merge_gap_ms >= 0.0)) return L2L_E_ARG;
+  prof_resolve(c);
+  typedef std::vector<std::pair<float, float>> Iv;
+  const auto merged = [](Iv v, float gap) {
+    std::sort(v.begin(), v.end());
+    Iv out;
+    for (const auto& p : v) {
+      if (!out.empty() && p.first <= out.back().second + gap) out.back().second = std::max(out.back().second, p.second);
+      else out.push_back(p);
+    }
+    return out;
+  };
+  const auto length = [](const Iv& v) {
+    double s = 0.0;
+    for (const auto& p : v) s += (double)p.second - p.first;
+    return s;
+  };
+  const Iv a = merged(c->iv_compute, (float)merge_gap_ms), b = merged(c->iv_copy, 0.f);
+  double both = 0.0;
+  for (size_t i = 0, j = 0; i < a.size() && j < b.size();) {
+    const float lo = std::max(a[i].first, b[j].first), hi = std::min(a[i].second, b[j].second);
+    if (lo < hi) both += (double)hi - lo;
+    if (a[i].second < b[j].second) ++i; else ++j;
+  }
+  double first = 1e300, last = -1e300;
+  for (const Iv* v : {&a, &b})
+    for (const auto& p : *v) { first = std::min<double>(first, p.first); last = std::max<double>(last, p.second); }
+  if (compute_busy_ms) *compute_busy_ms = length(a);
+  if (copy_busy_ms) *copy_busy_ms = length(b);
+  if (copy_hidden_ms) *copy_hidden_ms = both;
+  if (span_ms) *span_ms = last > first ? last - first : 0.0;
   return L2L_OK;
 }
 
