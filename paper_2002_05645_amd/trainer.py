@@ -82,6 +82,7 @@ class L2LTrainer:
         self.stash = [torch.empty(shape, dtype=tdt, device=self.device) for _ in range(n_stash)]
         if stash == "host":
             self.host_stash = [torch.empty(shape, dtype=tdt, pin_memory=True) for _ in range(layers + 1)]
+            self.stash_stream = torch.cuda.Stream(device=self.device)
             self.stash_ev = [torch.cuda.Event() for _ in range(2)]
             self.stash_free = [torch.cuda.Event() for _ in range(2)]
         self.dy = torch.empty(shape, dtype=tdt, device=self.device)
@@ -92,6 +93,7 @@ class L2LTrainer:
         self.eager = eager
         self._landed = [torch.cuda.Event() for _ in range(layers + 1)]
         self._bwd_done = [torch.cuda.Event() for _ in range(layers)]
+        self._fwd_done = [torch.cuda.Event() for _ in range(layers)]
         self._work = queue.Queue()
         self._worker_error = None
         self._worker = None
@@ -144,8 +146,11 @@ class L2LTrainer:
                 c.param_stage(l + 1, e.ship_ptr(2 + l), (l + 1) % 2)
             if host_mode:
                 self.compute.wait_event(self.stash_free[(l + 1) % 2])
+                if self.run_ahead and l >= self.run_ahead:     # the stash offloads are device-to-host copies too
+                    self._fwd_done[l - self.run_ahead].synchronize()
             c.layer_fwd(l, l % 2, self._stash_slot(l), self._stash_slot(l + 1))
             if host_mode:
+                self._fwd_done[l].record(self.compute)
                 self._offload(l + 1)
         c.head_loss(self._stash_slot(L), labels, self.dy, self.loss_dev)
         for l in reversed(range(L)):
@@ -197,25 +202,28 @@ class L2LTrainer:
                 self._work.task_done()
 
     def _offload(self, l):
-        """device stash slot -> pinned host, on the copy stream, after the producing kernels."""
+        """device stash slot -> pinned host after the producing kernels, on a stream of its own: the stash traffic
+        then runs beside the parameter stages and gradient drains of the copy stream (the host link is full duplex)."""
         ev = self.stash_ev[l % 2]
         ev.record(self.compute)
-        self.copy.wait_event(ev)
-        with torch.cuda.stream(self.copy):
+        self.stash_stream.wait_event(ev)
+        with torch.cuda.stream(self.stash_stream):
             self.host_stash[l].copy_(self.stash[l % 2], non_blocking=True)
-            self.stash_free[l % 2].record(self.copy)
+            self.stash_free[l % 2].record(self.stash_stream)
 
     def _reload(self, l):
         """pinned host -> device stash slot before layer l's backward (layer L's input is not needed)."""
-        self.copy.wait_event(self.stash_free[l % 2])
-        with torch.cuda.stream(self.copy):
+        self.stash_stream.wait_event(self.stash_free[l % 2])
+        with torch.cuda.stream(self.stash_stream):
             self.stash[l % 2].copy_(self.host_stash[l], non_blocking=True)
             ev = self.stash_ev[l % 2]
-            ev.record(self.copy)
+            ev.record(self.stash_stream)
         self.compute.wait_event(ev)
 
     def finish(self) -> float:
         self.ctx.sync()
+        if self.stash_mode == "host":
+            self.stash_stream.synchronize()
         return float(self.loss_dev.item())
 
     def optimizer_step(self):
