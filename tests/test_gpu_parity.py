@@ -229,6 +229,14 @@ def test_layer_unfused_attention_path_still_matches(monkeypatch):
     _assert_errs(_layer_case(w), TOL["bf16"])
 
 
+@pytest.mark.parametrize("hidden,heads", [(1536, 24), (2304, 36), (6144, 48)])
+def test_layer_wide_hidden_bf16(hidden, heads):
+    # LayerNorm backward with its column sums in one pass takes up to 2048 columns (four column chunks per lane at
+    # 1536); wider rows (2304; 6144 is the deep-wide workload's width) go through the separate dx and column-sum kernels
+    w = S.Workload("wide", 1, hidden, heads, 256, 32, 50, 2, 2, "bf16", 1.0, 90 + heads)
+    _assert_errs(_layer_case(w), TOL["bf16"])
+
+
 def test_layer_seq512_bf16():
     w = S.WORKLOADS[3].scaled(num_ubatches=2, ubatch=1)
     _assert_errs(_layer_case(w), TOL["bf16"])
@@ -370,6 +378,33 @@ def test_step_head_in_several_passes(monkeypatch, head_rows, label_prob):
     monkeypatch.setenv("L2L_HEAD_ROWS", str(head_rows))
     errs, _, _ = _step_case(S.WORKLOADS[0].scaled(label_prob=label_prob))
     _assert_errs({k: v for k, v in errs.items() if not k.startswith("adam.")}, TOL["fp32"])
+
+
+def test_step_with_a_micro_batch_without_labels():
+    # one of the four micro-batches carries no label at all: its rows must contribute nothing to the loss and to
+    # the head's gradients, and the normalisation is by the labelled count of the whole mini-batch
+    w = S.WORKLOADS[0]
+    tr = L2LTrainer(layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, vocab=w.vocab, ubatch=w.ubatch,
+                    num_ubatches=w.num_ubatches, dtype="fp32", eps_threads=4)
+    try:
+        emb = S.embed_params(w)
+        layers = [S.layer_params(w, l) for l in range(w.layers)]
+        tr.load_params(emb, layers)
+        tok, lab = S.tokens_and_labels(w)
+        lab = lab.copy()
+        lab[2] = -1
+        lab[0, 1, 5:] = -1                                   # and a ragged count elsewhere
+        tr.device_pipeline(torch.from_numpy(tok).cuda(), torch.from_numpy(lab).cuda())
+        loss = tr.finish()
+        loss_ref, gemb, gl = O.run_l2l({k: v.astype(np.float64) for k, v in emb.items()},
+                                       [{k: v.astype(np.float64) for k, v in p.items()} for p in layers], tok, lab, w.heads, 1e-12)
+        assert abs(loss - loss_ref) / abs(loss_ref) < 1e-4
+        ge, glayers = tr.grads()
+        errs = {"emb." + k: O.rel_l2(ge[k], gemb[k]) for k in gemb}
+        errs.update({f"l{l}.{k}": O.rel_l2(glayers[l][k], gl[l][k]) for l in range(w.layers) for k in gl[l]})
+        _assert_errs(errs, TOL["fp32"])
+    finally:
+        tr.close()
 
 
 def test_step_bf16_small_depth():
