@@ -23,7 +23,7 @@ cpu-baseline leg of the benchmark may import it.
 Pins (tests/test_oracle_*.py): central finite differences for every backward
 formula, Algorithm 1 == Algorithm 2 == one concatenated minibatch, closed
 forms for softmax / LayerNorm / GELU / cross-entropy / Adam / LAMB (plus LAMB's
-step-length and scale invariances), exhaustive bf16 round trip.  Unpinned: end-to-end task accuracy against the paper's Table 7
+step-length and scale invariances), exhaustive bf16 and fp16 round trips with hand-built ties.  Unpinned: end-to-end task accuracy against the paper's Table 7
 (needs the GLUE data and pretrained weights) -- parity unpinned.
 """
 from __future__ import annotations
@@ -342,6 +342,19 @@ def bf16_bits(x):
 
 def bf16_to_f32(bits):
     return (np.asarray(bits, np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def fp16_bits(x):
+    """Round float32 values to IEEE half precision (nearest, ties to even, overflow to infinity, gradual
+    underflow); returns the uint16 patterns.  The FP16 of the paper's cross mixed precision (Section 2.3)."""
+    with np.errstate(over="ignore"):
+        return np.asarray(x, np.float32).astype(np.float16).view(np.uint16)
+
+
+def fp16_round(x):
+    """float32 -> nearest half-precision value, returned as float32."""
+    x = np.asarray(x, np.float32)
+    return fp16_bits(x).view(np.float16).astype(np.float32).reshape(x.shape)
 
 
 def bf16_round(x):

@@ -341,3 +341,28 @@ def test_bf16_exhaustive_round_trip_and_ties():
     x = np.random.default_rng(0).normal(size=1000).astype(np.float32)
     r = O.bf16_round(x)
     assert np.all(np.abs(r - x) <= np.abs(x) * 2.0 ** -8)
+
+
+def test_fp16_exhaustive_round_trip_ties_and_range():
+    bits = np.arange(65536, dtype=np.uint16)
+    f = bits.view(np.float16).astype(np.float32)
+    finite = np.isfinite(f)
+    assert np.array_equal(O.fp16_bits(f[finite]), bits[finite])
+    # layout: 1 sign, 5 exponent (bias 15), 10 fraction bits
+    assert O.fp16_bits(np.float32(1.0)) == 0x3C00
+    assert O.fp16_bits(np.float32(-2.0)) == 0xC000
+    assert O.fp16_bits(np.float32(65504.0)) == 0x7BFF                # largest finite
+    assert O.fp16_bits(np.float32(2.0 ** -14)) == 0x0400             # smallest normal
+    assert O.fp16_bits(np.float32(2.0 ** -24)) == 0x0001             # smallest subnormal
+    # ties go to the even pattern; just above a tie goes up
+    assert O.fp16_bits(np.float32(1.0 + 2.0 ** -11)) == 0x3C00
+    assert O.fp16_bits(np.float32(1.0 + 3 * 2.0 ** -11)) == 0x3C02
+    assert O.fp16_bits(np.float32(1.0 + 2.0 ** -11 + 2.0 ** -20)) == 0x3C01
+    assert O.fp16_bits(np.float32(2.0 ** -25)) == 0x0000             # tie between 0 and the smallest subnormal
+    assert O.fp16_bits(np.float32(3 * 2.0 ** -25)) == 0x0002
+    # overflow: 65520 is the tie between 65504 and 2^16 and rounds to infinity
+    assert O.fp16_bits(np.float32(65519.0)) == 0x7BFF
+    assert O.fp16_bits(np.float32(65520.0)) == 0x7C00
+    assert np.isinf(O.fp16_round(np.float32(1e6)))
+    x = np.float32(0.1)
+    assert abs(float(O.fp16_round(x)) - 0.1) <= 0.1 * 2.0 ** -11
