@@ -60,6 +60,8 @@ def main():
     ap.add_argument("--tail-adam", action="store_true",
                     help="run the host Adam after all gradients arrived instead of eagerly per layer during backward")
     ap.add_argument("--ubatches", type=int, default=0, help="override U, the number of micro-batches (sweeps of the paper's Tables 3 and 4)")
+    ap.add_argument("--dtype", default="", choices=["", "bf16", "fp16", "fp32"],
+                    help="override the workload's device dtype (fp16: the paper's CMP precision, with dynamic loss scaling)")
     ap.add_argument("--optimizer", default="adam", choices=["adam", "lamb"],
                     help="host optimizer (lamb: per-tensor trust ratio, learning rate 1e-3, weight decay 0.01 on matrices)")
     a = ap.parse_args()
@@ -75,6 +77,8 @@ def main():
         w = w.scaled(layers=a.layers)
     if a.ubatches:
         w = w.scaled(num_ubatches=a.ubatches)
+    if a.dtype:
+        w = w.scaled(dtype=a.dtype)
     tr = L2LTrainer(layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, vocab=w.vocab,
                     ubatch=w.ubatch, num_ubatches=w.num_ubatches, dtype=w.dtype, ubatch_group=a.group, stash=a.stash,
                     eager=not a.tail_adam, optimizer=a.optimizer,
@@ -135,7 +139,7 @@ def main():
     out = {
         "metric": "train samples/sec, BERT-Large L2L batch 256", "value": samples * a.steps / total_s,
         "unit": "samples/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if w.dtype == "bf16" else "f32",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": {"bf16": "bf16", "fp16": "f16", "fp32": "f32"}[w.dtype],
         "data": "synthetic",
         "config": {"workload": f"{w.name}: L={w.layers} H={w.hidden} A={w.heads} F={w.ffn} S={w.seq} V={w.vocab} "
                                f"U={w.num_ubatches} x ub={w.ubatch}", "stash": a.stash, "ubatch_group": tr.ctx.cfg.ubatch_group,
@@ -157,7 +161,7 @@ def main():
                      "frac": achieved / PEAK_BF16_TFLOPS,
                      # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (profiles/bench_bert_large_gemm_hbm_traffic.md);
                      # measured on the headline workload only
-                     "traffic": 608.7e6 if (a.config == 2 and not a.layers and not a.group and not a.ubatches) else None,
+                     "traffic": 608.7e6 if (a.config == 2 and not a.layers and not a.group and not a.ubatches and not a.dtype) else None,
                      "kernel": "gemm_mfma_dlds_kernel / gemm_mfma_kernel: the layer's dense GEMMs (QKV, out-proj, FFN1, FFN2; forward, recompute, dX, dW)",
                      "gemm_ms_per_step": g["ms"] / a.steps, "launches_per_step": g["launches"] / a.steps,
                      "avg_launch_us": 1e3 * g["ms"] / max(g["launches"], 1),

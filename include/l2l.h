@@ -19,8 +19,10 @@
  *    inside the library.  No call blocks the host except l2l_sync, l2l_drain_wait, l2l_embed_drain_wait
  *    and l2l_create/l2l_destroy.
  *  - Tensors are row-major, token-major.  T = ubatch * seq tokens per micro-batch.  In dtype
- *    L2L_BF16 activations and parameters are bfloat16 with fp32 accumulation everywhere; in
- *    L2L_F32 everything is fp32.  Gradients of parameters are always accumulated in fp32.
+ *    L2L_BF16 activations and parameters are bfloat16 with fp32 accumulation everywhere, in
+ *    L2L_FP16 IEEE half (the FP16 of the paper's cross mixed precision, Section 2.3; use it with a
+ *    loss scale, l2l_set_loss_scale); in L2L_F32 everything is fp32.  Gradients of parameters are
+ *    always accumulated in fp32.
  *
  * Packed parameter block of one encoder layer (one contiguous DMA, Section 2.1 "receives each
  * layer's weights from EPS one at a time"), in elements of the configured dtype, every sub-block
@@ -51,7 +53,7 @@ typedef enum {
   L2L_E_NOMEM = -4
 } l2l_status;
 
-enum { L2L_F32 = 0, L2L_BF16 = 1 };
+enum { L2L_F32 = 0, L2L_BF16 = 1, L2L_FP16 = 2 };
 
 typedef struct l2l_ctx l2l_ctx;
 
@@ -62,7 +64,7 @@ typedef struct {
   int seq;           /* S; multiple of 8 */
   int ubatch;        /* ub: sequences per micro-batch */
   int num_ubatches;  /* U */
-  int dtype;         /* L2L_F32 or L2L_BF16 */
+  int dtype;         /* L2L_F32, L2L_BF16 or L2L_FP16 */
   float ln_eps;      /* LayerNorm epsilon */
   int vocab;         /* V; 0 = no embedding / head buffers */
   int ubatch_group;  /* micro-batches handed to one kernel launch (rows are independent, so this
@@ -152,6 +154,12 @@ int l2l_embed_fwd(l2l_ctx*, const int32_t* tokens, void* x_out);
    dy_out: device U x [ub,S,H], receives dL/dx (zero at unlabelled positions).
    loss_out: device float[1].  Adds dE and dbv into the embedding-block accumulator. */
 int l2l_head_loss(l2l_ctx*, const void* x_last, const int32_t* labels, void* dy_out, float* loss_out);
+/* Loss scaling (Section 2.3: FP16 on the device needs it, the gradient of the loss being ~1/(N V) per
+   logit, below half precision's range): from the next l2l_head_loss on, the gradient of the loss is
+   multiplied by `scale` before it is rounded to the device dtype, so every activation and parameter
+   gradient downstream carries that factor (the reported loss does not); the host divides it out of the
+   drained gradients (eps_grad_unscale).  Default 1.  L2L_E_ARG unless 0 < scale < inf. */
+int l2l_set_loss_scale(l2l_ctx*, float scale);
 /* Backward of l2l_embed_fwd: adds dE (scatter-add over token ids), dPpos, dge, dbe into the
    embedding-block accumulator.  dy: device U x [ub,S,H] (read only). */
 int l2l_embed_bwd(l2l_ctx*, const int32_t* tokens, const void* dy);
@@ -214,6 +222,10 @@ int   eps_refresh_ship(eps_store*, int first, int last);
 /* One bias-corrected Adam step (no weight decay) on blocks [first, last] from their landing
    buffers, then refreshes their shipping copies.  t >= 1 is the step number. */
 int   eps_adam_step(eps_store*, int first, int last, int t, double lr, double beta1, double beta2, double eps_a);
+/* Multiplies the landing buffers of blocks [first, last] by inv_scale (1 / loss scale) and sets
+   *nonfinite to 1 if any of them holds an inf or NaN (an overflow on the device: the caller then skips
+   the update and lowers the scale), else 0.  nonfinite may be null. */
+int   eps_grad_unscale(eps_store*, int first, int last, double inv_scale, int* nonfinite);
 /* One LAMB step (the optimizer of Table 1; update rule of the LAMB publication the paper cites, with
    bias correction): per tensor, u = mhat / (sqrt(vhat) + eps_a) + weight_decay * w and
    w -= lr * (||w|| / ||u||) * u, the ratio taken as 1 where either norm is zero.  The tensors of a

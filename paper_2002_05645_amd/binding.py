@@ -13,7 +13,8 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libl2l.so")
 
 L2L_OK, L2L_E_ARG, L2L_E_STATE, L2L_E_HIP, L2L_E_NOMEM = 0, -1, -2, -3, -4
-L2L_F32, L2L_BF16 = 0, 1
+L2L_F32, L2L_BF16, L2L_FP16 = 0, 1, 2
+DTYPES = {"fp32": L2L_F32, "bf16": L2L_BF16, "fp16": L2L_FP16}
 PROF_GEMM, PROF_ATTN, PROF_ROWWISE, PROF_COLSUM, PROF_OTHER = range(5)
 PROF_NAMES = ("gemm", "attn", "rowwise", "colsum", "other", "copy")
 
@@ -82,9 +83,11 @@ _SIGS = {
     "eps_grad": (C.POINTER(C.c_float), [_P, C.c_int]),
     "eps_moment": (C.POINTER(C.c_float), [_P, C.c_int, C.c_int]),
     "eps_refresh_ship": (C.c_int, [_P, C.c_int, C.c_int]),
+    "l2l_set_loss_scale": (C.c_int, [_P, C.c_float]),
     "l2l_stream_create_cu_masked": (C.c_int, [C.c_int, C.POINTER(C.c_void_p)]),
     "l2l_stream_destroy": (C.c_int, [C.c_void_p]),
     "eps_adam_step": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_double, C.c_double, C.c_double, C.c_double]),
+    "eps_grad_unscale": (C.c_int, [_P, C.c_int, C.c_int, C.c_double, C.POINTER(C.c_int)]),
     "eps_lamb_step": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_double, C.c_double, C.c_double, C.c_double, C.c_double,
                                 C.c_int, C.POINTER(C.c_longlong), C.POINTER(C.c_longlong), C.POINTER(C.c_double)]),
     "eps_host_bytes": (C.c_size_t, [_P]),
@@ -109,7 +112,7 @@ def lib():
 
 
 def make_config(hidden, heads, ffn, seq, ubatch, num_ubatches, dtype, ln_eps=1e-12, vocab=0, ubatch_group=0):
-    d = {"fp32": L2L_F32, "bf16": L2L_BF16}.get(dtype, dtype)
+    d = DTYPES.get(dtype, dtype)
     return l2l_config(hidden, heads, ffn, seq, ubatch, num_ubatches, d, ln_eps, vocab, ubatch_group)
 
 
@@ -236,6 +239,9 @@ class Context:
             out[name] = dict(launches=n.value, ms=ms.value, flops=fl.value, bytes=by.value)
         return out
 
+    def set_loss_scale(self, scale):
+        self._ck(lib().l2l_set_loss_scale(self._h, float(scale)))
+
     def profile_overlap(self, merge_gap_ms=0.0):
         """dict(compute_busy_ms, copy_busy_ms, copy_hidden_ms, span_ms) since profile(1)"""
         v = [C.c_double() for _ in range(4)]
@@ -258,7 +264,7 @@ class EPS:
 
     def __init__(self, elems, ship_dtype, threads=0):
         self.elems = [int(e) for e in elems]
-        self.ship_dtype = {"fp32": L2L_F32, "bf16": L2L_BF16}.get(ship_dtype, ship_dtype)
+        self.ship_dtype = DTYPES.get(ship_dtype, ship_dtype)
         arr = (C.c_size_t * len(self.elems))(*self.elems)
         self._h = _P()
         rc = lib().eps_create(len(self.elems), arr, self.ship_dtype, threads, C.byref(self._h))
@@ -296,7 +302,7 @@ class EPS:
 
     def ship(self, i):
         p = lib().eps_ship(self._h, i)
-        if self.ship_dtype == L2L_BF16:
+        if self.ship_dtype in (L2L_BF16, L2L_FP16):     # the 16-bit patterns
             return np.ctypeslib.as_array(C.cast(p, C.POINTER(C.c_uint16)), shape=(self.elems[i],))
         return np.ctypeslib.as_array(C.cast(p, C.POINTER(C.c_float)), shape=(self.elems[i],))
 
@@ -310,6 +316,14 @@ class EPS:
         rc = lib().eps_adam_step(self._h, first, last, t, lr, beta1, beta2, eps_a)
         if rc != L2L_OK:
             raise L2LError(rc, "eps_adam_step")
+
+    def grad_unscale(self, first, last, inv_scale) -> bool:
+        """landing buffers *= inv_scale; True if they hold an inf or NaN."""
+        bad = C.c_int(0)
+        rc = lib().eps_grad_unscale(self._h, first, last, inv_scale, C.byref(bad))
+        if rc != L2L_OK:
+            raise L2LError(rc, "eps_grad_unscale")
+        return bool(bad.value)
 
     def lamb_step(self, first, last, t, segments, lr=1e-3, beta1=0.9, beta2=0.999, eps_a=1e-6, weight_decay=0.0,
                   decay_mask=None):

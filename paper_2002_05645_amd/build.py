@@ -19,7 +19,7 @@ HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
              "-Wno-unused-result"]
 with open(os.path.join(CSRC, "gemm_variants.h")) as _f:
     NUM_GEMM_VARIANTS = int(re.search(r"kNumGemmVariants\s*=\s*(\d+)", _f.read()).group(1))
-HOST_FLAGS = ["-O3", "-std=c++17", "-fPIC", "-mavx2", "-mfma", "-D__HIP_PLATFORM_AMD__", f"-I{ROCM}/include", "-pthread"]
+HOST_FLAGS = ["-O3", "-std=c++17", "-fPIC", "-mavx2", "-mfma", "-mf16c", "-D__HIP_PLATFORM_AMD__", f"-I{ROCM}/include", "-pthread"]
 
 
 def _run(cmd):
@@ -39,10 +39,11 @@ def build(verbose: bool = False) -> str:
     jobs = [[HIPCC, *HIP_FLAGS, "-c", os.path.join(CSRC, "l2l.hip"), "-o", o_hip],
             ["g++", *HOST_FLAGS, "-c", os.path.join(CSRC, "eps.cpp"), "-o", o_eps]]
     objs = [o_hip, o_eps]
-    for v in range(NUM_GEMM_VARIANTS):        # one translation unit per MFMA tile variant
-        o = os.path.join(obj_dir, f"gemm_v{v}.o")
-        jobs.append([HIPCC, *HIP_FLAGS, f"-DL2L_VARIANT={v}", "-c", os.path.join(CSRC, "gemm_variant.hip"), "-o", o])
-        objs.append(o)
+    for v in range(NUM_GEMM_VARIANTS):        # one translation unit per MFMA tile variant and 16-bit format
+        for tag, extra in (("v", []), ("h", ["-DL2L_ELEM_FP16=1"])):
+            o = os.path.join(obj_dir, f"gemm_{tag}{v}.o")
+            jobs.append([HIPCC, *HIP_FLAGS, f"-DL2L_VARIANT={v}", *extra, "-c", os.path.join(CSRC, "gemm_variant.hip"), "-o", o])
+            objs.append(o)
     with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
         list(ex.map(_run, jobs))
     _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB, "-pthread"])

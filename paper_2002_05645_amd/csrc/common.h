@@ -5,6 +5,8 @@
 
 typedef __bf16 bf16;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef _Float16 fp16;
+typedef __attribute__((ext_vector_type(8))) _Float16 fp16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
@@ -14,9 +16,11 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 __device__ __forceinline__ float to_f32(float x) { return x; }
 __device__ __forceinline__ float to_f32(bf16 x) { return (float)x; }
+__device__ __forceinline__ float to_f32(fp16 x) { return (float)x; }
 template <typename T> __device__ __forceinline__ T from_f32(float x);
 template <> __device__ __forceinline__ float from_f32<float>(float x) { return x; }
 template <> __device__ __forceinline__ bf16 from_f32<bf16>(float x) { return (bf16)x; }  // round to nearest even
+template <> __device__ __forceinline__ fp16 from_f32<fp16>(float x) { return (fp16)x; }  // round to nearest even, overflow to inf
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -39,6 +43,11 @@ __device__ __forceinline__ void load8(const bf16* p, float v[8]) {
 #pragma unroll
   for (int i = 0; i < 8; ++i) v[i] = (float)a[i];
 }
+__device__ __forceinline__ void load8(const fp16* p, float v[8]) {
+  const fp16x8 a = *(const fp16x8*)p;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v[i] = (float)a[i];
+}
 __device__ __forceinline__ void store8(float* p, const float v[8]) {
   *(f32x4*)p = f32x4{v[0], v[1], v[2], v[3]};
   *(f32x4*)(p + 4) = f32x4{v[4], v[5], v[6], v[7]};
@@ -48,6 +57,23 @@ __device__ __forceinline__ void store8(bf16* p, const float v[8]) {
 #pragma unroll
   for (int i = 0; i < 8; ++i) a[i] = (bf16)v[i];
   *(bf16x8*)p = a;
+}
+
+__device__ __forceinline__ void store8(fp16* p, const float v[8]) {
+  fp16x8 a;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a[i] = (fp16)v[i];
+  *(fp16x8*)p = a;
+}
+
+// One 32x32x16 MFMA step on 16-bit operands of element type E (fragments are carried as 8 x 16 bits).
+template <typename E>
+__device__ __forceinline__ f32x16 mfma_32x32x16(bf16x8 a, bf16x8 b, f32x16 c) {
+  if constexpr (sizeof(E) == 2 && __is_same(E, fp16)) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(fp16x8, a), __builtin_bit_cast(fp16x8, b), c, 0, 0, 0);
+  } else {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+  }
 }
 
 // GELU in its exact (erf) form and its derivative.
@@ -90,6 +116,15 @@ __device__ __forceinline__ float gelu_grad_fast_f(float u) {
   p = fmaf(p, t, -2.418076579e+01f);
   p = fmaf(p, t, 3.590171402e+00f);
   return fmaf(p, s, 0.5f);
+}
+
+// GELU of the 16-bit epilogues: the polynomial forms for bf16; fp16, whose rounding step is eight times finer,
+// keeps the exact ones.
+template <typename E> __device__ __forceinline__ float gelu_epi(float u) {
+  if constexpr (__is_same(E, bf16)) return gelu_fast_f(u); else return gelu_f(u);
+}
+template <typename E> __device__ __forceinline__ float gelu_grad_epi(float u) {
+  if constexpr (__is_same(E, bf16)) return gelu_grad_fast_f(u); else return gelu_grad_f(u);
 }
 
 // Epilogue flags of the GEMM kernels.

@@ -4,6 +4,8 @@
 // (cross mixed precision, Section 2.3, with bf16 in place of FP16).
 #include <hip/hip_runtime_api.h>
 
+#include <immintrin.h>
+
 #include <atomic>
 #include <cmath>
 #include <condition_variable>
@@ -111,6 +113,9 @@ static void ship_range(const eps_store* e, const Block& b, size_t lo, size_t hi)
   if (e->ship_dtype == L2L_BF16) {
     uint16_t* d = (uint16_t*)b.ship;
     for (size_t i = lo; i < hi; ++i) d[i] = f32_to_bf16_rne(b.w[i]);
+  } else if (e->ship_dtype == L2L_FP16) {
+    uint16_t* d = (uint16_t*)b.ship;
+    for (size_t i = lo; i < hi; ++i) d[i] = _cvtss_sh(b.w[i], _MM_FROUND_TO_NEAREST_INT | _MM_FROUND_NO_EXC);   // IEEE half, ties to even
   } else {
     std::memcpy((float*)b.ship + lo, b.w + lo, (hi - lo) * sizeof(float));
   }
@@ -119,7 +124,7 @@ static void ship_range(const eps_store* e, const Block& b, size_t lo, size_t hi)
 extern "C" {
 
 int eps_create(int n_blocks, const size_t* elems, int ship_dtype, int threads, eps_store** out) {
-  if (!out || !elems || n_blocks <= 0 || (ship_dtype != L2L_F32 && ship_dtype != L2L_BF16)) return L2L_E_ARG;
+  if (!out || !elems || n_blocks <= 0 || (ship_dtype != L2L_F32 && ship_dtype != L2L_BF16 && ship_dtype != L2L_FP16)) return L2L_E_ARG;
   *out = nullptr;
   if (threads <= 0) threads = (int)std::thread::hardware_concurrency();
   if (threads <= 0) threads = 1;
@@ -131,7 +136,7 @@ int eps_create(int n_blocks, const size_t* elems, int ship_dtype, int threads, e
     e->pinned = hipGetDeviceCount(&ndev) == hipSuccess && ndev > 0;
     if (!e->pinned) (void)hipGetLastError();
   }
-  const size_t se = ship_dtype == L2L_BF16 ? 2 : 4;
+  const size_t se = ship_dtype == L2L_F32 ? 4 : 2;
   for (int i = 0; i < n_blocks; ++i) {
     Block& b = e->blocks[i];
     b.n = elems[i];
@@ -234,6 +239,27 @@ int eps_adam_step(eps_store* e, int first, int last, int t, double lr_d, double 
       ship_range(e, b, lo, hi);
     });
   }
+  return L2L_OK;
+}
+
+int eps_grad_unscale(eps_store* e, int first, int last, double inv_scale, int* nonfinite) {
+  if (!e || first < 0 || last >= (int)e->blocks.size() || first > last || !std::isfinite(inv_scale)) return L2L_E_ARG;
+  const float s = (float)inv_scale;
+  std::atomic<int> bad{0};
+  for (int i = first; i <= last; ++i) {
+    const Block& b = e->blocks[i];
+    float* __restrict g = b.grad;
+    e->pool->run(b.n, [&](size_t lo, size_t hi) {
+      float worst = 0.f;   // a NaN or inf anywhere turns this sum of |g| * 0 into NaN
+      for (size_t k = lo; k < hi; ++k) {
+        const float v = g[k] * s;
+        g[k] = v;
+        worst += v * 0.f;
+      }
+      if (!(worst == 0.f)) bad.store(1);
+    });
+  }
+  if (nonfinite) *nonfinite = bad.load();
   return L2L_OK;
 }
 

@@ -240,26 +240,26 @@ __device__ __forceinline__ void gemm_epilogue_atomic(const GemmArgs& g, float* C
 }
 
 // 8 consecutive outputs of one row: v[] = alpha * acc on entry.
-template <typename TC>
+template <typename E, typename TC>
 __device__ __forceinline__ void epilogue8(const GemmArgs& g, TC* C, long long m, long long n, float v[8], bool atomic) {
   float t[8];
   if (g.epi & EPI_BIAS) {
-    load8((const bf16*)g.bias + n, t);
+    load8((const E*)g.bias + n, t);
 #pragma unroll
     for (int i = 0; i < 8; ++i) v[i] += t[i];
   }
   if (g.epi & EPI_GELU) {
-    if (g.aux_out) store8((bf16*)g.aux_out + m * g.ldaux + n, v);
+    if (g.aux_out) store8((E*)g.aux_out + m * g.ldaux + n, v);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] = gelu_fast_f(v[i]);
+    for (int i = 0; i < 8; ++i) v[i] = gelu_epi<E>(v[i]);
   }
   if (g.epi & EPI_GELUGRAD) {
-    load8((const bf16*)g.aux + m * g.ldaux + n, t);
+    load8((const E*)g.aux + m * g.ldaux + n, t);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] *= gelu_grad_fast_f(t[i]);
+    for (int i = 0; i < 8; ++i) v[i] *= gelu_grad_epi<E>(t[i]);
   }
   if (g.epi & EPI_RESID) {
-    load8((const bf16*)g.resid + m * g.ldr + n, t);
+    load8((const E*)g.resid + m * g.ldr + n, t);
 #pragma unroll
     for (int i = 0; i < 8; ++i) v[i] += t[i];
   }
@@ -279,7 +279,7 @@ __device__ __forceinline__ void epilogue8(const GemmArgs& g, TC* C, long long m,
   store8(c, v);
 }
 
-template <int BM, int BN, int BK, int WM, int WN, bool AKC, bool BKC, typename TC>
+template <int BM, int BN, int BK, int WM, int WN, bool AKC, bool BKC, typename TC, typename E = bf16>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_kernel(GemmArgs g) {
   constexpr int NWM = BM / WM, NWN = BN / WN, NT = NWM * NWN * 64;
   constexpr int FM = WM / 32, FN = WN / 32, KK = BK / 16;
@@ -357,7 +357,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_kernel(G
       static_for<0, FM * FN>([&](auto t) {
         constexpr int T = decltype(t)::value;
         constexpr int i = T / FN, j = T % FN;
-        acc[T] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cs * FM + i], bfr[cs * FN + j], acc[T], 0, 0, 0);
+        acc[T] = mfma_32x32x16<E>(af[cs * FM + i], bfr[cs * FN + j], acc[T]);
       });
       __builtin_amdgcn_sched_barrier(0);  // keep at most two fragment sets live
     });
@@ -399,7 +399,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_kernel(G
         if (m < M && n < N) {
           float v[8];
           load8(strip + row * EP_PITCH + c8, v);
-          epilogue8<TC>(g, C, m, n, v, atomic);
+          epilogue8<E, TC>(g, C, m, n, v, atomic);
         }
       }
     } else {
@@ -412,7 +412,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_kernel(G
           if constexpr (sizeof(TC) == 4) {
             if (atomic) { gemm_epilogue_atomic(g, (float*)C, m, n, v); continue; }
           }
-          gemm_epilogue<bf16, TC>(g, C, m, n, v);
+          gemm_epilogue<E, TC>(g, C, m, n, v);
         }
       }
     }
@@ -524,7 +524,7 @@ __device__ __forceinline__ void wait_vm0_lds0() { __builtin_amdgcn_s_waitcnt(0x0
 template <int BM, int BN, int WM, int WN>
 constexpr int dlds_lds_bytes() { return 2 * (BM + BN) * 128; }
 
-template <int BM, int BN, int WM, int WN, bool AKC, bool BKC, typename TC>
+template <int BM, int BN, int WM, int WN, bool AKC, bool BKC, typename TC, typename E = bf16>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_kernel(GemmArgs g) {
   constexpr int BK = 64;
   constexpr int NWM = BM / WM, NWN = BN / WN, NT = NWM * NWN * 64;
@@ -614,7 +614,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
       static_for<0, FM * FN>([&](auto t) {
         constexpr int T = decltype(t)::value;
         constexpr int i = T / FN, j = T % FN;
-        acc[T] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cs * FM + i], bfr[cs * FN + j], acc[T], 0, 0, 0);
+        acc[T] = mfma_32x32x16<E>(af[cs * FM + i], bfr[cs * FN + j], acc[T]);
       });
       __builtin_amdgcn_sched_barrier(0);
     });
@@ -654,7 +654,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
         if (m < M && n < N) {
           float v[8];
           load8(strip + row * EP_PITCH + c8, v);
-          epilogue8<TC>(g, C, m, n, v, atomic);
+          epilogue8<E, TC>(g, C, m, n, v, atomic);
         }
       }
     } else {
@@ -667,7 +667,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
           if constexpr (sizeof(TC) == 4) {
             if (atomic) { gemm_epilogue_atomic(g, (float*)C, m, n, v); continue; }
           }
-          gemm_epilogue<bf16, TC>(g, C, m, n, v);
+          gemm_epilogue<E, TC>(g, C, m, n, v);
         }
       }
     }

@@ -1,5 +1,5 @@
-// One tile variant of the bf16 MFMA GEMM (selected with -DL2L_VARIANT=<index>): all four operand
-// layouts, bf16 and fp32 outputs.
+// One tile variant of the 16-bit MFMA GEMM (selected with -DL2L_VARIANT=<index>): all four operand
+// layouts, 16-bit and fp32 outputs.
 #include "gemm.h"
 #include "gemm_variants.h"
 
@@ -9,11 +9,11 @@
 
 namespace {
 
-template <int BM, int BN, int BK, int WM, int WN, bool AKC, bool BKC, typename TC>
+template <int BM, int BN, int BK, int WM, int WN, bool AKC, bool BKC, typename TC, typename E>
 void launch_one(const GemmArgs& g, hipStream_t s, int splits) {
   constexpr int LDS = 2 * (TileLds<BM, BK>::BYTES + TileLds<BN, BK>::BYTES);
   static_assert(LDS <= 160 * 1024, "tile does not fit the 160 KB LDS");
-  auto kern = gemm_mfma_kernel<BM, BN, BK, WM, WN, AKC, BKC, TC>;
+  auto kern = gemm_mfma_kernel<BM, BN, BK, WM, WN, AKC, BKC, TC, E>;
   static const bool once = [&] {
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     return true;
@@ -24,21 +24,21 @@ void launch_one(const GemmArgs& g, hipStream_t s, int splits) {
   hipLaunchKernelGGL(kern, grid, block, LDS, s, g);
 }
 
-template <int BM, int BN, int BK, int WM, int WN, typename TC>
+template <int BM, int BN, int BK, int WM, int WN, typename TC, typename E>
 void launch_layout(const GemmArgs& g, hipStream_t s, int splits) {
-  if (g.a_kc && g.b_kc) launch_one<BM, BN, BK, WM, WN, true, true, TC>(g, s, splits);
-  else if (g.a_kc && !g.b_kc) launch_one<BM, BN, BK, WM, WN, true, false, TC>(g, s, splits);
-  else if (!g.a_kc && g.b_kc) launch_one<BM, BN, BK, WM, WN, false, true, TC>(g, s, splits);
-  else launch_one<BM, BN, BK, WM, WN, false, false, TC>(g, s, splits);
+  if (g.a_kc && g.b_kc) launch_one<BM, BN, BK, WM, WN, true, true, TC, E>(g, s, splits);
+  else if (g.a_kc && !g.b_kc) launch_one<BM, BN, BK, WM, WN, true, false, TC, E>(g, s, splits);
+  else if (!g.a_kc && g.b_kc) launch_one<BM, BN, BK, WM, WN, false, true, TC, E>(g, s, splits);
+  else launch_one<BM, BN, BK, WM, WN, false, false, TC, E>(g, s, splits);
 }
 
 }  // namespace
 
-template <int BM, int BN, int WM, int WN, bool AKC, bool BKC, typename TC>
+template <int BM, int BN, int WM, int WN, bool AKC, bool BKC, typename TC, typename E>
 void launch_direct_one(const GemmArgs& g, hipStream_t s, int splits) {
   constexpr int LDS = dlds_lds_bytes<BM, BN, WM, WN>();
   static_assert(LDS <= 160 * 1024, "tile does not fit the 160 KB LDS");
-  auto kern = gemm_mfma_dlds_kernel<BM, BN, WM, WN, AKC, BKC, TC>;
+  auto kern = gemm_mfma_dlds_kernel<BM, BN, WM, WN, AKC, BKC, TC, E>;
   static const bool once = [&] {
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     return true;
@@ -51,11 +51,11 @@ void launch_direct_one(const GemmArgs& g, hipStream_t s, int splits) {
 
 // the direct-to-LDS kernel is built for the two layout pairs that carry the layer's work: both operands
 // K-contiguous (forward with transposed weights, dX) and both K-strided (dW)
-template <int BM, int BN, int WM, int WN, typename TC>
+template <int BM, int BN, int WM, int WN, typename TC, typename E>
 void launch_direct(const GemmArgs& g, hipStream_t s, int splits) {
-  if (g.a_kc && g.b_kc) launch_direct_one<BM, BN, WM, WN, true, true, TC>(g, s, splits);
-  else if (g.a_kc) launch_direct_one<BM, BN, WM, WN, true, false, TC>(g, s, splits);
-  else launch_direct_one<BM, BN, WM, WN, false, false, TC>(g, s, splits);
+  if (g.a_kc && g.b_kc) launch_direct_one<BM, BN, WM, WN, true, true, TC, E>(g, s, splits);
+  else if (g.a_kc) launch_direct_one<BM, BN, WM, WN, true, false, TC, E>(g, s, splits);
+  else launch_direct_one<BM, BN, WM, WN, false, false, TC, E>(g, s, splits);
 }
 
 struct TileCfg { int bm, bn, bk, wm, wn, direct; };
@@ -66,12 +66,22 @@ constexpr TileCfg kThis = kCfg[L2L_VARIANT];
 
 #define L2L_CAT2(a, b) a##b
 #define L2L_CAT(a, b) L2L_CAT2(a, b)
-void L2L_CAT(l2l_launch_mfma_v, L2L_VARIANT)(const GemmArgs& g, hipStream_t s, int splits, bool out_f32) {
-  if constexpr (kThis.direct) {   // callers pick these variants only for K-contiguous operand pairs
-    if (out_f32) launch_direct<kThis.bm, kThis.bn, kThis.wm, kThis.wn, float>(g, s, splits);
-    else launch_direct<kThis.bm, kThis.bn, kThis.wm, kThis.wn, bf16>(g, s, 1);
+// The element type of the 16-bit operands is fixed per translation unit (-DL2L_ELEM_FP16 selects IEEE half, default
+// bfloat16), so that each format's kernels sit in a code object of their own.
+#ifdef L2L_ELEM_FP16
+typedef fp16 Elem;
+#define L2L_LAUNCH_NAME L2L_CAT(l2l_launch_mfma_h, L2L_VARIANT)
+#else
+typedef bf16 Elem;
+#define L2L_LAUNCH_NAME L2L_CAT(l2l_launch_mfma_v, L2L_VARIANT)
+#endif
+
+void L2L_LAUNCH_NAME(const GemmArgs& g, hipStream_t s, int splits, bool out_f32) {
+  if constexpr (kThis.direct) {   // callers pick these variants for every layout pair but (A K-strided, B K-contiguous)
+    if (out_f32) launch_direct<kThis.bm, kThis.bn, kThis.wm, kThis.wn, float, Elem>(g, s, splits);
+    else launch_direct<kThis.bm, kThis.bn, kThis.wm, kThis.wn, Elem, Elem>(g, s, 1);
   } else {
-    if (out_f32) launch_layout<kThis.bm, kThis.bn, kThis.bk, kThis.wm, kThis.wn, float>(g, s, splits);
-    else launch_layout<kThis.bm, kThis.bn, kThis.bk, kThis.wm, kThis.wn, bf16>(g, s, 1);
+    if (out_f32) launch_layout<kThis.bm, kThis.bn, kThis.bk, kThis.wm, kThis.wn, float, Elem>(g, s, splits);
+    else launch_layout<kThis.bm, kThis.bn, kThis.bk, kThis.wm, kThis.wn, Elem, Elem>(g, s, 1);
   }
 }

@@ -19,6 +19,8 @@
 constexpr int kNumGemmVariants = 9;
 
 // launches variant `index` (layouts and output type taken from the arguments)
-#define L2L_DECLARE(i, bm, bn, bk, wm, wn, d) void l2l_launch_mfma_v##i(const GemmArgs& g, hipStream_t s, int splits, bool out_f32);
+#define L2L_DECLARE(i, bm, bn, bk, wm, wn, d)                                                      \
+  void l2l_launch_mfma_v##i(const GemmArgs& g, hipStream_t s, int splits, bool out_f32); /* bf16 */ \
+  void l2l_launch_mfma_h##i(const GemmArgs& g, hipStream_t s, int splits, bool out_f32); /* fp16 */
 L2L_GEMM_VARIANTS(L2L_DECLARE)
 #undef L2L_DECLARE

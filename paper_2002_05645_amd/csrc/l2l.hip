@@ -40,7 +40,7 @@ bool config_ok(const l2l_config* c) {
   if (c->hidden <= 0 || c->heads <= 0 || c->ffn <= 0 || c->seq <= 0 || c->ubatch <= 0 || c->num_ubatches <= 0) return false;
   if (c->hidden % 8 || c->ffn % 8 || c->seq % 8) return false;
   if (c->hidden % c->heads || (c->hidden / c->heads) % 8) return false;
-  if (c->dtype != L2L_F32 && c->dtype != L2L_BF16) return false;
+  if (c->dtype != L2L_F32 && c->dtype != L2L_BF16 && c->dtype != L2L_FP16) return false;
   if (c->vocab < 0 || c->vocab % 2) return false;
   if (c->ubatch_group < 0 || c->ubatch_group > c->num_ubatches) return false;
   if (!(c->ln_eps >= 0.f)) return false;
@@ -62,7 +62,8 @@ Layout make_layout(const l2l_config* c) {
   return L;
 }
 
-inline size_t esize(int dtype) { return dtype == L2L_BF16 ? 2 : 4; }
+inline size_t esize(int dtype) { return dtype == L2L_F32 ? 4 : 2; }
+inline bool is16(int dtype) { return dtype == L2L_BF16 || dtype == L2L_FP16; }
 
 }  // namespace
 
@@ -140,6 +141,7 @@ struct l2l_ctx {
   float *emean = nullptr, *erstd = nullptr;
   int32_t *lab_idx = nullptr, *lab_cnt = nullptr, *lab_total = nullptr, *lab_gidx = nullptr, *chunk_cnt = nullptr;
   long long head_rows = 0;   // labelled rows per pass of the head
+  float loss_scale = 1.0f;   // factor on the loss gradient (fp16 training)
   void *xl = nullptr, *dz = nullptr, *dxl = nullptr;
   float* logits = nullptr;
   long long Vp = 0;
@@ -270,9 +272,10 @@ constexpr TileCfg kTiles[] = {L2L_GEMM_VARIANTS(L2L_ROW)};
 #undef L2L_ROW
 constexpr int kNumTiles = kNumGemmVariants;
 
-void launch_mfma_variant(int v, const GemmArgs& g, hipStream_t s, int splits, bool out_f32) {
+void launch_mfma_variant(int v, const GemmArgs& g, hipStream_t s, int splits, bool out_f32, bool fp16_in) {
   switch (v) {
-#define L2L_CASE(i, bm, bn, bk, wm, wn, d) case i: l2l_launch_mfma_v##i(g, s, splits, out_f32); break;
+#define L2L_CASE(i, bm, bn, bk, wm, wn, d) \
+  case i: fp16_in ? l2l_launch_mfma_h##i(g, s, splits, out_f32) : l2l_launch_mfma_v##i(g, s, splits, out_f32); break;
     L2L_GEMM_VARIANTS(L2L_CASE)
 #undef L2L_CASE
     default: break;
@@ -315,7 +318,7 @@ void pick_tile(const GemmArgs& g, bool out_f32, int* variant, int* splits) {
 int gemm(l2l_ctx* c, int dtype, bool out_f32, const GemmArgs& g, int impl = 0, int cls = L2L_PROF_GEMM) {
   if (g.M <= 0 || g.N <= 0 || g.nbatch <= 0) return L2L_OK;
   if (g.nbatch > 65535 || (g.M + 63) / 64 > 65535) return fail(c, L2L_E_ARG, "gemm: grid too large");
-  const bool can_mfma = dtype == L2L_BF16 && mfma_ok(g);
+  const bool can_mfma = is16(dtype) && mfma_ok(g);
   if (impl >= 2 && !can_mfma) return fail(c, L2L_E_ARG, "gemm: shape/alignment not supported by the MFMA kernel");
   if (impl >= 100 + kNumTiles) return fail(c, L2L_E_ARG, "gemm: no such tile variant");
   const bool use_mfma = impl >= 2 || (impl == 0 && can_mfma);
@@ -330,10 +333,13 @@ int gemm(l2l_ctx* c, int dtype, bool out_f32, const GemmArgs& g, int impl = 0, i
       if (kTiles[v].direct && !g.a_kc && g.b_kc) v = 3;   // no direct-to-LDS kernel for A K-strided with B K-contiguous
       if (const char* e = getenv("L2L_FORCE_SPLITS")) g_force_splits = atoi(e);
       if (g_force_splits > 0 && out_f32 && g.epi == EPI_ACCUM) splits = g_force_splits;
-      launch_mfma_variant(v, g, c->cs, splits, out_f32);
+      launch_mfma_variant(v, g, c->cs, splits, out_f32, dtype == L2L_FP16);
     } else if (dtype == L2L_BF16) {
       if (out_f32) launch_plain<bf16, float>(g, c->cs);
       else launch_plain<bf16, bf16>(g, c->cs);
+    } else if (dtype == L2L_FP16) {
+      if (out_f32) launch_plain<fp16, float>(g, c->cs);
+      else launch_plain<fp16, fp16>(g, c->cs);
     } else {
       launch_plain<float, float>(g, c->cs);
     }
@@ -431,7 +437,7 @@ int fill_zero(l2l_ctx* c, void* p, size_t bytes) {
 // transposed once, on the copy stream right behind the stage's DMA, so that the work overlaps the
 // previous layer's compute and all micro-batches share the result.
 int transpose_weights(l2l_ctx* c, int slot) {
-  if (c->cfg.dtype != L2L_BF16) return L2L_OK;
+  if (!is16(c->cfg.dtype)) return L2L_OK;   // the transpose moves 16-bit elements whatever their format
   const int H = c->cfg.hidden, F = c->cfg.ffn;
   const long long* off = c->lay.off;
   const struct { int t, rows, cols; } m[4] = {{T_WQKV, H, 3 * H}, {T_WO, H, H}, {T_W1, H, F}, {T_W2, F, H}};
@@ -460,7 +466,7 @@ int layer_forward_group(l2l_ctx* c, int slot, const void* x, void* y, int ng, bo
   const long long* off = c->lay.off;
   T* qkv = (T*)c->qkv;
   // weight operand of a forward GEMM: [out, in] copy (bf16) or the packed [in, out] matrix (fp32)
-  const bool tw = dt == L2L_BF16;
+  const bool tw = is16(dt);
   const T* W = tw ? (const T*)c->wt[slot] : P;
   auto wld = [&](int in, int out) { return (long long)(tw ? in : out); };
 
@@ -669,7 +675,7 @@ int head_loss_t(l2l_ctx* c, const void* x_last, const int32_t* labels, void* dy_
     L2L_TRY(gemm(c, dt, true, g, 0, L2L_PROF_OTHER));
     L2L_TRY(timed(c, L2L_PROF_OTHER, 0, 0, [&] {
       hipLaunchKernelGGL(ce_kernel<T>, dim3(rows), dim3(256), 0, c->cs, c->logits, Vp, labels, idx, cnt, c->lab_total, (T*)c->dz,
-                         loss_out, V, (int)Vp);
+                         loss_out, V, (int)Vp, c->loss_scale);
     }));
     // dXl = dz E
     GemmArgs h = gemm_args(rows, H, V, c->dz, Vp, 1, E + eo[E_E], H, 0, c->dxl, H);
@@ -775,7 +781,7 @@ int l2l_create(const l2l_config* cfg, void* compute_stream, void* copy_stream, l
       {&c->ga, Mg * F}, {&c->r2, Mg * H}, {&c->dr2, Mg * H}, {&c->du1, Mg * F}, {&c->dy1, Mg * H}, {&c->dr1, Mg * H},
       {&c->dc, Mg * H}, {&c->dp, pe}, {&c->dqkv, Mg * 3 * H}, {&c->ytmp, Mg * H}};
   for (auto& b : bufs) L2L_TRY(dev_alloc(c, b.p, b.n * es));
-  if (cfg->dtype == L2L_BF16)
+  if (is16(cfg->dtype))
     for (int i = 0; i < 2; ++i) L2L_TRY(dev_alloc(c, &c->wt[i], c->lay.total * es));
   float** stats[] = {&c->mean1, &c->rstd1, &c->mean2, &c->rstd2};
   for (auto s : stats) L2L_TRY(dev_alloc(c, (void**)s, Mg * 4));
@@ -861,6 +867,7 @@ int l2l_layer_fwd(l2l_ctx* c, int layer, int slot, const void* x_stash, void* y_
     const void* x = (const char*)x_stash + o;
     void* y = (char*)y_out + o;
     if (c->cfg.dtype == L2L_BF16) L2L_TRY(layer_forward_group<bf16>(c, slot, x, y, ng, false));
+    else if (c->cfg.dtype == L2L_FP16) L2L_TRY(layer_forward_group<fp16>(c, slot, x, y, ng, false));
     else L2L_TRY(layer_forward_group<float>(c, slot, x, y, ng, false));
   }
   HIP_TRY(c, hipEventRecord(c->slot_released[slot], c->cs));
@@ -885,6 +892,9 @@ int l2l_layer_bwd(l2l_ctx* c, int layer, int slot, const void* x_stash, void* dy
     if (c->cfg.dtype == L2L_BF16) {
       L2L_TRY(layer_forward_group<bf16>(c, slot, x, nullptr, ng, true));  // recompute
       L2L_TRY(layer_backward_group<bf16>(c, c->slot[slot], x, dy, G, ng));
+    } else if (c->cfg.dtype == L2L_FP16) {
+      L2L_TRY(layer_forward_group<fp16>(c, slot, x, nullptr, ng, true));
+      L2L_TRY(layer_backward_group<fp16>(c, c->slot[slot], x, dy, G, ng));
     } else {
       L2L_TRY(layer_forward_group<float>(c, slot, x, nullptr, ng, true));
       L2L_TRY(layer_backward_group<float>(c, c->slot[slot], x, dy, G, ng));
@@ -957,6 +967,7 @@ int l2l_embed_fwd(l2l_ctx* c, const int32_t* tokens, void* x_out) {
   if (c->egacc_state == 2) HIP_TRY(c, hipStreamWaitEvent(c->cs, c->egacc_drained, 0));
   c->egacc_state = 0;   // the accumulator is zero: cleared at creation and after every drain
   if (c->cfg.dtype == L2L_BF16) L2L_TRY(embed_fwd_t<bf16>(c, tokens, x_out));
+  else if (c->cfg.dtype == L2L_FP16) L2L_TRY(embed_fwd_t<fp16>(c, tokens, x_out));
   else L2L_TRY(embed_fwd_t<float>(c, tokens, x_out));
   HIP_TRY(c, hipEventRecord(c->emb_released_ev, c->cs));
   return L2L_OK;
@@ -969,6 +980,7 @@ int l2l_head_loss(l2l_ctx* c, const void* x_last, const int32_t* labels, void* d
   if (!c->emb_staged) return fail(c, L2L_E_STATE, "l2l_head_loss: embedding block never staged");
   HIP_TRY(c, hipStreamWaitEvent(c->cs, c->emb_staged_ev, 0));
   if (c->cfg.dtype == L2L_BF16) L2L_TRY(head_loss_t<bf16>(c, x_last, labels, dy_out, loss_out));
+  else if (c->cfg.dtype == L2L_FP16) L2L_TRY(head_loss_t<fp16>(c, x_last, labels, dy_out, loss_out));
   else L2L_TRY(head_loss_t<float>(c, x_last, labels, dy_out, loss_out));
   HIP_TRY(c, hipEventRecord(c->emb_released_ev, c->cs));
   return L2L_OK;
@@ -980,6 +992,7 @@ int l2l_embed_bwd(l2l_ctx* c, const int32_t* tokens, const void* dy) {
   if (!tokens || !dy) return fail(c, L2L_E_ARG, "l2l_embed_bwd: null pointer");
   if (!c->emb_staged) return fail(c, L2L_E_STATE, "l2l_embed_bwd: embedding block never staged");
   if (c->cfg.dtype == L2L_BF16) L2L_TRY(embed_bwd_t<bf16>(c, tokens, dy));
+  else if (c->cfg.dtype == L2L_FP16) L2L_TRY(embed_bwd_t<fp16>(c, tokens, dy));
   else L2L_TRY(embed_bwd_t<float>(c, tokens, dy));
   HIP_TRY(c, hipEventRecord(c->emb_released_ev, c->cs));
   HIP_TRY(c, hipEventRecord(c->egacc_ready, c->cs));
@@ -1006,6 +1019,13 @@ int l2l_embed_drain_wait(l2l_ctx* c) {
   L2L_TRY(need_vocab(c, "l2l_embed_drain_wait"));
   if (c->egacc_state != 2) return fail(c, L2L_E_STATE, "l2l_embed_drain_wait: no drain in flight");
   HIP_TRY(c, hipEventSynchronize(c->egacc_landed));
+  return L2L_OK;
+}
+
+int l2l_set_loss_scale(l2l_ctx* c, float scale) {
+  if (!c) return L2L_E_ARG;
+  if (!(scale > 0.f) || !std::isfinite(scale)) return fail(c, L2L_E_ARG, "l2l_set_loss_scale: scale must be positive and finite");
+  c->loss_scale = scale;
   return L2L_OK;
 }
 
@@ -1129,7 +1149,7 @@ int l2l_op_gemm(l2l_ctx* c, int in_dtype, int out_f32, int a_kc, int b_kc, int M
   if (!c) return L2L_E_ARG;
   if (!A || !B || !C) return fail(c, L2L_E_ARG, "l2l_op_gemm: null pointer");
   if (M < 0 || N < 0 || K < 0 || lda <= 0 || ldb <= 0 || ldc < N) return fail(c, L2L_E_ARG, "l2l_op_gemm: bad shape");
-  if (in_dtype != L2L_F32 && in_dtype != L2L_BF16) return fail(c, L2L_E_ARG, "l2l_op_gemm: bad dtype");
+  if (in_dtype != L2L_F32 && in_dtype != L2L_BF16 && in_dtype != L2L_FP16) return fail(c, L2L_E_ARG, "l2l_op_gemm: bad dtype");
   if (in_dtype == L2L_F32) out_f32 = 1;
   if (accumulate && !out_f32) return fail(c, L2L_E_ARG, "l2l_op_gemm: accumulate needs an fp32 output");
   if (impl < 0 || (impl > 2 && impl < 100)) return fail(c, L2L_E_ARG, "l2l_op_gemm: impl %d", impl);
@@ -1149,6 +1169,7 @@ int l2l_op_layernorm(l2l_ctx* c, int dtype, int rows, int n, const void* x, cons
   if (rows < 0 || n <= 0 || n % 8) return fail(c, L2L_E_ARG, "l2l_op_layernorm: n must be a positive multiple of 8");
   if ((mean == nullptr) != (rstd == nullptr)) return fail(c, L2L_E_ARG, "l2l_op_layernorm: mean and rstd go together");
   if (dtype == L2L_BF16) return ln_fwd<bf16>(c, x, gamma, beta, y, mean, rstd, rows, n, eps);
+  if (dtype == L2L_FP16) return ln_fwd<fp16>(c, x, gamma, beta, y, mean, rstd, rows, n, eps);
   if (dtype == L2L_F32) return ln_fwd<float>(c, x, gamma, beta, y, mean, rstd, rows, n, eps);
   return fail(c, L2L_E_ARG, "l2l_op_layernorm: bad dtype");
 }

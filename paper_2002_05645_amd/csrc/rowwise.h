@@ -387,11 +387,12 @@ __global__ __launch_bounds__(256) void rows_by_index_kernel(const T* src, T* dst
 }
 
 // Cross-entropy over one row of logits z[Vp] (first V valid): adds (lse - z[label]) / N to *loss and
-// writes dz = (softmax(z) - onehot) / N in T, zero in the padding columns.  One block per row.
+// writes dz = scale * (softmax(z) - onehot) / N in T (scale: the loss scale of fp16 training, 1 otherwise),
+// zero in the padding columns.  One block per row.
 template <typename T>
 __global__ __launch_bounds__(256) void ce_kernel(const float* z, long long ldz, const int32_t* labels,
                                                  const int32_t* idx, const int32_t* cnt, const int32_t* total, T* dz,
-                                                 float* loss, int V, int Vp) {
+                                                 float* loss, int V, int Vp, float scale) {
   __shared__ float red[4];
   const int i = blockIdx.x;
   if (i >= *cnt) return;
@@ -418,7 +419,7 @@ __global__ __launch_bounds__(256) void ce_kernel(const float* z, long long ldz, 
   const float inv_s = 1.0f / s;
   for (int j = t; j < Vp; j += 256) {
     float v = 0.f;
-    if (j < V) v = (__expf(row[j] - mx) * inv_s - (j == label ? 1.0f : 0.0f)) * inv_n;
+    if (j < V) v = (__expf(row[j] - mx) * inv_s - (j == label ? 1.0f : 0.0f)) * (inv_n * scale);
     d[j] = from_f32<T>(v);
   }
 }

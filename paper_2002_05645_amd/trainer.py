@@ -30,11 +30,37 @@ def unpack(layout, shapes, flat) -> dict:
     return {k: np.array(flat[off:off + n]).reshape(shapes[k]) for k, (off, n) in layout.items()}
 
 
+class LossScaler:
+    """Dynamic loss scale of mixed-precision training (Section 2.3 leaves the policy open; this is the usual one):
+    an overflow (a non-finite gradient) skips the update and halves the scale; `growth_interval` consecutive good
+    steps double it.  static=True keeps the scale fixed and only reports overflows."""
+
+    def __init__(self, scale=2.0 ** 15, growth_interval=1000, static=False, min_scale=1.0, max_scale=2.0 ** 24):
+        self.scale, self.growth_interval, self.static = float(scale), int(growth_interval), bool(static)
+        self.min_scale, self.max_scale = float(min_scale), float(max_scale)
+        self.good_steps = 0
+        self.skipped = 0
+
+    def update(self, overflow: bool) -> bool:
+        """Call once per step with whether the gradients overflowed; returns whether to apply the update."""
+        if overflow:
+            self.skipped += 1
+            self.good_steps = 0
+            if not self.static:
+                self.scale = max(self.min_scale, self.scale / 2.0)
+            return False
+        self.good_steps += 1
+        if not self.static and self.good_steps >= self.growth_interval:
+            self.scale = min(self.max_scale, self.scale * 2.0)
+            self.good_steps = 0
+        return True
+
+
 class L2LTrainer:
     def __init__(self, *, layers, hidden, heads, ffn, seq, vocab, ubatch, num_ubatches, dtype="bf16",
                  ln_eps=1e-12, lr=1e-4, beta1=0.9, beta2=0.999, eps_a=1e-8, ubatch_group=0,
                  eps_threads=0, stash="device", device="cuda:0", eager=False, optimizer="adam", weight_decay=0.0,
-                 copy_cus=0, run_ahead=2):
+                 copy_cus=0, run_ahead=2, loss_scale=None, dynamic_loss_scale=True, scale_growth_interval=1000):
         assert stash in ("device", "host")
         assert optimizer in ("adam", "lamb")
         self.optimizer = optimizer
@@ -76,7 +102,14 @@ class L2LTrainer:
         else:
             self.copy = torch.cuda.Stream(device=self.device)
         self.ctx = B.Context(self.cfg, self.compute.cuda_stream, self.copy.cuda_stream)
-        tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+        tdt = {"bf16": torch.bfloat16, "fp16": torch.float16, "fp32": torch.float32}[dtype]
+        # Loss scaling: on by default for fp16 (2^15, dynamic), off otherwise.  The eager per-layer update commits a
+        # layer before the rest of the step's gradients are known, so it cannot skip a step: there the scale is static
+        # and an overflow raises.
+        if loss_scale is None:
+            loss_scale = 2.0 ** 15 if dtype == "fp16" else 1.0
+        self.scaler = LossScaler(loss_scale, scale_growth_interval, static=eager or not dynamic_loss_scale or loss_scale == 1.0)
+        self.ctx.set_loss_scale(self.scaler.scale)
         shape = (num_ubatches, ubatch, seq, hidden)
         n_stash = layers + 1 if stash == "device" else 2
         self.stash = [torch.empty(shape, dtype=tdt, device=self.device) for _ in range(n_stash)]
@@ -170,7 +203,10 @@ class L2LTrainer:
         c.embed_grad_drain(e.grad_ptr(0))
         self._after_drain(0)
 
-    def _eps_update(self, first, last, t):
+    def _eps_update(self, first, last, t, unscale=True):
+        if unscale and self.scaler.scale != 1.0:
+            if self.eps.grad_unscale(first, last, 1.0 / self.scaler.scale):
+                raise FloatingPointError(f"gradient overflow in blocks {first}..{last} at loss scale {self.scaler.scale}")
         if self.optimizer == "adam":
             self.eps.adam_step(first, last, t, **self.hp)
             return
@@ -234,8 +270,16 @@ class L2LTrainer:
                 raise self._worker_error
             self.t += 1
             return
+        if self.scaler.scale != 1.0:
+            overflow = self.eps.grad_unscale(0, self.L, 1.0 / self.scaler.scale)
+            if self.scaler.static and overflow:
+                raise FloatingPointError(f"gradient overflow at loss scale {self.scaler.scale}")
+            apply = self.scaler.update(overflow)
+            self.ctx.set_loss_scale(self.scaler.scale)
+            if not apply:
+                return                    # step skipped: weights, moments and t unchanged
         self.t += 1
-        self._eps_update(0, self.L, self.t)
+        self._eps_update(0, self.L, self.t, unscale=False)
 
     def step(self, tokens, labels) -> float:
         self.device_pipeline(tokens, labels)

@@ -16,8 +16,10 @@ from gpu_util import to_dev, to_host, rounded, pinned
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"fp32": 1e-4, "bf16": 2e-2}
-DT = {"fp32": P.L2L_F32, "bf16": P.L2L_BF16}
+# fp16 carries 11 significand bits against bf16's 8: its bar is 8x tighter
+TOL = {"fp32": 1e-4, "bf16": 2e-2, "fp16": 2.5e-3}
+DT = {"fp32": P.L2L_F32, "bf16": P.L2L_BF16, "fp16": P.L2L_FP16}
+OUT16 = {"fp32": 2e-6, "bf16": 3e-3, "fp16": 4e-4}      # one rounding of a 16-bit (or no rounding of an fp32) output
 
 
 @pytest.fixture(scope="module")
@@ -74,18 +76,18 @@ def _gemm_case(ctx, dtype, impl, a_kc, b_kc, M, N, K, bias=False, resid=False, g
 
 
 @pytest.mark.parametrize("a_kc,b_kc", [(1, 0), (1, 1), (0, 0), (0, 1)])
-@pytest.mark.parametrize("dtype,impl", [("fp32", 1), ("bf16", 1), ("bf16", 2)])
+@pytest.mark.parametrize("dtype,impl", [("fp32", 1), ("bf16", 1), ("bf16", 2), ("fp16", 1), ("fp16", 2)])
 def test_gemm_layouts_ragged(ctx, dtype, impl, a_kc, b_kc):
     for (M, N, K) in [(200, 136, 96), (128, 128, 32), (1, 8, 8), (300, 72, 264), (130, 258, 40)]:
         err = _gemm_case(ctx, dtype, impl, a_kc, b_kc, M, N, K, out_f32=True, seed=M + N)
         assert err < 2e-6, (M, N, K, err)
         err = _gemm_case(ctx, dtype, impl, a_kc, b_kc, M, N, K, bias=True, resid=True, seed=M)
-        assert err < (2e-6 if dtype == "fp32" else 3e-3), (M, N, K, err)
+        assert err < OUT16[dtype], (M, N, K, err)
 
 
-@pytest.mark.parametrize("dtype,impl", [("fp32", 1), ("bf16", 1), ("bf16", 2)])
+@pytest.mark.parametrize("dtype,impl", [("fp32", 1), ("bf16", 1), ("bf16", 2), ("fp16", 1), ("fp16", 2)])
 def test_gemm_epilogues(ctx, dtype, impl):
-    lim = 2e-6 if dtype == "fp32" else 3e-3
+    lim = OUT16[dtype]
     assert _gemm_case(ctx, dtype, impl, 1, 0, 256, 192, 128, bias=True, gelu=True, alpha=0.1) < lim
     assert _gemm_case(ctx, dtype, impl, 0, 0, 192, 256, 520, accumulate=True, out_f32=True) < 2e-6
     assert _gemm_case(ctx, dtype, impl, 1, 1, 264, 136, 64, alpha=0.125, out_f32=True) < 2e-6
@@ -98,6 +100,8 @@ def test_gemm_large_tile_sweep(ctx):
     assert _gemm_case(ctx, "bf16", 2, 1, 0, 1000, 520, 264, bias=True, out_f32=True) < 2e-6
     assert _gemm_case(ctx, "bf16", 2, 1, 1, 520, 1000, 136, out_f32=True) < 2e-6
     assert _gemm_case(ctx, "bf16", 2, 0, 0, 520, 392, 1000, out_f32=True) < 2e-6
+    assert _gemm_case(ctx, "fp16", 2, 1, 1, 520, 1000, 136, bias=True) < OUT16["fp16"]
+    assert _gemm_case(ctx, "fp16", 2, 0, 0, 520, 392, 1000, out_f32=True) < 2e-6
 
 
 def test_gemm_rejects_bad_arguments(ctx):
@@ -112,7 +116,7 @@ def test_gemm_rejects_bad_arguments(ctx):
 
 
 # ------------------------------------------------------------------------------------- LayerNorm kernel
-@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("dtype", ["fp32", "bf16", "fp16"])
 @pytest.mark.parametrize("rows,n", [(1, 8), (37, 1024), (5, 200), (130, 6144)])
 def test_layernorm(ctx, dtype, rows, n):
     rng = np.random.default_rng(rows)
@@ -126,7 +130,7 @@ def test_layernorm(ctx, dtype, rows, n):
     ctx.op_layernorm(DT[dtype], rows, n, xd, gd, bd, 1e-12, yd, mean, rstd)
     torch.cuda.synchronize()
     ref, (xhat, rs) = O.layer_norm_fwd(rounded(x, dtype), rounded(g, dtype), rounded(b, dtype), 1e-12)
-    assert O.rel_l2(to_host(yd), ref) < (2e-6 if dtype == "fp32" else 3e-3)
+    assert O.rel_l2(to_host(yd), ref) < OUT16[dtype]
     assert O.rel_l2(to_host(rstd), rs[:, 0]) < 1e-5
     assert O.rel_l2(to_host(mean), rounded(x, dtype).mean(-1)) < 1e-5
 
@@ -141,7 +145,7 @@ def _layer_case(w: S.Workload, group=0, x_scale=1.0, check_fwd_only=False):
         total = P.lib().l2l_layer_packed_elems(cfg)
         p32 = S.layer_params(w, 0)
         flat = pack(lay, total, p32)
-        host = pinned(O.bf16_bits(flat).view(np.int16) if dtype == "bf16" else flat)
+        host = pinned(O.bf16_bits(flat).view(np.int16) if dtype == "bf16" else O.fp16_bits(flat).view(np.int16) if dtype == "fp16" else flat)
         pr = {k: rounded(v, dtype) for k, v in p32.items()}
         X = S.activations(w) * x_scale
         dY = S.output_grads(w)
@@ -198,6 +202,14 @@ def test_layer_ragged_bf16():
     _assert_errs(_layer_case(w32, group=2), TOL["fp32"])
 
 
+def test_layer_fp16():
+    # the paper's device precision (Section 2.3): same kernels on IEEE half; ragged and tile-sized shapes
+    w = S.Workload("ragged16", 1, 96, 3, 200, 24, 50, 3, 3, "fp16", 1.0, 177)
+    _assert_errs(_layer_case(w, group=2), TOL["fp16"])
+    w = S.WORKLOADS[1].scaled(num_ubatches=2, ubatch=4, dtype="fp16")
+    _assert_errs(_layer_case(w), TOL["fp16"])
+
+
 def test_layer_single_sequence_single_ubatch():
     w = S.Workload("one", 1, 64, 1, 64, 8, 50, 1, 1, "bf16", 1.0, 78)
     _assert_errs(_layer_case(w), TOL["bf16"])
@@ -243,11 +255,11 @@ def test_layer_seq512_bf16():
 
 
 # ------------------------------------------------------------------------------------- whole step
-def _step_case(w: S.Workload, stash="device", group=0, lr=1e-4, eager=False):
+def _step_case(w: S.Workload, stash="device", group=0, lr=1e-4, eager=False, **trainer_kw):
     dtype = w.dtype
     tr = L2LTrainer(layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, vocab=w.vocab,
                     ubatch=w.ubatch, num_ubatches=w.num_ubatches, dtype=dtype, lr=lr, stash=stash, ubatch_group=group,
-                    eps_threads=8, eager=eager)
+                    eps_threads=8, eager=eager, **trainer_kw)
     try:
         assert tr.eps.is_pinned()
         emb = S.embed_params(w)
@@ -403,6 +415,51 @@ def test_step_with_a_micro_batch_without_labels():
         errs = {"emb." + k: O.rel_l2(ge[k], gemb[k]) for k in gemb}
         errs.update({f"l{l}.{k}": O.rel_l2(glayers[l][k], gl[l][k]) for l in range(w.layers) for k in gl[l]})
         _assert_errs(errs, TOL["fp32"])
+    finally:
+        tr.close()
+
+
+# ------------------------------------------------------------------------------------- fp16 with loss scaling
+@pytest.mark.parametrize("eager", [False, True])
+def test_step_fp16_with_loss_scale(eager):
+    # Section 2.3's device precision: IEEE half with the loss gradient scaled by 2^15 and the scale divided out on the host
+    w = S.WORKLOADS[0].scaled(dtype="fp16")
+    errs, loss, loss_ref = _step_case(w, eager=eager)
+    _assert_errs({k: v for k, v in errs.items() if not k.startswith("adam.")}, TOL["fp16"])
+    _assert_errs({k: v for k, v in errs.items() if k.startswith("adam.")}, 2e-3)
+
+
+def test_fp16_without_loss_scale_loses_the_small_gradients():
+    # the loss gradient per logit is ~1/(N V) ~ 1e-6, in half precision's subnormal range: without scaling the
+    # gradients come out several times less accurate than with it (why Section 2.3 scales the loss)
+    w = S.WORKLOADS[0].scaled(dtype="fp16")
+    scaled, _, _ = _step_case(w)
+    unscaled, _, _ = _step_case(w, loss_scale=1.0)
+    grads = [k for k in scaled if not k.startswith("adam.") and k != "loss"]
+    assert max(unscaled[k] for k in grads) > 4 * max(scaled[k] for k in grads)
+
+
+def test_fp16_overflow_skips_the_step_and_halves_the_scale():
+    w = S.WORKLOADS[0].scaled(dtype="fp16")
+    tr = L2LTrainer(layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, vocab=w.vocab, ubatch=w.ubatch,
+                    num_ubatches=w.num_ubatches, dtype="fp16", eps_threads=4, loss_scale=2.0 ** 40, scale_growth_interval=2)
+    try:
+        tr.load_params(S.embed_params(w), [S.layer_params(w, l) for l in range(w.layers)])
+        tok, lab = S.tokens_and_labels(w)
+        tokd, labd = torch.from_numpy(tok).cuda(), torch.from_numpy(lab).cuda()
+        before = tr.eps.master(1).copy()
+        loss = tr.step(tokd, labd)                          # 2^40 / N overflows half precision: step skipped
+        assert math.isfinite(loss)                          # the loss itself is not scaled
+        assert tr.t == 0 and tr.scaler.skipped == 1 and tr.scaler.scale == 2.0 ** 39
+        assert np.array_equal(tr.eps.master(1), before)
+        assert not tr.eps.moment(1, 0).any()
+        tr.scaler.scale = 2.0 ** 12                          # a workable scale: the next steps go through and grow it
+        tr.ctx.set_loss_scale(tr.scaler.scale)
+        tr.step(tokd, labd)
+        tr.step(tokd, labd)
+        assert tr.t == 2 and tr.scaler.scale == 2.0 ** 13
+        assert not np.array_equal(tr.eps.master(1), before)
+        assert np.isfinite(tr.eps.master(1)).all()
     finally:
         tr.close()
 

@@ -129,6 +129,40 @@ def test_eps_adam_matches_oracle(threads):
     e2.close()
 
 
+def test_eps_fp16_ship_and_grad_unscale():
+    n = 1 << 17
+    rng = np.random.default_rng(9)
+    w = (rng.normal(size=n) * np.exp(rng.normal(size=n) * 6)).astype(np.float32)     # from subnormal halves to overflow
+    w[:4] = [65504.0, 65520.0, 2.0 ** -25, -(1.0 + 2.0 ** -11)]
+    e = P.EPS([n], "fp16", 3)
+    e.master(0)[:] = w
+    e.refresh_ship()
+    assert np.array_equal(e.ship(0), O.fp16_bits(w))                                # IEEE half, ties to even, bit for bit
+    g = rng.normal(size=n).astype(np.float32) * 1024.0
+    e.grad(0)[:] = g
+    assert e.grad_unscale(0, 0, 1.0 / 1024.0) is False
+    assert np.array_equal(e.grad(0), g / np.float32(1024.0))                        # a power of two divides out exactly
+    for bad in (np.inf, -np.inf, np.nan):
+        e.grad(0)[n // 2] = bad
+        assert e.grad_unscale(0, 0, 0.5) is True
+        e.grad(0)[n // 2] = 0.0
+    assert e.grad_unscale(0, 0, 1.0) is False
+    e.close()
+
+
+def test_loss_scaler_policy():
+    from paper_2002_05645_amd.trainer import LossScaler
+    s = LossScaler(scale=1024.0, growth_interval=3)
+    assert [s.update(False), s.update(False)] == [True, True] and s.scale == 1024.0
+    assert s.update(True) is False and s.scale == 512.0 and s.skipped == 1      # overflow: skip, halve, restart the count
+    assert [s.update(False) for _ in range(3)] == [True] * 3 and s.scale == 1024.0
+    assert s.update(False) and s.scale == 1024.0
+    floor = LossScaler(scale=1.0, growth_interval=1, min_scale=1.0)
+    assert floor.update(True) is False and floor.scale == 1.0                       # never below the floor
+    fixed = LossScaler(scale=64.0, growth_interval=1, static=True)
+    assert fixed.update(False) and fixed.update(True) is False and fixed.scale == 64.0
+
+
 @pytest.mark.parametrize("threads", [1, 5])
 def test_eps_lamb_matches_oracle_per_tensor(threads):
     # three tensors of different size inside one block, with padding between them that must stay untouched
