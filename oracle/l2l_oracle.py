@@ -22,7 +22,7 @@ cpu-baseline leg of the benchmark may import it.
 
 Pins (tests/test_oracle_*.py): central finite differences for every backward
 formula, Algorithm 1 == Algorithm 2 == one concatenated minibatch, closed
-forms for softmax / LayerNorm / GELU / cross-entropy / Adam / LAMB (plus LAMB's
+forms for softmax / LayerNorm / GELU / cross-entropy / both heads / Adam / LAMB (plus LAMB's
 step-length and scale invariances), exhaustive bf16 and fp16 round trips with hand-built ties.  Unpinned: end-to-end task accuracy against the paper's Table 7
 (needs the GLUE data and pretrained weights) -- parity unpinned.
 """
@@ -196,6 +196,37 @@ def head_loss(xL, labels, e, n_lab_total):
     return loss, dx.reshape(n, S, H), {"E": dE, "bv": dbv}
 
 
+def cls_head_loss(xL, seq_labels, c, n_lab_total):
+    """Sequence-classification head (the GLUE task head of Section 5's fine-tuning runs; the paper does not
+    write it out: this is the usual BERT one): pooled = tanh(x_[first token] Wp + bp), z = pooled Wc + bc,
+    loss contribution = -(1/N) sum_q log softmax(z_q)[label_q] over the sequences with label >= 0, N being
+    the labelled count of the WHOLE minibatch.  xL: [n, S, H]; seq_labels: [n].
+    Returns (loss_contribution, d xL, {Wp, bp, Wc, bc} grads)."""
+    n, S, H = xL.shape
+    lab = np.asarray(seq_labels).reshape(-1)
+    dx = np.zeros_like(xL)
+    g = {k: np.zeros_like(v, dtype=F64) for k, v in c.items()}
+    idx = np.nonzero(lab >= 0)[0]
+    if idx.size == 0:
+        return 0.0, dx, g
+    x0 = xL[idx, 0, :]
+    pooled = np.tanh(x0 @ c["Wp"] + c["bp"])
+    z = pooled @ c["Wc"] + c["bc"]
+    zmax = z.max(axis=-1, keepdims=True)
+    lse = zmax[:, 0] + np.log(np.exp(z - zmax).sum(axis=-1))
+    loss = float((lse - z[np.arange(idx.size), lab[idx]]).sum() / n_lab_total)
+    dz = np.exp(z - lse[:, None])
+    dz[np.arange(idx.size), lab[idx]] -= 1.0
+    dz /= n_lab_total
+    g["Wc"] += pooled.T @ dz
+    g["bc"] += dz.sum(axis=0)
+    du = (dz @ c["Wc"].T) * (1.0 - pooled * pooled)
+    g["Wp"] += x0.T @ du
+    g["bp"] += du.sum(axis=0)
+    dx[idx, 0, :] = du @ c["Wp"].T
+    return loss, dx, g
+
+
 # --------------------------------------------------------------------------- whole-model drivers
 def _to64(d):
     return {k: np.asarray(v, F64) for k, v in d.items()}
@@ -278,6 +309,40 @@ def run_l2l(emb, layers, tokens, labels, heads, eps, return_stash=False):
     if return_stash:
         return loss, gemb, glayers, stash
     return loss, gemb, glayers
+
+
+def run_l2l_cls(emb, layers, cls, tokens, seq_labels, heads, eps):
+    """Algorithm 2 with the sequence-classification head in place of the LM head: as run_l2l, but the last
+    resident "layer" is cls_head_loss over each micro-batch's sequences.  seq_labels: [U, ub].
+    Returns (loss, embedding grads, per-layer grads, head grads)."""
+    emb, layers, cls = _to64(emb), [_to64(p) for p in layers], _to64(cls)
+    U = tokens.shape[0]
+    L = len(layers)
+    n_lab = int((np.asarray(seq_labels) >= 0).sum())
+    gemb, glayers = _zeros_like_params(emb, layers)
+    gcls = {k: np.zeros_like(v) for k, v in cls.items()}
+    x = [None] * U
+    ln_e = [None] * U
+    stash = [[None] * U for _ in range(L + 1)]
+    for u in range(U):
+        stash[0][u], ln_e[u] = embed_fwd(tokens[u], emb, eps)
+    for l in range(L):
+        for u in range(U):
+            stash[l + 1][u], _ = encoder_layer_fwd(stash[l][u], layers[l], heads, eps)
+    loss = 0.0
+    g = [None] * U
+    for u in range(U):
+        l_u, g[u], gh = cls_head_loss(stash[L][u], seq_labels[u], cls, n_lab)
+        loss += l_u
+        _acc(gcls, gh)
+    for l in reversed(range(L)):
+        for u in range(U):
+            _, cache = encoder_layer_fwd(stash[l][u], layers[l], heads, eps)
+            g[u], gl = encoder_layer_bwd(g[u], cache, layers[l], heads)
+            _acc(glayers[l], gl)
+    for u in range(U):
+        _acc(gemb, embed_bwd(g[u], tokens[u], ln_e[u], emb))
+    return loss, gemb, glayers, gcls
 
 
 def layer_l2l_fwd(X, p, heads, eps):

@@ -366,3 +366,62 @@ def test_fp16_exhaustive_round_trip_ties_and_range():
     assert np.isinf(O.fp16_round(np.float32(1e6)))
     x = np.float32(0.1)
     assert abs(float(O.fp16_round(x)) - 0.1) <= 0.1 * 2.0 ** -11
+
+
+# ----------------------------------------------------------------------------- sequence-classification head
+def _cls_params(H, C, rng):
+    return {"Wp": rng.normal(size=(H, H)) * 0.3, "bp": rng.normal(size=H) * 0.1,
+            "Wc": rng.normal(size=(H, C)) * 0.3, "bc": rng.normal(size=C) * 0.1}
+
+
+def test_cls_head_gradients_by_finite_differences_and_closed_forms():
+    H, S, C, n = 6, 3, 4, 5
+    rng = np.random.default_rng(11)
+    c = _cls_params(H, C, rng)
+    x = rng.normal(size=(n, S, H))
+    lab = np.array([1, -1, 3, 0, 2])
+    N = 7                                                   # labelled count of a larger minibatch
+    loss, dx, g = O.cls_head_loss(x, lab, c, N)
+    f = lambda: O.cls_head_loss(x, lab, c, N)[0]
+    h = 1e-6
+    for name, arr, grad in [("x", x, dx)] + [(k, c[k], g[k]) for k in c]:
+        num = np.zeros_like(arr)
+        it = np.nditer(arr, flags=["multi_index"])
+        for _ in it:
+            i = it.multi_index
+            old = arr[i]
+            arr[i] = old + h
+            lp = f()
+            arr[i] = old - h
+            lm = f()
+            arr[i] = old
+            num[i] = (lp - lm) / (2 * h)
+        assert np.linalg.norm(num - grad) / max(np.linalg.norm(num), 1e-30) < 1e-7, name
+    # only the first token of a labelled sequence receives a gradient
+    assert not dx[:, 1:, :].any() and not dx[1].any() and dx[0, 0].any()
+    # the gradient of bc sums to zero (softmax rows minus one-hot rows), and shifting bc leaves the loss alone
+    assert abs(g["bc"].sum()) < 1e-15
+    c2 = dict(c, bc=c["bc"] + 3.7)
+    assert abs(O.cls_head_loss(x, lab, c2, N)[0] - loss) < 1e-12
+    # a zero classifier predicts uniformly: loss = (labelled here / N) ln C
+    c0 = dict(c, Wc=np.zeros((H, C)), bc=np.zeros(C))
+    assert abs(O.cls_head_loss(x, lab, c0, N)[0] - 4 / N * np.log(C)) < 1e-14
+    # no labelled sequence: nothing
+    l0, dx0, g0 = O.cls_head_loss(x, np.full(n, -1), c, N)
+    assert l0 == 0.0 and not dx0.any() and not any(v.any() for v in g0.values())
+
+
+def test_l2l_with_cls_head_equals_one_concatenated_minibatch():
+    H, A, F, S, V, L, C = 8, 2, 16, 4, 11, 2, 3
+    rng = np.random.default_rng(12)
+    emb, layers = tiny_model(H, A, F, S, V, L, rng)
+    cls = _cls_params(H, C, rng)
+    tok = rng.integers(0, V, size=(3, 2, S))                 # U = 3 micro-batches of 2 sequences
+    lab = np.array([[0, 2], [-1, 1], [2, 2]])
+    loss, gemb, gl, gcls = O.run_l2l_cls(emb, layers, cls, tok, lab, A, EPS)
+    loss1, gemb1, gl1, gcls1 = O.run_l2l_cls(emb, layers, cls, tok.reshape(1, 6, S), lab.reshape(1, 6), A, EPS)
+    assert abs(loss - loss1) < 1e-13
+    for a, b in [(gemb, gemb1), (gcls, gcls1)] + list(zip(gl, gl1)):
+        for k in a:
+            assert np.allclose(a[k], b[k], rtol=1e-11, atol=1e-14), k
+    assert not gemb["bv"].any()                               # the LM head is not in this graph
