@@ -62,6 +62,8 @@ def main():
     ap.add_argument("--ubatches", type=int, default=0, help="override U, the number of micro-batches (sweeps of the paper's Tables 3 and 4)")
     ap.add_argument("--dtype", default="", choices=["", "bf16", "fp16", "fp32"],
                     help="override the workload's device dtype (fp16: the paper's CMP precision, with dynamic loss scaling)")
+    ap.add_argument("--classes", type=int, default=0,
+                    help="> 0: the sequence-classification head with this many classes (one synthetic label per sequence) instead of the LM head")
     ap.add_argument("--optimizer", default="adam", choices=["adam", "lamb"],
                     help="host optimizer (lamb: per-tensor trust ratio, learning rate 1e-3, weight decay 0.01 on matrices)")
     a = ap.parse_args()
@@ -81,10 +83,12 @@ def main():
         w = w.scaled(dtype=a.dtype)
     tr = L2LTrainer(layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, vocab=w.vocab,
                     ubatch=w.ubatch, num_ubatches=w.num_ubatches, dtype=w.dtype, ubatch_group=a.group, stash=a.stash,
-                    eager=not a.tail_adam, optimizer=a.optimizer,
+                    eager=not a.tail_adam, optimizer=a.optimizer, num_classes=a.classes,
                     **(dict(lr=1e-3, eps_a=1e-6, weight_decay=0.01) if a.optimizer == "lamb" else {}))
-    tr.load_params(S.embed_params(w), [S.layer_params(w, l) for l in range(w.layers)])
+    tr.load_params(S.embed_params(w), [S.layer_params(w, l) for l in range(w.layers)], S.cls_params(w, a.classes) if a.classes else None)
     tok, lab = S.tokens_and_labels(w)
+    if a.classes:
+        lab = S.seq_labels(w, a.classes)
     tok, lab = torch.from_numpy(tok).cuda(), torch.from_numpy(lab).cuda()
 
     loss0 = None
@@ -144,7 +148,7 @@ def main():
         "config": {"workload": f"{w.name}: L={w.layers} H={w.hidden} A={w.heads} F={w.ffn} S={w.seq} V={w.vocab} "
                                f"U={w.num_ubatches} x ub={w.ubatch}", "stash": a.stash, "ubatch_group": tr.ctx.cfg.ubatch_group,
                    "device_pipeline_samples_per_s": samples * a.steps / dev_s, "device_pipeline_ms": 1e3 * dev_s / a.steps,
-                   "host_adam_exposed_ms": 1e3 * adam_s / a.steps, "eps": "tail" if a.tail_adam else "eager", "optimizer": a.optimizer, "loss_first": loss0, "loss_last": loss, "losses": [round(x, 4) for x in losses],
+                   "host_adam_exposed_ms": 1e3 * adam_s / a.steps, "eps": "tail" if a.tail_adam else "eager", "optimizer": a.optimizer, "head": f"classification, {a.classes} classes" if a.classes else "tied LM head", "loss_first": loss0, "loss_last": loss, "losses": [round(x, 4) for x in losses],
                    "peak_device_bytes": int(peak_mem), "ctx_device_bytes": int(tr.ctx.device_bytes()),
                    "instrumented_ms_per_step": 1e3 * prof_total_s / a.steps,
                    # sum of kernel durations over the un-instrumented device-pipeline time; and the fraction of the
@@ -161,7 +165,7 @@ def main():
                      "frac": achieved / PEAK_BF16_TFLOPS,
                      # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (profiles/bench_bert_large_gemm_hbm_traffic.md);
                      # measured on the headline workload only
-                     "traffic": 608.7e6 if (a.config == 2 and not a.layers and not a.group and not a.ubatches and not a.dtype) else None,
+                     "traffic": 608.7e6 if (a.config == 2 and not a.layers and not a.group and not a.ubatches and not a.dtype and not a.classes) else None,
                      "kernel": "gemm_mfma_dlds_kernel / gemm_mfma_kernel: the layer's dense GEMMs (QKV, out-proj, FFN1, FFN2; forward, recompute, dX, dW)",
                      "gemm_ms_per_step": g["ms"] / a.steps, "launches_per_step": g["launches"] / a.steps,
                      "avg_launch_us": 1e3 * g["ms"] / max(g["launches"], 1),

@@ -154,6 +154,29 @@ int l2l_embed_fwd(l2l_ctx*, const int32_t* tokens, void* x_out);
    dy_out: device U x [ub,S,H], receives dL/dx (zero at unlabelled positions).
    loss_out: device float[1].  Adds dE and dbv into the embedding-block accumulator. */
 int l2l_head_loss(l2l_ctx*, const void* x_last, const int32_t* labels, void* dy_out, float* loss_out);
+/* ---- sequence-classification head (the task head of the paper's GLUE fine-tuning runs, Section 5; the
+   paper does not write it out, this is the usual BERT one): pooled = tanh(x0 Wp + bp) on the first
+   token x0 of each sequence, z = pooled Wc + bc, cross-entropy over the sequences with label >= 0,
+   normalised by their count over the whole mini-batch.  An alternative to l2l_head_loss; it needs no
+   vocabulary.  Packed block (elements of the configured dtype, sub-blocks at multiples of 128):
+       Wp[H,H] | bp[H] | Wc[H,C] | bc[C]          (gradient block: same layout, fp32)               */
+int    l2l_cls_tensor_count(void);
+const char* l2l_cls_tensor_name(int i);
+long long   l2l_cls_tensor_offset(const l2l_config*, int num_classes, int i);   /* -1 on bad arguments */
+long long   l2l_cls_tensor_size(const l2l_config*, int num_classes, int i);
+size_t l2l_cls_packed_elems(const l2l_config*, int num_classes);                /* 0 on bad arguments */
+/* Async H2D of the head's packed parameters (pinned host memory) on the copy stream.  The first call
+   fixes num_classes (>= 2) for the context and allocates the head's buffers. */
+int l2l_cls_stage(l2l_ctx*, const void* host_params, int num_classes);
+/* Forward and backward of the head over all U x ub sequences.  x_last: device U x [ub,S,H];
+   seq_labels: device int32 [U x ub], -1 = no label; dy_out: device U x [ub,S,H], receives dL/dx
+   (non-zero only in the first-token rows of labelled sequences); loss_out: device float[1].
+   Adds the four tensors' gradients into the head's fp32 accumulator.  The loss scale applies. */
+int l2l_cls_head_loss(l2l_ctx*, const void* x_last, const int32_t* seq_labels, void* dy_out, float* loss_out);
+/* Async D2H of the head's gradients (fp32, packed) into pinned host memory, then clears them. */
+int l2l_cls_grad_drain(l2l_ctx*, void* host_grads);
+int l2l_cls_drain_wait(l2l_ctx*);
+
 /* Loss scaling (Section 2.3: FP16 on the device needs it, the gradient of the loss being ~1/(N V) per
    logit, below half precision's range): from the next l2l_head_loss on, the gradient of the loss is
    multiplied by `scale` before it is rounded to the device dtype, so every activation and parameter

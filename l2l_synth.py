@@ -146,6 +146,35 @@ def tokens_and_labels(w: Workload):
     return tok.reshape(shape).astype(np.int32), lab.reshape(shape).astype(np.int32)
 
 
+_ST_CLS = {"Wp": 20, "bp": 21, "Wc": 22, "bc": 23}
+_ST_SEQ_LABEL, _ST_SEQ_MASK = 24, 25
+CLS_TENSORS = tuple(_ST_CLS)              # packed order of the sequence-classification head
+
+
+def cls_shapes(w: Workload, num_classes: int) -> dict:
+    H = w.hidden
+    return {"Wp": (H, H), "bp": (H,), "Wc": (H, num_classes), "bc": (num_classes,)}
+
+
+def cls_params(w: Workload, num_classes: int, sigma: float = 0.02) -> dict:
+    """fp32 parameters of the sequence-classification head (pooler and classifier), N(0, sigma)."""
+    shp = cls_shapes(w, num_classes)
+    return {k: _param(w.seed, s, shp[k], k, sigma) for k, s in _ST_CLS.items()}
+
+
+def seq_labels(w: Workload, num_classes: int, label_prob: float = 1.0) -> np.ndarray:
+    """int32 [U, ub]: one class per sequence, uniform in [0, num_classes); with probability 1 - label_prob a
+    sequence carries no label (-1); sequence 0 is forced to carry one if the draw left none."""
+    n = w.num_ubatches * w.ubatch
+    lab = integers(w.seed, _ST_SEQ_LABEL, n, num_classes)
+    if label_prob < 1.0:
+        keep = uniform01(w.seed, _ST_SEQ_MASK, n) < label_prob
+        if not keep.any():
+            keep[0] = True
+        lab = np.where(keep, lab, -1)
+    return lab.reshape(w.num_ubatches, w.ubatch).astype(np.int32)
+
+
 def activations(w: Workload, stream_offset: int = 0) -> np.ndarray:
     """fp32 N(0,1) layer-boundary activations [U, ub, S, H] for single-layer parity runs."""
     shape = (w.num_ubatches, w.ubatch, w.seq, w.hidden)

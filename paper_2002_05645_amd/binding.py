@@ -83,6 +83,15 @@ _SIGS = {
     "eps_grad": (C.POINTER(C.c_float), [_P, C.c_int]),
     "eps_moment": (C.POINTER(C.c_float), [_P, C.c_int, C.c_int]),
     "eps_refresh_ship": (C.c_int, [_P, C.c_int, C.c_int]),
+    "l2l_cls_tensor_count": (C.c_int, []),
+    "l2l_cls_tensor_name": (C.c_char_p, [C.c_int]),
+    "l2l_cls_tensor_offset": (C.c_longlong, [_CFGP, C.c_int, C.c_int]),
+    "l2l_cls_tensor_size": (C.c_longlong, [_CFGP, C.c_int, C.c_int]),
+    "l2l_cls_packed_elems": (C.c_size_t, [_CFGP, C.c_int]),
+    "l2l_cls_stage": (C.c_int, [_P, _P, C.c_int]),
+    "l2l_cls_head_loss": (C.c_int, [_P, _P, _P, _P, _P]),
+    "l2l_cls_grad_drain": (C.c_int, [_P, _P]),
+    "l2l_cls_drain_wait": (C.c_int, [_P]),
     "l2l_set_loss_scale": (C.c_int, [_P, C.c_float]),
     "l2l_stream_create_cu_masked": (C.c_int, [C.c_int, C.POINTER(C.c_void_p)]),
     "l2l_stream_destroy": (C.c_int, [C.c_void_p]),
@@ -129,6 +138,14 @@ def embed_layout(cfg):
     return {L.l2l_embed_tensor_name(i).decode(): (L.l2l_embed_tensor_offset(C.byref(cfg), i),
                                                    L.l2l_embed_tensor_size(C.byref(cfg), i))
             for i in range(L.l2l_embed_tensor_count())}
+
+
+def cls_layout(cfg, num_classes):
+    """{name: (element offset, element count)} of the sequence-classification head's packed block."""
+    L = lib()
+    return {L.l2l_cls_tensor_name(i).decode(): (L.l2l_cls_tensor_offset(C.byref(cfg), num_classes, i),
+                                                 L.l2l_cls_tensor_size(C.byref(cfg), num_classes, i))
+            for i in range(L.l2l_cls_tensor_count())}
 
 
 def stream_create_cu_masked(cus_per_32: int) -> int:
@@ -238,6 +255,18 @@ class Context:
             self._ck(lib().l2l_profile_read(self._h, i, C.byref(n), C.byref(ms), C.byref(fl), C.byref(by)))
             out[name] = dict(launches=n.value, ms=ms.value, flops=fl.value, bytes=by.value)
         return out
+
+    def cls_stage(self, host_params, num_classes):
+        self._ck(lib().l2l_cls_stage(self._h, _ptr(host_params), num_classes))
+
+    def cls_head_loss(self, x_last, seq_labels, dy_out, loss_out):
+        self._ck(lib().l2l_cls_head_loss(self._h, _ptr(x_last), _ptr(seq_labels), _ptr(dy_out), _ptr(loss_out)))
+
+    def cls_grad_drain(self, host_grads):
+        self._ck(lib().l2l_cls_grad_drain(self._h, _ptr(host_grads)))
+
+    def cls_drain_wait(self):
+        self._ck(lib().l2l_cls_drain_wait(self._h))
 
     def set_loss_scale(self, scale):
         self._ck(lib().l2l_set_loss_scale(self._h, float(scale)))

@@ -65,6 +65,20 @@ Layout make_layout(const l2l_config* c) {
 inline size_t esize(int dtype) { return dtype == L2L_F32 ? 4 : 2; }
 inline bool is16(int dtype) { return dtype == L2L_BF16 || dtype == L2L_FP16; }
 
+// packed block of the sequence-classification head: Wp[H,H] | bp[H] | Wc[H,C] | bc[C]
+enum { C_WP, C_BP, C_WC, C_BC, N_CLS_T };
+const char* kClsNames[N_CLS_T] = {"Wp", "bp", "Wc", "bc"};
+struct ClsLayout { long long off[N_CLS_T], size[N_CLS_T], total; };
+ClsLayout make_cls_layout(const l2l_config* c, int classes) {
+  ClsLayout L;
+  const long long H = c->hidden, C = classes;
+  const long long s[N_CLS_T] = {H * H, H, H * C, C};
+  long long o = 0;
+  for (int i = 0; i < N_CLS_T; ++i) { L.size[i] = s[i]; L.off[i] = o; o = up(o + s[i], ALIGN); }
+  L.total = o;
+  return L;
+}
+
 }  // namespace
 
 extern "C" {
@@ -93,6 +107,17 @@ size_t l2l_layer_packed_elems(const l2l_config* c) { return config_ok(c) ? (size
 size_t l2l_layer_param_bytes(const l2l_config* c) { return config_ok(c) ? (size_t)make_layout(c).total * esize(c->dtype) : 0; }
 size_t l2l_layer_grad_bytes(const l2l_config* c) { return config_ok(c) ? (size_t)make_layout(c).total * 4 : 0; }
 size_t l2l_embed_packed_elems(const l2l_config* c) { return config_ok(c) ? (size_t)make_layout(c).etotal : 0; }
+int l2l_cls_tensor_count(void) { return N_CLS_T; }
+const char* l2l_cls_tensor_name(int i) { return (i < 0 || i >= N_CLS_T) ? nullptr : kClsNames[i]; }
+long long l2l_cls_tensor_offset(const l2l_config* c, int classes, int i) {
+  return (!config_ok(c) || classes < 2 || i < 0 || i >= N_CLS_T) ? -1 : make_cls_layout(c, classes).off[i];
+}
+long long l2l_cls_tensor_size(const l2l_config* c, int classes, int i) {
+  return (!config_ok(c) || classes < 2 || i < 0 || i >= N_CLS_T) ? -1 : make_cls_layout(c, classes).size[i];
+}
+size_t l2l_cls_packed_elems(const l2l_config* c, int classes) {
+  return (config_ok(c) && classes >= 2) ? (size_t)make_cls_layout(c, classes).total : 0;
+}
 size_t l2l_embed_param_bytes(const l2l_config* c) { return config_ok(c) ? (size_t)make_layout(c).etotal * esize(c->dtype) : 0; }
 size_t l2l_embed_grad_bytes(const l2l_config* c) { return config_ok(c) ? (size_t)make_layout(c).etotal * 4 : 0; }
 int l2l_config_check(const l2l_config* c) { return config_ok(c) ? L2L_OK : L2L_E_ARG; }
@@ -140,6 +165,13 @@ struct l2l_ctx {
   hipEvent_t emb_staged_ev = nullptr, emb_released_ev = nullptr, egacc_ready = nullptr, egacc_landed = nullptr, egacc_drained = nullptr;
   float *emean = nullptr, *erstd = nullptr;
   int32_t *lab_idx = nullptr, *lab_cnt = nullptr, *lab_total = nullptr, *lab_gidx = nullptr, *chunk_cnt = nullptr;
+  // sequence-classification head (allocated at the first l2l_cls_stage)
+  int cls_classes = 0, cls_staged = 0, cls_state = 0;       // state: 0 clean, 1 gradients ready, 2 drain in flight
+  long long cls_off[4] = {}, cls_size[4] = {}, cls_total = 0, cls_cp = 0;
+  void *cls_w = nullptr, *cls_x = nullptr, *cls_u = nullptr, *cls_p = nullptr, *cls_dz = nullptr, *cls_dp = nullptr, *cls_du = nullptr,
+       *cls_dx = nullptr;
+  float *cls_g = nullptr, *cls_z = nullptr;
+  hipEvent_t cls_staged_ev = nullptr, cls_released_ev = nullptr, cls_ready = nullptr, cls_landed = nullptr, cls_drained = nullptr;
   long long head_rows = 0;   // labelled rows per pass of the head
   float loss_scale = 1.0f;   // factor on the loss gradient (fp16 training)
   void *xl = nullptr, *dz = nullptr, *dxl = nullptr;
@@ -713,6 +745,60 @@ int embed_bwd_t(l2l_ctx* c, const int32_t* tokens, const void* dy) {
   });
 }
 
+// Sequence-classification head, forward and backward over all sequences of the mini-batch: pooled = tanh(x0 Wp + bp),
+// z = pooled Wc + bc, cross-entropy over the labelled sequences; gradients of the four tensors into cls_g, dL/dx into
+// the first-token rows of dy_out (zero elsewhere).
+template <typename T>
+int cls_head_t(l2l_ctx* c, const void* x_last, const int32_t* seq_labels, void* dy_out, float* loss_out) {
+  const l2l_config& f = c->cfg;
+  const int H = f.hidden, S = f.seq, C = c->cls_classes, dt = f.dtype;
+  const int nseq = f.ubatch * f.num_ubatches;
+  const int Cp = (int)c->cls_cp;
+  const T* W = (const T*)c->cls_w;
+  const long long* o = c->cls_off;
+  float* G = c->cls_g;
+  const unsigned rb = (unsigned)((nseq + 3) / 4);
+  L2L_TRY(fill_zero(c, dy_out, (size_t)nseq * S * H * sizeof(T)));
+  L2L_TRY(timed(c, L2L_PROF_OTHER, 0, 0, [&] {
+    hipLaunchKernelGGL((first_token_rows_kernel<T, false>), dim3(rb), dim3(256), 0, c->cs, (const T*)x_last, (T*)c->cls_x, nseq, S, H);
+  }));
+  GemmArgs g = gemm_args(nseq, H, H, c->cls_x, H, 1, W + o[C_WP], H, 0, c->cls_u, H);
+  g.epi = EPI_BIAS; g.bias = W + o[C_BP];
+  L2L_TRY(gemm(c, dt, false, g, 0, L2L_PROF_OTHER));
+  const long long ne = (long long)nseq * H;
+  const unsigned eb = (unsigned)((ne / 8 + 255) / 256);
+  L2L_TRY(timed(c, L2L_PROF_OTHER, 0, 0, [&] {
+    hipLaunchKernelGGL((tanh_kernel<T, false>), dim3(eb), dim3(256), 0, c->cs, (const T*)c->cls_u, (const T*)nullptr, (T*)c->cls_p, ne);
+  }));
+  GemmArgs z = gemm_args(nseq, C, H, c->cls_p, H, 1, W + o[C_WC], C, 0, c->cls_z, Cp);
+  z.epi = EPI_BIAS; z.bias = W + o[C_BC];
+  L2L_TRY(gemm(c, dt, true, z, 0, L2L_PROF_OTHER));
+  L2L_TRY(timed(c, L2L_PROF_OTHER, 0, 0, [&] {
+    hipLaunchKernelGGL(cls_ce_kernel<T>, dim3(1), dim3(256), 0, c->cs, c->cls_z, Cp, seq_labels, (T*)c->cls_dz, loss_out, nseq, C,
+                       c->loss_scale);
+  }));
+  // dWc += pooled^T dz ; dbc += colsum(dz) ; dpooled = dz Wc^T
+  GemmArgs wc = gemm_args(H, C, nseq, c->cls_p, H, 0, c->cls_dz, Cp, 0, G + o[C_WC], C);
+  wc.epi = EPI_ACCUM;
+  L2L_TRY(gemm(c, dt, true, wc, 0, L2L_PROF_OTHER));
+  L2L_TRY(bias_grad<T>(c, c->cls_dz, Cp, G + o[C_BC], nseq, C, nullptr));
+  GemmArgs dp = gemm_args(nseq, H, C, c->cls_dz, Cp, 1, W + o[C_WC], C, 1, c->cls_dp, H);
+  L2L_TRY(gemm(c, dt, false, dp, 0, L2L_PROF_OTHER));
+  L2L_TRY(timed(c, L2L_PROF_OTHER, 0, 0, [&] {
+    hipLaunchKernelGGL((tanh_kernel<T, true>), dim3(eb), dim3(256), 0, c->cs, (const T*)c->cls_dp, (const T*)c->cls_p, (T*)c->cls_du, ne);
+  }));
+  // dWp += x0^T du ; dbp += colsum(du) ; dx0 = du Wp^T
+  GemmArgs wp = gemm_args(H, H, nseq, c->cls_x, H, 0, c->cls_du, H, 0, G + o[C_WP], H);
+  wp.epi = EPI_ACCUM;
+  L2L_TRY(gemm(c, dt, true, wp, 0, L2L_PROF_OTHER));
+  L2L_TRY(bias_grad<T>(c, c->cls_du, H, G + o[C_BP], nseq, H, nullptr));
+  GemmArgs dx = gemm_args(nseq, H, H, c->cls_du, H, 1, W + o[C_WP], H, 1, c->cls_dx, H);
+  L2L_TRY(gemm(c, dt, false, dx, 0, L2L_PROF_OTHER));
+  return timed(c, L2L_PROF_OTHER, 0, 0, [&] {
+    hipLaunchKernelGGL((first_token_rows_kernel<T, true>), dim3(rb), dim3(256), 0, c->cs, (const T*)c->cls_dx, (T*)dy_out, nseq, S, H);
+  });
+}
+
 int check_slot_call(l2l_ctx* c, int layer, int slot, const void* a, const void* b, const char* who) {
   if (!c) return L2L_E_ARG;
   if (!a || !b) return fail(c, L2L_E_ARG, "%s: null pointer", who);
@@ -1019,6 +1105,77 @@ int l2l_embed_drain_wait(l2l_ctx* c) {
   L2L_TRY(need_vocab(c, "l2l_embed_drain_wait"));
   if (c->egacc_state != 2) return fail(c, L2L_E_STATE, "l2l_embed_drain_wait: no drain in flight");
   HIP_TRY(c, hipEventSynchronize(c->egacc_landed));
+  return L2L_OK;
+}
+
+int l2l_cls_stage(l2l_ctx* c, const void* host_params, int classes) {
+  if (!c) return L2L_E_ARG;
+  if (!host_params) return fail(c, L2L_E_ARG, "l2l_cls_stage: null host pointer");
+  if (classes < 2) return fail(c, L2L_E_ARG, "l2l_cls_stage: %d classes", classes);
+  if (c->cls_classes && c->cls_classes != classes)
+    return fail(c, L2L_E_ARG, "l2l_cls_stage: the head was set up for %d classes, not %d", c->cls_classes, classes);
+  const size_t es = esize(c->cfg.dtype);
+  if (!c->cls_classes) {   // first use: the head's buffers
+    const ClsLayout L = make_cls_layout(&c->cfg, classes);
+    for (int i = 0; i < N_CLS_T; ++i) { c->cls_off[i] = L.off[i]; c->cls_size[i] = L.size[i]; }
+    c->cls_total = L.total;
+    c->cls_cp = up(classes, 8);
+    const long long nseq = (long long)c->cfg.ubatch * c->cfg.num_ubatches, H = c->cfg.hidden;
+    L2L_TRY(dev_alloc(c, &c->cls_w, L.total * es));
+    L2L_TRY(dev_alloc(c, (void**)&c->cls_g, L.total * 4));
+    HIP_TRY(c, hipMemset(c->cls_g, 0, L.total * 4));
+    void** rows[] = {&c->cls_x, &c->cls_u, &c->cls_p, &c->cls_dp, &c->cls_du, &c->cls_dx};
+    for (void** p : rows) L2L_TRY(dev_alloc(c, p, nseq * H * es));
+    L2L_TRY(dev_alloc(c, (void**)&c->cls_z, nseq * c->cls_cp * 4));
+    L2L_TRY(dev_alloc(c, &c->cls_dz, nseq * c->cls_cp * es));
+    hipEvent_t* evs[] = {&c->cls_staged_ev, &c->cls_released_ev, &c->cls_ready, &c->cls_landed, &c->cls_drained};
+    for (hipEvent_t* e : evs) HIP_TRY(c, hipEventCreateWithFlags(e, hipEventDisableTiming));
+    c->cls_classes = classes;
+  }
+  if (c->cls_staged) HIP_TRY(c, hipStreamWaitEvent(c->xs, c->cls_released_ev, 0));
+  const CopyMark mark = copy_begin(c);
+  HIP_TRY(c, hipMemcpyAsync(c->cls_w, host_params, c->cls_total * es, hipMemcpyHostToDevice, c->xs));
+  copy_end(c, mark, (double)c->cls_total * es);
+  HIP_TRY(c, hipEventRecord(c->cls_staged_ev, c->xs));
+  c->cls_staged = 1;
+  return L2L_OK;
+}
+
+int l2l_cls_head_loss(l2l_ctx* c, const void* x_last, const int32_t* seq_labels, void* dy_out, float* loss_out) {
+  if (!c) return L2L_E_ARG;
+  if (!x_last || !seq_labels || !dy_out || !loss_out) return fail(c, L2L_E_ARG, "l2l_cls_head_loss: null pointer");
+  if (!c->cls_staged) return fail(c, L2L_E_STATE, "l2l_cls_head_loss: head parameters never staged");
+  if (c->cls_state == 1) return fail(c, L2L_E_STATE, "l2l_cls_head_loss: the head's gradients of the previous step were never drained");
+  HIP_TRY(c, hipStreamWaitEvent(c->cs, c->cls_staged_ev, 0));
+  if (c->cls_state == 2) HIP_TRY(c, hipStreamWaitEvent(c->cs, c->cls_drained, 0));
+  if (c->cfg.dtype == L2L_BF16) L2L_TRY(cls_head_t<bf16>(c, x_last, seq_labels, dy_out, loss_out));
+  else if (c->cfg.dtype == L2L_FP16) L2L_TRY(cls_head_t<fp16>(c, x_last, seq_labels, dy_out, loss_out));
+  else L2L_TRY(cls_head_t<float>(c, x_last, seq_labels, dy_out, loss_out));
+  HIP_TRY(c, hipEventRecord(c->cls_released_ev, c->cs));
+  HIP_TRY(c, hipEventRecord(c->cls_ready, c->cs));
+  c->cls_state = 1;
+  return L2L_OK;
+}
+
+int l2l_cls_grad_drain(l2l_ctx* c, void* host_grads) {
+  if (!c) return L2L_E_ARG;
+  if (!host_grads) return fail(c, L2L_E_ARG, "l2l_cls_grad_drain: null host pointer");
+  if (c->cls_state != 1) return fail(c, L2L_E_STATE, "l2l_cls_grad_drain: no un-drained head gradients");
+  HIP_TRY(c, hipStreamWaitEvent(c->xs, c->cls_ready, 0));
+  const CopyMark mark = copy_begin(c);
+  HIP_TRY(c, hipMemcpyAsync(host_grads, c->cls_g, c->cls_total * 4, hipMemcpyDeviceToHost, c->xs));
+  HIP_TRY(c, hipEventRecord(c->cls_landed, c->xs));
+  L2L_TRY(fill_zero_copy_stream(c, c->cls_g, c->cls_total * 4));
+  copy_end(c, mark, (double)c->cls_total * 4);
+  HIP_TRY(c, hipEventRecord(c->cls_drained, c->xs));
+  c->cls_state = 2;
+  return L2L_OK;
+}
+
+int l2l_cls_drain_wait(l2l_ctx* c) {
+  if (!c) return L2L_E_ARG;
+  if (c->cls_state != 2) return fail(c, L2L_E_STATE, "l2l_cls_drain_wait: no drain in flight");
+  HIP_TRY(c, hipEventSynchronize(c->cls_landed));
   return L2L_OK;
 }
 

@@ -424,6 +424,82 @@ __global__ __launch_bounds__(256) void ce_kernel(const float* z, long long ldz, 
   }
 }
 
+// ---- sequence-classification head --------------------------------------------------------------------
+// dst[q,:] = src[q * S,:] (first token of sequence q) or, SCATTER, dst[q * S,:] = src[q,:]; wave per sequence.
+template <typename T, bool SCATTER>
+__global__ __launch_bounds__(256) void first_token_rows_kernel(const T* src, T* dst, int nseq, int S, int n) {
+  const int lane = threadIdx.x & 63;
+  const int q = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (q >= nseq) return;
+  const long long a = SCATTER ? q : (long long)q * S, b = SCATTER ? (long long)q * S : q;
+  for (int j = lane * 8; j < n; j += WAVE * 8) {
+    float v[8];
+    load8(src + a * n + j, v);
+    store8(dst + b * n + j, v);
+  }
+}
+
+// y = tanh(x), or BWD: y = x * (1 - t^2) with t the forward result; n elements, a multiple of 8.
+template <typename T, bool BWD>
+__global__ __launch_bounds__(256) void tanh_kernel(const T* x, const T* t, T* y, long long n) {
+  const long long i = ((long long)blockIdx.x * 256 + threadIdx.x) * 8;
+  if (i >= n) return;
+  float v[8], w[8];
+  load8(x + i, v);
+  if (BWD) {
+    load8(t + i, w);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] *= 1.0f - w[k] * w[k];
+  } else {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = tanhf(v[k]);
+  }
+  store8(y + i, v);
+}
+
+// Cross-entropy over the C class logits of each sequence (z: [nseq, ldz] fp32), one block for the whole
+// mini-batch: N = number of sequences with label >= 0; *loss = (1/N) sum (lse - z[label]);
+// dz = scale * (softmax(z) - onehot) / N in T, zero for unlabelled sequences and in the padding columns.
+template <typename T>
+__global__ __launch_bounds__(256) void cls_ce_kernel(const float* z, int ldz, const int32_t* labels, T* dz, float* loss,
+                                                     int nseq, int C, float scale) {
+  __shared__ int cnt[4];
+  __shared__ float part[4];
+  const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+  int mine = 0;
+  for (int q = t; q < nseq; q += 256) mine += labels[q] >= 0;
+  mine = (int)wave_sum((float)mine);
+  if (lane == 0) cnt[w] = mine;
+  __syncthreads();
+  const int N = cnt[0] + cnt[1] + cnt[2] + cnt[3];
+  const float inv_n = N > 0 ? 1.0f / (float)N : 0.f;
+  float l = 0.f;
+  for (int q = t; q < nseq; q += 256) {
+    const float* row = z + (long long)q * ldz;
+    T* d = dz + (long long)q * ldz;
+    const int label = labels[q];
+    if (label < 0) {
+      for (int j = 0; j < ldz; ++j) d[j] = from_f32<T>(0.f);
+      continue;
+    }
+    float mx = -INFINITY;
+    for (int j = 0; j < C; ++j) mx = fmaxf(mx, row[j]);
+    float s = 0.f;
+    for (int j = 0; j < C; ++j) s += __expf(row[j] - mx);
+    l += (mx + __logf(s) - row[label]) * inv_n;
+    const float inv_s = 1.0f / s;
+    for (int j = 0; j < ldz; ++j) {
+      float v = 0.f;
+      if (j < C) v = (__expf(row[j] - mx) * inv_s - (j == label ? 1.0f : 0.0f)) * (inv_n * scale);
+      d[j] = from_f32<T>(v);
+    }
+  }
+  l = wave_sum(l);
+  if (lane == 0) part[w] = l;
+  __syncthreads();
+  if (t == 0) *loss = part[0] + part[1] + part[2] + part[3];
+}
+
 // out[c, r] = in[r, c] for a bf16 matrix [R, C] (both multiples of 8): 128 x 128 tiles through LDS, so that
 // both the reads and the writes are 256-byte row segments moved with 16-byte accesses.  The LDS tile is
 // kept as dwords holding (row 2i, row 2i+1) pairs of one column: a 16-byte output chunk (8 consecutive

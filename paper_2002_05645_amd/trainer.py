@@ -60,7 +60,8 @@ class L2LTrainer:
     def __init__(self, *, layers, hidden, heads, ffn, seq, vocab, ubatch, num_ubatches, dtype="bf16",
                  ln_eps=1e-12, lr=1e-4, beta1=0.9, beta2=0.999, eps_a=1e-8, ubatch_group=0,
                  eps_threads=0, stash="device", device="cuda:0", eager=False, optimizer="adam", weight_decay=0.0,
-                 copy_cus=0, run_ahead=2, loss_scale=None, dynamic_loss_scale=True, scale_growth_interval=1000):
+                 copy_cus=0, run_ahead=2, loss_scale=None, dynamic_loss_scale=True, scale_growth_interval=1000,
+                 num_classes=0):
         assert stash in ("device", "host")
         assert optimizer in ("adam", "lamb")
         self.optimizer = optimizer
@@ -81,7 +82,15 @@ class L2LTrainer:
         self.embed_layout = B.embed_layout(self.cfg)
         self.layer_elems = B.lib().l2l_layer_packed_elems(self.cfg)
         self.embed_elems = B.lib().l2l_embed_packed_elems(self.cfg)
-        self.eps = B.EPS([self.embed_elems] + [self.layer_elems] * layers, dtype, eps_threads)
+        # num_classes > 0: the sequence-classification head (one class label per sequence) replaces the tied LM head;
+        # its parameters are one more EPS block, after the layers'
+        self.num_classes = int(num_classes)
+        blocks = [self.embed_elems] + [self.layer_elems] * layers
+        if self.num_classes:
+            self.cls_layout = B.cls_layout(self.cfg, self.num_classes)
+            self.cls_elems = B.lib().l2l_cls_packed_elems(self.cfg, self.num_classes)
+            blocks.append(self.cls_elems)
+        self.eps = B.EPS(blocks, dtype, eps_threads)
         if optimizer == "lamb":
             # LAMB (Table 1's optimizer) works tensor by tensor: the tensors of a block, in packing order, with
             # biases and LayerNorm parameters (everything that is not a matrix) exempt from weight decay
@@ -91,6 +100,8 @@ class L2LTrainer:
                 return ([(layout[k][0], layout[k][0] + layout[k][1]) for k in names],
                         [1.0 if len(shapes[k]) == 2 else 0.0 for k in names])
             self._segs = {True: segs(self.embed_layout, self.embed_shapes()), False: segs(self.layer_layout, self.layer_shapes())}
+            if self.num_classes:
+                self._segs["cls"] = segs(self.cls_layout, self.cls_shapes())
         torch.cuda.set_device(self.device)
         self.compute = torch.cuda.Stream(device=self.device)
         self._copy_handle = None
@@ -124,7 +135,7 @@ class L2LTrainer:
         # eager EPS (Section 2.1 "reduces ... eagerly", Section 4.1): a host thread runs Adam on a block as
         # soon as its gradients have landed, while the device is still busy with the layers below it
         self.eager = eager
-        self._landed = [torch.cuda.Event() for _ in range(layers + 1)]
+        self._landed = [torch.cuda.Event() for _ in range(layers + 2)]
         self._bwd_done = [torch.cuda.Event() for _ in range(layers)]
         self._fwd_done = [torch.cuda.Event() for _ in range(layers)]
         self._work = queue.Queue()
@@ -135,11 +146,22 @@ class L2LTrainer:
             self._worker.start()
 
     # ---- parameters -------------------------------------------------------------------------------
-    def load_params(self, emb: dict, layers: list):
+    def load_params(self, emb: dict, layers: list, cls: dict = None):
         self.eps.master(0)[:] = pack(self.embed_layout, self.embed_elems, emb)
         for l, p in enumerate(layers):
             self.eps.master(1 + l)[:] = pack(self.layer_layout, self.layer_elems, p)
+        if self.num_classes:
+            self.eps.master(1 + self.L)[:] = pack(self.cls_layout, self.cls_elems, cls)
         self.eps.refresh_ship()
+
+    def cls_shapes(self):
+        return {"Wp": (self.H, self.H), "bp": (self.H,), "Wc": (self.H, self.num_classes), "bc": (self.num_classes,)}
+
+    def cls_grads(self):
+        return unpack(self.cls_layout, self.cls_shapes(), self.eps.grad(1 + self.L))
+
+    def cls_master(self):
+        return unpack(self.cls_layout, self.cls_shapes(), self.eps.master(1 + self.L))
 
     def layer_shapes(self):
         H, F = self.cfg.hidden, self.cfg.ffn
@@ -185,7 +207,13 @@ class L2LTrainer:
             if host_mode:
                 self._fwd_done[l].record(self.compute)
                 self._offload(l + 1)
-        c.head_loss(self._stash_slot(L), labels, self.dy, self.loss_dev)
+        if self.num_classes:                 # labels: int32 [U, ub], one class per sequence
+            c.cls_stage(e.ship_ptr(1 + L), self.num_classes)
+            c.cls_head_loss(self._stash_slot(L), labels, self.dy, self.loss_dev)
+            c.cls_grad_drain(e.grad_ptr(1 + L))
+            self._after_drain(1 + L)
+        else:
+            c.head_loss(self._stash_slot(L), labels, self.dy, self.loss_dev)
         for l in reversed(range(L)):
             if l - 1 >= 0:
                 c.param_stage(l - 1, e.ship_ptr(l), (l - 1) % 2)
@@ -214,9 +242,16 @@ class L2LTrainer:
             seg, mask = self._segs[True]
             self.eps.lamb_step(0, 0, t, seg, decay_mask=mask, **self.hp)
             first = 1
+        if self.num_classes and last == self.L + 1:      # the classification head's block has its own tensors too
+            seg, mask = self._segs["cls"]
+            self.eps.lamb_step(last, last, t, seg, decay_mask=mask, **self.hp)
+            last -= 1
         if first <= last:
             seg, mask = self._segs[False]
             self.eps.lamb_step(first, last, t, seg, decay_mask=mask, **self.hp)
+
+    def _last_block(self):
+        return self.L + 1 if self.num_classes else self.L
 
     def _after_drain(self, block):
         if self.eager:
@@ -271,7 +306,7 @@ class L2LTrainer:
             self.t += 1
             return
         if self.scaler.scale != 1.0:
-            overflow = self.eps.grad_unscale(0, self.L, 1.0 / self.scaler.scale)
+            overflow = self.eps.grad_unscale(0, self._last_block(), 1.0 / self.scaler.scale)
             if self.scaler.static and overflow:
                 raise FloatingPointError(f"gradient overflow at loss scale {self.scaler.scale}")
             apply = self.scaler.update(overflow)
@@ -279,7 +314,7 @@ class L2LTrainer:
             if not apply:
                 return                    # step skipped: weights, moments and t unchanged
         self.t += 1
-        self._eps_update(0, self.L, self.t, unscale=False)
+        self._eps_update(0, self._last_block(), self.t, unscale=False)
 
     def step(self, tokens, labels) -> float:
         self.device_pipeline(tokens, labels)

@@ -419,6 +419,41 @@ def test_step_with_a_micro_batch_without_labels():
         tr.close()
 
 
+# ------------------------------------------------------------------------------------- sequence-classification head
+@pytest.mark.parametrize("dtype,classes,label_prob,eager", [("fp32", 2, 1.0, False), ("fp32", 5, 0.6, True), ("bf16", 3, 1.0, False),
+                                                            ("fp16", 2, 0.8, False)])
+def test_step_with_sequence_classification_head(dtype, classes, label_prob, eager):
+    # the paper's fine-tuning task head (one label per sequence) in place of the LM head: loss, every gradient of the
+    # embedding, the layers and the head, and the head's Adam update, against the oracle's Algorithm 2 with that head
+    w = S.WORKLOADS[0].scaled(dtype=dtype)
+    lr = 1e-4
+    tr = L2LTrainer(layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, vocab=w.vocab, ubatch=w.ubatch,
+                    num_ubatches=w.num_ubatches, dtype=dtype, lr=lr, eps_threads=4, eager=eager, num_classes=classes)
+    try:
+        emb, layers, cls = S.embed_params(w), [S.layer_params(w, l) for l in range(w.layers)], S.cls_params(w, classes)
+        tr.load_params(emb, layers, cls)
+        tok, _ = S.tokens_and_labels(w)
+        lab = S.seq_labels(w, classes, label_prob)
+        assert (lab < 0).any() == (label_prob < 1.0)
+        rd = lambda d: {k: rounded(v, dtype) for k, v in d.items()}
+        loss_ref, gemb, gl, gcls = O.run_l2l_cls(rd(emb), [rd(p) for p in layers], rd(cls), tok, lab, w.heads, 1e-12)
+        loss = tr.step(torch.from_numpy(tok).cuda(), torch.from_numpy(lab).cuda())
+        errs = {"loss": abs(loss - loss_ref) / abs(loss_ref)}
+        ge, glayers = tr.grads()
+        gc = tr.cls_grads()
+        errs.update({"cls.d" + k: O.rel_l2(gc[k], gcls[k]) for k in gcls})
+        errs.update({"emb.d" + k: O.rel_l2(ge[k], gemb[k]) for k in gemb if gemb[k].any()})
+        errs.update({f"l{l}.d{k}": O.rel_l2(glayers[l][k], gl[l][k]) for l in range(w.layers) for k in gl[l]})
+        _assert_errs(errs, TOL[dtype])
+        assert not ge["bv"].any()                                  # the LM head took no part
+        cm = tr.cls_master()
+        for k in cls:
+            wref, _, _ = O.adam_step(cls[k].astype(np.float64), gc[k].astype(np.float64), 0.0, 0.0, 1, lr=lr)
+            assert O.rel_l2(cm[k] - cls[k], wref - cls[k]) < 2e-3, k
+    finally:
+        tr.close()
+
+
 # ------------------------------------------------------------------------------------- fp16 with loss scaling
 @pytest.mark.parametrize("eager", [False, True])
 def test_step_fp16_with_loss_scale(eager):

@@ -129,6 +129,21 @@ def test_eps_adam_matches_oracle(threads):
     e2.close()
 
 
+def test_cls_head_layout():
+    cfg = P.make_config(768, 12, 3072, 128, 4, 2, "bf16", 1e-12, 0)
+    lay = P.cls_layout(cfg, 3)
+    assert list(lay) == ["Wp", "bp", "Wc", "bc"]
+    assert [n for _, n in lay.values()] == [768 * 768, 768, 768 * 3, 3]
+    end = 0
+    for off, n in lay.values():
+        assert off % 128 == 0 and off >= end
+        end = off + n
+    assert P.lib().l2l_cls_packed_elems(cfg, 3) == (end + 127) // 128 * 128
+    assert P.lib().l2l_cls_packed_elems(cfg, 1) == 0                     # at least two classes
+    assert P.lib().l2l_cls_tensor_offset(cfg, 3, 4) == -1
+    assert P.lib().l2l_cls_stage(None, None, 2) == P.L2L_E_ARG
+
+
 def test_eps_fp16_ship_and_grad_unscale():
     n = 1 << 17
     rng = np.random.default_rng(9)
