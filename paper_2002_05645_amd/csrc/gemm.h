@@ -548,15 +548,19 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
   const int N = g.N;
 
   const int tiles_n = (N + BN - 1) / BN, tiles_m = (g.M + BM - 1) / BM;
-  int tm, tn;
-  tile_of_block(blockIdx.x, tiles_m, tiles_n, tm, tn);
-  const int m0 = tm * BM, n0 = tn * BN;
-  if (m0 >= M) return;
-
   const int nk_all = (K + BK - 1) / BK;
   const int per_split = (nk_all + gridDim.y - 1) / gridDim.y;
   const int kt0 = blockIdx.y * per_split, kt1 = min(nk_all, kt0 + per_split);
   if (kt0 >= kt1) return;
+
+  // A workgroup takes tiles blockIdx.x, blockIdx.x + gridDim.x, ...: launched with one workgroup per tile it runs
+  // once, launched with one workgroup per CU it stays resident and walks its share of the tile order, which
+  // saves the dispatch of a 512-thread, 128 KB workgroup per tile.
+  for (int vb = blockIdx.x; vb < tiles_m * tiles_n; vb += gridDim.x) {
+  int tm, tn;
+  tile_of_block(vb, tiles_m, tiles_n, tm, tn);
+  const int m0 = tm * BM, n0 = tn * BN;
+  if (m0 >= M) continue;
 
   const int z = blockIdx.z, zo = z / g.zdiv, zi = z % g.zdiv;
   const bf16* A = (const bf16*)g.A + zo * g.a_zo + zi * g.a_zi + (AKC ? (long long)m0 * g.lda : (long long)m0);
@@ -675,4 +679,6 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   });
+  __syncthreads();   // every wave is done with its strips before the next tile's loads overwrite them
+  }
 }
