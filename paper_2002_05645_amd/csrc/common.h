@@ -66,6 +66,15 @@ __device__ __forceinline__ void store8(fp16* p, const float v[8]) {
   *(fp16x8*)p = a;
 }
 
+// 8 x 16-bit values already in registers (as loaded with one 16-byte access) to fp32
+template <typename E>
+__device__ __forceinline__ void unpack8(u32x4 raw, float v[8]) {
+  typedef __attribute__((ext_vector_type(8))) E e8;
+  const e8 a = __builtin_bit_cast(e8, raw);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v[i] = (float)a[i];
+}
+
 // One 32x32x16 MFMA step on 16-bit operands of element type E (fragments are carried as 8 x 16 bits).
 template <typename E>
 __device__ __forceinline__ f32x16 mfma_32x32x16(bf16x8 a, bf16x8 b, f32x16 c) {

@@ -636,6 +636,26 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
                       (!(g.epi & EPI_RESID) || (g.ldr % 8 == 0 && al16(g.resid))) &&
                       (!(g.epi & EPI_GELUGRAD) || (g.ldaux % 8 == 0 && al16(g.aux))) &&
                       (!((g.epi & EPI_GELU) && g.aux_out) || (g.ldaux % 8 == 0 && al16(g.aux_out)));
+  // vector path: 8-column chunk and row-in-pass of this lane, its bias values, and the first pass's prefetch
+  constexpr int CPR = WN / 8, RPP = 64 / CPR, PASSES = 32 / RPP;
+  const int c8 = (lane % CPR) * 8, prow = lane / CPR;
+  const int ncol = n0 + wn * WN + c8;
+  float bias8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  // one 16-byte operand per pass is prefetched: the residual, or the pre-activation of GELU' (no epilogue of the
+  // layer uses both; a launch that did would take the residual from memory in the pass itself)
+  const bool pre_aux = (g.epi & EPI_GELUGRAD) != 0, pre_res = !pre_aux && (g.epi & EPI_RESID);
+  u32x4 pre[2];
+  const auto fetch = [&](int fi, int fp, u32x4& d) {
+    const int m = m0 + wm * WM + fi * 32 + fp * RPP + prow;
+    if (m < M && ncol < N) {
+      if (pre_aux) d = *(const u32x4*)((const E*)g.aux + (long long)m * g.ldaux + ncol);
+      else if (pre_res) d = *(const u32x4*)((const E*)g.resid + (long long)m * g.ldr + ncol);
+    }
+  };
+  if (vec_ok && !atomic) {
+    if ((g.epi & EPI_BIAS) && ncol < N) load8((const E*)g.bias + ncol, bias8);
+    fetch(0, 0, pre[0]);
+  }
   static_for<0, FM>([&](auto ic) {
     constexpr int i = decltype(ic)::value;
     __builtin_amdgcn_sched_barrier(0);
@@ -651,16 +671,45 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     const int mrow0 = m0 + wm * WM + i * 32, ncol0 = n0 + wn * WN;
     if (vec_ok && !atomic) {
-#pragma unroll 1
-      for (int u = lane; u < 32 * (WN / 8); u += 64) {
-        const int row = u / (WN / 8), c8 = (u % (WN / 8)) * 8;
-        const int m = mrow0 + row, n = ncol0 + c8;
-        if (m < M && n < N) {
-          float v[8];
+      // a lane keeps its 8 columns through the tile: bias8 was loaded once, and the residual / pre-activation
+      // values of a pass were requested one pass earlier (pre[]), so that no pass waits for memory
+      static_for<0, PASSES>([&](auto pc) {
+        constexpr int p = decltype(pc)::value, idx = i * PASSES + p;
+        if constexpr (idx + 1 < FM * PASSES) fetch((idx + 1) / PASSES, (idx + 1) % PASSES, pre[(idx + 1) & 1]);
+        const int row = p * RPP + prow;
+        const int m = mrow0 + row;
+        if (m < M && ncol < N) {
+          float v[8], tt[8];
           load8(strip + row * EP_PITCH + c8, v);
-          epilogue8<E, TC>(g, C, m, n, v, atomic);
+          if (g.epi & EPI_BIAS) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] += bias8[e];
+          }
+          if (g.epi & EPI_GELU) {
+            if (g.aux_out) store8((E*)g.aux_out + (long long)m * g.ldaux + ncol, v);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = gelu_epi<E>(v[e]);
+          }
+          if (pre_aux) {
+            unpack8<E>(pre[idx & 1], tt);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_epi<E>(tt[e]);
+          }
+          if (g.epi & EPI_RESID) {
+            if (pre_res) unpack8<E>(pre[idx & 1], tt);
+            else load8((const E*)g.resid + (long long)m * g.ldr + ncol, tt);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] += tt[e];
+          }
+          TC* cp = C + (long long)m * g.ldc + ncol;
+          if (g.epi & EPI_ACCUM) {
+            load8(cp, tt);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] += tt[e];
+          }
+          store8(cp, v);
         }
-      }
+      });
     } else {
 #pragma unroll 1
       for (int u = lane; u < 32 * WN; u += 64) {
