@@ -32,13 +32,13 @@ def ctx():
 
 # ------------------------------------------------------------------------------------- GEMM kernel
 def _gemm_case(ctx, dtype, impl, a_kc, b_kc, M, N, K, bias=False, resid=False, gelu=False, accumulate=False,
-               out_f32=False, alpha=1.0, seed=0):
+               out_f32=False, alpha=1.0, seed=0, pad=3):
     rng = np.random.default_rng(seed)
     A = rng.normal(size=(M, K)).astype(np.float32)
     Bm = rng.normal(size=(K, N)).astype(np.float32)
     lda = ((K if a_kc else M) + 7) // 8 * 8 + 8
     ldb = ((K if b_kc else N) + 7) // 8 * 8 + 8
-    ldc = N + 3
+    ldc = N + pad   # pad 3: rows not 16-byte aligned (element-wise epilogue); pad 8: the vector epilogue
     Ah = np.zeros((M, lda) if a_kc else (K, lda), np.float32)
     Bh = np.zeros((N, ldb) if b_kc else (K, ldb), np.float32)
     if a_kc:
@@ -102,6 +102,19 @@ def test_gemm_large_tile_sweep(ctx):
     assert _gemm_case(ctx, "bf16", 2, 0, 0, 520, 392, 1000, out_f32=True) < 2e-6
     assert _gemm_case(ctx, "fp16", 2, 1, 1, 520, 1000, 136, bias=True) < OUT16["fp16"]
     assert _gemm_case(ctx, "fp16", 2, 0, 0, 520, 392, 1000, out_f32=True) < 2e-6
+
+
+@pytest.mark.parametrize("variant", range(9))
+def test_gemm_every_tile_variant(ctx, variant):
+    # each compiled tile shape of the MFMA kernel, forced: ragged edges, all three layouts, both output types
+    impl = 100 + variant
+    assert _gemm_case(ctx, "bf16", impl, 1, 0, 600, 520, 264, bias=True, out_f32=True) < 2e-6
+    assert _gemm_case(ctx, "bf16", impl, 1, 1, 520, 776, 136, bias=True, resid=True, alpha=0.5, pad=8) < OUT16["bf16"]
+    assert _gemm_case(ctx, "bf16", impl, 0, 0, 520, 392, 1000, accumulate=True, out_f32=True, pad=8) < 2e-6
+    assert _gemm_case(ctx, "fp16", impl, 1, 0, 264, 520, 200, bias=True, gelu=True, pad=8) < OUT16["fp16"]
+    with pytest.raises(P.L2LError):
+        x = torch.zeros(64, 64, device="cuda", dtype=torch.bfloat16)
+        ctx.op_gemm(P.L2L_BF16, False, 1, 0, 64, 64, 64, x, 64, x, 64, x, 64, impl=100 + 9)   # one past the last variant
 
 
 def test_gemm_rejects_bad_arguments(ctx):
