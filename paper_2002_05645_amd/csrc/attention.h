@@ -1,6 +1,6 @@
-// Fused attention for the bf16 path, head width d = 64, sequence length a multiple of 32 up to 128:
-// scores, softmax and context (forward) and all five attention gradients (backward) of one
-// (sequence, head) pair in one workgroup, without the S x S matrices ever leaving the chip.
+// Fused attention for the 16-bit paths (element type E = bf16 or fp16), head width d = 64, sequence length a
+// multiple of 32 up to 128: scores, softmax and context (forward) and all five attention gradients (backward)
+// of one (sequence, head) pair in one workgroup, without the S x S matrices ever leaving the chip.
 //
 // Everything is computed "transposed": the MFMA tiles are S^T = K Q^T (keys along the accumulator's
 // register axis, queries along its lane axis), so that a softmax row lives in the registers of one
@@ -13,7 +13,7 @@
 // strided in memory (V^T, K^T, and everything contracted over queries) come out of their natural
 // [row][64] LDS image through ds_read_b64_tr_b16.
 //
-// LDS images are [row][64] bf16 (128-byte rows) with the 16-byte chunk c of row r at slot
+// LDS images are [row][64] 16-bit elements (128-byte rows) with the 16-byte chunk c of row r at slot
 // c ^ ((r >> 1) & 7): conflict-free for 16-byte fragment reads, two-way for the transpose reads.
 #pragma once
 #include "gemm.h"
@@ -58,11 +58,16 @@ __device__ __forceinline__ bf16x8 frag_keys_T(const char* img, int kb, int s, in
   return __builtin_bit_cast(bf16x8, v);
 }
 
+// fragments travel as 8 x 16 bits (bf16x8) whatever the element type; only conversions and the MFMA look at E
+template <typename E>
+struct Vec { typedef __attribute__((ext_vector_type(8))) E x8; typedef __attribute__((ext_vector_type(4))) E x4; };
+
+template <typename E>
 __device__ __forceinline__ bf16x8 pack8(const f32x16& a, int r0) {
-  bf16x8 v;
+  typename Vec<E>::x8 v;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) v[i] = (bf16)a[r0 + i];
-  return v;
+  for (int i = 0; i < 8; ++i) v[i] = from_f32<E>(a[r0 + i]);
+  return __builtin_bit_cast(bf16x8, v);
 }
 
 __device__ __forceinline__ float xor32_max(float v) { return fmaxf(v, __shfl_xor(v, 32, 64)); }
@@ -70,17 +75,17 @@ __device__ __forceinline__ float xor32_sum(float v) { return v + __shfl_xor(v, 3
 
 // store a transposed 2 x (32 x 32) accumulator pair (rows = 64 columns of the output, lane = output row) as
 // out[(row0 + lane % 32) * ld + 8 blk + 4 (lane / 32) + {0..3} (+32 for the second tile)], scaled
-__device__ __forceinline__ void store_T(const f32x16 (&acc)[2], bf16* out, long long ld, int lane, float scale) {
-  bf16* p = out + (long long)(lane & 31) * ld + 4 * (lane >> 5);
+template <typename E>
+__device__ __forceinline__ void store_T(const f32x16 (&acc)[2], E* out, long long ld, int lane, float scale) {
+  E* p = out + (long long)(lane & 31) * ld + 4 * (lane >> 5);
 #pragma unroll
   for (int t = 0; t < 2; ++t)
 #pragma unroll
     for (int blk = 0; blk < 4; ++blk) {
-      typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-      bf16x4 v;
+      typename Vec<E>::x4 v;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) v[i] = (bf16)(acc[t][blk * 4 + i] * scale);
-      *(bf16x4*)(p + t * 32 + blk * 8) = v;
+      for (int i = 0; i < 4; ++i) v[i] = from_f32<E>(acc[t][blk * 4 + i] * scale);
+      *(typename Vec<E>::x4*)(p + t * 32 + blk * 8) = v;
     }
 }
 
@@ -89,14 +94,15 @@ constexpr int NKB = SMAX / 32;
 
 // Forward: out[b*S + q, h*64 ..] = softmax_rows(Q K^T * alpha) V for one (b, h) per workgroup; wave w owns queries
 // 32 w .. 32 w + 31.  qkv: [rows, 3H] with Q | K | V column groups.
-__global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16* qkv, bf16* out, int S, int H, int A, float alpha) {
+template <typename E>
+__global__ __launch_bounds__(256) void attn_fwd_kernel(const E* qkv, E* out, int S, int H, int A, float alpha) {
   __shared__ __attribute__((aligned(1024))) char lds[2 * SMAX * 128];
   char* Ks = lds;
   char* Vs = lds + SMAX * 128;
   const int b = blockIdx.x / A, h = blockIdx.x % A;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const long long ld = 3LL * H;
-  const bf16* base = qkv + (long long)b * S * ld + h * 64;
+  const E* base = qkv + (long long)b * S * ld + h * 64;
   const uint32_t bytes = (uint32_t)(((long long)(S - 1) * ld + 64) * 2);
   load_rows(make_rsrc(base + H, bytes), (uint32_t)ld, S, Ks, wave, 4, lane);
   load_rows(make_rsrc(base + 2 * H, bytes), (uint32_t)ld, S, Vs, wave, 4, lane);
@@ -105,7 +111,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16* qkv, bf16* ou
   // this wave's queries as B-operand fragments, straight from memory
   bf16x8 qf[4];
   if (active) {
-    const bf16* qrow = base + (long long)(wave * 32 + (lane & 31)) * ld + (lane >> 5) * 8;
+    const E* qrow = base + (long long)(wave * 32 + (lane & 31)) * ld + (lane >> 5) * 8;
 #pragma unroll
     for (int st = 0; st < 4; ++st) qf[st] = *(const bf16x8*)(qrow + st * 16);
   }
@@ -121,7 +127,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16* qkv, bf16* ou
       f32x16 a = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int s4 = 0; s4 < 4; ++s4)
-        a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Ks, kb * 32 + (lane & 31), s4, lane), qf[s4], a, 0, 0, 0);
+        a = mfma_32x32x16<E>(frag_rows(Ks, kb * 32 + (lane & 31), s4, lane), qf[s4], a);
 #pragma unroll
       for (int r = 0; r < 16; ++r) { a[r] *= alpha; m = fmaxf(m, a[r]); }
       st_[kb] = a;
@@ -146,9 +152,9 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16* qkv, bf16* ou
     if (kb < nkb) {
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
-        const bf16x8 pf = pack8(st_[kb], 8 * s2);
+        const bf16x8 pf = pack8<E>(st_[kb], 8 * s2);
 #pragma unroll
-        for (int t = 0; t < 2; ++t) o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_keys_T(Vs, kb, s2, t, lane), pf, o[t], 0, 0, 0);
+        for (int t = 0; t < 2; ++t) o[t] = mfma_32x32x16<E>(frag_keys_T(Vs, kb, s2, t, lane), pf, o[t]);
       }
     }
   store_T(o, out + ((long long)b * S + wave * 32) * H + h * 64, H, lane, inv);
@@ -156,18 +162,18 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16* qkv, bf16* ou
 
 
 // ---- backward ------------------------------------------------------------------------------------------
-// image of P or dS for products over queries: [q][SMAX] bf16, 256-byte rows, the 32-byte group holding keys
+// image of P or dS for products over queries: [q][SMAX] 16-bit elements, 256-byte rows, the 32-byte group holding keys
 // 16 p .. 16 p + 15 of row q at group slot p ^ (q & 3) (so that four consecutive query rows hit different banks)
 __device__ __forceinline__ int pq_addr(int q, int key) { return q * 256 + (((key >> 4) ^ (q & 3)) * 32) + (key & 15) * 2; }
 
+template <typename E>
 __device__ __forceinline__ void pq_store(char* img, const f32x16& a, int q, int kb, int lane) {
-  typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 #pragma unroll
   for (int blk = 0; blk < 4; ++blk) {
-    bf16x4 v;
+    typename Vec<E>::x4 v;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) v[i] = (bf16)a[blk * 4 + i];
-    *(bf16x4*)(img + pq_addr(q, kb * 32 + 8 * blk + 4 * (lane >> 5))) = v;
+    for (int i = 0; i < 4; ++i) v[i] = from_f32<E>(a[blk * 4 + i]);
+    *(typename Vec<E>::x4*)(img + pq_addr(q, kb * 32 + 8 * blk + 4 * (lane >> 5))) = v;
   }
 }
 
@@ -195,8 +201,8 @@ constexpr int BWD_LDS = 4 * SMAX * 128 + 2 * SMAX * 256;
 // Backward for one (b, h) per workgroup.  dout: [rows, H] gradient of the context; dqkv: [rows, 3H] receives
 // dQ | dK | dV.  Phase 1 (wave w = queries 32 w ..): recompute P, dP = dO V^T, dS = P (dP - rowsum(P dP)),
 // dQ = alpha dS K, and park P and dS in LDS.  Phase 2 (wave w = keys 32 w ..): dV = P^T dO, dK = alpha dS^T Q.
-__global__ __launch_bounds__(256) void attn_bwd_kernel(const bf16* qkv, const bf16* dout, bf16* dqkv, int S, int H, int A,
-                                                       float alpha) {
+template <typename E>
+__global__ __launch_bounds__(256) void attn_bwd_kernel(const E* qkv, const E* dout, E* dqkv, int S, int H, int A, float alpha) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   char* Ks = lds;
   char* Vs = lds + SMAX * 128;
@@ -207,19 +213,19 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(const bf16* qkv, const bf
   const int b = blockIdx.x / A, h = blockIdx.x % A;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const long long ld = 3LL * H;
-  const bf16* base = qkv + (long long)b * S * ld + h * 64;
+  const E* base = qkv + (long long)b * S * ld + h * 64;
   const uint32_t bytes = (uint32_t)(((long long)(S - 1) * ld + 64) * 2);
   load_rows(make_rsrc(base, bytes), (uint32_t)ld, S, Qs, wave, 4, lane);
   load_rows(make_rsrc(base + H, bytes), (uint32_t)ld, S, Ks, wave, 4, lane);
   load_rows(make_rsrc(base + 2 * H, bytes), (uint32_t)ld, S, Vs, wave, 4, lane);
-  const bf16* dob = dout + (long long)b * S * H + h * 64;
+  const E* dob = dout + (long long)b * S * H + h * 64;
   load_rows(make_rsrc(dob, (uint32_t)(((long long)(S - 1) * H + 64) * 2)), (uint32_t)H, S, Os, wave, 4, lane);
   const int nkb = S / 32;
   const bool active = wave < nkb;
   wait_vm0();
   __syncthreads();
 
-  bf16* dq_out = dqkv + ((long long)b * S + wave * 32) * ld + h * 64;
+  E* dq_out = dqkv + ((long long)b * S + wave * 32) * ld + h * 64;
   if (active) {
     const int qrow = wave * 32 + (lane & 31);
     bf16x8 qf[4], of[4];
@@ -235,8 +241,8 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(const bf16* qkv, const bf
         const int krow = kb * 32 + (lane & 31);
 #pragma unroll
         for (int s4 = 0; s4 < 4; ++s4) {
-          a = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Ks, krow, s4, lane), qf[s4], a, 0, 0, 0);
-          d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Vs, krow, s4, lane), of[s4], d, 0, 0, 0);
+          a = mfma_32x32x16<E>(frag_rows(Ks, krow, s4, lane), qf[s4], a);
+          d = mfma_32x32x16<E>(frag_rows(Vs, krow, s4, lane), of[s4], d);
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) { a[r] *= alpha; m = fmaxf(m, a[r]); }
@@ -268,13 +274,13 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(const bf16* qkv, const bf
       if (kb < nkb) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) dp_[kb][r] = p_[kb][r] * (dp_[kb][r] - dsum);   // dS
-        pq_store(Ps, p_[kb], qrow, kb, lane);
-        pq_store(Ds, dp_[kb], qrow, kb, lane);
+        pq_store<E>(Ps, p_[kb], qrow, kb, lane);
+        pq_store<E>(Ds, dp_[kb], qrow, kb, lane);
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
-          const bf16x8 df = pack8(dp_[kb], 8 * s2);
+          const bf16x8 df = pack8<E>(dp_[kb], 8 * s2);
 #pragma unroll
-          for (int t = 0; t < 2; ++t) dq[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_keys_T(Ks, kb, s2, t, lane), df, dq[t], 0, 0, 0);
+          for (int t = 0; t < 2; ++t) dq[t] = mfma_32x32x16<E>(frag_keys_T(Ks, kb, s2, t, lane), df, dq[t]);
         }
       }
     store_T(dq, dq_out, ld, lane, alpha);
@@ -291,8 +297,8 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(const bf16* qkv, const bf
       const bf16x8 pf = pq_frag(Ps, s, wave, lane), df = pq_frag(Ds, s, wave, lane);
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
-        dv[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_queries_T(Os, s, t, lane), pf, dv[t], 0, 0, 0);
-        dk[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_queries_T(Qs, s, t, lane), df, dk[t], 0, 0, 0);
+        dv[t] = mfma_32x32x16<E>(frag_queries_T(Os, s, t, lane), pf, dv[t]);
+        dk[t] = mfma_32x32x16<E>(frag_queries_T(Qs, s, t, lane), df, dk[t]);
       }
     }
     store_T(dv, dq_out + 2 * H, ld, lane, 1.0f);

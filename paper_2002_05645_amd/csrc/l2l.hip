@@ -8,6 +8,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <type_traits>
 #include <utility>
 #include <vector>
 
@@ -449,10 +450,12 @@ int fill_zero_copy_stream(l2l_ctx* c, void* p, size_t bytes) {
   return L2L_OK;
 }
 
-// the fused attention kernels take bf16, head width 64 and sequences of 32, 64, 96 or 128 tokens
+// the fused attention kernels take the 16-bit formats, head width 64 and sequences of 32, 64, 96 or 128 tokens
+template <typename T>
+using attn_elem = typename std::conditional<std::is_same<T, fp16>::value, fp16, bf16>::type;   // (fp32 never gets there)
 bool fused_attention_ok(const l2l_ctx* c) {
   const l2l_config& f = c->cfg;
-  return f.dtype == L2L_BF16 && f.hidden / f.heads == 64 && f.seq % 32 == 0 && f.seq <= attn::SMAX && !c->no_fused_attention;
+  return is16(f.dtype) && f.hidden / f.heads == 64 && f.seq % 32 == 0 && f.seq <= attn::SMAX && !c->no_fused_attention;
 }
 
 int fill_zero(l2l_ctx* c, void* p, size_t bytes) {
@@ -512,7 +515,8 @@ int layer_forward_group(l2l_ctx* c, int slot, const void* x, void* y, int ng, bo
   if (fused_attention_ok(c)) {
     const double fl = 4.0 * S * S * d * nseq * A;
     L2L_TRY(timed(c, L2L_PROF_ATTN, fl, (3.0 + 1.0) * M * H * sizeof(T), [&] {
-      hipLaunchKernelGGL(attn::attn_fwd_kernel, dim3(nseq * A), dim3(256), 0, c->cs, (const bf16*)qkv, (bf16*)c->c, S, H, A,
+      using E = attn_elem<T>;
+      hipLaunchKernelGGL(attn::attn_fwd_kernel<E>, dim3(nseq * A), dim3(256), 0, c->cs, (const E*)qkv, (E*)c->c, S, H, A,
                          1.0f / sqrtf((float)d));
     }));
   } else
@@ -609,8 +613,9 @@ int layer_backward_group(l2l_ctx* c, const void* params, const void* x, void* dy
   if (fused_attention_ok(c)) {
     const double fl = 10.0 * S * S * d * nseq * A;
     L2L_TRY(timed(c, L2L_PROF_ATTN, fl, (3.0 + 1.0 + 3.0) * M * H * sizeof(T), [&] {
-      hipLaunchKernelGGL(attn::attn_bwd_kernel, dim3(nseq * A), dim3(256), attn::BWD_LDS, c->cs, (const bf16*)qkv,
-                         (const bf16*)c->dc, (bf16*)dqkv, S, H, A, alpha);
+      using E = attn_elem<T>;
+      hipLaunchKernelGGL(attn::attn_bwd_kernel<E>, dim3(nseq * A), dim3(256), attn::BWD_LDS, c->cs, (const E*)qkv,
+                         (const E*)c->dc, (E*)dqkv, S, H, A, alpha);
     }));
   } else
   {
@@ -846,7 +851,8 @@ int l2l_create(const l2l_config* cfg, void* compute_stream, void* copy_stream, l
   c->group = g;
   c->Mg = g * c->T;
   if (const char* e = getenv("L2L_NO_FUSED_ATTENTION")) c->no_fused_attention = atoi(e) != 0;
-  (void)hipFuncSetAttribute((const void*)attn::attn_bwd_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, attn::BWD_LDS);
+  (void)hipFuncSetAttribute((const void*)attn::attn_bwd_kernel<bf16>, hipFuncAttributeMaxDynamicSharedMemorySize, attn::BWD_LDS);
+  (void)hipFuncSetAttribute((const void*)attn::attn_bwd_kernel<fp16>, hipFuncAttributeMaxDynamicSharedMemorySize, attn::BWD_LDS);
   *out = c;  // from here on the caller can read l2l_last_error and must l2l_destroy
 
   const size_t es = esize(cfg->dtype);

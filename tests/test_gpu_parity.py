@@ -240,18 +240,20 @@ def test_layer_bert_large_full_shape_bf16():
     _assert_errs(_layer_case(w), TOL["bf16"])
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
 @pytest.mark.parametrize("seq", [32, 64, 96, 128])
-def test_layer_fused_attention_sequence_lengths(seq):
+def test_layer_fused_attention_sequence_lengths(seq, dtype):
     # head width 64 and S a multiple of 32 up to 128: the fused attention kernels (forward and backward)
-    w = S.Workload("fused", 1, 128, 2, 256, seq, 50, 3, 2, "bf16", 1.0, 79 + seq)
-    _assert_errs(_layer_case(w), TOL["bf16"])
+    w = S.Workload("fused", 1, 128, 2, 256, seq, 50, 3, 2, dtype, 1.0, 79 + seq)
+    _assert_errs(_layer_case(w), TOL[dtype])
 
 
-def test_layer_unfused_attention_path_still_matches(monkeypatch):
+@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
+def test_layer_unfused_attention_path_still_matches(monkeypatch, dtype):
     # the batched-GEMM attention path (used for other head widths / sequence lengths), forced at a fused shape
     monkeypatch.setenv("L2L_NO_FUSED_ATTENTION", "1")
-    w = S.Workload("unfused", 1, 128, 2, 256, 64, 50, 3, 2, "bf16", 1.0, 80)
-    _assert_errs(_layer_case(w), TOL["bf16"])
+    w = S.Workload("unfused", 1, 128, 2, 256, 64, 50, 3, 2, dtype, 1.0, 80)
+    _assert_errs(_layer_case(w), TOL[dtype])
 
 
 @pytest.mark.parametrize("hidden,heads", [(1536, 24), (2304, 36), (6144, 48)])
