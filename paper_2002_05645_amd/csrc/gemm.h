@@ -454,7 +454,13 @@ struct DirectLoader {
 
   __device__ __forceinline__ static void load(__amdgpu_buffer_rsrc_t rs, uint32_t ld, int k0, int K, char* stage, int wave,
                                               int lane) {
-    static_for<0, PER>([&](auto ic) {
+    load_part<0, PER>(rs, ld, k0, K, stage, wave, lane);
+  }
+  // blocks [I0, I1) of this wave's PER blocks
+  template <int I0, int I1>
+  __device__ __forceinline__ static void load_part(__amdgpu_buffer_rsrc_t rs, uint32_t ld, int k0, int K, char* stage,
+                                                   int wave, int lane) {
+    static_for<(I0 < PER ? I0 : PER), (I1 < PER ? I1 : PER)>([&](auto ic) {
       constexpr int i = decltype(ic)::value;
       const int blk = i * (NT / 64) + wave;
       uint32_t off;
@@ -576,6 +582,22 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
     acc[T] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   });
 
+  // A wave's loads of a tile (PER blocks of A, then PER blocks of B) are not issued in one burst: the memory
+  // pipeline of a CU takes them at about 30 bytes per clock, a wave that issues into a full queue stands still, MFMAs
+  // included, and the other waves then wait for it at the barrier.  The loads of tile t + 2 are spread over the
+  // window in which their stage is free: LS0 of them right after the barrier (last k16-step of tile t), then up to
+  // LS1, LS2, LS3 in total by the first three k16-steps of tile t + 1; the barrier of tile t + 1 needs them landed.
+  constexpr int NLD = DA::PER + DB::PER;
+  // Measured (256 x 256 tile, 8 loads per wave): K-contiguous x K-contiguous gains 6-8 % with 2 + 3 + 3 + 0 against all
+  // 8 at once (per k-tile: 3250 -> 2700 clocks, of which load issue 920 -> 90 and barrier wait 620 -> 310);
+  // K-strided operands, whose fragment reads already load the LDS pipe more, do best with the burst.
+  constexpr int SPLIT0 = (AKC && BKC) ? 2 : (AKC || BKC) ? 4 : 8, SPLIT1 = (AKC && BKC) ? 5 : 8, SPLIT2 = 8;   // cumulative eighths
+  constexpr int LS0 = (NLD * SPLIT0 + 7) / 8, LS1 = (NLD * SPLIT1 + 7) / 8, LS2 = (NLD * SPLIT2 + 7) / 8;
+  const auto load_ab = [&](auto i0c, auto i1c, int kbase, char* stage) {
+    constexpr int I0 = decltype(i0c)::value, I1 = decltype(i1c)::value;
+    DA::template load_part<I0, I1>(ra, lda, kbase, K, stage, wave, lane);
+    DB::template load_part<(I0 > DA::PER ? I0 - DA::PER : 0), (I1 > DA::PER ? I1 - DA::PER : 0)>(rb, ldb, kbase, K, stage + DA::BYTES, wave, lane);
+  };
   FragAddr<BM, AKC> fa;
   FragAddr<BN, BKC> fb;
   fa.init(wm * WM, lane);
@@ -590,8 +612,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
   DB::load(rb, ldb, kt0 * BK, K, lds + DA::BYTES, wave, lane);
   wait_vm0();
   __syncthreads();
-  DA::load(ra, lda, (kt0 + 1) * BK, K, lds + STAGE, wave, lane);
-  DB::load(rb, ldb, (kt0 + 1) * BK, K, lds + STAGE + DA::BYTES, wave, lane);
+  load_ab(std::integral_constant<int, 0>{}, std::integral_constant<int, LS0>{}, (kt0 + 1) * BK, lds + STAGE);
 
   bf16x8 af[2 * FM], bfr[2 * FN];
   static_for<0, FM>([&](auto i) { af[i] = fa.template read<decltype(i)::value, 0>(lds); });
@@ -604,13 +625,15 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
       constexpr int kk = decltype(kkc)::value;
       constexpr int cs = (kk & 1), ns = ((kk + 1) & 1);
       if constexpr (kk + 1 < KK) {
+        // the rest of tile kt + 1's loads (its stage was released at the previous barrier)
+        constexpr int P0 = kk == 0 ? LS0 : kk == 1 ? LS1 : LS2, P1 = kk == 0 ? LS1 : kk == 1 ? LS2 : NLD;
+        if constexpr (P1 > P0) load_ab(std::integral_constant<int, P0>{}, std::integral_constant<int, P1>{}, (kt + 1) * BK, (char*)nxt);
         static_for<0, FM>([&](auto i) { af[ns * FM + i] = fa.template read<decltype(i)::value, kk + 1>(cur); });
         static_for<0, FN>([&](auto j) { bfr[ns * FN + j] = fb.template read<decltype(j)::value, kk + 1>(cur + DA::BYTES); });
       } else {
         // every fragment of this tile is in registers and this wave's part of the next tile has landed
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        DA::load(ra, lda, (kt + 2) * BK, K, cur, wave, lane);
-        DB::load(rb, ldb, (kt + 2) * BK, K, cur + DA::BYTES, wave, lane);
+        load_ab(std::integral_constant<int, 0>{}, std::integral_constant<int, LS0>{}, (kt + 2) * BK, cur);
         static_for<0, FM>([&](auto i) { af[ns * FM + i] = fa.template read<decltype(i)::value, 0>(nxt); });
         static_for<0, FN>([&](auto j) { bfr[ns * FN + j] = fb.template read<decltype(j)::value, 0>(nxt + DA::BYTES); });
       }
