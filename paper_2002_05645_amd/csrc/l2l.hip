@@ -395,12 +395,17 @@ int ln_fwd(l2l_ctx* c, const void* x, const void* gamma, const void* beta, void*
 template <typename T>
 int bias_grad(l2l_ctx* c, const void* a, long long lda, float* out, long long rows, int n, const int* rows_dev = nullptr);
 
-// LayerNorm backward: dx, dgamma, dbeta, and dbias = colsum(dx) (the bias in front of the LayerNorm)
+// whether LayerNorm backward runs as the one-pass kernel, which can also compute the row statistics itself
+bool ln_bwd_one_pass(int n) { return n % 8 == 0 && n <= 2048; }
+
+// LayerNorm backward: dx, dgamma, dbeta, and dbias = colsum(dx) (the bias in front of the LayerNorm).
+// mean == rstd == nullptr (one-pass kernel only): the statistics are recomputed from x with `eps`.
 template <typename T>
 int ln_bwd(l2l_ctx* c, const void* dy, const void* x, const float* mean, const float* rstd, const void* gamma, void* dx,
-           float* dgamma, float* dbeta, float* dbias, long long rows, int n) {
+           float* dgamma, float* dbeta, float* dbias, long long rows, int n, float eps) {
   if (rows <= 0) return L2L_OK;
-  if (n % 8 == 0 && n <= 2048) {   // one pass, column sums included
+  if (!mean && !ln_bwd_one_pass(n)) return fail(c, L2L_E_STATE, "ln_bwd: statistics missing");
+  if (ln_bwd_one_pass(n)) {   // one pass, column sums included
     const int nch = n <= 512 ? 1 : n <= 1024 ? 2 : 4;
     const size_t lds = (size_t)4 * 3 * nch * 512 * sizeof(float);
     return timed(c, L2L_PROF_ROWWISE, 0, 3.0 * rows * n * sizeof(T), [&] {
@@ -408,7 +413,7 @@ int ln_bwd(l2l_ctx* c, const void* dy, const void* x, const float* mean, const f
       auto go = [&](auto kern) {
         static_cast<void>(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         hipLaunchKernelGGL(kern, grid, dim3(256), lds, c->cs, (const T*)dy, (const T*)x, mean, rstd, (const T*)gamma, (T*)dx,
-                           dgamma, dbeta, dbias, (int)rows, n);
+                           dgamma, dbeta, dbias, (int)rows, n, eps);
       };
       if (nch == 1) go(ln_bwd_fused_kernel<T, 1>);
       else if (nch == 2) go(ln_bwd_fused_kernel<T, 2>);
@@ -555,8 +560,10 @@ int layer_forward_group(l2l_ctx* c, int slot, const void* x, void* y, int ng, bo
     h.epi = EPI_BIAS | EPI_RESID; h.bias = P + off[T_B2]; h.resid = c->y1; h.ldr = H;
     L2L_TRY(gemm(c, dt, false, h));
     if (keep) {
-      // backward needs only the statistics of LN2; y itself was stashed by the forward pass
-      L2L_TRY(ln_fwd<T>(c, c->r2, P + off[T_G2], P + off[T_BE2], c->ytmp, c->mean2, c->rstd2, M, H, f.ln_eps));
+      // backward needs only the statistics of LN2 (y itself was stashed by the forward pass), and the one-pass
+      // backward kernel computes them itself
+      if (!ln_bwd_one_pass(H))
+        L2L_TRY(ln_fwd<T>(c, c->r2, P + off[T_G2], P + off[T_BE2], c->ytmp, c->mean2, c->rstd2, M, H, f.ln_eps));
     } else {
       L2L_TRY(ln_fwd<T>(c, c->r2, P + off[T_G2], P + off[T_BE2], y, nullptr, nullptr, M, H, f.ln_eps));
     }
@@ -579,7 +586,9 @@ int layer_backward_group(l2l_ctx* c, const void* params, const void* x, void* dy
   const float alpha = 1.0f / sqrtf((float)d);
 
   // LN2 backward
-  L2L_TRY(ln_bwd<T>(c, dydx, c->r2, c->mean2, c->rstd2, P + off[T_G2], c->dr2, G + off[T_G2], G + off[T_BE2], G + off[T_B2], M, H));
+  const bool own_stats = ln_bwd_one_pass(H);   // then the recompute pass did not run LN2
+  L2L_TRY(ln_bwd<T>(c, dydx, c->r2, own_stats ? nullptr : c->mean2, own_stats ? nullptr : c->rstd2, P + off[T_G2], c->dr2,
+                    G + off[T_G2], G + off[T_BE2], G + off[T_B2], M, H, f.ln_eps));
   // FFN2 backward: dU1 = (dR2 W2^T) * gelu'(U1); dW2 += G^T dR2 (db2 came with LN2's backward)
   {
     GemmArgs g = gemm_args((int)M, F, H, c->dr2, H, 1, P + off[T_W2], H, 1, c->du1, F);
@@ -600,7 +609,7 @@ int layer_backward_group(l2l_ctx* c, const void* params, const void* x, void* dy
     L2L_TRY(bias_grad<T>(c, c->du1, F, G + off[T_B1], M, F));
   }
   // LN1 backward
-  L2L_TRY(ln_bwd<T>(c, c->dy1, c->r1, c->mean1, c->rstd1, P + off[T_G1], c->dr1, G + off[T_G1], G + off[T_BE1], G + off[T_BO], M, H));
+  L2L_TRY(ln_bwd<T>(c, c->dy1, c->r1, c->mean1, c->rstd1, P + off[T_G1], c->dr1, G + off[T_G1], G + off[T_BE1], G + off[T_BO], M, H, f.ln_eps));
   // output projection backward
   {
     GemmArgs g = gemm_args((int)M, H, H, c->dr1, H, 1, P + off[T_WO], H, 1, c->dc, H);

@@ -139,7 +139,9 @@ constexpr int LNF_ROWS = 64;   // measured best of 16 .. 128 at 32768 x 1024: fe
 template <typename T, int NCH>
 __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* dy, const T* x, const float* mean, const float* rstd,
                                                            const T* gamma, T* dx, float* dgamma, float* dbeta,
-                                                           float* dbias, int rows, int n) {
+                                                           float* dbias, int rows, int n, float eps) {
+  // mean == nullptr: the row statistics are computed here, from the row already held in registers (same two
+  // passes as the forward kernel), which spares a forward-statistics kernel where nothing else needs its output
   extern __shared__ float lnf_red[];   // [4 waves][3][NCH * 512]
   constexpr int NC = NCH * 512;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -153,15 +155,41 @@ __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* dy, const T*
   }
   const int r0 = blockIdx.x * LNF_ROWS, r1 = min(rows, r0 + LNF_ROWS);
   for (int r = r0 + w; r < r1; r += 4) {
-    const float mu = mean[r], rs = rstd[r];
     float xh[NCH][8], d[NCH][8];
-    float c1 = 0.f, c2 = 0.f;
 #pragma unroll
     for (int k = 0; k < NCH; ++k) {
       const int j = lane * 8 + k * 512;
       if (j < n) {
         load8(x + (long long)r * n + j, xh[k]);
         load8(dy + (long long)r * n + j, d[k]);
+      }
+    }
+    float mu, rs;
+    if (mean) {
+      mu = mean[r];
+      rs = rstd[r];
+    } else {
+      float s = 0.f, q = 0.f;
+#pragma unroll
+      for (int k = 0; k < NCH; ++k)
+        if (lane * 8 + k * 512 < n) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) s += xh[k][i];
+        }
+      mu = wave_sum(s) / n;
+#pragma unroll
+      for (int k = 0; k < NCH; ++k)
+        if (lane * 8 + k * 512 < n) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) q += (xh[k][i] - mu) * (xh[k][i] - mu);
+        }
+      rs = rsqrtf(wave_sum(q) / n + eps);
+    }
+    float c1 = 0.f, c2 = 0.f;
+#pragma unroll
+    for (int k = 0; k < NCH; ++k) {
+      const int j = lane * 8 + k * 512;
+      if (j < n) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           xh[k][i] = (xh[k][i] - mu) * rs;
