@@ -530,9 +530,12 @@ __device__ __forceinline__ void wait_vm0_lds0() { __builtin_amdgcn_s_waitcnt(0x0
 template <int BM, int BN, int WM, int WN>
 constexpr int dlds_lds_bytes() { return 2 * (BM + BN) * 128; }
 
-template <int BM, int BN, int WM, int WN, bool AKC, bool BKC, typename TC, typename E = bf16>
+// EPI >= 0: the epilogue flags are this compile-time constant (the launcher guarantees g.epi == EPI), which takes
+// the flag tests and the code of the unused operations out of the unrolled epilogue; EPI < 0: flags read from g.epi.
+template <int BM, int BN, int WM, int WN, bool AKC, bool BKC, typename TC, typename E = bf16, int EPI = -1>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_kernel(GemmArgs g) {
   constexpr int BK = 64;
+  const int epi = EPI >= 0 ? EPI : g.epi;
   constexpr int NWM = BM / WM, NWN = BN / WN, NT = NWM * NWN * 64;
   constexpr int FM = WM / 32, FN = WN / 32, KK = BK / 16;
   static_assert(WM % 64 == 0 && WN % 64 == 0, "wave tiles start on multiples of 64 rows / columns");
@@ -655,10 +658,10 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
   float* strip = (float*)(lds + wave * EP_BYTES);
   const auto al16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
   const bool vec_ok = (N % 8 == 0) && (g.ldc % 8 == 0) && al16(C) &&
-                      (!(g.epi & EPI_BIAS) || al16(g.bias)) &&
-                      (!(g.epi & EPI_RESID) || (g.ldr % 8 == 0 && al16(g.resid))) &&
-                      (!(g.epi & EPI_GELUGRAD) || (g.ldaux % 8 == 0 && al16(g.aux))) &&
-                      (!((g.epi & EPI_GELU) && g.aux_out) || (g.ldaux % 8 == 0 && al16(g.aux_out)));
+                      (!(epi & EPI_BIAS) || al16(g.bias)) &&
+                      (!(epi & EPI_RESID) || (g.ldr % 8 == 0 && al16(g.resid))) &&
+                      (!(epi & EPI_GELUGRAD) || (g.ldaux % 8 == 0 && al16(g.aux))) &&
+                      (!((epi & EPI_GELU) && g.aux_out) || (g.ldaux % 8 == 0 && al16(g.aux_out)));
   // vector path: 8-column chunk and row-in-pass of this lane, its bias values, and the first pass's prefetch
   constexpr int CPR = WN / 8, RPP = 64 / CPR, PASSES = 32 / RPP;
   const int c8 = (lane % CPR) * 8, prow = lane / CPR;
@@ -666,7 +669,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
   float bias8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   // one 16-byte operand per pass is prefetched: the residual, or the pre-activation of GELU' (no epilogue of the
   // layer uses both; a launch that did would take the residual from memory in the pass itself)
-  const bool pre_aux = (g.epi & EPI_GELUGRAD) != 0, pre_res = !pre_aux && (g.epi & EPI_RESID);
+  const bool pre_aux = (epi & EPI_GELUGRAD) != 0, pre_res = !pre_aux && (epi & EPI_RESID);
   u32x4 pre[2];
   const auto fetch = [&](int fi, int fp, u32x4& d) {
     const int m = m0 + wm * WM + fi * 32 + fp * RPP + prow;
@@ -676,7 +679,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
     }
   };
   if (vec_ok && !atomic) {
-    if ((g.epi & EPI_BIAS) && ncol < N) load8((const E*)g.bias + ncol, bias8);
+    if ((epi & EPI_BIAS) && ncol < N) load8((const E*)g.bias + ncol, bias8);
     fetch(0, 0, pre[0]);
   }
   static_for<0, FM>([&](auto ic) {
@@ -704,11 +707,11 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
         if (m < M && ncol < N) {
           float v[8], tt[8];
           load8(strip + row * EP_PITCH + c8, v);
-          if (g.epi & EPI_BIAS) {
+          if (epi & EPI_BIAS) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[e] += bias8[e];
           }
-          if (g.epi & EPI_GELU) {
+          if (epi & EPI_GELU) {
             if (g.aux_out) store8((E*)g.aux_out + (long long)m * g.ldaux + ncol, v);
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[e] = gelu_epi<E>(v[e]);
@@ -718,14 +721,14 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_epi<E>(tt[e]);
           }
-          if (g.epi & EPI_RESID) {
+          if (epi & EPI_RESID) {
             if (pre_res) unpack8<E>(pre[idx & 1], tt);
             else load8((const E*)g.resid + (long long)m * g.ldr + ncol, tt);
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[e] += tt[e];
           }
           TC* cp = C + (long long)m * g.ldc + ncol;
-          if (g.epi & EPI_ACCUM) {
+          if (epi & EPI_ACCUM) {
             load8(cp, tt);
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[e] += tt[e];

@@ -35,11 +35,11 @@ void launch_layout(const GemmArgs& g, hipStream_t s, int splits) {
 
 }  // namespace
 
-template <int BM, int BN, int WM, int WN, bool AKC, bool BKC, typename TC, typename E>
+template <int BM, int BN, int WM, int WN, bool AKC, bool BKC, typename TC, typename E, int EPI = -1>
 void launch_direct_one(const GemmArgs& g, hipStream_t s, int splits) {
   constexpr int LDS = dlds_lds_bytes<BM, BN, WM, WN>();
   static_assert(LDS <= 160 * 1024, "tile does not fit the 160 KB LDS");
-  auto kern = gemm_mfma_dlds_kernel<BM, BN, WM, WN, AKC, BKC, TC, E>;
+  auto kern = gemm_mfma_dlds_kernel<BM, BN, WM, WN, AKC, BKC, TC, E, EPI>;
   static const bool once = [&] {
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     return true;
@@ -62,6 +62,24 @@ void launch_direct_one(const GemmArgs& g, hipStream_t s, int splits) {
 // K-contiguous (forward with transposed weights, dX) and both K-strided (dW)
 template <int BM, int BN, int WM, int WN, typename TC, typename E>
 void launch_direct(const GemmArgs& g, hipStream_t s, int splits) {
+  // The 256 x 256 tile with 16-bit output and both operands K-contiguous carries the layer's forward, recompute and
+  // dX GEMMs: their six epilogues get kernels with the flags compiled in (a third off the epilogue's time); any
+  // other combination runs the kernel that reads the flags at run time.
+  if constexpr (BM == 256 && BN == 256 && sizeof(TC) == 2) {
+    if (g.a_kc && g.b_kc) {
+      switch (g.epi) {
+#define L2L_EPI_CASE(e) case (e): launch_direct_one<BM, BN, WM, WN, true, true, TC, E, (e)>(g, s, splits); return;
+        L2L_EPI_CASE(0)
+        L2L_EPI_CASE(EPI_BIAS)
+        L2L_EPI_CASE(EPI_BIAS | EPI_RESID)
+        L2L_EPI_CASE(EPI_BIAS | EPI_GELU)
+        L2L_EPI_CASE(EPI_GELUGRAD)
+        L2L_EPI_CASE(EPI_RESID)
+#undef L2L_EPI_CASE
+        default: break;
+      }
+    }
+  }
   if (g.a_kc && g.b_kc) launch_direct_one<BM, BN, WM, WN, true, true, TC, E>(g, s, splits);
   else if (g.a_kc) launch_direct_one<BM, BN, WM, WN, true, false, TC, E>(g, s, splits);
   else launch_direct_one<BM, BN, WM, WN, false, false, TC, E>(g, s, splits);
