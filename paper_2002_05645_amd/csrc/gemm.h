@@ -536,6 +536,7 @@ template <int BM, int BN, int WM, int WN, bool AKC, bool BKC, typename TC, typen
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_kernel(GemmArgs g) {
   constexpr int BK = 64;
   const int epi = EPI >= 0 ? EPI : g.epi;
+  const float alpha = EPI >= 0 ? 1.0f : g.alpha;   // the launcher sends only alpha = 1 to the kernels with compiled-in flags
   constexpr int NWM = BM / WM, NWN = BN / WN, NT = NWM * NWN * 64;
   constexpr int FM = WM / 32, FN = WN / 32, KK = BK / 16;
   static_assert(WM % 64 == 0 && WN % 64 == 0, "wave tiles start on multiples of 64 rows / columns");
@@ -671,11 +672,15 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
   // layer uses both; a launch that did would take the residual from memory in the pass itself)
   const bool pre_aux = (epi & EPI_GELUGRAD) != 0, pre_res = !pre_aux && (epi & EPI_RESID);
   u32x4 pre[2];
+  // row offsets: the lane's own part (row prow of a pass, its 8 columns) once per tile; the pass's first row is the
+  // same for the whole wave, so its product with the row stride is scalar work
+  const long long pre_ld = pre_aux ? g.ldaux : g.ldr;
+  const E* pre_lane = (pre_aux ? (const E*)g.aux : (const E*)g.resid) + (long long)prow * pre_ld + ncol;
+  TC* c_lane = C + (long long)prow * g.ldc + ncol;
   const auto fetch = [&](int fi, int fp, u32x4& d) {
-    const int m = m0 + wm * WM + fi * 32 + fp * RPP + prow;
-    if (m < M && ncol < N) {
-      if (pre_aux) d = *(const u32x4*)((const E*)g.aux + (long long)m * g.ldaux + ncol);
-      else if (pre_res) d = *(const u32x4*)((const E*)g.resid + (long long)m * g.ldr + ncol);
+    const int mu = m0 + wm * WM + fi * 32 + fp * RPP;   // wave-uniform
+    if (mu + prow < M && ncol < N) {
+      if (pre_aux || pre_res) d = *(const u32x4*)(pre_lane + (long long)mu * pre_ld);
     }
   };
   if (vec_ok && !atomic) {
@@ -685,11 +690,18 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
   static_for<0, FM>([&](auto ic) {
     constexpr int i = decltype(ic)::value;
     __builtin_amdgcn_sched_barrier(0);
-    static_for<0, FN>([&](auto jc) {
-      constexpr int j = decltype(jc)::value;
-      static_for<0, 16>([&](auto rc) {
-        constexpr int rr = decltype(rc)::value;
-        strip[(8 * (rr >> 2) + 4 * (lane >> 5) + (rr & 3)) * EP_PITCH + j * 32 + (lane & 31)] = g.alpha * acc[i * FN + j][rr];
+    // register rr of a lane: row 8 (rr / 4) + 4 (lane / 32) + rr % 4, column lane % 32.  One base address per group
+    // of four registers keeps the offsets of its stores within the range of the two-address LDS store.
+    static_for<0, 4>([&](auto gc) {
+      constexpr int g4 = decltype(gc)::value;
+      int so = (8 * g4 + 4 * (lane >> 5)) * EP_PITCH + (lane & 31);
+      asm volatile("" : "+v"(so));   // opaque, or the four bases are folded back into one with large offsets
+      static_for<0, FN>([&](auto jc) {
+        constexpr int j = decltype(jc)::value;
+        static_for<0, 4>([&](auto rc) {
+          constexpr int r4 = decltype(rc)::value;
+          strip[so + r4 * EP_PITCH + j * 32] = alpha * acc[i * FN + j][4 * g4 + r4];
+        });
       });
     });
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -727,7 +739,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[e] += tt[e];
           }
-          TC* cp = C + (long long)m * g.ldc + ncol;
+          TC* cp = c_lane + (long long)(mrow0 + p * RPP) * g.ldc;
           if (epi & EPI_ACCUM) {
             load8(cp, tt);
 #pragma unroll

@@ -66,7 +66,7 @@ void launch_direct(const GemmArgs& g, hipStream_t s, int splits) {
   // dX GEMMs: their six epilogues get kernels with the flags compiled in (a third off the epilogue's time); any
   // other combination runs the kernel that reads the flags at run time.
   if constexpr (BM == 256 && BN == 256 && sizeof(TC) == 2) {
-    if (g.a_kc && g.b_kc) {
+    if (g.a_kc && g.b_kc && g.alpha == 1.0f) {
       switch (g.epi) {
 #define L2L_EPI_CASE(e) case (e): launch_direct_one<BM, BN, WM, WN, true, true, TC, E, (e)>(g, s, splits); return;
         L2L_EPI_CASE(0)
