@@ -333,14 +333,19 @@ void pick_tile(const GemmArgs& g, bool out_f32, int* variant, int* splits) {
   else if (g.M >= 256 && g.N >= 128) v = kc ? 8 : 2;
   else if (g.N <= 64) v = 1;
   else v = kc ? 7 : 0;
+  const bool splittable = out_f32 && (g.epi == EPI_ACCUM) && !g.k_dev;
+  // a split-K GEMM with at most 16 of the 256 x 256 tiles (dW of the output projection: 1024 x 1024 over 32768
+  // tokens) does better with 128 x 128 tiles, two workgroups per CU and half the split depth: 109 against 128 us
+  if (splittable && v == 6 && g.nbatch == 1 && (long long)((g.M + 255) / 256) * ((g.N + 255) / 256) <= 16) v = 7;
   const TileCfg t = kTiles[v];
   // split K when an accumulating fp32 GEMM has too few tiles to fill 256 CUs
-  if (out_f32 && (g.epi == EPI_ACCUM) && !g.k_dev) {
+  if (splittable) {
     const long long tiles = (long long)((g.M + t.bm - 1) / t.bm) * ((g.N + t.bn - 1) / t.bn) * g.nbatch;
     const int nk = (g.K + t.bk - 1) / t.bk;
-    // one resident workgroup per CU: tiles x splits as close to the 256 CUs as it gets without exceeding
-    // them (measured best for the dW shapes: 64 x 4, 48 x 5, 16 x 16)
-    long long want = tiles < 256 ? 256 / tiles : 1;
+    // one resident workgroup per CU (two for the 64 KB 128 x 128 tile): tiles x splits as close to that as it gets
+    // without exceeding it (measured best for the dW shapes: 64 x 4, 48 x 5; 64 x 8 with the small tile)
+    const long long slots = (v == 7) ? 512 : 256;
+    long long want = tiles < slots ? slots / tiles : 1;
     want = std::min<long long>(want, std::max(1, nk / 8));
     *splits = (int)std::max<long long>(1, std::min<long long>(want, 64));
   }
