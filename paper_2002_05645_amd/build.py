@@ -19,7 +19,8 @@ HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
              "-Wno-unused-result"]
 with open(os.path.join(CSRC, "gemm_variants.h")) as _f:
     NUM_GEMM_VARIANTS = int(re.search(r"kNumGemmVariants\s*=\s*(\d+)", _f.read()).group(1))
-HOST_FLAGS = ["-O3", "-std=c++17", "-fPIC", "-mavx2", "-mfma", "-mf16c", "-D__HIP_PLATFORM_AMD__", f"-I{ROCM}/include", "-pthread"]
+HOST_FLAGS = ["-O3", "-std=c++17", "-fPIC", "-mavx2", "-mfma", "-mf16c", "-fno-math-errno",   # (sqrt without errno: the optimizer loops vectorise)
+              "-D__HIP_PLATFORM_AMD__", f"-I{ROCM}/include", "-pthread"]
 
 
 def _run(cmd):
