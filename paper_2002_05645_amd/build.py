@@ -19,7 +19,7 @@ HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
              "-Wno-unused-result"]
 with open(os.path.join(CSRC, "gemm_variants.h")) as _f:
     NUM_GEMM_VARIANTS = int(re.search(r"kNumGemmVariants\s*=\s*(\d+)", _f.read()).group(1))
-HOST_FLAGS = ["-O3", "-std=c++17", "-fPIC", "-mavx2", "-mfma", "-mf16c", "-fno-math-errno",   # (sqrt without errno: the optimizer loops vectorise)
+HOST_FLAGS = ["-O3", "-std=c++17", "-fPIC", "-mavx2", "-mfma", "-mf16c", "-fno-math-errno", "-fopenmp-simd",   # (sqrt without errno, simd reductions: the optimizer loops vectorise)
               "-D__HIP_PLATFORM_AMD__", f"-I{ROCM}/include", "-pthread"]
 
 

@@ -228,6 +228,7 @@ int eps_adam_step(eps_store* e, int first, int last, int t, double lr_d, double 
       float* __restrict m = b.m;
       float* __restrict v = b.v;
       const float* __restrict g = b.grad;
+#pragma omp simd   // the four arrays are distinct allocations: iterations are independent
       for (size_t k = lo; k < hi; ++k) {
         const float gk = g[k];
         const float mk = beta1 * m[k] + omb1 * gk;
@@ -294,15 +295,23 @@ int eps_lamb_step(eps_store* e, int first, int last, int t, double lr_d, double 
       double wn2 = 0.0, un2 = 0.0;
       e->pool->run(len, [&](size_t lo, size_t hi) {
         double a = 0.0, c = 0.0;
-        for (size_t k = lo; k < hi; ++k) {
-          const float gk = g[k];
-          const float mk = beta1 * m[k] + omb1 * gk;
-          const float vk = beta2 * v[k] + omb2 * gk * gk;
-          m[k] = mk;
-          v[k] = vk;
-          const float u = (mk * c1) / (std::sqrt(vk * c2) + eps_a) + wd * w[k];
-          a += (double)w[k] * w[k];
-          c += (double)u * u;
+        // the squares are summed in fp32 over runs of 256 elements (a loop the compiler vectorises) and the runs in double
+        for (size_t k0 = lo; k0 < hi; k0 += 256) {
+          const size_t k1 = std::min(hi, k0 + 256);
+          float fa = 0.f, fc = 0.f;
+#pragma omp simd reduction(+ : fa, fc)
+          for (size_t k = k0; k < k1; ++k) {
+            const float gk = g[k];
+            const float mk = beta1 * m[k] + omb1 * gk;
+            const float vk = beta2 * v[k] + omb2 * gk * gk;
+            m[k] = mk;
+            v[k] = vk;
+            const float u = (mk * c1) / (std::sqrt(vk * c2) + eps_a) + wd * w[k];
+            fa += w[k] * w[k];
+            fc += u * u;
+          }
+          a += fa;
+          c += fc;
         }
         std::lock_guard<std::mutex> l(sum_mu);
         wn2 += a;
