@@ -145,6 +145,12 @@ int l2l_drain_wait(l2l_ctx*, int layer);   /* host blocks until that drain has l
 /* ---- first and last resident "layers": embedding and tied LM head (Section 2.1: "a 3 layer model") */
 /* Async H2D of the packed embedding block (pinned host pointer) on copy_stream. */
 int l2l_embed_stage(l2l_ctx*, const void* host_embed_params);
+/* The same for elements [first, first + count) of the packed block only (host_embed_params still points at
+   element 0).  Lets the host ship the block piece by piece while its optimizer is still working on the rest
+   (the embedding block is the last to be updated in a step and the first to be needed in the next: Section 2.2's
+   eager update has nothing left to hide it behind).  The caller stages every element before l2l_embed_fwd.
+   L2L_E_ARG for a range outside the block. */
+int l2l_embed_stage_part(l2l_ctx*, const void* host_embed_params, long long first, long long count);
 /* x0[u][b,s] = LN_e(E[tok] + Ppos[s]).  tokens: device int32 [U, ub, S]; x_out: device U x [ub,S,H].
    Zeroes the embedding-block gradient accumulator (start of a step). */
 int l2l_embed_fwd(l2l_ctx*, const int32_t* tokens, void* x_out);
@@ -189,6 +195,11 @@ int l2l_embed_bwd(l2l_ctx*, const int32_t* tokens, const void* dy);
 /* Async D2H of the embedding-block gradients (fp32, packed) into host memory, after the above. */
 int l2l_embed_grad_drain(l2l_ctx*, void* host_grads);
 int l2l_embed_drain_wait(l2l_ctx*);
+/* The same drain in pieces: elements [first, first + count) of the packed gradients go to host_grads + first
+   (host_grads points at element 0 of the landing buffer).  Pieces are issued in ascending order without gaps; the
+   piece that ends the block also clears and releases the accumulator.  L2L_E_ARG for a piece out of order or
+   outside the block, L2L_E_STATE without un-drained gradients. */
+int l2l_embed_grad_drain_part(l2l_ctx*, void* host_grads, long long first, long long count);
 
 /* ---- profiling: HIP-event timing of kernel classes on the compute stream ----------------------
    GEMM = the layer's dense projections (QKV, out-proj, FFN1, FFN2 and their dX / dW GEMMs);
@@ -245,6 +256,10 @@ int   eps_refresh_ship(eps_store*, int first, int last);
 /* One bias-corrected Adam step (no weight decay) on blocks [first, last] from their landing
    buffers, then refreshes their shipping copies.  t >= 1 is the step number. */
 int   eps_adam_step(eps_store*, int first, int last, int t, double lr, double beta1, double beta2, double eps_a);
+/* The same update for elements [first_elem, first_elem + count) of one block only (its gradients landed, the rest may
+   still be on their way). */
+int   eps_adam_step_range(eps_store*, int block, long long first_elem, long long count, int t, double lr, double beta1,
+                          double beta2, double eps);
 /* Multiplies the landing buffers of blocks [first, last] by inv_scale (1 / loss scale) and sets
    *nonfinite to 1 if any of them holds an inf or NaN (an overflow on the device: the caller then skips
    the update and lowers the scale), else 0.  nonfinite may be null. */

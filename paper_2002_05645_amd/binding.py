@@ -67,6 +67,8 @@ _SIGS = {
     "l2l_head_loss": (C.c_int, [_P, _P, _P, _P, _P]),
     "l2l_embed_bwd": (C.c_int, [_P, _P, _P]),
     "l2l_embed_grad_drain": (C.c_int, [_P, _P]),
+    "l2l_embed_grad_drain_part": (C.c_int, [_P, _P, C.c_longlong, C.c_longlong]),
+    "l2l_embed_stage_part": (C.c_int, [_P, _P, C.c_longlong, C.c_longlong]),
     "l2l_embed_drain_wait": (C.c_int, [_P]),
     "l2l_profile": (C.c_int, [_P, C.c_int]),
     "l2l_profile_overlap": (C.c_int, [_P, C.c_double, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double),
@@ -96,6 +98,8 @@ _SIGS = {
     "l2l_stream_create_cu_masked": (C.c_int, [C.c_int, C.POINTER(C.c_void_p)]),
     "l2l_stream_destroy": (C.c_int, [C.c_void_p]),
     "eps_adam_step": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_double, C.c_double, C.c_double, C.c_double]),
+    "eps_adam_step_range": (C.c_int, [_P, C.c_int, C.c_longlong, C.c_longlong, C.c_int, C.c_double, C.c_double, C.c_double,
+                                      C.c_double]),
     "eps_grad_unscale": (C.c_int, [_P, C.c_int, C.c_int, C.c_double, C.POINTER(C.c_int)]),
     "eps_lamb_step": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_double, C.c_double, C.c_double, C.c_double, C.c_double,
                                 C.c_int, C.POINTER(C.c_longlong), C.POINTER(C.c_longlong), C.POINTER(C.c_double)]),
@@ -229,6 +233,9 @@ class Context:
     def embed_stage(self, host_embed):
         self._ck(lib().l2l_embed_stage(self._h, _ptr(host_embed)))
 
+    def embed_stage_part(self, host_embed, first, count):
+        self._ck(lib().l2l_embed_stage_part(self._h, _ptr(host_embed), int(first), int(count)))
+
     def embed_fwd(self, tokens, x_out):
         self._ck(lib().l2l_embed_fwd(self._h, _ptr(tokens), _ptr(x_out)))
 
@@ -240,6 +247,9 @@ class Context:
 
     def embed_grad_drain(self, host_grads):
         self._ck(lib().l2l_embed_grad_drain(self._h, _ptr(host_grads)))
+
+    def embed_grad_drain_part(self, host_grads, first, count):
+        self._ck(lib().l2l_embed_grad_drain_part(self._h, _ptr(host_grads), int(first), int(count)))
 
     def embed_drain_wait(self):
         self._ck(lib().l2l_embed_drain_wait(self._h))
@@ -345,6 +355,11 @@ class EPS:
         rc = lib().eps_adam_step(self._h, first, last, t, lr, beta1, beta2, eps_a)
         if rc != L2L_OK:
             raise L2LError(rc, "eps_adam_step")
+
+    def adam_step_range(self, block, first_elem, count, t, lr=1e-4, beta1=0.9, beta2=0.999, eps_a=1e-8):
+        rc = lib().eps_adam_step_range(self._h, block, int(first_elem), int(count), t, lr, beta1, beta2, eps_a)
+        if rc != L2L_OK:
+            raise L2LError(rc, "eps_adam_step_range")
 
     def grad_unscale(self, first, last, inv_scale) -> bool:
         """landing buffers *= inv_scale; True if they hold an inf or NaN."""

@@ -121,6 +121,27 @@ static void ship_range(const eps_store* e, const Block& b, size_t lo, size_t hi)
   }
 }
 
+// bias-corrected Adam on elements [e0, e0 + n) of a block, master -> shipping copy included
+static void adam_range(eps_store* e, const Block& b, size_t e0, size_t n, float lr, float beta1, float beta2, float eps_a,
+                       float omb1, float omb2, float c1, float c2) {
+  e->pool->run(n, [&](size_t lo, size_t hi) {
+    float* __restrict w = b.w;
+    float* __restrict m = b.m;
+    float* __restrict v = b.v;
+    const float* __restrict g = b.grad;
+#pragma omp simd   // the four arrays are distinct allocations: iterations are independent
+    for (size_t k = e0 + lo; k < e0 + hi; ++k) {
+      const float gk = g[k];
+      const float mk = beta1 * m[k] + omb1 * gk;
+      const float vk = beta2 * v[k] + omb2 * gk * gk;
+      m[k] = mk;
+      v[k] = vk;
+      w[k] -= lr * (mk * c1) / (std::sqrt(vk * c2) + eps_a);
+    }
+    ship_range(e, b, e0 + lo, e0 + hi);
+  });
+}
+
 extern "C" {
 
 int eps_create(int n_blocks, const size_t* elems, int ship_dtype, int threads, eps_store** out) {
@@ -221,25 +242,19 @@ int eps_adam_step(eps_store* e, int first, int last, int t, double lr_d, double 
   const float omb1 = (float)(1.0 - beta1_d), omb2 = (float)(1.0 - beta2_d);
   const float c1 = (float)(1.0 / (1.0 - std::pow(beta1_d, t)));
   const float c2 = (float)(1.0 / (1.0 - std::pow(beta2_d, t)));
-  for (int i = first; i <= last; ++i) {
-    const Block& b = e->blocks[i];
-    e->pool->run(b.n, [&](size_t lo, size_t hi) {
-      float* __restrict w = b.w;
-      float* __restrict m = b.m;
-      float* __restrict v = b.v;
-      const float* __restrict g = b.grad;
-#pragma omp simd   // the four arrays are distinct allocations: iterations are independent
-      for (size_t k = lo; k < hi; ++k) {
-        const float gk = g[k];
-        const float mk = beta1 * m[k] + omb1 * gk;
-        const float vk = beta2 * v[k] + omb2 * gk * gk;
-        m[k] = mk;
-        v[k] = vk;
-        w[k] -= lr * (mk * c1) / (std::sqrt(vk * c2) + eps_a);
-      }
-      ship_range(e, b, lo, hi);
-    });
-  }
+  for (int i = first; i <= last; ++i) adam_range(e, e->blocks[i], 0, e->blocks[i].n, lr, beta1, beta2, eps_a, omb1, omb2, c1, c2);
+  return L2L_OK;
+}
+
+int eps_adam_step_range(eps_store* e, int block, long long first_elem, long long count, int t, double lr_d, double beta1_d,
+                        double beta2_d, double eps_a_d) {
+  if (!e || block < 0 || block >= (int)e->blocks.size() || t < 1) return L2L_E_ARG;
+  if (first_elem < 0 || count <= 0 || (size_t)(first_elem + count) > e->blocks[block].n) return L2L_E_ARG;
+  const float lr = (float)lr_d, beta1 = (float)beta1_d, beta2 = (float)beta2_d, eps_a = (float)eps_a_d;
+  const float omb1 = (float)(1.0 - beta1_d), omb2 = (float)(1.0 - beta2_d);
+  const float c1 = (float)(1.0 / (1.0 - std::pow(beta1_d, t)));
+  const float c2 = (float)(1.0 / (1.0 - std::pow(beta2_d, t)));
+  adam_range(e, e->blocks[block], (size_t)first_elem, (size_t)count, lr, beta1, beta2, eps_a, omb1, omb2, c1, c2);
   return L2L_OK;
 }
 

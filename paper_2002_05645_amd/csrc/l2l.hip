@@ -163,6 +163,7 @@ struct l2l_ctx {
   void* emb = nullptr;
   float* egacc = nullptr;
   int emb_staged = 0, egacc_state = 0;
+  long long egacc_part_next = 0;   // l2l_embed_grad_drain_part: first element of the next piece
   hipEvent_t emb_staged_ev = nullptr, emb_released_ev = nullptr, egacc_ready = nullptr, egacc_landed = nullptr, egacc_drained = nullptr;
   float *emean = nullptr, *erstd = nullptr;
   int32_t *lab_idx = nullptr, *lab_cnt = nullptr, *lab_total = nullptr, *lab_gidx = nullptr, *chunk_cnt = nullptr;
@@ -1064,6 +1065,21 @@ int l2l_embed_stage(l2l_ctx* c, const void* host) {
 }
 
 
+int l2l_embed_stage_part(l2l_ctx* c, const void* host, long long first, long long count) {
+  L2L_TRY(need_vocab(c, "l2l_embed_stage_part"));
+  if (!host) return fail(c, L2L_E_ARG, "l2l_embed_stage_part: null host pointer");
+  if (first < 0 || count <= 0 || first + count > c->lay.etotal)
+    return fail(c, L2L_E_ARG, "l2l_embed_stage_part: elements %lld..%lld outside the block of %lld", first, first + count, c->lay.etotal);
+  if (c->emb_staged) HIP_TRY(c, hipStreamWaitEvent(c->xs, c->emb_released_ev, 0));
+  const size_t es = esize(c->cfg.dtype);
+  const CopyMark mark = copy_begin(c);
+  HIP_TRY(c, hipMemcpyAsync((char*)c->emb + first * es, (const char*)host + first * es, count * es, hipMemcpyHostToDevice, c->xs));
+  copy_end(c, mark, (double)count * es);
+  HIP_TRY(c, hipEventRecord(c->emb_staged_ev, c->xs));
+  c->emb_staged = 1;
+  return L2L_OK;
+}
+
 int l2l_embed_fwd(l2l_ctx* c, const int32_t* tokens, void* x_out) {
   L2L_TRY(need_vocab(c, "l2l_embed_fwd"));
   if (!tokens || !x_out) return fail(c, L2L_E_ARG, "l2l_embed_fwd: null pointer");
@@ -1110,6 +1126,7 @@ int l2l_embed_grad_drain(l2l_ctx* c, void* host_grads) {
   L2L_TRY(need_vocab(c, "l2l_embed_grad_drain"));
   if (!host_grads) return fail(c, L2L_E_ARG, "l2l_embed_grad_drain: null host pointer");
   if (c->egacc_state != 1) return fail(c, L2L_E_STATE, "l2l_embed_grad_drain: no un-drained embedding gradients");
+  if (c->egacc_part_next != 0) return fail(c, L2L_E_STATE, "l2l_embed_grad_drain: a drain in pieces is under way");
   HIP_TRY(c, hipStreamWaitEvent(c->xs, c->egacc_ready, 0));
   const CopyMark mark = copy_begin(c);
   HIP_TRY(c, hipMemcpyAsync(host_grads, c->egacc, c->lay.etotal * 4, hipMemcpyDeviceToHost, c->xs));
@@ -1118,6 +1135,30 @@ int l2l_embed_grad_drain(l2l_ctx* c, void* host_grads) {
   copy_end(c, mark, (double)c->lay.etotal * 4);
   HIP_TRY(c, hipEventRecord(c->egacc_drained, c->xs));
   c->egacc_state = 2;
+  return L2L_OK;
+}
+
+int l2l_embed_grad_drain_part(l2l_ctx* c, void* host_grads, long long first, long long count) {
+  L2L_TRY(need_vocab(c, "l2l_embed_grad_drain_part"));
+  if (!host_grads) return fail(c, L2L_E_ARG, "l2l_embed_grad_drain_part: null host pointer");
+  if (c->egacc_state != 1) return fail(c, L2L_E_STATE, "l2l_embed_grad_drain_part: no un-drained embedding gradients");
+  if (first != c->egacc_part_next || count <= 0 || first + count > c->lay.etotal)
+    return fail(c, L2L_E_ARG, "l2l_embed_grad_drain_part: piece %lld..%lld, expected one starting at %lld within %lld elements", first,
+                first + count, c->egacc_part_next, c->lay.etotal);
+  if (first == 0) HIP_TRY(c, hipStreamWaitEvent(c->xs, c->egacc_ready, 0));
+  const CopyMark mark = copy_begin(c);
+  HIP_TRY(c, hipMemcpyAsync((float*)host_grads + first, c->egacc + first, count * 4, hipMemcpyDeviceToHost, c->xs));
+  c->egacc_part_next = first + count;
+  if (c->egacc_part_next == c->lay.etotal) {   // the block is out: clear and release the accumulator
+    HIP_TRY(c, hipEventRecord(c->egacc_landed, c->xs));
+    L2L_TRY(fill_zero_copy_stream(c, c->egacc, c->lay.etotal * 4));
+    copy_end(c, mark, (double)count * 4);
+    HIP_TRY(c, hipEventRecord(c->egacc_drained, c->xs));
+    c->egacc_state = 2;
+    c->egacc_part_next = 0;
+  } else {
+    copy_end(c, mark, (double)count * 4);
+  }
   return L2L_OK;
 }
 

@@ -61,7 +61,7 @@ class L2LTrainer:
                  ln_eps=1e-12, lr=1e-4, beta1=0.9, beta2=0.999, eps_a=1e-8, ubatch_group=0,
                  eps_threads=0, stash="device", device="cuda:0", eager=False, optimizer="adam", weight_decay=0.0,
                  copy_cus=0, run_ahead=2, loss_scale=None, dynamic_loss_scale=True, scale_growth_interval=1000,
-                 num_classes=0):
+                 num_classes=0, tail_parts=8):
         assert stash in ("device", "host")
         assert optimizer in ("adam", "lamb")
         self.optimizer = optimizer
@@ -141,12 +141,27 @@ class L2LTrainer:
         self._work = queue.Queue()
         self._worker_error = None
         self._worker = None
+        # The embedding block is the last to be updated in a step and the first needed in the next, so its drain, its
+        # Adam and its next stage are exposed.  With eager Adam they run as a pipeline over `tail_parts` pieces of the
+        # block: piece k is updated while piece k + 1 is still on its way to the host, and shipped back while piece
+        # k + 1 is being updated.  (LAMB needs whole tensors for its norms, a loss scale the whole block for its overflow
+        # check: both keep the one-piece path.)
+        self._parts = []
+        self._prestaged = False
+        tail_parts = int(os.environ.get("L2L_TAIL_PARTS", tail_parts))
+        if eager and optimizer == "adam" and self.scaler.scale == 1.0 and tail_parts > 1:
+            step = -(-self.embed_elems // tail_parts)
+            step = -(-step // 256) * 256     # (whole kilobytes of fp32)
+            self._parts = [(a, min(step, self.embed_elems - a)) for a in range(0, self.embed_elems, step)]
+            self._part_landed = [torch.cuda.Event() for _ in self._parts]
+            self._part_done = [threading.Event() for _ in self._parts]
         if eager:
             self._worker = threading.Thread(target=self._eager_loop, daemon=True)
             self._worker.start()
 
     # ---- parameters -------------------------------------------------------------------------------
     def load_params(self, emb: dict, layers: list, cls: dict = None):
+        self._prestaged = False
         self.eps.master(0)[:] = pack(self.embed_layout, self.embed_elems, emb)
         for l, p in enumerate(layers):
             self.eps.master(1 + l)[:] = pack(self.layer_layout, self.layer_elems, p)
@@ -191,7 +206,10 @@ class L2LTrainer:
         call finish() (or read the loss) to wait.  tokens / labels: int32 device tensors [U, ub, S]."""
         c, e, L = self.ctx, self.eps, self.L
         host_mode = self.stash_mode == "host"
-        c.embed_stage(e.ship_ptr(0))
+        if self._prestaged:          # the previous step's optimizer shipped the block piece by piece already
+            self._prestaged = False
+        else:
+            c.embed_stage(e.ship_ptr(0))
         c.param_stage(0, e.ship_ptr(1), 0)
         c.embed_fwd(tokens, self._stash_slot(0))
         if host_mode:
@@ -228,8 +246,15 @@ class L2LTrainer:
             c.grad_drain(l, e.grad_ptr(1 + l))
             self._after_drain(1 + l)
         c.embed_bwd(tokens, self.dy)
-        c.embed_grad_drain(e.grad_ptr(0))
-        self._after_drain(0)
+        if self._parts:
+            for k, (first, count) in enumerate(self._parts):
+                c.embed_grad_drain_part(e.grad_ptr(0), first, count)
+                self._part_landed[k].record(self.copy)
+                self._part_done[k].clear()
+                self._work.put(("part", k, self.t + 1))
+        else:
+            c.embed_grad_drain(e.grad_ptr(0))
+            self._after_drain(0)
 
     def _eps_update(self, first, last, t, unscale=True):
         if unscale and self.scaler.scale != 1.0:
@@ -263,13 +288,21 @@ class L2LTrainer:
             item = self._work.get()
             if item is None:
                 return
-            block, t = item
             try:
-                self._landed[block].synchronize()
-                self._eps_update(block, block, t)
+                if item[0] == "part":     # one piece of the embedding block
+                    _, k, t = item
+                    first, count = self._parts[k]
+                    self._part_landed[k].synchronize()
+                    self.eps.adam_step_range(0, first, count, t, **self.hp)
+                else:
+                    block, t = item
+                    self._landed[block].synchronize()
+                    self._eps_update(block, block, t)
             except Exception as ex:       # surfaced by optimizer_step
                 self._worker_error = ex
             finally:
+                if item[0] == "part":
+                    self._part_done[item[1]].set()
                 self._work.task_done()
 
     def _offload(self, l):
@@ -300,6 +333,12 @@ class L2LTrainer:
     def optimizer_step(self):
         """EPS Adam over every block, after all gradients have landed (Algorithm 2's tail loop)."""
         if self.eager:
+            if self._parts:               # ship each piece of the embedding block back as soon as it is updated
+                for k, (first, count) in enumerate(self._parts):
+                    self._part_done[k].wait()
+                    if self._worker_error is None:
+                        self.ctx.embed_stage_part(self.eps.ship_ptr(0), first, count)
+                self._prestaged = self._worker_error is None
             self._work.join()             # every block was queued by device_pipeline; wait for the stragglers
             if self._worker_error is not None:
                 raise self._worker_error

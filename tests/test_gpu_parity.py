@@ -529,6 +529,66 @@ def test_step_bert_base_bf16_full():
     assert abs(loss_ref - (math.log(w.vocab) + w.hidden * 0.02 ** 2 / 2)) < 0.03
 
 
+def test_embedding_block_staged_and_drained_in_pieces():
+    # l2l_embed_stage_part / l2l_embed_grad_drain_part: same bytes as the one-piece calls, pieces in order only
+    w = S.WORKLOADS[0]
+    cfg = P.make_config(w.hidden, w.heads, w.ffn, w.seq, w.ubatch, w.num_ubatches, "fp32", 1e-12, w.vocab)
+    n = P.lib().l2l_embed_packed_elems(cfg)
+    lay = P.embed_layout(cfg)
+    host = pinned(pack(lay, n, S.embed_params(w)).astype(np.float32))
+    tok, lab = S.tokens_and_labels(w)
+    tokd, labd = torch.from_numpy(tok).cuda(), torch.from_numpy(lab).cuda()
+    shape = (w.num_ubatches, w.ubatch, w.seq, w.hidden)
+    pieces = [(0, 1000), (1000, 7), (1007, n - 1007)]
+    outs, grads = [], []
+    for in_pieces in (False, True):
+        c = P.Context(cfg)
+        try:
+            x, dy = torch.zeros(shape, device="cuda"), torch.zeros(shape, device="cuda")
+            loss = torch.zeros(1, device="cuda")
+            if in_pieces:
+                with pytest.raises(P.L2LError) as e:
+                    c.embed_stage_part(host, n - 5, 6)
+                assert e.value.code == P.L2L_E_ARG
+                for first, count in reversed(pieces):       # any order: the caller only has to cover the block
+                    c.embed_stage_part(host, first, count)
+            else:
+                c.embed_stage(host)
+            c.embed_fwd(tokd, x)
+            c.head_loss(x, labd, dy, loss)
+            c.embed_bwd(tokd, dy)
+            g = torch.zeros(n, dtype=torch.float32).pin_memory()
+            if in_pieces:
+                with pytest.raises(P.L2LError) as e:
+                    c.embed_grad_drain_part(g, 1000, 7)      # must start at element 0
+                assert e.value.code == P.L2L_E_ARG
+                c.embed_grad_drain_part(g, *pieces[0])
+                with pytest.raises(P.L2LError) as e:
+                    c.embed_grad_drain(g)                    # a drain in pieces is under way
+                assert e.value.code == P.L2L_E_STATE
+                with pytest.raises(P.L2LError) as e:
+                    c.embed_grad_drain_part(g, 1007, 5)      # gap
+                assert e.value.code == P.L2L_E_ARG
+                c.embed_grad_drain_part(g, *pieces[1])
+                c.embed_grad_drain_part(g, *pieces[2])
+                with pytest.raises(P.L2LError) as e:
+                    c.embed_grad_drain_part(g, 0, 10)        # nothing left to drain
+                assert e.value.code == P.L2L_E_STATE
+            else:
+                c.embed_grad_drain(g)
+            c.embed_drain_wait()
+            c.sync()
+            outs.append(x.cpu().numpy())
+            grads.append(g.numpy().copy())
+            c.embed_fwd(tokd, x)                             # the accumulator was released: the next step may start
+            c.sync()
+        finally:
+            c.close()
+    assert np.array_equal(outs[0], outs[1])
+    assert O.rel_l2(grads[1], grads[0]) < 1e-6               # (fp32 atomics: the order of the additions is not fixed)
+    assert np.abs(grads[0]).max() > 0
+
+
 # ------------------------------------------------------------------------------------- call-order errors
 def test_call_order_errors():
     cfg = P.make_config(64, 2, 128, 16, 2, 2, "fp32", 1e-5, 0)

@@ -98,6 +98,33 @@ def test_eps_bf16_ship_is_round_to_nearest_even_bit_exact():
     e.close()
 
 
+def test_eps_adam_in_pieces_equals_the_whole_block():
+    # the ranged step (the embedding block is updated piece by piece as its gradients land) is the same arithmetic
+    n = 200000
+    rng = np.random.default_rng(3)
+    w0 = rng.normal(size=n).astype(np.float32)
+    a, b = P.EPS([n], "bf16", 3), P.EPS([5, n], "bf16", 4)
+    a.master(0)[:] = w0
+    b.master(1)[:] = w0
+    pieces = [(0, 70000), (70000, 1), (70001, 129999)]
+    for t in range(1, 3):
+        g = rng.normal(size=n).astype(np.float32)
+        a.grad(0)[:] = g
+        b.grad(1)[:] = g
+        a.adam_step(0, 0, t, lr=1e-3)
+        for first, count in pieces:
+            b.adam_step_range(1, first, count, t, lr=1e-3)
+        assert np.array_equal(a.master(0), b.master(1))
+        assert np.array_equal(a.moment(0, 0), b.moment(1, 0)) and np.array_equal(a.moment(0, 1), b.moment(1, 1))
+        assert np.array_equal(a.ship(0), b.ship(1))
+    assert np.all(b.master(0) == 0)
+    for bad in [(1, -1, 5), (1, 0, 0), (1, n - 3, 4), (2, 0, 1)]:
+        with pytest.raises(P.L2LError):
+            b.adam_step_range(bad[0], bad[1], bad[2], 1)
+    a.close()
+    b.close()
+
+
 @pytest.mark.parametrize("threads", [1, 5])
 def test_eps_adam_matches_oracle(threads):
     n = 300001
