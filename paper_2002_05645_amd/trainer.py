@@ -206,11 +206,11 @@ class L2LTrainer:
         call finish() (or read the loss) to wait.  tokens / labels: int32 device tensors [U, ub, S]."""
         c, e, L = self.ctx, self.eps, self.L
         host_mode = self.stash_mode == "host"
-        if self._prestaged:          # the previous step's optimizer shipped the block piece by piece already
+        if self._prestaged:          # the previous step's optimizer shipped the block (and layer 0) already
             self._prestaged = False
         else:
             c.embed_stage(e.ship_ptr(0))
-        c.param_stage(0, e.ship_ptr(1), 0)
+            c.param_stage(0, e.ship_ptr(1), 0)
         c.embed_fwd(tokens, self._stash_slot(0))
         if host_mode:
             self._offload(0)
@@ -337,6 +337,8 @@ class L2LTrainer:
                 for k, (first, count) in enumerate(self._parts):
                     self._part_done[k].wait()
                     if self._worker_error is None:
+                        if k == 0:        # the worker takes blocks in order: layer 0's update is complete as well
+                            self.ctx.param_stage(0, self.eps.ship_ptr(1), 0)
                         self.ctx.embed_stage_part(self.eps.ship_ptr(0), first, count)
                 self._prestaged = self._worker_error is None
             self._work.join()             # every block was queued by device_pipeline; wait for the stragglers
