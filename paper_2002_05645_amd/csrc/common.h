@@ -137,7 +137,9 @@ template <typename E> __device__ __forceinline__ float gelu_grad_epi(float u) {
 }
 
 // Epilogue flags of the GEMM kernels.
-enum { EPI_BIAS = 1, EPI_GELU = 2, EPI_GELUGRAD = 4, EPI_RESID = 8, EPI_ACCUM = 16 };
+// EPI_COLSUM: also leave the column sums of the stored values in GemmArgs::colsum (a bias gradient that would
+// otherwise cost a pass over the output); the direct-to-LDS kernel's 16-byte epilogue path only.
+enum { EPI_BIAS = 1, EPI_GELU = 2, EPI_GELUGRAD = 4, EPI_RESID = 8, EPI_ACCUM = 16, EPI_COLSUM = 32 };
 
 // One GEMM launch: C[M,N] = epi(alpha * sum_k A(m,k) B(k,n)), optionally batched over z.
 struct GemmArgs {
@@ -159,4 +161,17 @@ struct GemmArgs {
   long long ldaux;
   const int* m_dev;       // optional device-side bound on M (rows beyond it are not computed)
   const int* k_dev;       // optional device-side bound on K
+  float* colsum;          // EPI_COLSUM: fp32 [ceil(M / WM)][N] (WM = rows of a wave's tile): row r receives the column sums
+                          // of the values stored to rows r WM .. r WM + WM - 1 of C (plain stores; the caller adds the rows up)
 };
+
+// Whether a launch takes the epilogue's 16-byte path (8 columns per lane); the kernels test it per launch, the host
+// tests it before it asks for EPI_COLSUM, which only that path provides.  C: the output of the batch entry.
+__host__ __device__ inline bool gemm_vec_ok(const GemmArgs& g, int epi, const void* C) {
+  const auto al16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
+  return (g.N % 8 == 0) && (g.ldc % 8 == 0) && al16(C) && (!(epi & EPI_BIAS) || al16(g.bias)) &&
+         (!(epi & EPI_RESID) || (g.ldr % 8 == 0 && al16(g.resid))) &&
+         (!(epi & EPI_GELUGRAD) || (g.ldaux % 8 == 0 && al16(g.aux))) &&
+         (!((epi & EPI_GELU) && g.aux_out) || (g.ldaux % 8 == 0 && al16(g.aux_out))) &&
+         (!(epi & EPI_COLSUM) || al16(g.colsum));
+}

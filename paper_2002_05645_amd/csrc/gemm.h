@@ -17,7 +17,7 @@ __device__ __forceinline__ void static_for(F&& f) {
 // ------------------------------------------------------------------------------------------------
 // Epilogue shared by both kernels.  v = alpha * acc already applied by the caller.
 template <typename T, typename TC>
-__device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, TC* C, long long m, long long n, float v) {
+__device__ __forceinline__ float gemm_epilogue(const GemmArgs& g, TC* C, long long m, long long n, float v) {
   if (g.epi & EPI_BIAS) v += to_f32(((const T*)g.bias)[n]);
   if (g.epi & EPI_GELU) {
     if (g.aux_out) ((T*)g.aux_out)[m * g.ldaux + n] = from_f32<T>(v);
@@ -28,6 +28,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, TC* C, long lon
   TC* c = C + m * g.ldc + n;
   if (g.epi & EPI_ACCUM) v += to_f32(*c);
   *c = from_f32<TC>(v);
+  return v;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -657,17 +658,13 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
   // ---- epilogue (as in gemm_mfma_kernel) ----------------------------------------------------------
   const bool atomic = gridDim.y > 1;
   float* strip = (float*)(lds + wave * EP_BYTES);
-  const auto al16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
-  const bool vec_ok = (N % 8 == 0) && (g.ldc % 8 == 0) && al16(C) &&
-                      (!(epi & EPI_BIAS) || al16(g.bias)) &&
-                      (!(epi & EPI_RESID) || (g.ldr % 8 == 0 && al16(g.resid))) &&
-                      (!(epi & EPI_GELUGRAD) || (g.ldaux % 8 == 0 && al16(g.aux))) &&
-                      (!((epi & EPI_GELU) && g.aux_out) || (g.ldaux % 8 == 0 && al16(g.aux_out)));
+  const bool vec_ok = gemm_vec_ok(g, epi, C);
   // vector path: 8-column chunk and row-in-pass of this lane, its bias values, and the first pass's prefetch
   constexpr int CPR = WN / 8, RPP = 64 / CPR, PASSES = 32 / RPP;
   const int c8 = (lane % CPR) * 8, prow = lane / CPR;
   const int ncol = n0 + wn * WN + c8;
   float bias8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  float csum8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};   // EPI_COLSUM: this lane's share of its 8 columns' sums
   // one 16-byte operand per pass is prefetched: the residual, or the pre-activation of GELU' (no epilogue of the
   // layer uses both; a launch that did would take the residual from memory in the pass itself)
   const bool pre_aux = (epi & EPI_GELUGRAD) != 0, pre_res = !pre_aux && (epi & EPI_RESID);
@@ -746,6 +743,10 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
             for (int e = 0; e < 8; ++e) v[e] += tt[e];
           }
           store8(cp, v);
+          if (epi & EPI_COLSUM) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) csum8[e] += v[e];
+          }
         }
       });
     } else {
@@ -758,7 +759,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
           if constexpr (sizeof(TC) == 4) {
             if (atomic) { gemm_epilogue_atomic(g, (float*)C, m, n, v); continue; }
           }
-          gemm_epilogue<E, TC>(g, C, m, n, v);
+          gemm_epilogue<E, TC>(g, C, m, n, v);   // (EPI_COLSUM is not served here: the host asks for it only when vec_ok holds)
         }
       }
     }
@@ -766,6 +767,16 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   });
+  if ((epi & EPI_COLSUM) && vec_ok && !atomic) {
+    // lanes l, l + CPR, l + 2 CPR, ... hold the same 8 columns (different rows): fold them; the wave's 8 x CPR sums go
+    // to its own row of the partial-sum matrix (atomics on the few lines of one [N] vector would queue up at L2)
+#pragma unroll
+    for (int o = CPR; o < 64; o <<= 1) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) csum8[e] += __shfl_xor(csum8[e], o, WAVE);
+    }
+    if (lane < CPR && ncol < N) store8(g.colsum + (long long)((m0 + wm * WM) / WM) * N + ncol, csum8);
+  }
   __syncthreads();   // every wave is done with its strips before the next tile's loads overwrite them
   }
 }

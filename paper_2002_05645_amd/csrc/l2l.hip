@@ -162,6 +162,8 @@ struct l2l_ctx {
   // embedding / head
   void* emb = nullptr;
   float* egacc = nullptr;
+  float* colsum_ws = nullptr;   // [rows / 64][max(F, 3H)] fp32: partial column sums written by a GEMM epilogue
+  size_t colsum_ws_elems = 0;
   int emb_staged = 0, egacc_state = 0;
   long long egacc_part_next = 0;   // l2l_embed_grad_drain_part: first element of the next piece
   hipEvent_t emb_staged_ev = nullptr, emb_released_ev = nullptr, egacc_ready = nullptr, egacc_landed = nullptr, egacc_drained = nullptr;
@@ -353,6 +355,18 @@ void pick_tile(const GemmArgs& g, bool out_f32, int* variant, int* splits) {
   *variant = v;
 }
 
+// whether gemm() will run this launch on the direct-to-LDS kernel, the one that honours EPI_COLSUM; otherwise the
+// caller runs the column-sum kernel itself
+// *rows: rows of the partial-sum matrix the kernel will fill (one per wave-tile row of C)
+bool colsum_in_gemm_ok(int dtype, bool out_f32, const GemmArgs& g, int* rows = nullptr) {
+  if (!is16(dtype) || out_f32 || !mfma_ok(g) || g.nbatch != 1 || g.m_dev || g.k_dev) return false;
+  int v, splits;
+  pick_tile(g, out_f32, &v, &splits);
+  if (!(kTiles[v].direct && (g.a_kc || !g.b_kc) && splits == 1)) return false;
+  if (rows) *rows = (g.M + kTiles[v].wm - 1) / kTiles[v].wm;
+  return gemm_vec_ok(g, g.epi | EPI_COLSUM, g.C);
+}
+
 // impl: 0 auto, 1 plain, 2 mfma (auto tile), 100 + v: mfma tile variant v (tuning)
 int gemm(l2l_ctx* c, int dtype, bool out_f32, const GemmArgs& g, int impl = 0, int cls = L2L_PROF_GEMM) {
   if (g.M <= 0 || g.N <= 0 || g.nbatch <= 0) return L2L_OK;
@@ -360,6 +374,8 @@ int gemm(l2l_ctx* c, int dtype, bool out_f32, const GemmArgs& g, int impl = 0, i
   const bool can_mfma = is16(dtype) && mfma_ok(g);
   if (impl >= 2 && !can_mfma) return fail(c, L2L_E_ARG, "gemm: shape/alignment not supported by the MFMA kernel");
   if (impl >= 100 + kNumTiles) return fail(c, L2L_E_ARG, "gemm: no such tile variant");
+  if ((g.epi & EPI_COLSUM) && (impl != 0 || !g.colsum || !colsum_in_gemm_ok(dtype, out_f32, g)))
+    return fail(c, L2L_E_ARG, "gemm: column sums are not available on this path");
   const bool use_mfma = impl >= 2 || (impl == 0 && can_mfma);
   const double flops = 2.0 * g.M * g.N * (double)g.K * g.nbatch;
   const double es = esize(dtype);
@@ -592,6 +608,7 @@ int layer_backward_group(l2l_ctx* c, const void* params, const void* x, void* dy
   const float alpha = 1.0f / sqrtf((float)d);
 
   // LN2 backward
+  bool db1_in_gemm = false;
   const bool own_stats = ln_bwd_one_pass(H);   // then the recompute pass did not run LN2
   L2L_TRY(ln_bwd<T>(c, dydx, c->r2, own_stats ? nullptr : c->mean2, own_stats ? nullptr : c->rstd2, P + off[T_G2], c->dr2,
                     G + off[T_G2], G + off[T_BE2], G + off[T_B2], M, H, f.ln_eps));
@@ -599,7 +616,14 @@ int layer_backward_group(l2l_ctx* c, const void* params, const void* x, void* dy
   {
     GemmArgs g = gemm_args((int)M, F, H, c->dr2, H, 1, P + off[T_W2], H, 1, c->du1, F);
     g.epi = EPI_GELUGRAD; g.aux = c->u1; g.ldaux = F;
+    // db1 = colsum(dU1) comes out of this GEMM's epilogue where it can: one row of partial sums per 128 rows of dU1,
+    // added up by the column-sum kernel (256 x F floats instead of M x F elements)
+    int ws_rows = 0;
+    g.colsum = c->colsum_ws;
+    db1_in_gemm = c->colsum_ws && colsum_in_gemm_ok(dt, false, g, &ws_rows) && (size_t)ws_rows * F <= c->colsum_ws_elems;
+    if (db1_in_gemm) g.epi |= EPI_COLSUM; else g.colsum = nullptr;
     L2L_TRY(gemm(c, dt, false, g));
+    if (db1_in_gemm) L2L_TRY(bias_grad<float>(c, c->colsum_ws, F, G + off[T_B1], ws_rows, F));
     GemmArgs w = gemm_args(F, H, (int)M, c->ga, F, 0, c->dr2, H, 0, G + off[T_W2], H);
     w.epi = EPI_ACCUM;
     L2L_TRY(gemm(c, dt, true, w));
@@ -612,7 +636,7 @@ int layer_backward_group(l2l_ctx* c, const void* params, const void* x, void* dy
     GemmArgs w = gemm_args(H, F, (int)M, c->y1, H, 0, c->du1, F, 0, G + off[T_W1], F);
     w.epi = EPI_ACCUM;
     L2L_TRY(gemm(c, dt, true, w));
-    L2L_TRY(bias_grad<T>(c, c->du1, F, G + off[T_B1], M, F));
+    if (!db1_in_gemm) L2L_TRY(bias_grad<T>(c, c->du1, F, G + off[T_B1], M, F));
   }
   // LN1 backward
   L2L_TRY(ln_bwd<T>(c, c->dy1, c->r1, c->mean1, c->rstd1, P + off[T_G1], c->dr1, G + off[T_G1], G + off[T_BE1], G + off[T_BO], M, H, f.ln_eps));
@@ -890,6 +914,10 @@ int l2l_create(const l2l_config* cfg, void* compute_stream, void* copy_stream, l
   for (auto& b : bufs) L2L_TRY(dev_alloc(c, b.p, b.n * es));
   if (is16(cfg->dtype))
     for (int i = 0; i < 2; ++i) L2L_TRY(dev_alloc(c, &c->wt[i], c->lay.total * es));
+  if (is16(cfg->dtype)) {   // partial column sums out of a GEMM epilogue: one row per 64 rows of the group at most
+    c->colsum_ws_elems = (size_t)((Mg + 63) / 64) * std::max(F, 3 * H);
+    L2L_TRY(dev_alloc(c, (void**)&c->colsum_ws, c->colsum_ws_elems * 4));
+  }
   float** stats[] = {&c->mean1, &c->rstd1, &c->mean2, &c->rstd2};
   for (auto s : stats) L2L_TRY(dev_alloc(c, (void**)s, Mg * 4));
 
