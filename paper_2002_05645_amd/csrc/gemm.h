@@ -17,7 +17,7 @@ __device__ __forceinline__ void static_for(F&& f) {
 // ------------------------------------------------------------------------------------------------
 // Epilogue shared by both kernels.  v = alpha * acc already applied by the caller.
 template <typename T, typename TC>
-__device__ __forceinline__ float gemm_epilogue(const GemmArgs& g, TC* C, long long m, long long n, float v) {
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, TC* C, long long m, long long n, float v) {
   if (g.epi & EPI_BIAS) v += to_f32(((const T*)g.bias)[n]);
   if (g.epi & EPI_GELU) {
     if (g.aux_out) ((T*)g.aux_out)[m * g.ldaux + n] = from_f32<T>(v);
@@ -28,7 +28,6 @@ __device__ __forceinline__ float gemm_epilogue(const GemmArgs& g, TC* C, long lo
   TC* c = C + m * g.ldc + n;
   if (g.epi & EPI_ACCUM) v += to_f32(*c);
   *c = from_f32<TC>(v);
-  return v;
 }
 
 // ------------------------------------------------------------------------------------------------
