@@ -575,7 +575,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
   const int z = blockIdx.z, zo = z / g.zdiv, zi = z % g.zdiv;
   const bf16* A = (const bf16*)g.A + zo * g.a_zo + zi * g.a_zi + (AKC ? (long long)m0 * g.lda : (long long)m0);
   const bf16* B = (const bf16*)g.B + zo * g.b_zo + zi * g.b_zi + (BKC ? (long long)n0 * g.ldb : (long long)n0);
-  TC* C = (TC*)g.C + zo * g.c_zo + zi * g.c_zi;
+  TC* C = (TC*)g.C + zo * g.c_zo + zi * g.c_zi + (long long)blockIdx.y * g.split_stride;
   const __amdgpu_buffer_rsrc_t ra = make_rsrc(A, tile_bytes<AKC>(g.lda, M - m0, K));
   const __amdgpu_buffer_rsrc_t rb = make_rsrc(B, tile_bytes<BKC>(g.ldb, N - n0, K));
   const uint32_t lda = (uint32_t)g.lda, ldb = (uint32_t)g.ldb;
@@ -655,7 +655,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
   __syncthreads();
 
   // ---- epilogue (as in gemm_mfma_kernel) ----------------------------------------------------------
-  const bool atomic = gridDim.y > 1;
+  const bool atomic = gridDim.y > 1 && g.split_stride == 0;
   float* strip = (float*)(lds + wave * EP_BYTES);
   const bool vec_ok = gemm_vec_ok(g, epi, C);
   // vector path: 8-column chunk and row-in-pass of this lane, its bias values, and the first pass's prefetch

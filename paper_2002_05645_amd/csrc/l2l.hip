@@ -162,6 +162,8 @@ struct l2l_ctx {
   // embedding / head
   void* emb = nullptr;
   float* egacc = nullptr;
+  float* split_ws = nullptr;    // partial results of K-split GEMMs (fp32, `splits` dense [M, N] matrices)
+  size_t split_ws_elems = 0;
   float* colsum_ws = nullptr;   // [rows / 64][max(F, 3H)] fp32: partial column sums written by a GEMM epilogue
   size_t colsum_ws_elems = 0;
   int emb_staged = 0, egacc_state = 0;
@@ -336,19 +338,14 @@ void pick_tile(const GemmArgs& g, bool out_f32, int* variant, int* splits) {
   else if (g.M >= 256 && g.N >= 128) v = kc ? 8 : 2;
   else if (g.N <= 64) v = 1;
   else v = kc ? 7 : 0;
-  const bool splittable = out_f32 && (g.epi == EPI_ACCUM) && !g.k_dev;
-  // a split-K GEMM with at most 16 of the 256 x 256 tiles (dW of the output projection: 1024 x 1024 over 32768
-  // tokens) does better with 128 x 128 tiles, two workgroups per CU and half the split depth: 109 against 128 us
-  if (splittable && v == 6 && g.nbatch == 1 && (long long)((g.M + 255) / 256) * ((g.N + 255) / 256) <= 16) v = 7;
   const TileCfg t = kTiles[v];
   // split K when an accumulating fp32 GEMM has too few tiles to fill 256 CUs
-  if (splittable) {
+  if (out_f32 && (g.epi == EPI_ACCUM) && !g.k_dev) {
     const long long tiles = (long long)((g.M + t.bm - 1) / t.bm) * ((g.N + t.bn - 1) / t.bn) * g.nbatch;
     const int nk = (g.K + t.bk - 1) / t.bk;
-    // one resident workgroup per CU (two for the 64 KB 128 x 128 tile): tiles x splits as close to that as it gets
-    // without exceeding it (measured best for the dW shapes: 64 x 4, 48 x 5; 64 x 8 with the small tile)
-    const long long slots = (v == 7) ? 512 : 256;
-    long long want = tiles < slots ? slots / tiles : 1;
+    // one resident workgroup per CU: tiles x splits as close to the 256 CUs as it gets without exceeding
+    // them (measured best for the dW shapes, partial results through the workspace: 64 x 4, 48 x 5, 16 x 16)
+    long long want = tiles < 256 ? 256 / tiles : 1;
     want = std::min<long long>(want, std::max(1, nk / 8));
     *splits = (int)std::max<long long>(1, std::min<long long>(want, 64));
   }
@@ -388,6 +385,24 @@ int gemm(l2l_ctx* c, int dtype, bool out_f32, const GemmArgs& g, int impl = 0, i
       if (kTiles[v].direct && !g.a_kc && g.b_kc) v = 3;   // no direct-to-LDS kernel for A K-strided with B K-contiguous
       if (const char* e = getenv("L2L_FORCE_SPLITS")) g_force_splits = atoi(e);
       if (g_force_splits > 0 && out_f32 && g.epi == EPI_ACCUM) splits = g_force_splits;
+      // K split over grid.y: with a workspace the splits store their partial tiles (16-byte stores) and one kernel
+      // adds them into C; without, they add into C with fp32 atomics, which run at the L2's atomic rate (65536 per
+      // workgroup: 40 % of the time of a 1024 x 1024 x 32768 GEMM) and in no fixed order
+      const long long slice = (long long)g.M * g.N;
+      if (splits > 1 && kTiles[v].direct && g.nbatch == 1 && g.N % 8 == 0 && g.ldc % 4 == 0 && ((uintptr_t)g.C & 15) == 0 &&
+          c->split_ws && !getenv("L2L_SPLIT_ATOMICS")) {
+        const int nk = (g.K + kTiles[v].bk - 1) / kTiles[v].bk, per = (nk + splits - 1) / splits;
+        splits = (nk + per - 1) / per;   // no empty split: every slice of the workspace gets written
+        if (splits > 1 && (size_t)splits * slice <= c->split_ws_elems) {
+          GemmArgs p = g;
+          p.C = c->split_ws; p.ldc = g.N; p.split_stride = slice; p.epi = 0;
+          launch_mfma_variant(v, p, c->cs, splits, out_f32, dtype == L2L_FP16);
+          const unsigned blocks = (unsigned)std::min<long long>((slice / 4 + 255) / 256, 4096);
+          hipLaunchKernelGGL(split_sum_kernel, dim3(blocks), dim3(256), 0, c->cs, c->split_ws, splits, (long long)g.M, g.N,
+                             (float*)g.C, g.ldc);
+          return;
+        }
+      }
       launch_mfma_variant(v, g, c->cs, splits, out_f32, dtype == L2L_FP16);
     } else if (dtype == L2L_BF16) {
       if (out_f32) launch_plain<bf16, float>(g, c->cs);
@@ -914,6 +929,23 @@ int l2l_create(const l2l_config* cfg, void* compute_stream, void* copy_stream, l
   for (auto& b : bufs) L2L_TRY(dev_alloc(c, b.p, b.n * es));
   if (is16(cfg->dtype))
     for (int i = 0; i < 2; ++i) L2L_TRY(dev_alloc(c, &c->wt[i], c->lay.total * es));
+  if (is16(cfg->dtype)) {   // workspace of the K-split dW GEMMs: the largest of the layer's four, by the split rule in use
+    size_t need = 0;
+    const int h = cfg->hidden, f = cfg->ffn;
+    const int shapes[4][2] = {{h, 3 * h}, {h, h}, {h, f}, {f, h}};
+    for (const auto& s : shapes) {
+      GemmArgs w = gemm_args(s[0], s[1], (int)Mg, nullptr, s[0], 0, nullptr, s[1], 0, nullptr, s[1]);
+      w.epi = EPI_ACCUM;
+      int v, splits;
+      pick_tile(w, true, &v, &splits);
+      if (splits > 1) need = std::max(need, (size_t)splits * s[0] * s[1]);
+    }
+    if (const char* e = getenv("L2L_SPLIT_WS_MB")) need = (size_t)atoll(e) << 18;   // tuning: room for other split factors
+    if (need > 0 && need * 4 <= (size_t)256 << 20) {
+      c->split_ws_elems = need;
+      L2L_TRY(dev_alloc(c, (void**)&c->split_ws, need * 4));
+    }
+  }
   if (is16(cfg->dtype)) {   // partial column sums out of a GEMM epilogue: one row per 64 rows of the group at most
     c->colsum_ws_elems = (size_t)((Mg + 63) / 64) * std::max(F, 3 * H);
     L2L_TRY(dev_alloc(c, (void**)&c->colsum_ws, c->colsum_ws_elems * 4));

@@ -566,6 +566,21 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16* in, bf1
   }
 }
 
+// Sum of the K-split partial results of a GEMM: out[m, n] += sum_s part[s][m, n] (part: `splits` dense [rows, n]
+// fp32 matrices, n a multiple of 4; out: row stride ldo, 16-byte aligned rows).
+__global__ __launch_bounds__(256) void split_sum_kernel(const float* part, int splits, long long rows, int n, float* out,
+                                                        long long ldo) {
+  const long long total4 = rows * n / 4, slice = rows * n;
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total4; i += (long long)gridDim.x * 256) {
+    const long long e = i * 4, r = e / n;
+    const int col = (int)(e - r * n);
+    f32x4 s = *(const f32x4*)(part + e);
+    for (int k = 1; k < splits; ++k) s += *(const f32x4*)(part + k * slice + e);
+    f32x4* o = (f32x4*)(out + r * ldo + col);
+    *o = *o + s;
+  }
+}
+
 // p[i] = v for i < n (a kernel rather than a memset so that callers can capture it in a graph).
 // 16-byte stores over the aligned body, dwords for the tail.
 __global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t* p, uint32_t v, long long n) {
