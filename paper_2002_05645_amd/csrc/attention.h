@@ -162,26 +162,28 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const E* qkv, E* out, int
 
 
 // ---- backward ------------------------------------------------------------------------------------------
-// image of P or dS for products over queries: [q][SMAX] 16-bit elements, 256-byte rows, the 32-byte group holding keys
-// 16 p .. 16 p + 15 of row q at group slot p ^ (q & 3) (so that four consecutive query rows hit different banks)
-__device__ __forceinline__ int pq_addr(int q, int key) { return q * 256 + (((key >> 4) ^ (q & 3)) * 32) + (key & 15) * 2; }
+// image of P or dS for products over queries, one half of the keys at a time: [q][64] 16-bit elements, 128-byte rows,
+// the 32-byte group holding keys 16 p .. 16 p + 15 of row q at group slot p ^ (q & 3) (so that four consecutive
+// query rows hit different banks)
+__device__ __forceinline__ int pq_addr(int q, int key) { return q * 128 + (((key >> 4) ^ (q & 3)) * 32) + (key & 15) * 2; }
 
+// key block kb2 (0 or 1) of the half
 template <typename E>
-__device__ __forceinline__ void pq_store(char* img, const f32x16& a, int q, int kb, int lane) {
+__device__ __forceinline__ void pq_store(char* img, const f32x16& a, int q, int kb2, int lane) {
 #pragma unroll
   for (int blk = 0; blk < 4; ++blk) {
     typename Vec<E>::x4 v;
 #pragma unroll
     for (int i = 0; i < 4; ++i) v[i] = from_f32<E>(a[blk * 4 + i]);
-    *(typename Vec<E>::x4*)(img + pq_addr(q, kb * 32 + 8 * blk + 4 * (lane >> 5))) = v;
+    *(typename Vec<E>::x4*)(img + pq_addr(q, kb2 * 32 + 8 * blk + 4 * (lane >> 5))) = v;
   }
 }
 
-// B-operand fragment over queries 16 s + 8 (lane / 32) .. + 7 for key column 32 w + lane % 32
-__device__ __forceinline__ bf16x8 pq_frag(const char* img, int s, int w, int lane) {
+// B-operand fragment over queries 16 s + 8 (lane / 32) .. + 7 for key column 32 kb2 + lane % 32 of the half
+__device__ __forceinline__ bf16x8 pq_frag(const char* img, int s, int kb2, int lane) {
   typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
   const int i16 = lane & 15, R = i16 >> 2, Q = i16 & 3;
-  const int q0 = 16 * s + 8 * (lane >> 5) + R, key = 32 * w + 16 * ((lane >> 4) & 1) + Q * 4;
+  const int q0 = 16 * s + 8 * (lane >> 5) + R, key = 32 * kb2 + 16 * ((lane >> 4) & 1) + Q * 4;
   const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(__attribute__((address_space(3))) char*)(img + pq_addr(q0, key)));
   const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(__attribute__((address_space(3))) char*)(img + pq_addr(q0 + 4, key)));
   const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
@@ -196,11 +198,27 @@ __device__ __forceinline__ bf16x8 frag_queries_T(const char* img, int s, int t, 
   return __builtin_bit_cast(bf16x8, v);
 }
 
-constexpr int BWD_LDS = 4 * SMAX * 128 + 2 * SMAX * 256;
+// one transposed 32 x 32 accumulator (rows = 32 columns of the output, lane = output row), as store_T
+template <typename E>
+__device__ __forceinline__ void store_T1(const f32x16& acc, E* out, long long ld, int lane, float scale) {
+  E* p = out + (long long)(lane & 31) * ld + 4 * (lane >> 5);
+#pragma unroll
+  for (int blk = 0; blk < 4; ++blk) {
+    typename Vec<E>::x4 v;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = from_f32<E>(acc[blk * 4 + i] * scale);
+    *(typename Vec<E>::x4*)(p + blk * 8) = v;
+  }
+}
+
+// 64 KB: two workgroups fit a CU, so that one's loads and stores run under the other's MFMAs
+constexpr int BWD_LDS = 4 * SMAX * 128;
 
 // Backward for one (b, h) per workgroup.  dout: [rows, H] gradient of the context; dqkv: [rows, 3H] receives
 // dQ | dK | dV.  Phase 1 (wave w = queries 32 w ..): recompute P, dP = dO V^T, dS = P (dP - rowsum(P dP)),
-// dQ = alpha dS K, and park P and dS in LDS.  Phase 2 (wave w = keys 32 w ..): dV = P^T dO, dK = alpha dS^T Q.
+// dQ = alpha dS K; P and dS stay in registers.  Phase 2, once per half of the keys (0..63, 64..127): the waves park
+// that half of P and dS in LDS, over the images of K and V, which nobody needs any more, and then wave w takes key
+// block w % 2 of the half and columns 32 (w / 2) .. of the head: dV = P^T dO, dK = alpha dS^T Q.
 template <typename E>
 __global__ __launch_bounds__(256) void attn_bwd_kernel(const E* qkv, const E* dout, E* dqkv, int S, int H, int A, float alpha) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
@@ -208,8 +226,8 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(const E* qkv, const E* do
   char* Vs = lds + SMAX * 128;
   char* Qs = lds + 2 * SMAX * 128;
   char* Os = lds + 3 * SMAX * 128;
-  char* Ps = lds + 4 * SMAX * 128;
-  char* Ds = Ps + SMAX * 256;
+  char* Ps = Ks;   // phase 2
+  char* Ds = Vs;
   const int b = blockIdx.x / A, h = blockIdx.x % A;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const long long ld = 3LL * H;
@@ -225,13 +243,13 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(const E* qkv, const E* do
   wait_vm0();
   __syncthreads();
 
-  E* dq_out = dqkv + ((long long)b * S + wave * 32) * ld + h * 64;
+  E* dqkv_b = dqkv + (long long)b * S * ld + h * 64;
+  const int qrow = wave * 32 + (lane & 31);
+  f32x16 p_[NKB], ds_[NKB];
   if (active) {
-    const int qrow = wave * 32 + (lane & 31);
     bf16x8 qf[4], of[4];
 #pragma unroll
     for (int s4 = 0; s4 < 4; ++s4) { qf[s4] = frag_rows(Qs, qrow, s4, lane); of[s4] = frag_rows(Os, qrow, s4, lane); }
-    f32x16 p_[NKB], dp_[NKB];
     float m = -INFINITY;
 #pragma unroll
     for (int kb = 0; kb < NKB; ++kb)
@@ -247,7 +265,7 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(const E* qkv, const E* do
 #pragma unroll
         for (int r = 0; r < 16; ++r) { a[r] *= alpha; m = fmaxf(m, a[r]); }
         p_[kb] = a;
-        dp_[kb] = d;
+        ds_[kb] = d;
       }
     m = xor32_max(m);
     float sum = 0.f;
@@ -263,7 +281,7 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(const E* qkv, const E* do
     for (int kb = 0; kb < NKB; ++kb)
       if (kb < nkb) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { p_[kb][r] *= inv; dsum += p_[kb][r] * dp_[kb][r]; }
+        for (int r = 0; r < 16; ++r) { p_[kb][r] *= inv; dsum += p_[kb][r] * ds_[kb][r]; }
       }
     dsum = xor32_sum(dsum);
     f32x16 dq[2];
@@ -273,36 +291,43 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(const E* qkv, const E* do
     for (int kb = 0; kb < NKB; ++kb)
       if (kb < nkb) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) dp_[kb][r] = p_[kb][r] * (dp_[kb][r] - dsum);   // dS
-        pq_store<E>(Ps, p_[kb], qrow, kb, lane);
-        pq_store<E>(Ds, dp_[kb], qrow, kb, lane);
+        for (int r = 0; r < 16; ++r) ds_[kb][r] = p_[kb][r] * (ds_[kb][r] - dsum);   // dP -> dS
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
-          const bf16x8 df = pack8<E>(dp_[kb], 8 * s2);
+          const bf16x8 df = pack8<E>(ds_[kb], 8 * s2);
 #pragma unroll
           for (int t = 0; t < 2; ++t) dq[t] = mfma_32x32x16<E>(frag_keys_T(Ks, kb, s2, t, lane), df, dq[t]);
         }
       }
-    store_T(dq, dq_out, ld, lane, alpha);
+    store_T(dq, dqkv_b + (long long)wave * 32 * ld, ld, lane, alpha);
   }
-  __syncthreads();
-  if (active) {
-    f32x16 dv[2], dk[2];
+  // phase 2: keys 64 half .. 64 half + 63
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      dv[t] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      dk[t] = dv[t];
+  for (int half = 0; half < NKB / 2; ++half) {
+    if (2 * half >= nkb) break;
+    __syncthreads();   // K and V (first half) or the previous half's P and dS are no longer read
+    if (active) {
+#pragma unroll
+      for (int kb2 = 0; kb2 < 2; ++kb2)
+        if (2 * half + kb2 < nkb) {
+          pq_store<E>(Ps, p_[2 * half + kb2], qrow, kb2, lane);
+          pq_store<E>(Ds, ds_[2 * half + kb2], qrow, kb2, lane);
+        }
     }
-    for (int s = 0; s < S / 16; ++s) {
-      const bf16x8 pf = pq_frag(Ps, s, wave, lane), df = pq_frag(Ds, s, wave, lane);
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        dv[t] = mfma_32x32x16<E>(frag_queries_T(Os, s, t, lane), pf, dv[t]);
-        dk[t] = mfma_32x32x16<E>(frag_queries_T(Qs, s, t, lane), df, dk[t]);
+    __syncthreads();
+    const int kb2 = wave & 1, t = wave >> 1, kb = 2 * half + kb2;
+    if (kb < nkb) {
+      f32x16 dv = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      f32x16 dk = dv;
+      for (int s = 0; s < S / 16; ++s) {
+        const bf16x8 pf = pq_frag(Ps, s, kb2, lane), df = pq_frag(Ds, s, kb2, lane);
+        dv = mfma_32x32x16<E>(frag_queries_T(Os, s, t, lane), pf, dv);
+        dk = mfma_32x32x16<E>(frag_queries_T(Qs, s, t, lane), df, dk);
       }
+      E* out = dqkv_b + (long long)kb * 32 * ld + t * 32;
+      store_T1(dv, out + 2 * H, ld, lane, 1.0f);
+      store_T1(dk, out + H, ld, lane, alpha);
     }
-    store_T(dv, dq_out + 2 * H, ld, lane, 1.0f);
-    store_T(dk, dq_out + H, ld, lane, alpha);
   }
 }
 
