@@ -165,7 +165,7 @@ def main():
                      "frac": achieved / PEAK_BF16_TFLOPS,
                      # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (profiles/bench_bert_large_gemm_hbm_traffic.md);
                      # measured on the headline workload only
-                     "traffic": 619.2e6 if (a.config == 2 and not a.layers and not a.group and not a.ubatches and not a.dtype and not a.classes) else None,
+                     "traffic": 631.1e6 if (a.config == 2 and not a.layers and not a.group and not a.ubatches and not a.dtype and not a.classes) else None,
                      "kernel": "gemm_mfma_dlds_kernel / gemm_mfma_kernel: the layer's dense GEMMs (QKV, out-proj, FFN1, FFN2; forward, recompute, dX, dW)",
                      "gemm_ms_per_step": g["ms"] / a.steps, "launches_per_step": g["launches"] / a.steps,
                      "avg_launch_us": 1e3 * g["ms"] / max(g["launches"], 1),
