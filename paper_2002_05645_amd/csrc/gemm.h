@@ -526,9 +526,13 @@ __device__ __forceinline__ void wait_vm0() { __builtin_amdgcn_s_waitcnt(0x0F70);
 // ... and until every LDS read this wave issued has returned (vmcnt(0) lgkmcnt(0))
 __device__ __forceinline__ void wait_vm0_lds0() { __builtin_amdgcn_s_waitcnt(0x0070); }
 
-// dynamic LDS of gemm_mfma_dlds_kernel: two stages
+// dynamic LDS of gemm_mfma_dlds_kernel: two stages; the epilogue's strips (one of 32 x (WN + 4) floats per wave) sit
+// behind the first stage, which by then is receiving the next tile
 template <int BM, int BN, int WM, int WN>
-constexpr int dlds_lds_bytes() { return 2 * (BM + BN) * 128; }
+constexpr int dlds_lds_bytes() {
+  constexpr int stage = (BM + BN) * 128, strips = (BM / WM) * (BN / WN) * 32 * (WN + 4) * 4;
+  return stage + (stage > strips ? stage : strips);
+}
 
 // EPI >= 0: the epilogue flags are this compile-time constant (the launcher guarantees g.epi == EPI), which takes
 // the flag tests and the code of the unused operations out of the unrolled epilogue; EPI < 0: flags read from g.epi.
@@ -545,7 +549,6 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
   constexpr int STAGE = DA::BYTES + DB::BYTES;
   constexpr int EP_PITCH = WN + 4;
   constexpr int EP_BYTES = 32 * EP_PITCH * 4;
-  static_assert(NWM * NWN * EP_BYTES <= 2 * STAGE, "epilogue strips must fit the staging buffers");
   extern __shared__ __attribute__((aligned(1024))) char lds[];  // dlds_lds_bytes<BM, BN, WM, WN>()
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -566,19 +569,25 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
   // A workgroup takes tiles blockIdx.x, blockIdx.x + gridDim.x, ...: launched with one workgroup per tile it runs
   // once, launched with one workgroup per CU it stays resident and walks its share of the tile order, which
   // saves the dispatch of a 512-thread, 128 KB workgroup per tile.
+  const int z = blockIdx.z, zo = z / g.zdiv, zi = z % g.zdiv;
+  const uint32_t lda = (uint32_t)g.lda, ldb = (uint32_t)g.ldb;
+  // buffer descriptors of the operand panels of the tile at (m0, n0)
+  const auto panels = [&](int m0, int n0, __amdgpu_buffer_rsrc_t& ra, __amdgpu_buffer_rsrc_t& rb) {
+    const bf16* A = (const bf16*)g.A + zo * g.a_zo + zi * g.a_zi + (AKC ? (long long)m0 * g.lda : (long long)m0);
+    const bf16* B = (const bf16*)g.B + zo * g.b_zo + zi * g.b_zi + (BKC ? (long long)n0 * g.ldb : (long long)n0);
+    ra = make_rsrc(A, tile_bytes<AKC>(g.lda, M - m0, K));
+    rb = make_rsrc(B, tile_bytes<BKC>(g.ldb, N - n0, K));
+  };
+  int staged_vb = -1;   // the tile whose first k-tile is already on its way into stage 0 (issued under the previous epilogue)
   for (int vb = blockIdx.x; vb < tiles_m * tiles_n; vb += gridDim.x) {
   int tm, tn;
   tile_of_block(vb, tiles_m, tiles_n, tm, tn);
   const int m0 = tm * BM, n0 = tn * BN;
   if (m0 >= M) continue;
 
-  const int z = blockIdx.z, zo = z / g.zdiv, zi = z % g.zdiv;
-  const bf16* A = (const bf16*)g.A + zo * g.a_zo + zi * g.a_zi + (AKC ? (long long)m0 * g.lda : (long long)m0);
-  const bf16* B = (const bf16*)g.B + zo * g.b_zo + zi * g.b_zi + (BKC ? (long long)n0 * g.ldb : (long long)n0);
   TC* C = (TC*)g.C + zo * g.c_zo + zi * g.c_zi + (long long)blockIdx.y * g.split_stride;
-  const __amdgpu_buffer_rsrc_t ra = make_rsrc(A, tile_bytes<AKC>(g.lda, M - m0, K));
-  const __amdgpu_buffer_rsrc_t rb = make_rsrc(B, tile_bytes<BKC>(g.ldb, N - n0, K));
-  const uint32_t lda = (uint32_t)g.lda, ldb = (uint32_t)g.ldb;
+  __amdgpu_buffer_rsrc_t ra, rb;
+  panels(m0, n0, ra, rb);
 
   f32x16 acc[FM * FN];
   static_for<0, FM * FN>([&](auto t) {
@@ -612,10 +621,12 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
   // that same barrier publishes tile t.  The barrier therefore sits between MFMA groups, and the
   // first fragments of the next tile are read while the last MFMAs of this one run.  Past the last
   // tile the loads fetch rows beyond K (zeros) or the next split's tile, neither of which is used.
-  DA::load(ra, lda, kt0 * BK, K, lds, wave, lane);
-  DB::load(rb, ldb, kt0 * BK, K, lds + DA::BYTES, wave, lane);
+  if (staged_vb != vb) {
+    DA::load(ra, lda, kt0 * BK, K, lds, wave, lane);
+    DB::load(rb, ldb, kt0 * BK, K, lds + DA::BYTES, wave, lane);
+  }
   wait_vm0();
-  __syncthreads();
+  __syncthreads();   // stage 0 is complete, and every wave has left the previous tile's strips, which lie over stage 1
   load_ab(std::integral_constant<int, 0>{}, std::integral_constant<int, LS0>{}, (kt0 + 1) * BK, lds + STAGE);
 
   bf16x8 af[2 * FM], bfr[2 * FN];
@@ -656,7 +667,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
 
   // ---- epilogue (as in gemm_mfma_kernel) ----------------------------------------------------------
   const bool atomic = gridDim.y > 1 && g.split_stride == 0;
-  float* strip = (float*)(lds + wave * EP_BYTES);
+  float* strip = (float*)(lds + STAGE + wave * EP_BYTES);   // behind stage 0, which the next tile is about to use
   const bool vec_ok = gemm_vec_ok(g, epi, C);
   // vector path: 8-column chunk and row-in-pass of this lane, its bias values, and the first pass's prefetch
   constexpr int CPR = WN / 8, RPP = 64 / CPR, PASSES = 32 / RPP;
@@ -682,6 +693,22 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
   if (vec_ok && !atomic) {
     if ((epi & EPI_BIAS) && ncol < N) load8((const E*)g.bias + ncol, bias8);
     fetch(0, 0, pre[0]);
+  }
+  // The first k-tile of this workgroup's next tile goes into stage 0 now, under the epilogue (issued after the
+  // epilogue's own first loads: loads return in order, and the passes must not wait for 64 KB of operands).
+  {
+    const int vbn = vb + gridDim.x;
+    if (vbn < tiles_m * tiles_n) {
+      int tmn, tnn;
+      tile_of_block(vbn, tiles_m, tiles_n, tmn, tnn);
+      if (tmn * BM < M) {
+        __amdgpu_buffer_rsrc_t ran, rbn;
+        panels(tmn * BM, tnn * BN, ran, rbn);
+        DA::load(ran, lda, kt0 * BK, K, lds, wave, lane);
+        DB::load(rbn, ldb, kt0 * BK, K, lds + DA::BYTES, wave, lane);
+        staged_vb = vbn;
+      }
+    }
   }
   static_for<0, FM>([&](auto ic) {
     constexpr int i = decltype(ic)::value;
@@ -776,6 +803,5 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
     }
     if (lane < CPR && ncol < N) store8(g.colsum + (long long)((m0 + wm * WM) / WM) * N + ncol, csum8);
   }
-  __syncthreads();   // every wave is done with its strips before the next tile's loads overwrite them
-  }
+  }   // (the next tile's first barrier comes before anything is loaded over the strips)
 }
