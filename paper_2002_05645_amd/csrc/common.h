@@ -127,14 +127,11 @@ __device__ __forceinline__ float gelu_grad_fast_f(float u) {
   return fmaf(p, s, 0.5f);
 }
 
-// GELU of the 16-bit epilogues: the polynomial forms for bf16; fp16, whose rounding step is eight times finer,
-// keeps the exact ones.
-template <typename E> __device__ __forceinline__ float gelu_epi(float u) {
-  if constexpr (__is_same(E, bf16)) return gelu_fast_f(u); else return gelu_f(u);
-}
-template <typename E> __device__ __forceinline__ float gelu_grad_epi(float u) {
-  if constexpr (__is_same(E, bf16)) return gelu_grad_fast_f(u); else return gelu_grad_f(u);
-}
+// GELU of the 16-bit epilogues: the polynomial forms.  Their absolute errors (4e-5 and 2e-4) are below half a unit
+// in the last place of bf16 everywhere and of fp16 (2.4e-4 relative) wherever the result exceeds 0.2 and 0.8; below
+// that they stay under one unit.
+template <typename E> __device__ __forceinline__ float gelu_epi(float u) { return gelu_fast_f(u); }
+template <typename E> __device__ __forceinline__ float gelu_grad_epi(float u) { return gelu_grad_fast_f(u); }
 
 // Epilogue flags of the GEMM kernels.
 // EPI_COLSUM: also leave the column sums of the stored values in GemmArgs::colsum (a bias gradient that would
