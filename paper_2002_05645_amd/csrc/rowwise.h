@@ -154,16 +154,37 @@ __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* dy, const T*
     if (j < n) load8(gamma + j, gam[k]);
   }
   const int r0 = blockIdx.x * LNF_ROWS, r1 = min(rows, r0 + LNF_ROWS);
+  // 16-bit rows: the wave's next row is requested (as packed 16-byte words) before the current one is worked on, so
+  // that its two reductions and its store run under the loads
+  constexpr bool AHEAD = sizeof(T) == 2;
+  u32x4 xr[NCH], dr[NCH];
+  const auto request = [&](int r) {
+#pragma unroll
+    for (int k = 0; k < NCH; ++k) {
+      const int j = lane * 8 + k * 512;
+      if (j < n && r < r1) {
+        xr[k] = *(const u32x4*)(x + (long long)r * n + j);
+        dr[k] = *(const u32x4*)(dy + (long long)r * n + j);
+      }
+    }
+  };
+  if constexpr (AHEAD) request(r0 + w);
   for (int r = r0 + w; r < r1; r += 4) {
     float xh[NCH][8], d[NCH][8];
 #pragma unroll
     for (int k = 0; k < NCH; ++k) {
       const int j = lane * 8 + k * 512;
       if (j < n) {
-        load8(x + (long long)r * n + j, xh[k]);
-        load8(dy + (long long)r * n + j, d[k]);
+        if constexpr (AHEAD) {
+          unpack8<T>(xr[k], xh[k]);
+          unpack8<T>(dr[k], d[k]);
+        } else {
+          load8(x + (long long)r * n + j, xh[k]);
+          load8(dy + (long long)r * n + j, d[k]);
+        }
       }
     }
+    if constexpr (AHEAD) request(r + 4);
     float mu, rs;
     if (mean) {
       mu = mean[r];
