@@ -117,6 +117,25 @@ def test_gemm_every_tile_variant(ctx, variant):
         ctx.op_gemm(P.L2L_BF16, False, 1, 0, 64, 64, 64, x, 64, x, 64, x, 64, impl=100 + 9)   # one past the last variant
 
 
+@pytest.mark.parametrize("workspace_mb", [0, 64])
+def test_gemm_split_k_through_workspace_and_with_atomics(monkeypatch, workspace_mb):
+    # an accumulating fp32 GEMM with few tiles and a long K is split over K; the splits either store partial tiles in a
+    # workspace that one kernel adds up (contexts size it from their layer shapes; forced here), or add with atomics
+    if workspace_mb:
+        monkeypatch.setenv("L2L_SPLIT_WS_MB", str(workspace_mb))
+    else:
+        monkeypatch.setenv("L2L_SPLIT_ATOMICS", "1")
+    c = P.Context(P.make_config(64, 2, 128, 16, 2, 2, "bf16", 1e-5, 0))
+    try:
+        for dtype in ("bf16", "fp16"):
+            assert _gemm_case(c, dtype, 0, 0, 0, 256, 512, 4096, accumulate=True, out_f32=True, pad=8) < 2e-6    # 2 tiles, 8 splits
+            assert _gemm_case(c, dtype, 0, 0, 0, 264, 520, 4200, accumulate=True, out_f32=True, pad=8) < 2e-6    # ragged everywhere
+            assert _gemm_case(c, dtype, 0, 1, 1, 256, 256, 4096 + 64, accumulate=True, out_f32=True, pad=8) < 2e-6    # K-contiguous operands
+            assert _gemm_case(c, dtype, 0, 0, 0, 200, 136, 8192, accumulate=True, out_f32=True, pad=3) < 2e-6    # rows not 16-byte aligned
+    finally:
+        c.close()
+
+
 def test_gemm_rejects_bad_arguments(ctx):
     x = torch.zeros(64, 64, device="cuda")
     with pytest.raises(P.L2LError) as e:
