@@ -66,6 +66,8 @@ def main():
                     help="> 0: the sequence-classification head with this many classes (one synthetic label per sequence) instead of the LM head")
     ap.add_argument("--optimizer", default="adam", choices=["adam", "lamb"],
                     help="host optimizer (lamb: per-tensor trust ratio, learning rate 1e-3, weight decay 0.01 on matrices)")
+    ap.add_argument("--grad-dtype", default="fp32", choices=["fp32", "bf16", "fp16"],
+                    help="format of the gradient drains over the host link (fp32 = the headline; 16-bit: rounded on the device, half the bytes)")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -83,7 +85,7 @@ def main():
         w = w.scaled(dtype=a.dtype)
     tr = L2LTrainer(layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, vocab=w.vocab,
                     ubatch=w.ubatch, num_ubatches=w.num_ubatches, dtype=w.dtype, ubatch_group=a.group, stash=a.stash,
-                    eager=not a.tail_adam, optimizer=a.optimizer, num_classes=a.classes,
+                    eager=not a.tail_adam, optimizer=a.optimizer, num_classes=a.classes, grad_dtype=a.grad_dtype,
                     **(dict(lr=1e-3, eps_a=1e-6, weight_decay=0.01) if a.optimizer == "lamb" else {}))
     tr.load_params(S.embed_params(w), [S.layer_params(w, l) for l in range(w.layers)], S.cls_params(w, a.classes) if a.classes else None)
     tok, lab = S.tokens_and_labels(w)
@@ -165,7 +167,7 @@ def main():
                      "frac": achieved / PEAK_BF16_TFLOPS,
                      # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (profiles/bench_bert_large_gemm_hbm_traffic.md);
                      # measured on the headline workload only
-                     "traffic": 631.1e6 if (a.config == 2 and not a.layers and not a.group and not a.ubatches and not a.dtype and not a.classes) else None,
+                     "traffic": 631.1e6 if (a.config == 2 and not a.layers and not a.group and not a.ubatches and not a.dtype and not a.classes and a.grad_dtype == "fp32") else None,
                      "kernel": "gemm_mfma_dlds_kernel / gemm_mfma_kernel: the layer's dense GEMMs (QKV, out-proj, FFN1, FFN2; forward, recompute, dX, dW)",
                      "gemm_ms_per_step": g["ms"] / a.steps, "launches_per_step": g["launches"] / a.steps,
                      "avg_launch_us": 1e3 * g["ms"] / max(g["launches"], 1),

@@ -189,6 +189,14 @@ int l2l_cls_drain_wait(l2l_ctx*);
    gradient downstream carries that factor (the reported loss does not); the host divides it out of the
    drained gradients (eps_grad_unscale).  Default 1.  L2L_E_ARG unless 0 < scale < inf. */
 int l2l_set_loss_scale(l2l_ctx*, float scale);
+
+/* Format in which the gradient drains (l2l_grad_drain, l2l_embed_grad_drain and its piecewise form, l2l_cls_grad_drain)
+   write to host memory: L2L_F32 (default: the accumulators as they are) or L2L_BF16 / L2L_FP16 (rounded to nearest
+   even on the device first, half the bytes over the host link; the paper's device holds and sends 16-bit values,
+   Section 2.3).  The gradients still accumulate in fp32 on the device.  With a 16-bit format `host_grads` of the
+   drain calls points at 16-bit elements, and element offsets count those.  Call between steps (no drain in flight).
+   L2L_E_ARG for another value, L2L_E_NOMEM if the staging buffer cannot be allocated. */
+int l2l_set_drain_dtype(l2l_ctx*, int dtype);
 /* Backward of l2l_embed_fwd: adds dE (scatter-add over token ids), dPpos, dge, dbe into the
    embedding-block accumulator.  dy: device U x [ub,S,H] (read only). */
 int l2l_embed_bwd(l2l_ctx*, const int32_t* tokens, const void* dy);
@@ -264,6 +272,19 @@ int   eps_adam_step_range(eps_store*, int block, long long first_elem, long long
    *nonfinite to 1 if any of them holds an inf or NaN (an overflow on the device: the caller then skips
    the update and lowers the scale), else 0.  nonfinite may be null. */
 int   eps_grad_unscale(eps_store*, int first, int last, double inv_scale, int* nonfinite);
+/* 16-bit gradient landing buffers (for l2l_set_drain_dtype): eps_enable_grad16 allocates one per block (pinned, 2 bytes
+   per element, once), eps_grad16 returns a block's, eps_grad_widen converts what landed there (dtype L2L_BF16 or
+   L2L_FP16) into the fp32 gradient buffers of blocks [first, last], which the optimizer steps read; the _range form
+   does elements [first_elem, first_elem + count) of one block. */
+int   eps_enable_grad16(eps_store*);
+void* eps_grad16(eps_store*, int block);
+int   eps_grad_widen(eps_store*, int first, int last, int dtype);
+int   eps_grad_widen_range(eps_store*, int block, long long first_elem, long long count, int dtype);
+/* eps_adam_step_range with the gradients taken from the block's 16-bit landing buffer (grad_dtype L2L_BF16 or L2L_FP16)
+   and widened on the fly: the same arithmetic as eps_grad_widen_range followed by eps_adam_step_range, without the
+   extra pass over host memory (the fp32 gradient buffer is left as it was). */
+int   eps_adam_step_range16(eps_store*, int block, long long first_elem, long long count, int t, double lr, double beta1,
+                            double beta2, double eps, int grad_dtype);
 /* One LAMB step (the optimizer of Table 1; update rule of the LAMB publication the paper cites, with
    bias correction): per tensor, u = mhat / (sqrt(vhat) + eps_a) + weight_decay * w and
    w -= lr * (||w|| / ||u||) * u, the ratio taken as 1 where either norm is zero.  The tensors of a

@@ -101,6 +101,13 @@ _SIGS = {
     "eps_adam_step_range": (C.c_int, [_P, C.c_int, C.c_longlong, C.c_longlong, C.c_int, C.c_double, C.c_double, C.c_double,
                                       C.c_double]),
     "eps_grad_unscale": (C.c_int, [_P, C.c_int, C.c_int, C.c_double, C.POINTER(C.c_int)]),
+    "eps_adam_step_range16": (C.c_int, [_P, C.c_int, C.c_longlong, C.c_longlong, C.c_int, C.c_double, C.c_double, C.c_double,
+                                        C.c_double, C.c_int]),
+    "eps_enable_grad16": (C.c_int, [_P]),
+    "eps_grad16": (C.c_void_p, [_P, C.c_int]),
+    "eps_grad_widen": (C.c_int, [_P, C.c_int, C.c_int, C.c_int]),
+    "eps_grad_widen_range": (C.c_int, [_P, C.c_int, C.c_longlong, C.c_longlong, C.c_int]),
+    "l2l_set_drain_dtype": (C.c_int, [_P, C.c_int]),
     "eps_lamb_step": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_double, C.c_double, C.c_double, C.c_double, C.c_double,
                                 C.c_int, C.POINTER(C.c_longlong), C.POINTER(C.c_longlong), C.POINTER(C.c_double)]),
     "eps_host_bytes": (C.c_size_t, [_P]),
@@ -251,6 +258,9 @@ class Context:
     def embed_grad_drain_part(self, host_grads, first, count):
         self._ck(lib().l2l_embed_grad_drain_part(self._h, _ptr(host_grads), int(first), int(count)))
 
+    def set_drain_dtype(self, dtype):
+        self._ck(lib().l2l_set_drain_dtype(self._h, DTYPES[dtype] if isinstance(dtype, str) else int(dtype)))
+
     def embed_drain_wait(self):
         self._ck(lib().l2l_embed_drain_wait(self._h))
 
@@ -360,6 +370,37 @@ class EPS:
         rc = lib().eps_adam_step_range(self._h, block, int(first_elem), int(count), t, lr, beta1, beta2, eps_a)
         if rc != L2L_OK:
             raise L2LError(rc, "eps_adam_step_range")
+
+    def adam_step_range16(self, block, first_elem, count, t, grad_dtype, lr=1e-4, beta1=0.9, beta2=0.999, eps_a=1e-8):
+        rc = lib().eps_adam_step_range16(self._h, block, int(first_elem), int(count), t, lr, beta1, beta2, eps_a,
+                                         DTYPES[grad_dtype] if isinstance(grad_dtype, str) else int(grad_dtype))
+        if rc != L2L_OK:
+            raise L2LError(rc, "eps_adam_step_range16")
+
+    def enable_grad16(self):
+        rc = lib().eps_enable_grad16(self._h)
+        if rc != L2L_OK:
+            raise L2LError(rc, "eps_enable_grad16")
+
+    def grad16_ptr(self, block):
+        return lib().eps_grad16(self._h, block)
+
+    def grad16(self, block) -> np.ndarray:
+        """the 16-bit landing buffer of a block, as raw bit patterns"""
+        p = lib().eps_grad16(self._h, block)
+        if not p:
+            raise L2LError(L2L_E_STATE, "eps_grad16: not enabled")
+        return np.ctypeslib.as_array(C.cast(p, C.POINTER(C.c_uint16)), shape=(self.elems[block],))
+
+    def grad_widen(self, first, last, dtype):
+        rc = lib().eps_grad_widen(self._h, first, last, DTYPES[dtype] if isinstance(dtype, str) else int(dtype))
+        if rc != L2L_OK:
+            raise L2LError(rc, "eps_grad_widen")
+
+    def grad_widen_range(self, block, first_elem, count, dtype):
+        rc = lib().eps_grad_widen_range(self._h, block, int(first_elem), int(count), DTYPES[dtype] if isinstance(dtype, str) else int(dtype))
+        if rc != L2L_OK:
+            raise L2LError(rc, "eps_grad_widen_range")
 
     def grad_unscale(self, first, last, inv_scale) -> bool:
         """landing buffers *= inv_scale; True if they hold an inf or NaN."""

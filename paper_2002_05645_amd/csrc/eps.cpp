@@ -90,6 +90,7 @@ struct Block {
   float *w = nullptr, *m = nullptr, *v = nullptr;  // pageable
   void* ship = nullptr;                             // pinned
   float* grad = nullptr;                            // pinned
+  uint16_t* grad16 = nullptr;                       // pinned, optional: landing buffer of 16-bit drains
 };
 
 inline uint16_t f32_to_bf16_rne(float f) {
@@ -121,22 +122,57 @@ static void ship_range(const eps_store* e, const Block& b, size_t lo, size_t hi)
   }
 }
 
-// bias-corrected Adam on elements [e0, e0 + n) of a block, master -> shipping copy included
-static void adam_range(eps_store* e, const Block& b, size_t e0, size_t n, float lr, float beta1, float beta2, float eps_a,
-                       float omb1, float omb2, float c1, float c2) {
+// bias-corrected Adam on elements [lo, hi) of a block with the gradients at g[k - lo0 ...]: g points at the gradient of
+// element `lo` (the fp32 gradient buffer, or a widened run of the 16-bit landing buffer)
+static void adam_run(const Block& b, size_t lo, size_t hi, const float* __restrict g, float lr, float beta1, float beta2,
+                     float eps_a, float omb1, float omb2, float c1, float c2) {
+  float* __restrict w = b.w + lo;
+  float* __restrict m = b.m + lo;
+  float* __restrict v = b.v + lo;
+  const size_t n = hi - lo;
+#pragma omp simd   // the arrays are distinct allocations: iterations are independent
+  for (size_t k = 0; k < n; ++k) {
+    const float gk = g[k];
+    const float mk = beta1 * m[k] + omb1 * gk;
+    const float vk = beta2 * v[k] + omb2 * gk * gk;
+    m[k] = mk;
+    v[k] = vk;
+    w[k] -= lr * (mk * c1) / (std::sqrt(vk * c2) + eps_a);
+  }
+}
+
+static void widen_run(const uint16_t* __restrict s, float* __restrict d, size_t n, int dtype) {
+  if (dtype == L2L_BF16) {
+#pragma omp simd
+    for (size_t k = 0; k < n; ++k) {
+      const uint32_t u = (uint32_t)s[k] << 16;
+      float f;
+      std::memcpy(&f, &u, 4);
+      d[k] = f;
+    }
+  } else {
+    size_t k = 0;
+    for (; k + 8 <= n; k += 8) _mm256_storeu_ps(d + k, _mm256_cvtph_ps(_mm_loadu_si128((const __m128i*)(s + k))));
+    for (; k < n; ++k) d[k] = _cvtsh_ss(s[k]);
+  }
+}
+
+// Adam on elements [e0, e0 + n) of a block, master -> shipping copy included.  gd: where the gradients are read from:
+// the fp32 buffer (L2L_F32) or the 16-bit landing buffer (L2L_BF16 / L2L_FP16), widened a cache-resident run at a time
+// (a loop that mixes 16- and 32-bit lanes does not vectorise; two loops over a run that stays in L1 do).
+static void adam_range(eps_store* e, const Block& b, size_t e0, size_t n, int gd, float lr, float beta1, float beta2,
+                       float eps_a, float omb1, float omb2, float c1, float c2) {
   e->pool->run(n, [&](size_t lo, size_t hi) {
-    float* __restrict w = b.w;
-    float* __restrict m = b.m;
-    float* __restrict v = b.v;
-    const float* __restrict g = b.grad;
-#pragma omp simd   // the four arrays are distinct allocations: iterations are independent
-    for (size_t k = e0 + lo; k < e0 + hi; ++k) {
-      const float gk = g[k];
-      const float mk = beta1 * m[k] + omb1 * gk;
-      const float vk = beta2 * v[k] + omb2 * gk * gk;
-      m[k] = mk;
-      v[k] = vk;
-      w[k] -= lr * (mk * c1) / (std::sqrt(vk * c2) + eps_a);
+    if (gd == L2L_F32) {
+      adam_run(b, e0 + lo, e0 + hi, b.grad + e0 + lo, lr, beta1, beta2, eps_a, omb1, omb2, c1, c2);
+    } else {
+      constexpr size_t RUN = 2048;
+      alignas(64) float tmp[RUN];
+      for (size_t k0 = e0 + lo; k0 < e0 + hi; k0 += RUN) {
+        const size_t k1 = std::min(e0 + hi, k0 + RUN);
+        widen_run(b.grad16 + k0, tmp, k1 - k0, gd);
+        adam_run(b, k0, k1, tmp, lr, beta1, beta2, eps_a, omb1, omb2, c1, c2);
+      }
     }
     ship_range(e, b, e0 + lo, e0 + hi);
   });
@@ -202,9 +238,11 @@ int eps_destroy(eps_store* e) {
     if (b.pinned) {
       if (b.ship) (void)hipHostFree(b.ship);
       if (b.grad) (void)hipHostFree(b.grad);
+      if (b.grad16) (void)hipHostFree(b.grad16);
     } else {
       free(b.ship);
       free(b.grad);
+      free(b.grad16);
     }
   }
   delete e;
@@ -242,7 +280,7 @@ int eps_adam_step(eps_store* e, int first, int last, int t, double lr_d, double 
   const float omb1 = (float)(1.0 - beta1_d), omb2 = (float)(1.0 - beta2_d);
   const float c1 = (float)(1.0 / (1.0 - std::pow(beta1_d, t)));
   const float c2 = (float)(1.0 / (1.0 - std::pow(beta2_d, t)));
-  for (int i = first; i <= last; ++i) adam_range(e, e->blocks[i], 0, e->blocks[i].n, lr, beta1, beta2, eps_a, omb1, omb2, c1, c2);
+  for (int i = first; i <= last; ++i) adam_range(e, e->blocks[i], 0, e->blocks[i].n, L2L_F32, lr, beta1, beta2, eps_a, omb1, omb2, c1, c2);
   return L2L_OK;
 }
 
@@ -254,7 +292,61 @@ int eps_adam_step_range(eps_store* e, int block, long long first_elem, long long
   const float omb1 = (float)(1.0 - beta1_d), omb2 = (float)(1.0 - beta2_d);
   const float c1 = (float)(1.0 / (1.0 - std::pow(beta1_d, t)));
   const float c2 = (float)(1.0 / (1.0 - std::pow(beta2_d, t)));
-  adam_range(e, e->blocks[block], (size_t)first_elem, (size_t)count, lr, beta1, beta2, eps_a, omb1, omb2, c1, c2);
+  adam_range(e, e->blocks[block], (size_t)first_elem, (size_t)count, L2L_F32, lr, beta1, beta2, eps_a, omb1, omb2, c1, c2);
+  return L2L_OK;
+}
+
+int eps_adam_step_range16(eps_store* e, int block, long long first_elem, long long count, int t, double lr_d, double beta1_d,
+                          double beta2_d, double eps_a_d, int grad_dtype) {
+  if (!e || block < 0 || block >= (int)e->blocks.size() || t < 1 || (grad_dtype != L2L_BF16 && grad_dtype != L2L_FP16)) return L2L_E_ARG;
+  const Block& b = e->blocks[block];
+  if (!b.grad16) return L2L_E_STATE;
+  if (first_elem < 0 || count <= 0 || (size_t)(first_elem + count) > b.n) return L2L_E_ARG;
+  const float lr = (float)lr_d, beta1 = (float)beta1_d, beta2 = (float)beta2_d, eps_a = (float)eps_a_d;
+  const float omb1 = (float)(1.0 - beta1_d), omb2 = (float)(1.0 - beta2_d);
+  const float c1 = (float)(1.0 / (1.0 - std::pow(beta1_d, t)));
+  const float c2 = (float)(1.0 / (1.0 - std::pow(beta2_d, t)));
+  adam_range(e, b, (size_t)first_elem, (size_t)count, grad_dtype, lr, beta1, beta2, eps_a, omb1, omb2, c1, c2);
+  return L2L_OK;
+}
+
+int eps_enable_grad16(eps_store* e) {
+  if (!e) return L2L_E_ARG;
+  for (Block& b : e->blocks) {
+    if (b.grad16) continue;
+    const size_t bytes = (b.n * 2 + 63) / 64 * 64;
+    if (b.pinned) {   // as the block's other host-link buffers
+      if (hipHostMalloc((void**)&b.grad16, bytes, hipHostMallocDefault) != hipSuccess) { b.grad16 = nullptr; return L2L_E_NOMEM; }
+    } else {
+      b.grad16 = (uint16_t*)aligned_alloc(64, bytes);
+      if (!b.grad16) return L2L_E_NOMEM;
+    }
+    std::memset(b.grad16, 0, bytes);
+    e->host_bytes += bytes;
+  }
+  return L2L_OK;
+}
+
+void* eps_grad16(eps_store* e, int i) { Block* b = blk(e, i); return b ? b->grad16 : nullptr; }
+
+static void widen_range(const Block& b, size_t lo, size_t hi, int dtype) { widen_run(b.grad16 + lo, b.grad + lo, hi - lo, dtype); }
+
+int eps_grad_widen_range(eps_store* e, int block, long long first_elem, long long count, int dtype) {
+  if (!e || block < 0 || block >= (int)e->blocks.size() || (dtype != L2L_BF16 && dtype != L2L_FP16)) return L2L_E_ARG;
+  const Block& b = e->blocks[block];
+  if (!b.grad16) return L2L_E_STATE;
+  if (first_elem < 0 || count <= 0 || (size_t)(first_elem + count) > b.n) return L2L_E_ARG;
+  const size_t e0 = (size_t)first_elem;
+  e->pool->run((size_t)count, [&](size_t lo, size_t hi) { widen_range(b, e0 + lo, e0 + hi, dtype); });
+  return L2L_OK;
+}
+
+int eps_grad_widen(eps_store* e, int first, int last, int dtype) {
+  if (!e || first < 0 || last >= (int)e->blocks.size() || first > last) return L2L_E_ARG;
+  for (int i = first; i <= last; ++i) {
+    const int rc = eps_grad_widen_range(e, i, 0, (long long)e->blocks[i].n, dtype);
+    if (rc != L2L_OK) return rc;
+  }
   return L2L_OK;
 }
 

@@ -162,6 +162,9 @@ struct l2l_ctx {
   // embedding / head
   void* emb = nullptr;
   float* egacc = nullptr;
+  int drain_dtype = L2L_F32;    // format of the drained gradients on the host (l2l_set_drain_dtype)
+  void* drain_stage = nullptr;  // 16-bit drains: the rounded copy a drain sends (one suffices: the copy stream runs in order)
+  size_t drain_stage_elems = 0;
   float* split_ws = nullptr;    // partial results of K-split GEMMs (fp32, `splits` dense [M, N] matrices)
   size_t split_ws_elems = 0;
   float* colsum_ws = nullptr;   // [rows / 64][max(F, 3H)] fp32: partial column sums written by a GEMM epilogue
@@ -1075,6 +1078,36 @@ int l2l_layer_bwd(l2l_ctx* c, int layer, int slot, const void* x_stash, void* dy
   return L2L_OK;
 }
 
+// elements [first, first + count) of an fp32 accumulator -> the same elements of the host landing buffer, in the drain
+// format, on the copy stream
+static int drain_copy(l2l_ctx* c, void* host, const float* acc, long long first, long long count) {
+  if (c->drain_dtype == L2L_F32) {
+    HIP_TRY(c, hipMemcpyAsync((float*)host + first, acc + first, count * 4, hipMemcpyDeviceToHost, c->xs));
+    return L2L_OK;
+  }
+  if ((size_t)count > c->drain_stage_elems) return fail(c, L2L_E_STATE, "drain: %lld elements exceed the 16-bit staging buffer", count);
+  const unsigned blocks = (unsigned)std::min<long long>((count / 4 + 255) / 256 + 1, 2048);
+  if (c->drain_dtype == L2L_BF16) hipLaunchKernelGGL(narrow_kernel<bf16>, dim3(blocks), dim3(256), 0, c->xs, acc + first, (bf16*)c->drain_stage, count);
+  else hipLaunchKernelGGL(narrow_kernel<fp16>, dim3(blocks), dim3(256), 0, c->xs, acc + first, (fp16*)c->drain_stage, count);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(c, L2L_E_HIP, "narrow launch: %s", hipGetErrorString(e));
+  HIP_TRY(c, hipMemcpyAsync((char*)host + first * 2, c->drain_stage, count * 2, hipMemcpyDeviceToHost, c->xs));
+  return L2L_OK;
+}
+static double drain_bytes(const l2l_ctx* c, long long count) { return (double)count * (c->drain_dtype == L2L_F32 ? 4 : 2); }
+
+int l2l_set_drain_dtype(l2l_ctx* c, int dtype) {
+  if (!c) return L2L_E_ARG;
+  if (dtype != L2L_F32 && dtype != L2L_BF16 && dtype != L2L_FP16) return fail(c, L2L_E_ARG, "l2l_set_drain_dtype: unknown dtype %d", dtype);
+  if (dtype != L2L_F32 && !c->drain_stage) {
+    const size_t n = (size_t)std::max<long long>(c->lay.total, c->cfg.vocab > 0 ? c->lay.etotal : 0);
+    L2L_TRY(dev_alloc(c, &c->drain_stage, n * 2));
+    c->drain_stage_elems = n;
+  }
+  c->drain_dtype = dtype;
+  return L2L_OK;
+}
+
 int l2l_grad_drain(l2l_ctx* c, int layer, void* host_grads) {
   if (!c) return L2L_E_ARG;
   if (!host_grads) return fail(c, L2L_E_ARG, "l2l_grad_drain: null host pointer");
@@ -1082,10 +1115,10 @@ int l2l_grad_drain(l2l_ctx* c, int layer, void* host_grads) {
     if (c->gacc_state[a] == 1 && c->gacc_layer[a] == layer) {
       HIP_TRY(c, hipStreamWaitEvent(c->xs, c->gacc_ready[a], 0));
       const CopyMark mark = copy_begin(c);
-      HIP_TRY(c, hipMemcpyAsync(host_grads, c->gacc[a], c->lay.total * 4, hipMemcpyDeviceToHost, c->xs));
+      L2L_TRY(drain_copy(c, host_grads, c->gacc[a], 0, c->lay.total));
       HIP_TRY(c, hipEventRecord(c->gacc_landed[a], c->xs));
       L2L_TRY(fill_zero_copy_stream(c, c->gacc[a], c->lay.total * 4));   // "erased from the device" (Section 2.1)
-      copy_end(c, mark, (double)c->lay.total * 4);
+      copy_end(c, mark, drain_bytes(c, c->lay.total));
       HIP_TRY(c, hipEventRecord(c->gacc_drained[a], c->xs));
       c->gacc_state[a] = 2;
       return L2L_OK;
@@ -1189,10 +1222,10 @@ int l2l_embed_grad_drain(l2l_ctx* c, void* host_grads) {
   if (c->egacc_part_next != 0) return fail(c, L2L_E_STATE, "l2l_embed_grad_drain: a drain in pieces is under way");
   HIP_TRY(c, hipStreamWaitEvent(c->xs, c->egacc_ready, 0));
   const CopyMark mark = copy_begin(c);
-  HIP_TRY(c, hipMemcpyAsync(host_grads, c->egacc, c->lay.etotal * 4, hipMemcpyDeviceToHost, c->xs));
+  L2L_TRY(drain_copy(c, host_grads, c->egacc, 0, c->lay.etotal));
   HIP_TRY(c, hipEventRecord(c->egacc_landed, c->xs));
   L2L_TRY(fill_zero_copy_stream(c, c->egacc, c->lay.etotal * 4));
-  copy_end(c, mark, (double)c->lay.etotal * 4);
+  copy_end(c, mark, drain_bytes(c, c->lay.etotal));
   HIP_TRY(c, hipEventRecord(c->egacc_drained, c->xs));
   c->egacc_state = 2;
   return L2L_OK;
@@ -1205,19 +1238,20 @@ int l2l_embed_grad_drain_part(l2l_ctx* c, void* host_grads, long long first, lon
   if (first != c->egacc_part_next || count <= 0 || first + count > c->lay.etotal)
     return fail(c, L2L_E_ARG, "l2l_embed_grad_drain_part: piece %lld..%lld, expected one starting at %lld within %lld elements", first,
                 first + count, c->egacc_part_next, c->lay.etotal);
+  if (c->drain_dtype != L2L_F32 && first % 4) return fail(c, L2L_E_ARG, "l2l_embed_grad_drain_part: 16-bit drains take pieces that start at multiples of 4 elements");
   if (first == 0) HIP_TRY(c, hipStreamWaitEvent(c->xs, c->egacc_ready, 0));
   const CopyMark mark = copy_begin(c);
-  HIP_TRY(c, hipMemcpyAsync((float*)host_grads + first, c->egacc + first, count * 4, hipMemcpyDeviceToHost, c->xs));
+  L2L_TRY(drain_copy(c, host_grads, c->egacc, first, count));
   c->egacc_part_next = first + count;
   if (c->egacc_part_next == c->lay.etotal) {   // the block is out: clear and release the accumulator
     HIP_TRY(c, hipEventRecord(c->egacc_landed, c->xs));
     L2L_TRY(fill_zero_copy_stream(c, c->egacc, c->lay.etotal * 4));
-    copy_end(c, mark, (double)count * 4);
+    copy_end(c, mark, drain_bytes(c, count));
     HIP_TRY(c, hipEventRecord(c->egacc_drained, c->xs));
     c->egacc_state = 2;
     c->egacc_part_next = 0;
   } else {
-    copy_end(c, mark, (double)count * 4);
+    copy_end(c, mark, drain_bytes(c, count));
   }
   return L2L_OK;
 }
@@ -1284,10 +1318,10 @@ int l2l_cls_grad_drain(l2l_ctx* c, void* host_grads) {
   if (c->cls_state != 1) return fail(c, L2L_E_STATE, "l2l_cls_grad_drain: no un-drained head gradients");
   HIP_TRY(c, hipStreamWaitEvent(c->xs, c->cls_ready, 0));
   const CopyMark mark = copy_begin(c);
-  HIP_TRY(c, hipMemcpyAsync(host_grads, c->cls_g, c->cls_total * 4, hipMemcpyDeviceToHost, c->xs));
+  L2L_TRY(drain_copy(c, host_grads, c->cls_g, 0, c->cls_total));
   HIP_TRY(c, hipEventRecord(c->cls_landed, c->xs));
   L2L_TRY(fill_zero_copy_stream(c, c->cls_g, c->cls_total * 4));
-  copy_end(c, mark, (double)c->cls_total * 4);
+  copy_end(c, mark, drain_bytes(c, c->cls_total));
   HIP_TRY(c, hipEventRecord(c->cls_drained, c->xs));
   c->cls_state = 2;
   return L2L_OK;

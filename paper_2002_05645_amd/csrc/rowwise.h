@@ -587,6 +587,19 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16* in, bf1
   }
 }
 
+// out[i] = in[i] rounded to the 16-bit format E, i < n (in: 16-byte aligned, out: 8-byte aligned)
+template <typename E>
+__global__ __launch_bounds__(256) void narrow_kernel(const float* in, E* out, long long n) {
+  const long long n4 = n / 4, stride = (long long)gridDim.x * 256;
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
+    const f32x4 v = *(const f32x4*)(in + 4 * i);
+    typedef __attribute__((ext_vector_type(4))) E e4;
+    const e4 o = {from_f32<E>(v.x), from_f32<E>(v.y), from_f32<E>(v.z), from_f32<E>(v.w)};
+    *(u32x2*)(out + 4 * i) = __builtin_bit_cast(u32x2, o);
+  }
+  for (long long i = n4 * 4 + (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) out[i] = from_f32<E>(in[i]);
+}
+
 // Sum of the K-split partial results of a GEMM: out[m, n] += sum_s part[s][m, n] (part: `splits` dense [rows, n]
 // fp32 matrices, n a multiple of 4; out: row stride ldo, 16-byte aligned rows).
 __global__ __launch_bounds__(256) void split_sum_kernel(const float* part, int splits, long long rows, int n, float* out,

@@ -61,7 +61,7 @@ class L2LTrainer:
                  ln_eps=1e-12, lr=1e-4, beta1=0.9, beta2=0.999, eps_a=1e-8, ubatch_group=0,
                  eps_threads=0, stash="device", device="cuda:0", eager=False, optimizer="adam", weight_decay=0.0,
                  copy_cus=0, run_ahead=2, loss_scale=None, dynamic_loss_scale=True, scale_growth_interval=1000,
-                 num_classes=0, tail_parts=8):
+                 num_classes=0, tail_parts=8, grad_dtype="fp32"):
         assert stash in ("device", "host")
         assert optimizer in ("adam", "lamb")
         self.optimizer = optimizer
@@ -121,6 +121,17 @@ class L2LTrainer:
             loss_scale = 2.0 ** 15 if dtype == "fp16" else 1.0
         self.scaler = LossScaler(loss_scale, scale_growth_interval, static=eager or not dynamic_loss_scale or loss_scale == 1.0)
         self.ctx.set_loss_scale(self.scaler.scale)
+        # Gradients accumulate in fp32 on the device; grad_dtype is the format in which they cross the host link
+        # (Section 2.3 sends 16-bit values): "fp32", or "bf16" / "fp16" = rounded on the device, half the drain
+        # traffic, widened into the EPS's fp32 gradient buffers before the optimizer reads them.
+        assert grad_dtype in ("fp32", "bf16", "fp16")
+        self.grad_dtype = grad_dtype
+        if grad_dtype != "fp32":
+            self.eps.enable_grad16()
+            self.ctx.set_drain_dtype(grad_dtype)
+        # plain Adam on unscaled gradients reads the 16-bit landing buffer directly; LAMB and the loss-scale check work
+        # on the fp32 gradient buffers, which are filled from it first
+        self._adam_from16 = grad_dtype != "fp32" and optimizer == "adam" and self.scaler.scale == 1.0 and self.scaler.static
         shape = (num_ubatches, ubatch, seq, hidden)
         n_stash = layers + 1 if stash == "device" else 2
         self.stash = [torch.empty(shape, dtype=tdt, device=self.device) for _ in range(n_stash)]
@@ -173,6 +184,8 @@ class L2LTrainer:
         return {"Wp": (self.H, self.H), "bp": (self.H,), "Wc": (self.H, self.num_classes), "bc": (self.num_classes,)}
 
     def cls_grads(self):
+        if self._adam_from16:
+            self.eps.grad_widen(1 + self.L, 1 + self.L, self.grad_dtype)
         return unpack(self.cls_layout, self.cls_shapes(), self.eps.grad(1 + self.L))
 
     def cls_master(self):
@@ -188,6 +201,8 @@ class L2LTrainer:
 
     def grads(self):
         """(embedding-block grads, per-layer grads) as dicts, from the EPS landing buffers."""
+        if self._adam_from16:                 # the optimizer read the 16-bit buffers; widen them for the caller
+            self.eps.grad_widen(0, self._last_block(), self.grad_dtype)
         ge = unpack(self.embed_layout, self.embed_shapes(), self.eps.grad(0))
         gl = [unpack(self.layer_layout, self.layer_shapes(), self.eps.grad(1 + l)) for l in range(self.L)]
         return ge, gl
@@ -198,6 +213,10 @@ class L2LTrainer:
         return e, ls
 
     # ---- one step -----------------------------------------------------------------------------------
+    def _land_ptr(self, block):
+        """where a block's drain writes: the fp32 gradient buffer, or the 16-bit landing buffer"""
+        return self.eps.grad_ptr(block) if self.grad_dtype == "fp32" else self.eps.grad16_ptr(block)
+
     def _stash_slot(self, l):
         return self.stash[l] if self.stash_mode == "device" else self.stash[l % 2]
 
@@ -228,7 +247,7 @@ class L2LTrainer:
         if self.num_classes:                 # labels: int32 [U, ub], one class per sequence
             c.cls_stage(e.ship_ptr(1 + L), self.num_classes)
             c.cls_head_loss(self._stash_slot(L), labels, self.dy, self.loss_dev)
-            c.cls_grad_drain(e.grad_ptr(1 + L))
+            c.cls_grad_drain(self._land_ptr(1 + L))
             self._after_drain(1 + L)
         else:
             c.head_loss(self._stash_slot(L), labels, self.dy, self.loss_dev)
@@ -243,20 +262,26 @@ class L2LTrainer:
             self._bwd_done[l].record(self.compute)
             if host_mode:
                 self.stash_free[l % 2].record(self.compute)
-            c.grad_drain(l, e.grad_ptr(1 + l))
+            c.grad_drain(l, self._land_ptr(1 + l))
             self._after_drain(1 + l)
         c.embed_bwd(tokens, self.dy)
         if self._parts:
             for k, (first, count) in enumerate(self._parts):
-                c.embed_grad_drain_part(e.grad_ptr(0), first, count)
+                c.embed_grad_drain_part(self._land_ptr(0), first, count)
                 self._part_landed[k].record(self.copy)
                 self._part_done[k].clear()
                 self._work.put(("part", k, self.t + 1))
         else:
-            c.embed_grad_drain(e.grad_ptr(0))
+            c.embed_grad_drain(self._land_ptr(0))
             self._after_drain(0)
 
     def _eps_update(self, first, last, t, unscale=True):
+        if self._adam_from16:
+            for b in range(first, last + 1):
+                self.eps.adam_step_range16(b, 0, self.eps.elems[b], t, self.grad_dtype, **self.hp)
+            return
+        if self.grad_dtype != "fp32" and unscale:       # (the tail loop has widened already, before its overflow check)
+            self.eps.grad_widen(first, last, self.grad_dtype)
         if unscale and self.scaler.scale != 1.0:
             if self.eps.grad_unscale(first, last, 1.0 / self.scaler.scale):
                 raise FloatingPointError(f"gradient overflow in blocks {first}..{last} at loss scale {self.scaler.scale}")
@@ -293,7 +318,10 @@ class L2LTrainer:
                     _, k, t = item
                     first, count = self._parts[k]
                     self._part_landed[k].synchronize()
-                    self.eps.adam_step_range(0, first, count, t, **self.hp)
+                    if self._adam_from16:
+                        self.eps.adam_step_range16(0, first, count, t, self.grad_dtype, **self.hp)
+                    else:
+                        self.eps.adam_step_range(0, first, count, t, **self.hp)
                 else:
                     block, t = item
                     self._landed[block].synchronize()
@@ -346,6 +374,8 @@ class L2LTrainer:
                 raise self._worker_error
             self.t += 1
             return
+        if self.grad_dtype != "fp32" and not self._adam_from16:
+            self.eps.grad_widen(0, self._last_block(), self.grad_dtype)
         if self.scaler.scale != 1.0:
             overflow = self.eps.grad_unscale(0, self._last_block(), 1.0 / self.scaler.scale)
             if self.scaler.static and overflow:

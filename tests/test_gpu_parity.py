@@ -548,6 +548,43 @@ def test_step_bert_base_bf16_full():
     assert abs(loss_ref - (math.log(w.vocab) + w.hidden * 0.02 ** 2 / 2)) < 0.03
 
 
+@pytest.mark.parametrize("compute,grad_dtype,eager", [("fp32", "bf16", False), ("fp32", "fp16", True), ("bf16", "bf16", True), ("fp16", "fp16", False)])
+def test_step_with_16_bit_gradient_drains(compute, grad_dtype, eager):
+    # l2l_set_drain_dtype: the fp32 accumulators are rounded on the device, cross the host link in 16 bits and are
+    # widened on the host; the optimizer then sees the rounded gradients
+    w = S.WORKLOADS[0].scaled(dtype=compute)
+    kw = dict(loss_scale=256.0) if compute == "fp16" else {}
+    tr = L2LTrainer(layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, vocab=w.vocab, ubatch=w.ubatch,
+                    num_ubatches=w.num_ubatches, dtype=compute, lr=1e-3, eager=eager, eps_threads=4, grad_dtype=grad_dtype, **kw)
+    try:
+        emb, layers = S.embed_params(w), [S.layer_params(w, l) for l in range(w.layers)]
+        tr.load_params(emb, layers)
+        tok, lab = S.tokens_and_labels(w)
+        loss = tr.step(torch.from_numpy(tok).cuda(), torch.from_numpy(lab).cuda())
+        e64 = {k: rounded(v, compute).astype(np.float64) for k, v in emb.items()}
+        l64 = [{k: rounded(v, compute).astype(np.float64) for k, v in l.items()} for l in layers]
+        loss_ref, gemb, gl = O.run_l2l(e64, l64, tok, lab, w.heads, 1e-12)
+        assert abs(loss - loss_ref) / abs(loss_ref) < (1e-4 if compute == "fp32" else 2e-2)
+        ge, gls = tr.grads()
+        scale = tr.scaler.scale
+        for name, got, ref in [("emb", ge, gemb)] + [(f"layer{i}", g, r) for i, (g, r) in enumerate(zip(gls, gl))]:
+            for k in ref:
+                # what landed (before the host's unscaling) is representable in the 16-bit format
+                raw = (got[k].astype(np.float64) * scale).astype(np.float32)
+                assert np.array_equal(rounded(raw, grad_dtype).astype(np.float32), raw), (name, k)
+                if np.abs(ref[k]).max() > 0:
+                    tol = 4e-3 if compute == "fp32" else TOL[compute]      # one 16-bit rounding on top of the fp32 path
+                    assert O.rel_l2(got[k], ref[k]) < tol, (name, k, O.rel_l2(got[k], ref[k]))
+        # and the block landed in 16 bits: the landing buffer holds the same values
+        if grad_dtype == "bf16":
+            landed = (tr.eps.grad16(1).astype(np.uint32) << 16).view(np.float32)
+        else:
+            landed = tr.eps.grad16(1).view(np.float16).astype(np.float32)
+        assert np.array_equal(landed.astype(np.float64) / scale, tr.eps.grad(1).astype(np.float64))
+    finally:
+        tr.close()
+
+
 def test_embedding_block_staged_and_drained_in_pieces():
     # l2l_embed_stage_part / l2l_embed_grad_drain_part: same bytes as the one-piece calls, pieces in order only
     w = S.WORKLOADS[0]

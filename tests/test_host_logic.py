@@ -98,6 +98,69 @@ def test_eps_bf16_ship_is_round_to_nearest_even_bit_exact():
     e.close()
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
+def test_eps_widens_16_bit_gradients(dtype):
+    # gradients that crossed the host link in 16 bits are widened into the fp32 buffers the optimizer reads
+    n = 100003
+    rng = np.random.default_rng(5)
+    e = P.EPS([9, n], dtype, 3)
+    with pytest.raises(P.L2LError):
+        e.grad_widen(0, 1, dtype)                      # landing buffers not enabled yet
+    e.enable_grad16()
+    e.enable_grad16()                                  # idempotent
+    vals = (rng.normal(size=n) * 10.0 ** rng.integers(-8, 4, size=n)).astype(np.float32)
+    if dtype == "bf16":
+        bits = O.bf16_bits(vals)
+        want = (bits.astype(np.uint32) << 16).view(np.float32)
+    else:
+        vals[:7] = [np.inf, -np.inf, 65504.0, 6e-8, -0.0, 1e-9, 70000.0]      # inf, max, subnormal, zero, underflow, overflow
+        with np.errstate(over="ignore"):
+            h = vals.astype(np.float16)
+        bits, want = h.view(np.uint16), h.astype(np.float32)
+    e.grad16(1)[:] = bits
+    e.grad(1)[:] = -1.0
+    e.grad_widen_range(1, 10, 50000, dtype)
+    assert np.array_equal(e.grad(1)[10:50010], want[10:50010]) and np.all(e.grad(1)[:10] == -1.0) and np.all(e.grad(1)[50010:] == -1.0)
+    e.grad_widen(0, 1, dtype)
+    assert np.array_equal(e.grad(1), want) and np.all(e.grad(0) == 0)
+    for bad in [(1, -1, 5), (1, 0, 0), (1, n - 3, 4), (2, 0, 1)]:
+        with pytest.raises(P.L2LError):
+            e.grad_widen_range(bad[0], bad[1], bad[2], dtype)
+    with pytest.raises(P.L2LError):
+        e.grad_widen(0, 1, "fp32")
+    e.close()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
+def test_eps_adam_from_16_bit_gradients_equals_widen_then_adam(dtype):
+    n = 70001
+    rng = np.random.default_rng(6)
+    a, b = P.EPS([n], "bf16", 3), P.EPS([n], "bf16", 2)
+    for e in (a, b):
+        e.enable_grad16()
+        e.master(0)[:] = np.linspace(-1, 1, n, dtype=np.float32)
+    for t in range(1, 4):
+        g = (rng.normal(size=n) * 1e-2).astype(np.float32)
+        bits = O.bf16_bits(g) if dtype == "bf16" else g.astype(np.float16).view(np.uint16)
+        a.grad16(0)[:] = bits
+        b.grad16(0)[:] = bits
+        b.grad(0)[:] = 7.0                                   # the fused step must not look at the fp32 buffer
+        a.grad_widen(0, 0, dtype)
+        a.adam_step(0, 0, t, lr=1e-3)
+        b.adam_step_range16(0, 0, 30000, t, dtype, lr=1e-3)
+        b.adam_step_range16(0, 30000, n - 30000, t, dtype, lr=1e-3)
+        assert np.array_equal(a.master(0), b.master(0)) and np.array_equal(a.ship(0), b.ship(0))
+        assert np.array_equal(a.moment(0, 0), b.moment(0, 0)) and np.array_equal(a.moment(0, 1), b.moment(0, 1))
+        assert np.all(b.grad(0) == 7.0)
+    with pytest.raises(P.L2LError):
+        b.adam_step_range16(0, 0, n, 1, "fp32")
+    c = P.EPS([n], "bf16", 1)
+    with pytest.raises(P.L2LError):
+        c.adam_step_range16(0, 0, n, 1, dtype)               # no 16-bit landing buffers
+    for e in (a, b, c):
+        e.close()
+
+
 def test_eps_adam_in_pieces_equals_the_whole_block():
     # the ranged step (the embedding block is updated piece by piece as its gradients land) is the same arithmetic
     n = 200000
