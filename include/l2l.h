@@ -136,7 +136,8 @@ int l2l_layer_fwd(l2l_ctx*, int layer, int slot, const void* x_stash, void* y_ou
 int l2l_layer_bwd(l2l_ctx*, int layer, int slot, const void* x_stash, void* dy_dx);
 
 /* Grad drain: asynchronous device->host copy, on copy_stream, of the gradients accumulated by the
-   last l2l_layer_bwd(layer) (l2l_layer_grad_bytes bytes, fp32, packed order) into host memory
+   last l2l_layer_bwd(layer) (l2l_layer_grad_bytes bytes, fp32, packed order; half of that, rounded to the
+   16-bit format, after l2l_set_drain_dtype) into host memory
    (pinned to overlap), ordered after that backward.  The accumulator is reusable once the copy
    lands; two accumulators alternate so the next layer's backward need not wait. */
 int l2l_grad_drain(l2l_ctx*, int layer, void* host_grads);
@@ -205,8 +206,9 @@ int l2l_embed_grad_drain(l2l_ctx*, void* host_grads);
 int l2l_embed_drain_wait(l2l_ctx*);
 /* The same drain in pieces: elements [first, first + count) of the packed gradients go to host_grads + first
    (host_grads points at element 0 of the landing buffer).  Pieces are issued in ascending order without gaps; the
-   piece that ends the block also clears and releases the accumulator.  L2L_E_ARG for a piece out of order or
-   outside the block, L2L_E_STATE without un-drained gradients. */
+   piece that ends the block also clears and releases the accumulator.  With 16-bit drains pieces start at
+   multiples of 4 elements.  L2L_E_ARG for a piece out of order, misaligned or outside the block, L2L_E_STATE
+   without un-drained gradients. */
 int l2l_embed_grad_drain_part(l2l_ctx*, void* host_grads, long long first, long long count);
 
 /* ---- profiling: HIP-event timing of kernel classes on the compute stream ----------------------
