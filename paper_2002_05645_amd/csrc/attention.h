@@ -1,6 +1,7 @@
 // Fused attention for the 16-bit paths (element type E = bf16 or fp16), head width d = 64, sequence length a
 // multiple of 32 up to 128: scores, softmax and context (forward) and all five attention gradients (backward)
-// of one (sequence, head) pair in one workgroup, without the S x S matrices ever leaving the chip.
+// of one (sequence, head) pair in one workgroup, without the S x S matrices ever leaving the chip.  Longer
+// sequences (multiples of 128) go through the chunked kernels at the end of this file.
 //
 // Everything is computed "transposed": the MFMA tiles are S^T = K Q^T (keys along the accumulator's
 // register axis, queries along its lane axis), so that a softmax row lives in the registers of one
@@ -328,6 +329,230 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(const E* qkv, const E* do
       store_T1(dv, out + 2 * H, ld, lane, 1.0f);
       store_T1(dk, out + H, ld, lane, alpha);
     }
+  }
+}
+
+// ---- long sequences: S a multiple of 128 beyond SMAX ----------------------------------------------------
+// A workgroup owns 128 queries (forward, dQ) or 128 keys (dK, dV) of one (sequence, head) pair and walks the other
+// index in chunks of 128 rows that pass through LDS.  The forward pass keeps a running row maximum and row sum and
+// rescales its context accumulators when the maximum moves; it leaves lse = max + log(sum) per query row, from which
+// the backward kernels get P = exp(alpha S - lse) without a reduction.  rowsum(P dP) is taken as rowsum(dO O)
+// (the same number: sum_k P_k dO . V_k = dO . O), computed by the dQ kernel from the stored context and passed on.
+constexpr int CH = 128;
+constexpr int LONG_DKV_LDS = 6 * CH * 128;   // K, V | Q, dO | P, dS of one half of the keys: 96 KB
+
+template <typename E>
+__global__ __launch_bounds__(256) void attn_fwd_long_kernel(const E* qkv, E* out, float* lse, int S, int H, int A, float alpha) {
+  __shared__ __attribute__((aligned(1024))) char lds[2 * CH * 128];
+  char* Ks = lds;
+  char* Vs = lds + CH * 128;
+  const int nch = S / CH;
+  const int qb = blockIdx.x % nch, bh = blockIdx.x / nch, b = bh / A, h = bh % A;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const long long ld = 3LL * H;
+  const E* base = qkv + (long long)b * S * ld + h * 64;
+  const uint32_t bytes = (uint32_t)(((long long)(CH - 1) * ld + 64) * 2);
+  const int q = qb * CH + wave * 32 + (lane & 31);
+  bf16x8 qf[4];
+  {
+    const E* qrow = base + (long long)q * ld + (lane >> 5) * 8;
+#pragma unroll
+    for (int st = 0; st < 4; ++st) qf[st] = *(const bf16x8*)(qrow + st * 16);
+  }
+  float m = -INFINITY, sum = 0.f;
+  f32x16 o[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) o[t] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int kc = 0; kc < nch; ++kc) {
+    if (kc) __syncthreads();   // every wave has left the previous chunk
+    load_rows(make_rsrc(base + H + (long long)kc * CH * ld, bytes), (uint32_t)ld, CH, Ks, wave, 4, lane);
+    load_rows(make_rsrc(base + 2 * H + (long long)kc * CH * ld, bytes), (uint32_t)ld, CH, Vs, wave, 4, lane);
+    wait_vm0();
+    __syncthreads();
+    f32x16 st_[CH / 32];
+    float cm = m;
+#pragma unroll
+    for (int kb = 0; kb < CH / 32; ++kb) {
+      f32x16 a = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s4 = 0; s4 < 4; ++s4) a = mfma_32x32x16<E>(frag_rows(Ks, kb * 32 + (lane & 31), s4, lane), qf[s4], a);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { a[r] *= alpha; cm = fmaxf(cm, a[r]); }
+      st_[kb] = a;
+    }
+    cm = xor32_max(cm);
+    const float rescale = __expf(m - cm);   // 0 on the first chunk
+    m = cm;
+    float cs = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < CH / 32; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { st_[kb][r] = __expf(st_[kb][r] - m); cs += st_[kb][r]; }
+    sum = sum * rescale + xor32_sum(cs);
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[t][r] *= rescale;
+#pragma unroll
+    for (int kb = 0; kb < CH / 32; ++kb)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const bf16x8 pf = pack8<E>(st_[kb], 8 * s2);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) o[t] = mfma_32x32x16<E>(frag_keys_T(Vs, kb, s2, t, lane), pf, o[t]);
+      }
+  }
+  store_T(o, out + ((long long)b * S + qb * CH + wave * 32) * H + h * 64, H, lane, 1.0f / sum);
+  if (lse && lane < 32) lse[(long long)bh * S + q] = m + __logf(sum);
+}
+
+// dQ = alpha dS K for 128 queries per workgroup; also leaves dsum[row] = rowsum(dO O) for the dK / dV kernel.
+// ctx: [rows, H], the forward pass's output.
+template <typename E>
+__global__ __launch_bounds__(256) void attn_bwd_dq_long_kernel(const E* qkv, const E* dout, const E* ctx, const float* lse,
+                                                               float* dsum, E* dqkv, int S, int H, int A, float alpha) {
+  __shared__ __attribute__((aligned(1024))) char lds[2 * CH * 128];
+  char* Ks = lds;
+  char* Vs = lds + CH * 128;
+  const int nch = S / CH;
+  const int qb = blockIdx.x % nch, bh = blockIdx.x / nch, b = bh / A, h = bh % A;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const long long ld = 3LL * H;
+  const E* base = qkv + (long long)b * S * ld + h * 64;
+  const uint32_t bytes = (uint32_t)(((long long)(CH - 1) * ld + 64) * 2);
+  const int q = qb * CH + wave * 32 + (lane & 31);
+  bf16x8 qf[4], of[4];
+  float D = 0.f;
+  {
+    const E* qrow = base + (long long)q * ld + (lane >> 5) * 8;
+    const long long orow = ((long long)b * S + q) * H + h * 64 + (lane >> 5) * 8;
+#pragma unroll
+    for (int st = 0; st < 4; ++st) {
+      qf[st] = *(const bf16x8*)(qrow + st * 16);
+      of[st] = *(const bf16x8*)(dout + orow + st * 16);
+      const typename Vec<E>::x8 gv = __builtin_bit_cast(typename Vec<E>::x8, of[st]);
+      const typename Vec<E>::x8 cv = *(const typename Vec<E>::x8*)(ctx + orow + st * 16);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) D += to_f32(gv[i]) * to_f32(cv[i]);
+    }
+  }
+  D = xor32_sum(D);
+  const long long srow = (long long)bh * S + q;
+  const float L = lse[srow];
+  if (lane < 32) dsum[srow] = D;
+  f32x16 dq[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) dq[t] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int kc = 0; kc < nch; ++kc) {
+    if (kc) __syncthreads();
+    load_rows(make_rsrc(base + H + (long long)kc * CH * ld, bytes), (uint32_t)ld, CH, Ks, wave, 4, lane);
+    load_rows(make_rsrc(base + 2 * H + (long long)kc * CH * ld, bytes), (uint32_t)ld, CH, Vs, wave, 4, lane);
+    wait_vm0();
+    __syncthreads();
+#pragma unroll
+    for (int kb = 0; kb < CH / 32; ++kb) {
+      f32x16 a = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      f32x16 d = a;
+      const int krow = kb * 32 + (lane & 31);
+#pragma unroll
+      for (int s4 = 0; s4 < 4; ++s4) {
+        a = mfma_32x32x16<E>(frag_rows(Ks, krow, s4, lane), qf[s4], a);
+        d = mfma_32x32x16<E>(frag_rows(Vs, krow, s4, lane), of[s4], d);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) d[r] = __expf(a[r] * alpha - L) * (d[r] - D);   // dP -> dS
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const bf16x8 df = pack8<E>(d, 8 * s2);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) dq[t] = mfma_32x32x16<E>(frag_keys_T(Ks, kb, s2, t, lane), df, dq[t]);
+      }
+    }
+  }
+  store_T(dq, dqkv + ((long long)b * S + qb * CH + wave * 32) * ld + h * 64, ld, lane, alpha);
+}
+
+// dV = P^T dO and dK = alpha dS^T Q for 128 keys per workgroup, over all queries in chunks of 128.  Per chunk: wave w
+// recomputes P and dS of queries 32 w .. against the workgroup's keys, one half of the keys (64) at a time; the waves
+// park that half in LDS and then wave w takes key block w % 2 of the half and columns 32 (w / 2) .. of the head.
+template <typename E>
+__global__ __launch_bounds__(256) void attn_bwd_dkv_long_kernel(const E* qkv, const E* dout, const float* lse, const float* dsum,
+                                                                E* dqkv, int S, int H, int A, float alpha) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  char* Ks = lds;
+  char* Vs = lds + CH * 128;
+  char* Qs = lds + 2 * CH * 128;
+  char* Os = lds + 3 * CH * 128;
+  char* Ps = lds + 4 * CH * 128;
+  char* Ds = lds + 5 * CH * 128;
+  const int nch = S / CH;
+  const int kc = blockIdx.x % nch, bh = blockIdx.x / nch, b = bh / A, h = bh % A;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const long long ld = 3LL * H;
+  const E* base = qkv + (long long)b * S * ld + h * 64;
+  const uint32_t bytes = (uint32_t)(((long long)(CH - 1) * ld + 64) * 2);
+  const E* dob = dout + (long long)b * S * H + h * 64;
+  const uint32_t obytes = (uint32_t)(((long long)(CH - 1) * H + 64) * 2);
+  load_rows(make_rsrc(base + H + (long long)kc * CH * ld, bytes), (uint32_t)ld, CH, Ks, wave, 4, lane);
+  load_rows(make_rsrc(base + 2 * H + (long long)kc * CH * ld, bytes), (uint32_t)ld, CH, Vs, wave, 4, lane);
+  const int qrow = wave * 32 + (lane & 31);
+  const int kb2 = wave & 1, t = wave >> 1;
+  f32x16 dv[2], dk[2];
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    dv[half] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    dk[half] = dv[half];
+  }
+  for (int qc = 0; qc < nch; ++qc) {
+    if (qc) __syncthreads();   // the previous chunk's products over queries are done with Q, dO, P and dS
+    load_rows(make_rsrc(base + (long long)qc * CH * ld, bytes), (uint32_t)ld, CH, Qs, wave, 4, lane);
+    load_rows(make_rsrc(dob + (long long)qc * CH * H, obytes), (uint32_t)H, CH, Os, wave, 4, lane);
+    const long long srow = (long long)bh * S + qc * CH + qrow;
+    const float L = lse[srow], D = dsum[srow];
+    wait_vm0();
+    __syncthreads();
+    bf16x8 qf[4], of[4];
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) { qf[s4] = frag_rows(Qs, qrow, s4, lane); of[s4] = frag_rows(Os, qrow, s4, lane); }
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      f32x16 p_[2], ds_[2];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        f32x16 a = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        f32x16 d = a;
+        const int krow = (2 * half + j) * 32 + (lane & 31);
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4) {
+          a = mfma_32x32x16<E>(frag_rows(Ks, krow, s4, lane), qf[s4], a);
+          d = mfma_32x32x16<E>(frag_rows(Vs, krow, s4, lane), of[s4], d);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float p = __expf(a[r] * alpha - L);
+          p_[j][r] = p;
+          ds_[j][r] = p * (d[r] - D);
+        }
+      }
+      if (half) __syncthreads();   // the first half's P and dS have been read
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        pq_store<E>(Ps, p_[j], qrow, j, lane);
+        pq_store<E>(Ds, ds_[j], qrow, j, lane);
+      }
+      __syncthreads();
+      for (int s = 0; s < CH / 16; ++s) {
+        const bf16x8 pf = pq_frag(Ps, s, kb2, lane), df = pq_frag(Ds, s, kb2, lane);
+        dv[half] = mfma_32x32x16<E>(frag_queries_T(Os, s, t, lane), pf, dv[half]);
+        dk[half] = mfma_32x32x16<E>(frag_queries_T(Qs, s, t, lane), df, dk[half]);
+      }
+    }
+  }
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    E* out = dqkv + ((long long)b * S + kc * CH + (2 * half + kb2) * 32) * ld + h * 64 + t * 32;
+    store_T1(dv[half], out + 2 * H, ld, lane, 1.0f);
+    store_T1(dk[half], out + H, ld, lane, alpha);
   }
 }
 

@@ -157,6 +157,7 @@ struct l2l_ctx {
   // workspace (group-sized)
   void *qkv, *p, *c, *r1, *y1, *u1, *ga, *r2, *dr2, *du1, *dy1, *dr1, *dc, *dp, *dqkv, *ytmp;
   float *mean1, *rstd1, *mean2, *rstd2;
+  float *lse = nullptr, *dsum = nullptr;   // chunked attention: row statistics between its kernels
   void* wt[2] = {nullptr, nullptr};  // bf16 mode: per slot, [out, in] copies of the four weight matrices (packed offsets)
 
   // embedding / head
@@ -495,12 +496,17 @@ int fill_zero_copy_stream(l2l_ctx* c, void* p, size_t bytes) {
   return L2L_OK;
 }
 
-// the fused attention kernels take the 16-bit formats, head width 64 and sequences of 32, 64, 96 or 128 tokens
+// the fused attention kernels take the 16-bit formats, head width 64 and sequences of 32, 64, 96 or 128 tokens ...
 template <typename T>
 using attn_elem = typename std::conditional<std::is_same<T, fp16>::value, fp16, bf16>::type;   // (fp32 never gets there)
 bool fused_attention_ok(const l2l_ctx* c) {
   const l2l_config& f = c->cfg;
   return is16(f.dtype) && f.hidden / f.heads == 64 && f.seq % 32 == 0 && f.seq <= attn::SMAX && !c->no_fused_attention;
+}
+// ... and the chunked ones longer sequences that are a multiple of 128
+bool fused_attention_long_ok(const l2l_ctx* c) {
+  const l2l_config& f = c->cfg;
+  return is16(f.dtype) && f.hidden / f.heads == 64 && f.seq % attn::CH == 0 && f.seq > attn::SMAX && !c->no_fused_attention;
 }
 
 int fill_zero(l2l_ctx* c, void* p, size_t bytes) {
@@ -563,6 +569,14 @@ int layer_forward_group(l2l_ctx* c, int slot, const void* x, void* y, int ng, bo
       using E = attn_elem<T>;
       hipLaunchKernelGGL(attn::attn_fwd_kernel<E>, dim3(nseq * A), dim3(256), 0, c->cs, (const E*)qkv, (E*)c->c, S, H, A,
                          1.0f / sqrtf((float)d));
+    }));
+  } else if (fused_attention_long_ok(c)) {
+    const double fl = 4.0 * S * S * d * nseq * A;
+    L2L_TRY(timed(c, L2L_PROF_ATTN, fl, (3.0 + 1.0) * M * H * sizeof(T), [&] {
+      using E = attn_elem<T>;
+      // (the row statistics are for the backward kernels: only the recompute pass keeps them)
+      hipLaunchKernelGGL(attn::attn_fwd_long_kernel<E>, dim3(nseq * A * (S / attn::CH)), dim3(256), 0, c->cs, (const E*)qkv,
+                         (E*)c->c, keep ? c->lse : nullptr, S, H, A, 1.0f / sqrtf((float)d));
     }));
   } else
   {
@@ -673,6 +687,17 @@ int layer_backward_group(l2l_ctx* c, const void* params, const void* x, void* dy
       using E = attn_elem<T>;
       hipLaunchKernelGGL(attn::attn_bwd_kernel<E>, dim3(nseq * A), dim3(256), attn::BWD_LDS, c->cs, (const E*)qkv,
                          (const E*)c->dc, (E*)dqkv, S, H, A, alpha);
+    }));
+  } else if (fused_attention_long_ok(c)) {
+    using E = attn_elem<T>;
+    const dim3 grid(nseq * A * (S / attn::CH));
+    L2L_TRY(timed(c, L2L_PROF_ATTN, 4.0 * S * S * d * nseq * A, (3.0 + 1.0 + 1.0 + 1.0) * M * H * sizeof(T), [&] {
+      hipLaunchKernelGGL(attn::attn_bwd_dq_long_kernel<E>, grid, dim3(256), 0, c->cs, (const E*)qkv, (const E*)c->dc,
+                         (const E*)c->c, c->lse, c->dsum, (E*)dqkv, S, H, A, alpha);
+    }));
+    L2L_TRY(timed(c, L2L_PROF_ATTN, 6.0 * S * S * d * nseq * A, (3.0 + 1.0 + 2.0) * M * H * sizeof(T), [&] {
+      hipLaunchKernelGGL(attn::attn_bwd_dkv_long_kernel<E>, grid, dim3(256), attn::LONG_DKV_LDS, c->cs, (const E*)qkv,
+                         (const E*)c->dc, c->lse, c->dsum, (E*)dqkv, S, H, A, alpha);
     }));
   } else
   {
@@ -910,11 +935,15 @@ int l2l_create(const l2l_config* cfg, void* compute_stream, void* copy_stream, l
   if (const char* e = getenv("L2L_NO_FUSED_ATTENTION")) c->no_fused_attention = atoi(e) != 0;
   (void)hipFuncSetAttribute((const void*)attn::attn_bwd_kernel<bf16>, hipFuncAttributeMaxDynamicSharedMemorySize, attn::BWD_LDS);
   (void)hipFuncSetAttribute((const void*)attn::attn_bwd_kernel<fp16>, hipFuncAttributeMaxDynamicSharedMemorySize, attn::BWD_LDS);
+  (void)hipFuncSetAttribute((const void*)attn::attn_bwd_dkv_long_kernel<bf16>, hipFuncAttributeMaxDynamicSharedMemorySize, attn::LONG_DKV_LDS);
+  (void)hipFuncSetAttribute((const void*)attn::attn_bwd_dkv_long_kernel<fp16>, hipFuncAttributeMaxDynamicSharedMemorySize, attn::LONG_DKV_LDS);
   *out = c;  // from here on the caller can read l2l_last_error and must l2l_destroy
 
   const size_t es = esize(cfg->dtype);
   const long long H = cfg->hidden, F = cfg->ffn, S = cfg->seq, A = cfg->heads, Mg = c->Mg;
-  const long long pe = (long long)g * cfg->ubatch * A * S * S;
+  // the attention matrices P and dP exist in memory only on the batched-GEMM path
+  const bool fused = fused_attention_ok(c) || fused_attention_long_ok(c);
+  const long long pe = fused ? 0 : (long long)g * cfg->ubatch * A * S * S;
   for (int i = 0; i < 2; ++i) {
     L2L_TRY(dev_alloc(c, &c->slot[i], c->lay.total * es));
     L2L_TRY(dev_alloc(c, (void**)&c->gacc[i], c->lay.total * 4));
@@ -955,6 +984,10 @@ int l2l_create(const l2l_config* cfg, void* compute_stream, void* copy_stream, l
   }
   float** stats[] = {&c->mean1, &c->rstd1, &c->mean2, &c->rstd2};
   for (auto s : stats) L2L_TRY(dev_alloc(c, (void**)s, Mg * 4));
+  if (fused_attention_long_ok(c)) {   // per (sequence, head, query): log-sum-exp of the scores, rowsum(dO O)
+    L2L_TRY(dev_alloc(c, (void**)&c->lse, Mg * A * 4));
+    L2L_TRY(dev_alloc(c, (void**)&c->dsum, Mg * A * 4));
+  }
 
   if (cfg->vocab > 0) {
     const long long V = cfg->vocab, UT = c->T * cfg->num_ubatches;

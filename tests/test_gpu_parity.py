@@ -168,7 +168,7 @@ def test_layernorm(ctx, dtype, rows, n):
 
 
 # ------------------------------------------------------------------------------------- one layer, all micro-batches
-def _layer_case(w: S.Workload, group=0, x_scale=1.0, check_fwd_only=False):
+def _layer_case(w: S.Workload, group=0, x_scale=1.0, check_fwd_only=False, dy_scale=1.0):
     dtype = w.dtype
     cfg = P.make_config(w.hidden, w.heads, w.ffn, w.seq, w.ubatch, w.num_ubatches, dtype, 1e-12, 0, group)
     c = P.Context(cfg)
@@ -180,7 +180,7 @@ def _layer_case(w: S.Workload, group=0, x_scale=1.0, check_fwd_only=False):
         host = pinned(O.bf16_bits(flat).view(np.int16) if dtype == "bf16" else O.fp16_bits(flat).view(np.int16) if dtype == "fp16" else flat)
         pr = {k: rounded(v, dtype) for k, v in p32.items()}
         X = S.activations(w) * x_scale
-        dY = S.output_grads(w)
+        dY = S.output_grads(w) * dy_scale
         Xd, dYd = to_dev(X, dtype), to_dev(dY, dtype)
         Yd = torch.empty_like(Xd)
         c.param_stage(0, host, 0)
@@ -265,6 +265,20 @@ def test_layer_fused_attention_sequence_lengths(seq, dtype):
     # head width 64 and S a multiple of 32 up to 128: the fused attention kernels (forward and backward)
     w = S.Workload("fused", 1, 128, 2, 256, seq, 50, 3, 2, dtype, 1.0, 79 + seq)
     _assert_errs(_layer_case(w), TOL[dtype])
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
+@pytest.mark.parametrize("seq", [256, 384, 512])
+def test_layer_chunked_attention_long_sequences(seq, dtype):
+    # head width 64 and S a multiple of 128 beyond 128: the chunked attention kernels (running softmax statistics in
+    # the forward pass; dQ and dK / dV kernels that rebuild P from the stored log-sum-exp in the backward pass)
+    w = S.Workload("long", 1, 128, 2, 256, seq, 50, 2, 3, dtype, 1.0, 300 + seq)
+    # fp16: with attention weights near 1 / S the score gradients of the synthetic dY fall into fp16's subnormals on
+    # any path (the batched-GEMM one included), which is what the loss scale of Section 2.3's FP16 mode is for: the
+    # incoming gradient carries a factor 256 here, as it would from a scaled loss
+    kw = dict(dy_scale=256.0) if dtype == "fp16" else {}
+    _assert_errs(_layer_case(w, **kw), TOL[dtype])
+    _assert_errs(_layer_case(w, group=2, **kw), TOL[dtype])     # ragged last group
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "fp16"])
