@@ -821,8 +821,11 @@ int embed_bwd_t(l2l_ctx* c, const int32_t* tokens, const void* dy) {
   const int H = c->cfg.hidden, S = c->cfg.seq;
   L2L_TRY(timed(c, L2L_PROF_ROWWISE, 0, 0, [&] {
     const unsigned nseq = (unsigned)(rows / S);
-    hipLaunchKernelGGL(embed_bwd_kernel<T>, dim3((unsigned)S * ((nseq + EMB_SEQS - 1) / EMB_SEQS)), dim3(256), (size_t)H * sizeof(float), c->cs, tokens, E + eo[E_E], E + eo[E_P],
-                       E + eo[E_GE], (const T*)dy, c->emean, c->erstd, c->egacc + eo[E_E], c->egacc + eo[E_P], (int)rows, S, H);
+    const bool turned = (size_t)5 * H * sizeof(float) <= (size_t)128 << 10;   // room for a row per wave in LDS
+    const size_t lds = (size_t)(turned ? 5 : 1) * H * sizeof(float);
+    static_cast<void>(hipFuncSetAttribute((const void*)embed_bwd_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(embed_bwd_kernel<T>, dim3((unsigned)S * ((nseq + EMB_SEQS - 1) / EMB_SEQS)), dim3(256), lds, c->cs, tokens, E + eo[E_E], E + eo[E_P],
+                       E + eo[E_GE], (const T*)dy, c->emean, c->erstd, c->egacc + eo[E_E], c->egacc + eo[E_P], (int)rows, S, H, turned);
   }));
   return timed(c, L2L_PROF_COLSUM, 0, 0, [&] {
     dim3 grid((H + 127) / 128, (unsigned)((rows + COLSUM_ROWS - 1) / COLSUM_ROWS));

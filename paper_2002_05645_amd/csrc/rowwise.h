@@ -261,31 +261,48 @@ __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* dy, const T*
 // Embedding backward: dr through LN_e, scatter-added (fp32 atomics) into dE[tok] and dPpos[s].
 // A block takes one position s of EMB_SEQS consecutive sequences (a wave one row at a time), so that the
 // rows' contributions to dPpos[s] meet in LDS first and leave as one global atomic per column and block;
-// the token rows are scattered, their atomics go to memory directly.  Dynamic LDS: n floats.
+// the token rows are scattered, their atomics go to memory directly.  Dynamic LDS: n floats, 5 n if `turned`.
 constexpr int EMB_SEQS = 16;
 template <typename T>
 __global__ __launch_bounds__(256) void embed_bwd_kernel(const int32_t* tokens, const T* E, const T* pos, const T* gamma,
                                                         const T* dy, const float* mean, const float* rstd, float* dE,
-                                                        float* dpos, int rows, int S, int n) {
-  extern __shared__ float pos_acc[];
+                                                        float* dpos, int rows, int S, int n, bool turned) {
+  extern __shared__ float pos_acc[];   // n floats, then (turned) one row of n floats per wave
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int s = blockIdx.x % S, grp = blockIdx.x / S;
   const int nseq = rows / S;
   for (int j = threadIdx.x; j < n; j += 256) pos_acc[j] = 0.f;
   __syncthreads();
   const int q1 = min(nseq, (grp + 1) * EMB_SEQS);
+  float* tw = pos_acc + (long long)(1 + w) * n;
   for (int q = grp * EMB_SEQS + w; q < q1; q += 4) {
     const int r = q * S + s;
     const long long tok = tokens[r];
     EmbedRow<T> row{E + tok * n, pos + (long long)s * n};
     float* de = dE + tok * n;
-    ln_bwd_row<T>(row, n, lane, mean[r], rstd[r], gamma, dy + (long long)r * n, [de](int j, const float v[8]) {
+    if (turned) {
+      // a lane computes 8 consecutive columns; the atomics go out with consecutive lanes on consecutive columns
+      // (whole cache lines per instruction in memory, no bank conflicts in LDS), so the row turns through LDS first
+      ln_bwd_row<T>(row, n, lane, mean[r], rstd[r], gamma, dy + (long long)r * n, [tw](int j, const float v[8]) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        atomicAdd(de + j + i, v[i]);
-        atomicAdd(pos_acc + j + i, v[i]);
+        for (int i = 0; i < 8; ++i) tw[j + i] = v[i];
+      });
+      __builtin_amdgcn_wave_barrier();
+      for (int col = lane; col < n; col += WAVE) {
+        const float x = tw[col];
+        atomicAdd(de + col, x);
+        atomicAdd(pos_acc + col, x);
       }
-    });
+      __builtin_amdgcn_wave_barrier();
+    } else {
+      ln_bwd_row<T>(row, n, lane, mean[r], rstd[r], gamma, dy + (long long)r * n, [de](int j, const float v[8]) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          atomicAdd(de + j + i, v[i]);
+          atomicAdd(pos_acc + j + i, v[i]);
+        }
+      });
+    }
   }
   __syncthreads();
   float* dp = dpos + (long long)s * n;
