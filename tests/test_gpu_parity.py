@@ -554,6 +554,15 @@ def test_step_bf16_small_depth():
     _assert_errs({k: v for k, v in errs.items() if not k.startswith("adam.")}, TOL["bf16"])
 
 
+@pytest.mark.parametrize("stash", ["device", "host"])
+def test_step_bf16_long_sequences(stash):
+    # S = 256: the chunked attention kernels inside whole steps (two layers, so that a layer's row statistics from the
+    # recompute pass are overwritten by the next layer's before its backward kernels run), device and host stash
+    w = S.Workload("long-step", 2, 128, 2, 256, 256, 500, 2, 3, "bf16", 0.15, 901)
+    errs, loss, loss_ref = _step_case(w, stash=stash, group=2)
+    _assert_errs({k: v for k, v in errs.items() if not k.startswith("adam.")}, TOL["bf16"])
+
+
 @pytest.mark.slow
 def test_step_bert_base_bf16_full():
     w = S.WORKLOADS[1]
