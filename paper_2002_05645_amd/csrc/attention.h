@@ -339,7 +339,6 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(const E* qkv, const E* do
 // the backward kernels get P = exp(alpha S - lse) without a reduction.  rowsum(P dP) is taken as rowsum(dO O)
 // (the same number: sum_k P_k dO . V_k = dO . O), computed by the dQ kernel from the stored context and passed on.
 constexpr int CH = 128;
-constexpr int LONG_DKV_LDS = 6 * CH * 128;   // K, V | Q, dO | P, dS of one half of the keys: 96 KB
 
 template <typename E>
 __global__ __launch_bounds__(256) void attn_fwd_long_kernel(const E* qkv, E* out, float* lse, int S, int H, int A, float alpha) {
@@ -472,19 +471,17 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_long_kernel(const E* qkv, con
   store_T(dq, dqkv + ((long long)b * S + qb * CH + wave * 32) * ld + h * 64, ld, lane, alpha);
 }
 
-// dV = P^T dO and dK = alpha dS^T Q for 128 keys per workgroup, over all queries in chunks of 128.  Per chunk: wave w
-// recomputes P and dS of queries 32 w .. against the workgroup's keys, one half of the keys (64) at a time; the waves
-// park that half in LDS and then wave w takes key block w % 2 of the half and columns 32 (w / 2) .. of the head.
+// dV = P^T dO and dK = alpha dS^T Q for 128 keys per workgroup (wave w: keys 32 w .., held as B-operand fragments of
+// K and V), over all queries in chunks of 128 that pass through LDS as images of Q and dO.  Here the tiles are
+// S = Q K^T with the queries along the register axis and the keys along the lanes, so P and dS leave the accumulators
+// as the B operands of the products over queries, and a wave needs nobody else's P or dS.
 template <typename E>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_long_kernel(const E* qkv, const E* dout, const float* lse, const float* dsum,
                                                                 E* dqkv, int S, int H, int A, float alpha) {
-  extern __shared__ __attribute__((aligned(1024))) char lds[];
-  char* Ks = lds;
-  char* Vs = lds + CH * 128;
-  char* Qs = lds + 2 * CH * 128;
-  char* Os = lds + 3 * CH * 128;
-  char* Ps = lds + 4 * CH * 128;
-  char* Ds = lds + 5 * CH * 128;
+  __shared__ __attribute__((aligned(1024))) char lds[2 * CH * 128];
+  __shared__ __attribute__((aligned(16))) float Ls[CH], Dsm[CH];
+  char* Qs = lds;
+  char* Os = lds + CH * 128;
   const int nch = S / CH;
   const int kc = blockIdx.x % nch, bh = blockIdx.x / nch, b = bh / A, h = bh % A;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -493,67 +490,68 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_long_kernel(const E* qkv, co
   const uint32_t bytes = (uint32_t)(((long long)(CH - 1) * ld + 64) * 2);
   const E* dob = dout + (long long)b * S * H + h * 64;
   const uint32_t obytes = (uint32_t)(((long long)(CH - 1) * H + 64) * 2);
-  load_rows(make_rsrc(base + H + (long long)kc * CH * ld, bytes), (uint32_t)ld, CH, Ks, wave, 4, lane);
-  load_rows(make_rsrc(base + 2 * H + (long long)kc * CH * ld, bytes), (uint32_t)ld, CH, Vs, wave, 4, lane);
-  const int qrow = wave * 32 + (lane & 31);
-  const int kb2 = wave & 1, t = wave >> 1;
+  bf16x8 kf[4], vf[4];
+  {
+    const E* krow = base + H + (long long)(kc * CH + wave * 32 + (lane & 31)) * ld + (lane >> 5) * 8;
+#pragma unroll
+    for (int st = 0; st < 4; ++st) {
+      kf[st] = *(const bf16x8*)(krow + st * 16);
+      vf[st] = *(const bf16x8*)(krow + H + st * 16);
+    }
+  }
   f32x16 dv[2], dk[2];
 #pragma unroll
-  for (int half = 0; half < 2; ++half) {
-    dv[half] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    dk[half] = dv[half];
+  for (int t = 0; t < 2; ++t) {
+    dv[t] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    dk[t] = dv[t];
   }
   for (int qc = 0; qc < nch; ++qc) {
-    if (qc) __syncthreads();   // the previous chunk's products over queries are done with Q, dO, P and dS
+    if (qc) __syncthreads();   // every wave has left the previous chunk
     load_rows(make_rsrc(base + (long long)qc * CH * ld, bytes), (uint32_t)ld, CH, Qs, wave, 4, lane);
     load_rows(make_rsrc(dob + (long long)qc * CH * H, obytes), (uint32_t)H, CH, Os, wave, 4, lane);
-    const long long srow = (long long)bh * S + qc * CH + qrow;
-    const float L = lse[srow], D = dsum[srow];
+    if (tid < CH) {
+      const long long srow = (long long)bh * S + qc * CH + tid;
+      Ls[tid] = lse[srow];
+      Dsm[tid] = dsum[srow];
+    }
     wait_vm0();
     __syncthreads();
-    bf16x8 qf[4], of[4];
 #pragma unroll
-    for (int s4 = 0; s4 < 4; ++s4) { qf[s4] = frag_rows(Qs, qrow, s4, lane); of[s4] = frag_rows(Os, qrow, s4, lane); }
+    for (int qb = 0; qb < CH / 32; ++qb) {
+      f32x16 a = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      f32x16 d = a;
+      const int qrow = qb * 32 + (lane & 31);
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      f32x16 p_[2], ds_[2];
+      for (int s4 = 0; s4 < 4; ++s4) {
+        a = mfma_32x32x16<E>(frag_rows(Qs, qrow, s4, lane), kf[s4], a);
+        d = mfma_32x32x16<E>(frag_rows(Os, qrow, s4, lane), vf[s4], d);
+      }
+      // register r of this lane belongs to query 32 qb + 8 (r / 4) + 4 (lane / 32) + r % 4
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        f32x16 a = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        f32x16 d = a;
-        const int krow = (2 * half + j) * 32 + (lane & 31);
+      for (int blk = 0; blk < 4; ++blk) {
+        const f32x4 L4 = *(const f32x4*)(Ls + qb * 32 + 8 * blk + 4 * (lane >> 5));
+        const f32x4 D4 = *(const f32x4*)(Dsm + qb * 32 + 8 * blk + 4 * (lane >> 5));
 #pragma unroll
-        for (int s4 = 0; s4 < 4; ++s4) {
-          a = mfma_32x32x16<E>(frag_rows(Ks, krow, s4, lane), qf[s4], a);
-          d = mfma_32x32x16<E>(frag_rows(Vs, krow, s4, lane), of[s4], d);
-        }
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float p = __expf(a[r] * alpha - L);
-          p_[j][r] = p;
-          ds_[j][r] = p * (d[r] - D);
+        for (int i = 0; i < 4; ++i) {
+          const float p = __expf(a[4 * blk + i] * alpha - L4[i]);
+          a[4 * blk + i] = p;
+          d[4 * blk + i] = p * (d[4 * blk + i] - D4[i]);
         }
       }
-      if (half) __syncthreads();   // the first half's P and dS have been read
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        pq_store<E>(Ps, p_[j], qrow, j, lane);
-        pq_store<E>(Ds, ds_[j], qrow, j, lane);
-      }
-      __syncthreads();
-      for (int s = 0; s < CH / 16; ++s) {
-        const bf16x8 pf = pq_frag(Ps, s, kb2, lane), df = pq_frag(Ds, s, kb2, lane);
-        dv[half] = mfma_32x32x16<E>(frag_queries_T(Os, s, t, lane), pf, dv[half]);
-        dk[half] = mfma_32x32x16<E>(frag_queries_T(Qs, s, t, lane), df, dk[half]);
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const bf16x8 pf = pack8<E>(a, 8 * s2), df = pack8<E>(d, 8 * s2);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          dv[t] = mfma_32x32x16<E>(frag_keys_T(Os, qb, s2, t, lane), pf, dv[t]);
+          dk[t] = mfma_32x32x16<E>(frag_keys_T(Qs, qb, s2, t, lane), df, dk[t]);
+        }
       }
     }
   }
-#pragma unroll
-  for (int half = 0; half < 2; ++half) {
-    E* out = dqkv + ((long long)b * S + kc * CH + (2 * half + kb2) * 32) * ld + h * 64 + t * 32;
-    store_T1(dv[half], out + 2 * H, ld, lane, 1.0f);
-    store_T1(dk[half], out + H, ld, lane, alpha);
-  }
+  E* out = dqkv + ((long long)b * S + kc * CH + wave * 32) * ld + h * 64;
+  store_T(dv, out + 2 * H, ld, lane, 1.0f);
+  store_T(dk, out + H, ld, lane, alpha);
 }
 
 }  // namespace attn

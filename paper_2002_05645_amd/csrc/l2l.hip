@@ -696,7 +696,7 @@ int layer_backward_group(l2l_ctx* c, const void* params, const void* x, void* dy
                          (const E*)c->c, c->lse, c->dsum, (E*)dqkv, S, H, A, alpha);
     }));
     L2L_TRY(timed(c, L2L_PROF_ATTN, 6.0 * S * S * d * nseq * A, (3.0 + 1.0 + 2.0) * M * H * sizeof(T), [&] {
-      hipLaunchKernelGGL(attn::attn_bwd_dkv_long_kernel<E>, grid, dim3(256), attn::LONG_DKV_LDS, c->cs, (const E*)qkv,
+      hipLaunchKernelGGL(attn::attn_bwd_dkv_long_kernel<E>, grid, dim3(256), 0, c->cs, (const E*)qkv,
                          (const E*)c->dc, c->lse, c->dsum, (E*)dqkv, S, H, A, alpha);
     }));
   } else
@@ -938,8 +938,6 @@ int l2l_create(const l2l_config* cfg, void* compute_stream, void* copy_stream, l
   if (const char* e = getenv("L2L_NO_FUSED_ATTENTION")) c->no_fused_attention = atoi(e) != 0;
   (void)hipFuncSetAttribute((const void*)attn::attn_bwd_kernel<bf16>, hipFuncAttributeMaxDynamicSharedMemorySize, attn::BWD_LDS);
   (void)hipFuncSetAttribute((const void*)attn::attn_bwd_kernel<fp16>, hipFuncAttributeMaxDynamicSharedMemorySize, attn::BWD_LDS);
-  (void)hipFuncSetAttribute((const void*)attn::attn_bwd_dkv_long_kernel<bf16>, hipFuncAttributeMaxDynamicSharedMemorySize, attn::LONG_DKV_LDS);
-  (void)hipFuncSetAttribute((const void*)attn::attn_bwd_dkv_long_kernel<fp16>, hipFuncAttributeMaxDynamicSharedMemorySize, attn::LONG_DKV_LDS);
   *out = c;  // from here on the caller can read l2l_last_error and must l2l_destroy
 
   const size_t es = esize(cfg->dtype);
