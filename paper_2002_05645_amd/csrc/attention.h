@@ -1,7 +1,7 @@
 // Fused attention for the 16-bit paths (element type E = bf16 or fp16), head width d = 64, sequence length a
 // multiple of 32 up to 128: scores, softmax and context (forward) and all five attention gradients (backward)
 // of one (sequence, head) pair in one workgroup, without the S x S matrices ever leaving the chip.  Longer
-// sequences (multiples of 128) go through the chunked kernels at the end of this file.
+// sequences (multiples of 32) go through the chunked kernels at the end of this file.
 //
 // Everything is computed "transposed": the MFMA tiles are S^T = K Q^T (keys along the accumulator's
 // register axis, queries along its lane axis), so that a softmax row lives in the registers of one
@@ -332,28 +332,30 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(const E* qkv, const E* do
   }
 }
 
-// ---- long sequences: S a multiple of 128 beyond SMAX ----------------------------------------------------
+// ---- long sequences: S a multiple of 32 beyond SMAX -----------------------------------------------------
 // A workgroup owns 128 queries (forward, dQ) or 128 keys (dK, dV) of one (sequence, head) pair and walks the other
-// index in chunks of 128 rows that pass through LDS.  The forward pass keeps a running row maximum and row sum and
+// index in chunks of 128 rows that pass through LDS.  When S is not a multiple of 128 the last chunk is short: its
+// missing 32-row blocks are skipped, and the waves whose own 32 rows lie beyond S only help with the loads (RAGGED
+// instantiations; with S a multiple of 128 none of these tests is compiled in).  The forward pass keeps a running row maximum and row sum and
 // rescales its context accumulators when the maximum moves; it leaves lse = max + log(sum) per query row, from which
 // the backward kernels get P = exp(alpha S - lse) without a reduction.  rowsum(P dP) is taken as rowsum(dO O)
 // (the same number: sum_k P_k dO . V_k = dO . O), computed by the dQ kernel from the stored context and passed on.
 constexpr int CH = 128;
 
-template <typename E>
+template <typename E, bool RAGGED>
 __global__ __launch_bounds__(256) void attn_fwd_long_kernel(const E* qkv, E* out, float* lse, int S, int H, int A, float alpha) {
   __shared__ __attribute__((aligned(1024))) char lds[2 * CH * 128];
   char* Ks = lds;
   char* Vs = lds + CH * 128;
-  const int nch = S / CH;
+  const int nch = (S + CH - 1) / CH;
   const int qb = blockIdx.x % nch, bh = blockIdx.x / nch, b = bh / A, h = bh % A;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const long long ld = 3LL * H;
   const E* base = qkv + (long long)b * S * ld + h * 64;
-  const uint32_t bytes = (uint32_t)(((long long)(CH - 1) * ld + 64) * 2);
   const int q = qb * CH + wave * 32 + (lane & 31);
+  const bool active = !RAGGED || qb * CH + wave * 32 < S;   // (per wave)
   bf16x8 qf[4];
-  {
+  if (active) {
     const E* qrow = base + (long long)q * ld + (lane >> 5) * 8;
 #pragma unroll
     for (int st = 0; st < 4; ++st) qf[st] = *(const bf16x8*)(qrow + st * 16);
@@ -363,30 +365,36 @@ __global__ __launch_bounds__(256) void attn_fwd_long_kernel(const E* qkv, E* out
 #pragma unroll
   for (int t = 0; t < 2; ++t) o[t] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   for (int kc = 0; kc < nch; ++kc) {
+    const int rows = RAGGED ? min(CH, S - kc * CH) : CH, nkb = rows / 32;   // this chunk's keys
+    const uint32_t bytes = (uint32_t)(((long long)(rows - 1) * ld + 64) * 2);
     if (kc) __syncthreads();   // every wave has left the previous chunk
-    load_rows(make_rsrc(base + H + (long long)kc * CH * ld, bytes), (uint32_t)ld, CH, Ks, wave, 4, lane);
-    load_rows(make_rsrc(base + 2 * H + (long long)kc * CH * ld, bytes), (uint32_t)ld, CH, Vs, wave, 4, lane);
+    load_rows(make_rsrc(base + H + (long long)kc * CH * ld, bytes), (uint32_t)ld, rows, Ks, wave, 4, lane);
+    load_rows(make_rsrc(base + 2 * H + (long long)kc * CH * ld, bytes), (uint32_t)ld, rows, Vs, wave, 4, lane);
     wait_vm0();
     __syncthreads();
+    if (!active) continue;
     f32x16 st_[CH / 32];
     float cm = m;
 #pragma unroll
-    for (int kb = 0; kb < CH / 32; ++kb) {
-      f32x16 a = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int kb = 0; kb < CH / 32; ++kb)
+      if (kb < nkb) {
+        f32x16 a = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int s4 = 0; s4 < 4; ++s4) a = mfma_32x32x16<E>(frag_rows(Ks, kb * 32 + (lane & 31), s4, lane), qf[s4], a);
+        for (int s4 = 0; s4 < 4; ++s4) a = mfma_32x32x16<E>(frag_rows(Ks, kb * 32 + (lane & 31), s4, lane), qf[s4], a);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { a[r] *= alpha; cm = fmaxf(cm, a[r]); }
-      st_[kb] = a;
-    }
+        for (int r = 0; r < 16; ++r) { a[r] *= alpha; cm = fmaxf(cm, a[r]); }
+        st_[kb] = a;
+      }
     cm = xor32_max(cm);
     const float rescale = __expf(m - cm);   // 0 on the first chunk
     m = cm;
     float cs = 0.f;
 #pragma unroll
     for (int kb = 0; kb < CH / 32; ++kb)
+      if (kb < nkb) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { st_[kb][r] = __expf(st_[kb][r] - m); cs += st_[kb][r]; }
+        for (int r = 0; r < 16; ++r) { st_[kb][r] = __expf(st_[kb][r] - m); cs += st_[kb][r]; }
+      }
     sum = sum * rescale + xor32_sum(cs);
 #pragma unroll
     for (int t = 0; t < 2; ++t)
@@ -394,35 +402,38 @@ __global__ __launch_bounds__(256) void attn_fwd_long_kernel(const E* qkv, E* out
       for (int r = 0; r < 16; ++r) o[t][r] *= rescale;
 #pragma unroll
     for (int kb = 0; kb < CH / 32; ++kb)
+      if (kb < nkb) {
 #pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2) {
-        const bf16x8 pf = pack8<E>(st_[kb], 8 * s2);
+        for (int s2 = 0; s2 < 2; ++s2) {
+          const bf16x8 pf = pack8<E>(st_[kb], 8 * s2);
 #pragma unroll
-        for (int t = 0; t < 2; ++t) o[t] = mfma_32x32x16<E>(frag_keys_T(Vs, kb, s2, t, lane), pf, o[t]);
+          for (int t = 0; t < 2; ++t) o[t] = mfma_32x32x16<E>(frag_keys_T(Vs, kb, s2, t, lane), pf, o[t]);
+        }
       }
   }
+  if (!active) return;
   store_T(o, out + ((long long)b * S + qb * CH + wave * 32) * H + h * 64, H, lane, 1.0f / sum);
   if (lse && lane < 32) lse[(long long)bh * S + q] = m + __logf(sum);
 }
 
 // dQ = alpha dS K for 128 queries per workgroup; also leaves dsum[row] = rowsum(dO O) for the dK / dV kernel.
 // ctx: [rows, H], the forward pass's output.
-template <typename E>
+template <typename E, bool RAGGED>
 __global__ __launch_bounds__(256) void attn_bwd_dq_long_kernel(const E* qkv, const E* dout, const E* ctx, const float* lse,
                                                                float* dsum, E* dqkv, int S, int H, int A, float alpha) {
   __shared__ __attribute__((aligned(1024))) char lds[2 * CH * 128];
   char* Ks = lds;
   char* Vs = lds + CH * 128;
-  const int nch = S / CH;
+  const int nch = (S + CH - 1) / CH;
   const int qb = blockIdx.x % nch, bh = blockIdx.x / nch, b = bh / A, h = bh % A;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const long long ld = 3LL * H;
   const E* base = qkv + (long long)b * S * ld + h * 64;
-  const uint32_t bytes = (uint32_t)(((long long)(CH - 1) * ld + 64) * 2);
   const int q = qb * CH + wave * 32 + (lane & 31);
+  const bool active = !RAGGED || qb * CH + wave * 32 < S;   // (per wave)
   bf16x8 qf[4], of[4];
   float D = 0.f;
-  {
+  if (active) {
     const E* qrow = base + (long long)q * ld + (lane >> 5) * 8;
     const long long orow = ((long long)b * S + q) * H + h * 64 + (lane >> 5) * 8;
 #pragma unroll
@@ -437,37 +448,42 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_long_kernel(const E* qkv, con
   }
   D = xor32_sum(D);
   const long long srow = (long long)bh * S + q;
-  const float L = lse[srow];
-  if (lane < 32) dsum[srow] = D;
+  const float L = active ? lse[srow] : 0.f;
+  if (active && lane < 32) dsum[srow] = D;
   f32x16 dq[2];
 #pragma unroll
   for (int t = 0; t < 2; ++t) dq[t] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   for (int kc = 0; kc < nch; ++kc) {
+    const int rows = RAGGED ? min(CH, S - kc * CH) : CH, nkb = rows / 32;   // this chunk's keys
+    const uint32_t bytes = (uint32_t)(((long long)(rows - 1) * ld + 64) * 2);
     if (kc) __syncthreads();
-    load_rows(make_rsrc(base + H + (long long)kc * CH * ld, bytes), (uint32_t)ld, CH, Ks, wave, 4, lane);
-    load_rows(make_rsrc(base + 2 * H + (long long)kc * CH * ld, bytes), (uint32_t)ld, CH, Vs, wave, 4, lane);
+    load_rows(make_rsrc(base + H + (long long)kc * CH * ld, bytes), (uint32_t)ld, rows, Ks, wave, 4, lane);
+    load_rows(make_rsrc(base + 2 * H + (long long)kc * CH * ld, bytes), (uint32_t)ld, rows, Vs, wave, 4, lane);
     wait_vm0();
     __syncthreads();
+    if (!active) continue;
 #pragma unroll
-    for (int kb = 0; kb < CH / 32; ++kb) {
-      f32x16 a = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      f32x16 d = a;
-      const int krow = kb * 32 + (lane & 31);
+    for (int kb = 0; kb < CH / 32; ++kb)
+      if (kb < nkb) {
+        f32x16 a = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        f32x16 d = a;
+        const int krow = kb * 32 + (lane & 31);
 #pragma unroll
-      for (int s4 = 0; s4 < 4; ++s4) {
-        a = mfma_32x32x16<E>(frag_rows(Ks, krow, s4, lane), qf[s4], a);
-        d = mfma_32x32x16<E>(frag_rows(Vs, krow, s4, lane), of[s4], d);
+        for (int s4 = 0; s4 < 4; ++s4) {
+          a = mfma_32x32x16<E>(frag_rows(Ks, krow, s4, lane), qf[s4], a);
+          d = mfma_32x32x16<E>(frag_rows(Vs, krow, s4, lane), of[s4], d);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) d[r] = __expf(a[r] * alpha - L) * (d[r] - D);   // dP -> dS
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          const bf16x8 df = pack8<E>(d, 8 * s2);
+#pragma unroll
+          for (int t = 0; t < 2; ++t) dq[t] = mfma_32x32x16<E>(frag_keys_T(Ks, kb, s2, t, lane), df, dq[t]);
+        }
       }
-#pragma unroll
-      for (int r = 0; r < 16; ++r) d[r] = __expf(a[r] * alpha - L) * (d[r] - D);   // dP -> dS
-#pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2) {
-        const bf16x8 df = pack8<E>(d, 8 * s2);
-#pragma unroll
-        for (int t = 0; t < 2; ++t) dq[t] = mfma_32x32x16<E>(frag_keys_T(Ks, kb, s2, t, lane), df, dq[t]);
-      }
-    }
   }
+  if (!active) return;
   store_T(dq, dqkv + ((long long)b * S + qb * CH + wave * 32) * ld + h * 64, ld, lane, alpha);
 }
 
@@ -475,23 +491,22 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_long_kernel(const E* qkv, con
 // K and V), over all queries in chunks of 128 that pass through LDS as images of Q and dO.  Here the tiles are
 // S = Q K^T with the queries along the register axis and the keys along the lanes, so P and dS leave the accumulators
 // as the B operands of the products over queries, and a wave needs nobody else's P or dS.
-template <typename E>
+template <typename E, bool RAGGED>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_long_kernel(const E* qkv, const E* dout, const float* lse, const float* dsum,
                                                                 E* dqkv, int S, int H, int A, float alpha) {
   __shared__ __attribute__((aligned(1024))) char lds[2 * CH * 128];
   __shared__ __attribute__((aligned(16))) float Ls[CH], Dsm[CH];
   char* Qs = lds;
   char* Os = lds + CH * 128;
-  const int nch = S / CH;
+  const int nch = (S + CH - 1) / CH;
   const int kc = blockIdx.x % nch, bh = blockIdx.x / nch, b = bh / A, h = bh % A;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const long long ld = 3LL * H;
   const E* base = qkv + (long long)b * S * ld + h * 64;
-  const uint32_t bytes = (uint32_t)(((long long)(CH - 1) * ld + 64) * 2);
   const E* dob = dout + (long long)b * S * H + h * 64;
-  const uint32_t obytes = (uint32_t)(((long long)(CH - 1) * H + 64) * 2);
+  const bool active = !RAGGED || kc * CH + wave * 32 < S;   // (per wave)
   bf16x8 kf[4], vf[4];
-  {
+  if (active) {
     const E* krow = base + H + (long long)(kc * CH + wave * 32 + (lane & 31)) * ld + (lane >> 5) * 8;
 #pragma unroll
     for (int st = 0; st < 4; ++st) {
@@ -506,18 +521,23 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_long_kernel(const E* qkv, co
     dk[t] = dv[t];
   }
   for (int qc = 0; qc < nch; ++qc) {
+    const int rows = RAGGED ? min(CH, S - qc * CH) : CH, nqb = rows / 32;   // this chunk's queries
+    const uint32_t bytes = (uint32_t)(((long long)(rows - 1) * ld + 64) * 2);
+    const uint32_t obytes = (uint32_t)(((long long)(rows - 1) * H + 64) * 2);
     if (qc) __syncthreads();   // every wave has left the previous chunk
-    load_rows(make_rsrc(base + (long long)qc * CH * ld, bytes), (uint32_t)ld, CH, Qs, wave, 4, lane);
-    load_rows(make_rsrc(dob + (long long)qc * CH * H, obytes), (uint32_t)H, CH, Os, wave, 4, lane);
-    if (tid < CH) {
+    load_rows(make_rsrc(base + (long long)qc * CH * ld, bytes), (uint32_t)ld, rows, Qs, wave, 4, lane);
+    load_rows(make_rsrc(dob + (long long)qc * CH * H, obytes), (uint32_t)H, rows, Os, wave, 4, lane);
+    if (tid < rows) {
       const long long srow = (long long)bh * S + qc * CH + tid;
       Ls[tid] = lse[srow];
       Dsm[tid] = dsum[srow];
     }
     wait_vm0();
     __syncthreads();
+    if (!active) continue;
 #pragma unroll
     for (int qb = 0; qb < CH / 32; ++qb) {
+      if (qb >= nqb) break;
       f32x16 a = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
       f32x16 d = a;
       const int qrow = qb * 32 + (lane & 31);
@@ -549,6 +569,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_long_kernel(const E* qkv, co
       }
     }
   }
+  if (!active) return;
   E* out = dqkv + ((long long)b * S + kc * CH + wave * 32) * ld + h * 64;
   store_T(dv, out + 2 * H, ld, lane, 1.0f);
   store_T(dk, out + H, ld, lane, alpha);

@@ -503,10 +503,10 @@ bool fused_attention_ok(const l2l_ctx* c) {
   const l2l_config& f = c->cfg;
   return is16(f.dtype) && f.hidden / f.heads == 64 && f.seq % 32 == 0 && f.seq <= attn::SMAX && !c->no_fused_attention;
 }
-// ... and the chunked ones longer sequences that are a multiple of 128
+// ... and the chunked ones longer sequences
 bool fused_attention_long_ok(const l2l_ctx* c) {
   const l2l_config& f = c->cfg;
-  return is16(f.dtype) && f.hidden / f.heads == 64 && f.seq % attn::CH == 0 && f.seq > attn::SMAX && !c->no_fused_attention;
+  return is16(f.dtype) && f.hidden / f.heads == 64 && f.seq % 32 == 0 && f.seq > attn::SMAX && !c->no_fused_attention;
 }
 
 int fill_zero(l2l_ctx* c, void* p, size_t bytes) {
@@ -575,8 +575,11 @@ int layer_forward_group(l2l_ctx* c, int slot, const void* x, void* y, int ng, bo
     L2L_TRY(timed(c, L2L_PROF_ATTN, fl, (3.0 + 1.0) * M * H * sizeof(T), [&] {
       using E = attn_elem<T>;
       // (the row statistics are for the backward kernels: only the recompute pass keeps them)
-      hipLaunchKernelGGL(attn::attn_fwd_long_kernel<E>, dim3(nseq * A * (S / attn::CH)), dim3(256), 0, c->cs, (const E*)qkv,
-                         (E*)c->c, keep ? c->lse : nullptr, S, H, A, 1.0f / sqrtf((float)d));
+      auto go = [&](auto kern) {
+        hipLaunchKernelGGL(kern, dim3(nseq * A * ((S + attn::CH - 1) / attn::CH)), dim3(256), 0, c->cs, (const E*)qkv, (E*)c->c,
+                           keep ? c->lse : nullptr, S, H, A, 1.0f / sqrtf((float)d));
+      };
+      if (S % attn::CH) go(attn::attn_fwd_long_kernel<E, true>); else go(attn::attn_fwd_long_kernel<E, false>);
     }));
   } else
   {
@@ -690,14 +693,20 @@ int layer_backward_group(l2l_ctx* c, const void* params, const void* x, void* dy
     }));
   } else if (fused_attention_long_ok(c)) {
     using E = attn_elem<T>;
-    const dim3 grid(nseq * A * (S / attn::CH));
+    const dim3 grid(nseq * A * ((S + attn::CH - 1) / attn::CH));
     L2L_TRY(timed(c, L2L_PROF_ATTN, 4.0 * S * S * d * nseq * A, (3.0 + 1.0 + 1.0 + 1.0) * M * H * sizeof(T), [&] {
-      hipLaunchKernelGGL(attn::attn_bwd_dq_long_kernel<E>, grid, dim3(256), 0, c->cs, (const E*)qkv, (const E*)c->dc,
-                         (const E*)c->c, c->lse, c->dsum, (E*)dqkv, S, H, A, alpha);
+      auto go = [&](auto kern) {
+        hipLaunchKernelGGL(kern, grid, dim3(256), 0, c->cs, (const E*)qkv, (const E*)c->dc, (const E*)c->c, c->lse, c->dsum,
+                           (E*)dqkv, S, H, A, alpha);
+      };
+      if (S % attn::CH) go(attn::attn_bwd_dq_long_kernel<E, true>); else go(attn::attn_bwd_dq_long_kernel<E, false>);
     }));
     L2L_TRY(timed(c, L2L_PROF_ATTN, 6.0 * S * S * d * nseq * A, (3.0 + 1.0 + 2.0) * M * H * sizeof(T), [&] {
-      hipLaunchKernelGGL(attn::attn_bwd_dkv_long_kernel<E>, grid, dim3(256), 0, c->cs, (const E*)qkv,
-                         (const E*)c->dc, c->lse, c->dsum, (E*)dqkv, S, H, A, alpha);
+      auto go = [&](auto kern) {
+        hipLaunchKernelGGL(kern, grid, dim3(256), 0, c->cs, (const E*)qkv, (const E*)c->dc, c->lse, c->dsum, (E*)dqkv, S, H, A,
+                           alpha);
+      };
+      if (S % attn::CH) go(attn::attn_bwd_dkv_long_kernel<E, true>); else go(attn::attn_bwd_dkv_long_kernel<E, false>);
     }));
   } else
   {

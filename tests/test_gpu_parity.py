@@ -268,10 +268,11 @@ def test_layer_fused_attention_sequence_lengths(seq, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "fp16"])
-@pytest.mark.parametrize("seq", [256, 384, 512])
+@pytest.mark.parametrize("seq", [160, 256, 320, 384, 512])
 def test_layer_chunked_attention_long_sequences(seq, dtype):
-    # head width 64 and S a multiple of 128 beyond 128: the chunked attention kernels (running softmax statistics in
-    # the forward pass; dQ and dK / dV kernels that rebuild P from the stored log-sum-exp in the backward pass)
+    # head width 64 and S a multiple of 32 beyond 128: the chunked attention kernels (running softmax statistics in
+    # the forward pass; dQ and dK / dV kernels that rebuild P from the stored log-sum-exp in the backward pass);
+    # 160 and 320 end in a short chunk of 32 and 64 rows
     w = S.Workload("long", 1, 128, 2, 256, seq, 50, 2, 3, dtype, 1.0, 300 + seq)
     # fp16: with attention weights near 1 / S the score gradients of the synthetic dY fall into fp16's subnormals on
     # any path (the batched-GEMM one included), which is what the loss scale of Section 2.3's FP16 mode is for: the
