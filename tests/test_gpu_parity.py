@@ -564,6 +564,14 @@ def test_step_bf16_long_sequences(stash):
     _assert_errs({k: v for k, v in errs.items() if not k.startswith("adam.")}, TOL["bf16"])
 
 
+def test_step_bf16_wide_hidden():
+    # H = 3584: the embedding backward kernel turns each row through LDS (5 H floats, more than the 64 KB a kernel gets
+    # without asking), LayerNorm backward takes its two-kernel form (H > 2048)
+    w = S.Workload("wide-step", 1, 3584, 56, 256, 32, 50, 2, 2, "bf16", 1.0, 555)
+    errs, loss, loss_ref = _step_case(w)
+    _assert_errs({k: v for k, v in errs.items() if not k.startswith("adam.")}, TOL["bf16"])
+
+
 @pytest.mark.slow
 def test_step_bert_base_bf16_full():
     w = S.WORKLOADS[1]
