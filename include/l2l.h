@@ -274,6 +274,8 @@ int   eps_adam_step_range(eps_store*, int block, long long first_elem, long long
    *nonfinite to 1 if any of them holds an inf or NaN (an overflow on the device: the caller then skips
    the update and lowers the scale), else 0.  nonfinite may be null. */
 int   eps_grad_unscale(eps_store*, int first, int last, double inv_scale, int* nonfinite);
+/* The same for elements [first_elem, first_elem + count) of one block (a piece of it that has landed). */
+int   eps_grad_unscale_range(eps_store*, int block, long long first_elem, long long count, double inv_scale, int* nonfinite);
 /* 16-bit gradient landing buffers (for l2l_set_drain_dtype): eps_enable_grad16 allocates one per block (pinned, 2 bytes
    per element, once), eps_grad16 returns a block's, eps_grad_widen converts what landed there (dtype L2L_BF16 or
    L2L_FP16) into the fp32 gradient buffers of blocks [first, last], which the optimizer steps read; the _range form

@@ -101,6 +101,7 @@ _SIGS = {
     "eps_adam_step_range": (C.c_int, [_P, C.c_int, C.c_longlong, C.c_longlong, C.c_int, C.c_double, C.c_double, C.c_double,
                                       C.c_double]),
     "eps_grad_unscale": (C.c_int, [_P, C.c_int, C.c_int, C.c_double, C.POINTER(C.c_int)]),
+    "eps_grad_unscale_range": (C.c_int, [_P, C.c_int, C.c_longlong, C.c_longlong, C.c_double, C.POINTER(C.c_int)]),
     "eps_adam_step_range16": (C.c_int, [_P, C.c_int, C.c_longlong, C.c_longlong, C.c_int, C.c_double, C.c_double, C.c_double,
                                         C.c_double, C.c_int]),
     "eps_enable_grad16": (C.c_int, [_P]),
@@ -408,6 +409,13 @@ class EPS:
         rc = lib().eps_grad_unscale(self._h, first, last, inv_scale, C.byref(bad))
         if rc != L2L_OK:
             raise L2LError(rc, "eps_grad_unscale")
+        return bool(bad.value)
+
+    def grad_unscale_range(self, block, first_elem, count, inv_scale) -> bool:
+        bad = C.c_int(0)
+        rc = lib().eps_grad_unscale_range(self._h, block, int(first_elem), int(count), inv_scale, C.byref(bad))
+        if rc != L2L_OK:
+            raise L2LError(rc, "eps_grad_unscale_range")
         return bool(bad.value)
 
     def lamb_step(self, first, last, t, segments, lr=1e-3, beta1=0.9, beta2=0.999, eps_a=1e-6, weight_decay=0.0,

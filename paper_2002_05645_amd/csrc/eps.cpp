@@ -371,6 +371,25 @@ int eps_grad_unscale(eps_store* e, int first, int last, double inv_scale, int* n
   return L2L_OK;
 }
 
+int eps_grad_unscale_range(eps_store* e, int block, long long first_elem, long long count, double inv_scale, int* nonfinite) {
+  if (!e || block < 0 || block >= (int)e->blocks.size() || !std::isfinite(inv_scale)) return L2L_E_ARG;
+  if (first_elem < 0 || count <= 0 || (size_t)(first_elem + count) > e->blocks[block].n) return L2L_E_ARG;
+  const float s = (float)inv_scale;
+  std::atomic<int> bad{0};
+  float* __restrict g = e->blocks[block].grad + first_elem;
+  e->pool->run((size_t)count, [&](size_t lo, size_t hi) {
+    float worst = 0.f;   // as in eps_grad_unscale
+    for (size_t k = lo; k < hi; ++k) {
+      const float v = g[k] * s;
+      g[k] = v;
+      worst += v * 0.f;
+    }
+    if (!(worst == 0.f)) bad.store(1);
+  });
+  if (nonfinite) *nonfinite = bad.load();
+  return L2L_OK;
+}
+
 int eps_lamb_step(eps_store* e, int first, int last, int t, double lr_d, double beta1_d, double beta2_d, double eps_a_d,
                   double weight_decay, int n_seg, const long long* seg_begin, const long long* seg_end,
                   const double* seg_decay) {

@@ -155,12 +155,12 @@ class L2LTrainer:
         # The embedding block is the last to be updated in a step and the first needed in the next, so its drain, its
         # Adam and its next stage are exposed.  With eager Adam they run as a pipeline over `tail_parts` pieces of the
         # block: piece k is updated while piece k + 1 is still on its way to the host, and shipped back while piece
-        # k + 1 is being updated.  (LAMB needs whole tensors for its norms, a loss scale the whole block for its overflow
-        # check: both keep the one-piece path.)
+        # k + 1 is being updated.  (LAMB needs whole tensors for its norms and keeps the one-piece path.  A loss scale is
+        # static in eager mode, so its unscale-and-check runs piece by piece as well.)
         self._parts = []
         self._prestaged = False
         tail_parts = int(os.environ.get("L2L_TAIL_PARTS", tail_parts))
-        if eager and optimizer == "adam" and self.scaler.scale == 1.0 and tail_parts > 1:
+        if eager and optimizer == "adam" and tail_parts > 1:
             step = -(-self.embed_elems // tail_parts)
             step = -(-step // 256) * 256     # (whole kilobytes of fp32)
             self._parts = [(a, min(step, self.embed_elems - a)) for a in range(0, self.embed_elems, step)]
@@ -321,6 +321,10 @@ class L2LTrainer:
                     if self._adam_from16:
                         self.eps.adam_step_range16(0, first, count, t, self.grad_dtype, **self.hp)
                     else:
+                        if self.grad_dtype != "fp32":
+                            self.eps.grad_widen_range(0, first, count, self.grad_dtype)
+                        if self.scaler.scale != 1.0 and self.eps.grad_unscale_range(0, first, count, 1.0 / self.scaler.scale):
+                            raise FloatingPointError(f"gradient overflow in the embedding block at loss scale {self.scaler.scale}")
                         self.eps.adam_step_range(0, first, count, t, **self.hp)
                 else:
                     block, t = item

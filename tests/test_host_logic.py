@@ -188,6 +188,27 @@ def test_eps_adam_in_pieces_equals_the_whole_block():
     b.close()
 
 
+def test_eps_grad_unscale_of_a_piece():
+    # the ranged form touches its elements only, and reports a non-finite value only if it lies inside them
+    n = 100000
+    e = P.EPS([7, n], "fp16", 3)
+    g0 = np.random.default_rng(5).normal(size=n).astype(np.float32)
+    e.grad(1)[:] = g0
+    assert e.grad_unscale_range(1, 1000, 70000, 0.25) is False
+    want = g0.copy()
+    want[1000:71000] *= np.float32(0.25)
+    assert np.array_equal(e.grad(1), want)
+    e.grad(1)[80000] = np.inf
+    assert e.grad_unscale_range(1, 0, 80000, 1.0) is False
+    assert e.grad_unscale_range(1, 79999, 2, 1.0) is True
+    e.grad(1)[80000] = np.nan
+    assert e.grad_unscale_range(1, 80000, n - 80000, 0.5) is True
+    for bad in [(1, -1, 5), (1, 0, 0), (1, n - 3, 4), (2, 0, 1)]:
+        with pytest.raises(P.L2LError):
+            e.grad_unscale_range(bad[0], bad[1], bad[2], 1.0)
+    e.close()
+
+
 @pytest.mark.parametrize("threads", [1, 5])
 def test_eps_adam_matches_oracle(threads):
     n = 300001
