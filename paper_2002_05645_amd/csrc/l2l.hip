@@ -797,8 +797,10 @@ int head_loss_t(l2l_ctx* c, const void* x_last, const int32_t* labels, void* dy_
       hipLaunchKernelGGL((rows_by_index_kernel<T, false>), dim3((rows + 3) / 4), dim3(256), 0, c->cs, (const T*)x_last, (T*)c->xl,
                          idx, cnt, H);
     }));
-    // logits = Xl E^T + bv
-    GemmArgs g = gemm_args(rows, V, H, c->xl, H, 1, E + eo[E_E], H, 1, c->logits, Vp);
+    // logits = Xl E^T + bv.  The GEMM runs over the padded vocabulary Vp (a multiple of 64; the logits buffer has that
+    // many columns) so that its epilogue takes the 16-byte path, which wants N % 8 == 0: columns V .. Vp - 1 come from
+    // the rows that follow E in the embedding block and from the bias tensor's padding, and nobody reads them.
+    GemmArgs g = gemm_args(rows, (int)Vp, H, c->xl, H, 1, E + eo[E_E], H, 1, c->logits, Vp);
     g.epi = EPI_BIAS; g.bias = E + eo[E_BV]; g.m_dev = cnt;
     L2L_TRY(gemm(c, dt, true, g, 0, L2L_PROF_OTHER));
     L2L_TRY(timed(c, L2L_PROF_OTHER, 0, 0, [&] {
@@ -1002,7 +1004,9 @@ int l2l_create(const l2l_config* cfg, void* compute_stream, void* copy_stream, l
   if (cfg->vocab > 0) {
     const long long V = cfg->vocab, UT = c->T * cfg->num_ubatches;
     c->Vp = up(V, 64);
-    L2L_TRY(dev_alloc(c, &c->emb, c->lay.etotal * es));
+    // (+ 64 rows: the logits GEMM reads the rows of E up to the padded vocabulary size, wherever the block ends)
+    L2L_TRY(dev_alloc(c, &c->emb, (c->lay.etotal + 64 * (long long)cfg->hidden) * es));
+    HIP_TRY(c, hipMemset(c->emb, 0, (c->lay.etotal + 64 * (long long)cfg->hidden) * es));
     L2L_TRY(dev_alloc(c, (void**)&c->egacc, c->lay.etotal * 4));
     HIP_TRY(c, hipMemset(c->egacc, 0, c->lay.etotal * 4));
     L2L_TRY(dev_alloc(c, (void**)&c->emean, UT * 4));
