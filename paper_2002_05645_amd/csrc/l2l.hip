@@ -185,6 +185,7 @@ struct l2l_ctx {
   long long head_rows = 0;   // labelled rows per pass of the head
   float loss_scale = 1.0f;   // factor on the loss gradient (fp16 training)
   void *xl = nullptr, *dz = nullptr, *dxl = nullptr;
+  float* dxl32 = nullptr;   // 16-bit modes: the head's dX in fp32, the target of a K-split GEMM
   float* logits = nullptr;
   long long Vp = 0;
 
@@ -808,9 +809,24 @@ int head_loss_t(l2l_ctx* c, const void* x_last, const int32_t* labels, void* dy_
                          loss_out, V, (int)Vp, c->loss_scale);
     }));
     // dXl = dz E
-    GemmArgs h = gemm_args(rows, H, V, c->dz, Vp, 1, E + eo[E_E], H, 0, c->dxl, H);
-    h.m_dev = cnt;
-    L2L_TRY(gemm(c, dt, false, h, 0, L2L_PROF_OTHER));
+    if constexpr (sizeof(T) == 2) {
+      // few tiles (rows x H) and a long contraction (the vocabulary): as an accumulating fp32 GEMM into a cleared
+      // buffer it is split over K like the dW GEMMs, and rounded to the 16-bit format afterwards
+      L2L_TRY(fill_zero(c, c->dxl32, (size_t)rows * H * 4));
+      GemmArgs h = gemm_args(rows, H, V, c->dz, Vp, 1, E + eo[E_E], H, 0, c->dxl32, H);
+      h.m_dev = cnt;
+      h.epi = EPI_ACCUM;
+      L2L_TRY(gemm(c, dt, true, h, 0, L2L_PROF_OTHER));
+      const long long n = (long long)rows * H;
+      L2L_TRY(timed(c, L2L_PROF_OTHER, 0, 6.0 * n, [&] {
+        const unsigned blocks = (unsigned)std::min<long long>((n / 4 + 255) / 256 + 1, 2048);
+        hipLaunchKernelGGL(narrow_kernel<T>, dim3(blocks), dim3(256), 0, c->cs, c->dxl32, (T*)c->dxl, n);
+      }));
+    } else {
+      GemmArgs h = gemm_args(rows, H, V, c->dz, Vp, 1, E + eo[E_E], H, 0, c->dxl, H);
+      h.m_dev = cnt;
+      L2L_TRY(gemm(c, dt, false, h, 0, L2L_PROF_OTHER));
+    }
     L2L_TRY(timed(c, L2L_PROF_OTHER, 0, 0, [&] {
       hipLaunchKernelGGL((rows_by_index_kernel<T, true>), dim3((rows + 3) / 4), dim3(256), 0, c->cs, (const T*)c->dxl, (T*)dy_out,
                          idx, cnt, H);
@@ -1021,6 +1037,7 @@ int l2l_create(const l2l_config* cfg, void* compute_stream, void* copy_stream, l
     L2L_TRY(dev_alloc(c, (void**)&c->chunk_cnt, ((UT + c->head_rows - 1) / c->head_rows) * 4));
     L2L_TRY(dev_alloc(c, &c->xl, c->head_rows * H * es));
     L2L_TRY(dev_alloc(c, &c->dxl, c->head_rows * H * es));
+    if (is16(cfg->dtype)) L2L_TRY(dev_alloc(c, (void**)&c->dxl32, c->head_rows * H * 4));
     L2L_TRY(dev_alloc(c, (void**)&c->logits, c->head_rows * c->Vp * 4));
     L2L_TRY(dev_alloc(c, &c->dz, c->head_rows * c->Vp * es));
     HIP_TRY(c, hipEventCreateWithFlags(&c->emb_staged_ev, hipEventDisableTiming));
