@@ -4,7 +4,10 @@ of 32; bf16 with fp32 accumulation; host EPS Adam), synthetic data, random-init 
 
 One step = embedding -> 24 x (param stage, layer forward over all micro-batches) -> head + loss ->
 24 x (param stage, layer backward with recompute, grad drain) -> embedding backward -> host Adam.
-Prints one JSON line (see README for the fields)."""
+Prints one JSON line: metric, value (samples/s over the timed steps), unit, n_gpus, steps, warmup, ms_per_step, dtype,
+data, config (workload and how the step went: device pipeline, exposed host optimizer time, overlap fractions, kernel
+time by class, peak device bytes), roofline (the layer GEMMs against the dense bf16 MFMA peak, from HIP events around
+every GEMM launch in a second set of steps) and cpu_baseline (the CPU oracle on a bounded sample of the workload)."""
 import argparse
 import json
 import os
