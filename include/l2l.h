@@ -97,13 +97,23 @@ int    l2l_config_check(const l2l_config*);
 
 /* ---- context ----------------------------------------------------------------------------------- */
 /* compute_stream / copy_stream: hipStream_t handles (may be the same; NULL = the null stream).
-   Allocates slots, accumulators and workspace on the current device. */
+   Allocates slots, accumulators and workspace on the current device.
+   Tuning and test switches are taken from the environment here, once, and from nowhere else:
+     L2L_NO_FUSED_ATTENTION=1  attention as batched GEMMs + softmax kernels with the score matrices in memory
+     L2L_HEAD_ROWS=n           labelled rows per pass of the LM head (default min(U T, 8192))
+     L2L_SPLIT_WS_MB=n         room for the partial results of K-split GEMMs (default: what the layer's dW GEMMs need)
+     L2L_SPLIT_ATOMICS=1       K-split GEMMs add their partial results with fp32 atomics instead
+     L2L_FORCE_SPLITS=n        split factor of the accumulating fp32 GEMMs (default: by shape)
+     L2L_GEMM_RESIDENT=0       one workgroup per GEMM tile instead of one resident workgroup per compute unit */
 int  l2l_create(const l2l_config*, void* compute_stream, void* copy_stream, l2l_ctx** out);
 int  l2l_destroy(l2l_ctx*);
 /* Device bytes owned by the context (slots + accumulators + workspace): depth-independent. */
 size_t l2l_device_bytes(const l2l_ctx*);
 const char* l2l_last_error(const l2l_ctx*);
-int  l2l_sync(l2l_ctx*);  /* host blocks until both streams are idle */
+/* Host blocks until both streams are idle.  L2L_E_ARG if, since the last call, a kernel met a token id or label
+   outside its range (ids in [0, V), labels < V resp. < num_classes): such ids are clamped on the device, never
+   followed out of a table, and the results computed from them mean nothing. */
+int  l2l_sync(l2l_ctx*);
 
 /* A HIP stream whose kernels run on a subset of the compute units only: of every 32 consecutive bits of
    the CU mask the first `cus_per_32` (1..32) are set, which spreads the subset over all XCDs whichever
@@ -161,8 +171,8 @@ int l2l_embed_fwd(l2l_ctx*, const int32_t* tokens, void* x_out);
    dy_out: device U x [ub,S,H], receives dL/dx (zero at unlabelled positions).
    loss_out: device float[1].  Adds dE and dbv into the embedding-block accumulator. */
 int l2l_head_loss(l2l_ctx*, const void* x_last, const int32_t* labels, void* dy_out, float* loss_out);
-/* ---- sequence-classification head (the task head of the paper's GLUE fine-tuning runs, Section 5; the
-   paper does not write it out, this is the usual BERT one): pooled = tanh(x0 Wp + bp) on the first
+/* ---- sequence-classification head (the task head of the paper's GLUE fine-tuning runs, Sections 3.1 and 3.5,
+   Table 7; the paper does not write it out, this is the usual BERT one): pooled = tanh(x0 Wp + bp) on the first
    token x0 of each sequence, z = pooled Wc + bc, cross-entropy over the sequences with label >= 0,
    normalised by their count over the whole mini-batch.  An alternative to l2l_head_loss; it needs no
    vocabulary.  Packed block (elements of the configured dtype, sub-blocks at multiples of 128):
@@ -212,6 +222,8 @@ int l2l_embed_drain_wait(l2l_ctx*);
 int l2l_embed_grad_drain_part(l2l_ctx*, void* host_grads, long long first, long long count);
 
 /* ---- profiling: HIP-event timing of kernel classes on the compute stream ----------------------
+   (the measurements behind the roofline and overlap figures: Section 2.2's cost model speaks of a layer's compute
+   time C and transfer time X; these calls measure both per class, and how much of X ran under C)
    GEMM = the layer's dense projections (QKV, out-proj, FFN1, FFN2 and their dX / dW GEMMs);
    ATTN = the per-(sequence, head) score/context products and softmax; ROWWISE = LayerNorm, embedding;
    COLSUM = bias / gain gradient reductions; OTHER = head, cross-entropy, fills. */
@@ -234,7 +246,10 @@ int l2l_profile_read(l2l_ctx*, int cls, long long* launches, double* ms, double*
 int l2l_profile_overlap(l2l_ctx*, double merge_gap_ms, double* compute_busy_ms, double* copy_busy_ms, double* copy_hidden_ms,
                         double* span_ms);
 
-/* ---- single operations, for kernel-level parity tests and micro-benchmarks --------------------- */
+/* ---- single operations, for kernel-level parity tests and micro-benchmarks ---------------------
+   The paper names no kernels; these expose the two building blocks of the encoder layer it executes (a projection
+   with its fused epilogue, a LayerNorm: Section 2.1's "encoder layer") one at a time, so that each compiled kernel
+   variant can be checked against its definition without the rest of the layer around it. */
 /* C[M,N] = epilogue(alpha * A B), device pointers, on compute_stream.
    a_kc: 1 = A stored [M,K] (K contiguous, row stride lda); 0 = A stored [K,M] (row stride lda).
    b_kc: 1 = B stored [N,K] (row stride ldb); 0 = B stored [K,N].
@@ -246,6 +261,22 @@ int l2l_profile_overlap(l2l_ctx*, double merge_gap_ms, double* compute_busy_ms, 
 int l2l_op_gemm(l2l_ctx*, int in_dtype, int out_f32, int a_kc, int b_kc, int M, int N, int K,
                 const void* A, long long lda, const void* B, long long ldb, void* C, long long ldc,
                 float alpha, const void* bias, const void* resid, int gelu, int accumulate, int impl);
+/* The same with every epilogue the layer uses.  epi: OR of the L2L_EPI_ flags.
+   resid: [M,N] with row stride ldr, or NULL.
+   L2L_EPI_GELU: GELU after the bias; aux_out (or NULL) receives the pre-activation, [M,N] in in_dtype, row stride ldaux.
+   L2L_EPI_GELUGRAD: the result is multiplied by gelu'(aux), aux: [M,N] in in_dtype, row stride ldaux (the FFN2
+     backward GEMM that turns dG into dU1).  Not together with L2L_EPI_GELU.
+   L2L_EPI_ACCUM: C += result (fp32 C).
+   L2L_EPI_COLSUM: also leaves partial column sums of the stored values: colsum is device fp32 [colsum_rows][N];
+     *colsum_rows_used (host int, may be NULL) receives how many rows were written; their sum over rows is the column
+     sum of C (the bias gradient db1 = colsum(dU1) without a pass over dU1).  Only where the direct-to-LDS MFMA
+     kernel takes the launch with 16-byte aligned rows (impl = 0, 16-bit output): otherwise L2L_E_ARG. */
+enum { L2L_EPI_GELU = 1, L2L_EPI_GELUGRAD = 2, L2L_EPI_ACCUM = 4, L2L_EPI_COLSUM = 8 };
+int l2l_op_gemm_ex(l2l_ctx*, int in_dtype, int out_f32, int a_kc, int b_kc, int M, int N, int K,
+                   const void* A, long long lda, const void* B, long long ldb, void* C, long long ldc,
+                   float alpha, const void* bias, const void* resid, long long ldr, int epi,
+                   const void* aux, void* aux_out, long long ldaux,
+                   float* colsum, long long colsum_rows, int* colsum_rows_used, int impl);
 /* y = LN(x) rows of length n; mean/rstd: device float[rows] or NULL. */
 int l2l_op_layernorm(l2l_ctx*, int dtype, int rows, int n, const void* x, const void* gamma,
                      const void* beta, float eps, void* y, float* mean, float* rstd);

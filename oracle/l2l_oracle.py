@@ -23,7 +23,7 @@ cpu-baseline leg of the benchmark may import it.
 Pins (tests/test_oracle_*.py): central finite differences for every backward
 formula, Algorithm 1 == Algorithm 2 == one concatenated minibatch, closed
 forms for softmax / LayerNorm / GELU / cross-entropy / both heads / Adam / LAMB (plus LAMB's
-step-length and scale invariances), exhaustive bf16 and fp16 round trips with hand-built ties.  Unpinned: end-to-end task accuracy against the paper's Table 7
+step-length and scale invariances), exhaustive bf16 and fp16 round trips with hand-built ties, the two error measures on hand values, the whole layer forward against nested scalar loops.  Unpinned: end-to-end task accuracy against the paper's Table 7
 (needs the GLUE data and pretrained weights) -- parity unpinned.
 """
 from __future__ import annotations
@@ -197,7 +197,7 @@ def head_loss(xL, labels, e, n_lab_total):
 
 
 def cls_head_loss(xL, seq_labels, c, n_lab_total):
-    """Sequence-classification head (the GLUE task head of Section 5's fine-tuning runs; the paper does not
+    """Sequence-classification head (the GLUE task head of the fine-tuning runs of Sections 3.1 and 3.5, Table 7; the paper does not
     write it out: this is the usual BERT one): pooled = tanh(x_[first token] Wp + bp), z = pooled Wc + bc,
     loss contribution = -(1/N) sum_q log softmax(z_q)[label_q] over the sequences with label >= 0, N being
     the labelled count of the WHOLE minibatch.  xL: [n, S, H]; seq_labels: [n].
@@ -457,3 +457,15 @@ def rel_l2(a, b):
     b = np.asarray(b, F64).ravel()
     nb = np.linalg.norm(b)
     return float(np.linalg.norm(a - b) / nb) if nb > 0 else float(np.linalg.norm(a))
+
+
+def max_rel(a, b):
+    """max | a - b | / max | b | with b the oracle value: the largest single error, in units of the tensor's
+    largest entry.  Unlike rel_l2 it cannot be averaged away: a few wrong rows of a large tensor show up in full."""
+    a = np.asarray(a, F64).ravel()
+    b = np.asarray(b, F64).ravel()
+    if a.size == 0:
+        return 0.0
+    mb = float(np.abs(b).max())
+    return float(np.abs(a - b).max() / mb) if mb > 0 else float(np.abs(a).max())
+

@@ -17,6 +17,7 @@ L2L_F32, L2L_BF16, L2L_FP16 = 0, 1, 2
 DTYPES = {"fp32": L2L_F32, "bf16": L2L_BF16, "fp16": L2L_FP16}
 PROF_GEMM, PROF_ATTN, PROF_ROWWISE, PROF_COLSUM, PROF_OTHER = range(5)
 PROF_NAMES = ("gemm", "attn", "rowwise", "colsum", "other", "copy")
+EPI_GELU, EPI_GELUGRAD, EPI_ACCUM, EPI_COLSUM = 1, 2, 4, 8
 
 
 class l2l_config(C.Structure):
@@ -77,6 +78,9 @@ _SIGS = {
                                    C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "l2l_op_gemm": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _P, C.c_longlong,
                               _P, C.c_longlong, _P, C.c_longlong, C.c_float, _P, _P, C.c_int, C.c_int, C.c_int]),
+    "l2l_op_gemm_ex": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _P, C.c_longlong,
+                                 _P, C.c_longlong, _P, C.c_longlong, C.c_float, _P, _P, C.c_longlong, C.c_int, _P, _P,
+                                 C.c_longlong, _P, C.c_longlong, C.POINTER(C.c_int), C.c_int]),
     "l2l_op_layernorm": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, _P, _P, _P, C.c_float, _P, _P, _P]),
     "eps_create": (C.c_int, [C.c_int, C.POINTER(C.c_size_t), C.c_int, C.c_int, C.POINTER(_P)]),
     "eps_destroy": (C.c_int, [_P]),
@@ -303,6 +307,15 @@ class Context:
         self._ck(lib().l2l_op_gemm(self._h, in_dtype, int(out_f32), int(a_kc), int(b_kc), M, N, K, _ptr(A), lda,
                                    _ptr(B), ldb, _ptr(Cm), ldc, alpha, _ptr(bias), _ptr(resid), int(gelu),
                                    int(accumulate), impl))
+
+    def op_gemm_ex(self, in_dtype, out_f32, a_kc, b_kc, M, N, K, A, lda, B, ldb, Cm, ldc, alpha=1.0, bias=None, resid=None,
+                   ldr=0, epi=0, aux=None, aux_out=None, ldaux=0, colsum=None, colsum_rows=0, impl=0) -> int:
+        """returns the number of rows of `colsum` that were written (0 without L2L_EPI_COLSUM)"""
+        used = C.c_int(0)
+        self._ck(lib().l2l_op_gemm_ex(self._h, in_dtype, int(out_f32), int(a_kc), int(b_kc), M, N, K, _ptr(A), lda, _ptr(B), ldb,
+                                      _ptr(Cm), ldc, alpha, _ptr(bias), _ptr(resid), ldr, int(epi), _ptr(aux), _ptr(aux_out),
+                                      ldaux, _ptr(colsum), int(colsum_rows), C.byref(used), impl))
+        return used.value
 
     def op_layernorm(self, dtype, rows, n, x, gamma, beta, eps, y, mean=None, rstd=None):
         self._ck(lib().l2l_op_layernorm(self._h, dtype, rows, n, _ptr(x), _ptr(gamma), _ptr(beta), eps, _ptr(y),

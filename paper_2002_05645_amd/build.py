@@ -53,5 +53,24 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+def build_host_sanitized(kind: str, driver: str, out: str) -> str:
+    """Host-only build of the EPS (csrc/eps.cpp) together with a driver program, under a sanitizer:
+    kind = "address,undefined" or "thread".  No GPU code and no GPU runtime is linked: the driver defines the few HIP
+    runtime functions the EPS calls.  Returns the path of the executable."""
+    if kind not in ("address,undefined", "thread"):
+        raise ValueError("sanitizer: 'address,undefined' or 'thread'")
+    os.makedirs(os.path.dirname(out), exist_ok=True)
+    _run(["g++", "-O1", "-g", "-std=c++17", "-mavx2", "-mfma", "-mf16c", "-fopenmp-simd", f"-fsanitize={kind}", "-fno-omit-frame-pointer",
+          "-D__HIP_PLATFORM_AMD__", f"-I{ROCM}/include", os.path.join(CSRC, "eps.cpp"), driver, "-o", out, "-pthread"])
+    return out
+
+
 if __name__ == "__main__":
+    if len(sys.argv) > 1 and sys.argv[1].startswith("--sanitize="):
+        # python -m paper_2002_05645_amd.build --sanitize=thread  (or address,undefined): builds and runs the EPS driver
+        kind = sys.argv[1].split("=", 1)[1]
+        root = os.path.dirname(PKG)
+        exe = build_host_sanitized(kind, os.path.join(root, "tests", "host", "eps_threads_driver.cpp"),
+                                   os.path.join(PKG, "_build", "eps_threads_" + kind.replace(",", "_")))
+        sys.exit(subprocess.run([exe]).returncode)
     build(verbose=True)

@@ -160,6 +160,8 @@ struct GemmArgs {
   const int* k_dev;       // optional device-side bound on K
   long long split_stride; // direct-to-LDS kernel with K split over grid.y: 0 = the splits add into C with atomics; otherwise
                           // split s stores its partial result at C + s * split_stride (elements) and the caller adds them up
+  int resident;           // direct-to-LDS kernel: > 0 = launch at most this many workgroups (one per compute unit) and let
+                          // each walk its share of the tile order; 0 = one workgroup per tile
   float* colsum;          // EPI_COLSUM: fp32 [ceil(M / WM)][N] (WM = rows of a wave's tile): row r receives the column sums
                           // of the values stored to rows r WM .. r WM + WM - 1 of C (plain stores; the caller adds the rows up)
 };

@@ -38,6 +38,9 @@ class Pool {
   int size() const { return n_; }
   void run(size_t n, const std::function<void(size_t, size_t)>& f) {
     if (n_ == 1 || n < 65536) { f(0, n); return; }
+    // one job at a time: a second caller (the eager-update thread and the training thread may both get here) waits
+    // for the first to finish instead of overwriting its job
+    std::lock_guard<std::mutex> serial(run_mu_);
     {
       std::lock_guard<std::mutex> l(mu_);
       fn_ = &f;
@@ -75,7 +78,7 @@ class Pool {
   }
   int n_;
   std::vector<std::thread> workers_;
-  std::mutex mu_;
+  std::mutex mu_, run_mu_;
   std::condition_variable cv_, done_;
   const std::function<void(size_t, size_t)>* fn_ = nullptr;
   size_t total_ = 0;

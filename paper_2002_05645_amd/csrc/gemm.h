@@ -801,7 +801,8 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
 #pragma unroll
       for (int e = 0; e < 8; ++e) csum8[e] += __shfl_xor(csum8[e], o, WAVE);
     }
-    if (lane < CPR && ncol < N) store8(g.colsum + (long long)((m0 + wm * WM) / WM) * N + ncol, csum8);
+    // (a wave whose rows all lie past M has nothing to report, and the partial-sum matrix has no row for it)
+    if (lane < CPR && ncol < N && m0 + wm * WM < M) store8(g.colsum + (long long)((m0 + wm * WM) / WM) * N + ncol, csum8);
   }
   }   // (the next tile's first barrier comes before anything is loaded over the strips)
 }

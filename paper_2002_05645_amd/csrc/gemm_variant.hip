@@ -1,6 +1,5 @@
 // One tile variant of the 16-bit MFMA GEMM (selected with -DL2L_VARIANT=<index>): all four operand
 // layouts, 16-bit and fp32 outputs.
-#include <cstdlib>
 #include "gemm.h"
 #include "gemm_variants.h"
 
@@ -45,12 +44,7 @@ void launch_direct_one(const GemmArgs& g, hipStream_t s, int splits) {
     return true;
   }();
   (void)once;
-  static const int num_cus = [] {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n = 0;
-    if (const char* e = getenv("L2L_GEMM_RESIDENT")) if (atoi(e) == 0) n = 0;   // 0: one workgroup per tile
-    return n / 8 * 8;   // a multiple of the 8 XCDs keeps each resident workgroup's tiles on its own XCD's range
-  }();
+  const int num_cus = g.resident / 8 * 8;   // a multiple of the 8 XCDs keeps each resident workgroup's tiles on its own XCD's range
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
   // more tiles than CUs: one resident workgroup per CU walks the tile order (the kernel's loop)
   const int gx = (num_cus > 0 && splits == 1 && g.nbatch == 1 && tiles > num_cus) ? num_cus : tiles;

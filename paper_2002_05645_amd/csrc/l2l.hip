@@ -138,7 +138,12 @@ struct l2l_ctx {
   Layout lay;
   hipStream_t cs = nullptr, xs = nullptr;  // compute, copy
   int group = 1;                            // micro-batches per launch
+  // tuning and test switches, read from the environment once, by l2l_create (see include/l2l.h)
   int no_fused_attention = 0;               // L2L_NO_FUSED_ATTENTION=1: use the batched-GEMM attention path
+  int force_splits = 0;                     // L2L_FORCE_SPLITS=n: split factor of the accumulating fp32 GEMMs
+  int split_atomics = 0;                    // L2L_SPLIT_ATOMICS=1: K splits add with atomics, not through the workspace
+  int resident_cus = 0;                     // workgroups of a resident GEMM launch (CUs of the device; L2L_GEMM_RESIDENT=0: none)
+  int32_t* bad_ids = nullptr;               // device flag: a token id or label outside the vocabulary was seen
   long long T = 0, Mg = 0;                  // tokens per micro-batch, rows per launch group
   size_t dev_bytes = 0;
   std::vector<void*> allocs;
@@ -305,6 +310,13 @@ bool mfma_ok(const GemmArgs& g) {
   if (g.a_kc ? g.lda < k8 : g.lda < m8) return false;
   if (g.b_kc ? g.ldb < k8 : g.ldb < n8) return false;
   if (g.a_kc && g.b_kc && g.K % 8) return false;  // nobody guarantees zero padding in both
+  // The kernels address an operand panel through a 32-bit buffer descriptor, with 0x80000000 as the offset that is
+  // out of range for sure: every panel (one batch entry's operand, seen from its first element) must end below
+  // 2 GiB, and the offsets of the K-strided loads that run up to three k-tiles past the end must not wrap.
+  const long long lim = (1LL << 31) - 1;
+  const long long ea = g.a_kc ? (long long)(g.M - 1) * g.lda + k8 : (long long)(g.K + 192) * g.lda + m8;
+  const long long eb = g.b_kc ? (long long)(g.N - 1) * g.ldb + k8 : (long long)(g.K + 192) * g.ldb + n8;
+  if (ea * 2 > lim || eb * 2 > lim) return false;
   return true;
 }
 
@@ -330,8 +342,6 @@ void launch_plain(const GemmArgs& g, hipStream_t s) {
   dim3 grid((g.N + 63) / 64, (g.M + 63) / 64, g.nbatch);
   hipLaunchKernelGGL((gemm_plain_kernel<T, TC>), grid, dim3(256), 0, s, g);
 }
-
-int g_force_splits = 0;  // tuning override
 
 // tile variant and split-K factor for one launch
 void pick_tile(const GemmArgs& g, bool out_f32, int* variant, int* splits) {
@@ -369,6 +379,28 @@ bool colsum_in_gemm_ok(int dtype, bool out_f32, const GemmArgs& g, int* rows = n
   return gemm_vec_ok(g, g.epi | EPI_COLSUM, g.C);
 }
 
+// An accumulating fp32 GEMM split over K whose splits store their partial tiles in `ws` (fp32, room for ws_elems
+// elements; `splits` dense [M, N] slices, every element of every slice written) and are then added into C by one
+// kernel.  Returns false, with nothing launched, where the shape, the tile variant or the room do not allow it.
+enum { SPLIT_NOT_APPLICABLE = 0, SPLIT_LAUNCHED = 1, SPLIT_NO_ROOM = 2 };
+int launch_split_through_workspace(int v, const GemmArgs& g, hipStream_t s, int splits, bool out_f32, bool fp16_in, float* ws,
+                                   size_t ws_elems) {
+  const long long slice = (long long)g.M * g.N;
+  if (!(splits > 1 && out_f32 && g.epi == EPI_ACCUM && kTiles[v].direct && g.nbatch == 1 && g.N % 8 == 0 && g.ldc % 4 == 0 &&
+        ((uintptr_t)g.C & 15) == 0 && ws && !g.m_dev && !g.k_dev))
+    return SPLIT_NOT_APPLICABLE;
+  const int nk = (g.K + kTiles[v].bk - 1) / kTiles[v].bk, per = (nk + splits - 1) / splits;
+  splits = (nk + per - 1) / per;   // no empty split: every slice of the workspace gets written
+  if (splits <= 1) return SPLIT_NOT_APPLICABLE;
+  if ((size_t)splits * slice > ws_elems) return SPLIT_NO_ROOM;
+  GemmArgs p = g;
+  p.C = ws; p.ldc = g.N; p.split_stride = slice; p.epi = 0;
+  launch_mfma_variant(v, p, s, splits, out_f32, fp16_in);
+  const unsigned blocks = (unsigned)std::min<long long>((slice / 4 + 255) / 256, 4096);
+  hipLaunchKernelGGL(split_sum_kernel, dim3(blocks), dim3(256), 0, s, ws, splits, (long long)g.M, g.N, (float*)g.C, g.ldc);
+  return SPLIT_LAUNCHED;
+}
+
 // impl: 0 auto, 1 plain, 2 mfma (auto tile), 100 + v: mfma tile variant v (tuning)
 int gemm(l2l_ctx* c, int dtype, bool out_f32, const GemmArgs& g, int impl = 0, int cls = L2L_PROF_GEMM) {
   if (g.M <= 0 || g.N <= 0 || g.nbatch <= 0) return L2L_OK;
@@ -388,27 +420,17 @@ int gemm(l2l_ctx* c, int dtype, bool out_f32, const GemmArgs& g, int impl = 0, i
       pick_tile(g, out_f32, &v, &splits);
       if (impl >= 100) v = impl - 100;
       if (kTiles[v].direct && !g.a_kc && g.b_kc) v = 3;   // no direct-to-LDS kernel for A K-strided with B K-contiguous
-      if (const char* e = getenv("L2L_FORCE_SPLITS")) g_force_splits = atoi(e);
-      if (g_force_splits > 0 && out_f32 && g.epi == EPI_ACCUM) splits = g_force_splits;
+      if (c->force_splits > 0 && out_f32 && g.epi == EPI_ACCUM) splits = c->force_splits;
+      GemmArgs gr = g;
+      gr.resident = c->resident_cus;
       // K split over grid.y: with a workspace the splits store their partial tiles (16-byte stores) and one kernel
       // adds them into C; without, they add into C with fp32 atomics, which run at the L2's atomic rate (65536 per
       // workgroup: 40 % of the time of a 1024 x 1024 x 32768 GEMM) and in no fixed order
-      const long long slice = (long long)g.M * g.N;
-      if (splits > 1 && kTiles[v].direct && g.nbatch == 1 && g.N % 8 == 0 && g.ldc % 4 == 0 && ((uintptr_t)g.C & 15) == 0 &&
-          c->split_ws && !getenv("L2L_SPLIT_ATOMICS")) {
-        const int nk = (g.K + kTiles[v].bk - 1) / kTiles[v].bk, per = (nk + splits - 1) / splits;
-        splits = (nk + per - 1) / per;   // no empty split: every slice of the workspace gets written
-        if (splits > 1 && (size_t)splits * slice <= c->split_ws_elems) {
-          GemmArgs p = g;
-          p.C = c->split_ws; p.ldc = g.N; p.split_stride = slice; p.epi = 0;
-          launch_mfma_variant(v, p, c->cs, splits, out_f32, dtype == L2L_FP16);
-          const unsigned blocks = (unsigned)std::min<long long>((slice / 4 + 255) / 256, 4096);
-          hipLaunchKernelGGL(split_sum_kernel, dim3(blocks), dim3(256), 0, c->cs, c->split_ws, splits, (long long)g.M, g.N,
-                             (float*)g.C, g.ldc);
-          return;
-        }
-      }
-      launch_mfma_variant(v, g, c->cs, splits, out_f32, dtype == L2L_FP16);
+      if (c->split_ws && !c->split_atomics &&
+          launch_split_through_workspace(v, gr, c->cs, splits, out_f32, dtype == L2L_FP16, c->split_ws, c->split_ws_elems) ==
+              SPLIT_LAUNCHED)
+        return;
+      launch_mfma_variant(v, gr, c->cs, splits, out_f32, dtype == L2L_FP16);
     } else if (dtype == L2L_BF16) {
       if (out_f32) launch_plain<bf16, float>(g, c->cs);
       else launch_plain<bf16, bf16>(g, c->cs);
@@ -470,7 +492,7 @@ int ln_bwd(l2l_ctx* c, const void* dy, const void* x, const float* mean, const f
     dim3 grid((n + 127) / 128, (unsigned)((rows + COLSUM_ROWS - 1) / COLSUM_ROWS));
     hipLaunchKernelGGL((colsum_kernel<T, 1>), grid, dim3(256), 0, c->cs, (const T*)dy, (long long)n, (const T*)x, mean, rstd,
                        (const int32_t*)nullptr, (const T*)nullptr, (const T*)nullptr, 0, dgamma, dbeta, (int)rows, n,
-                       (const int*)nullptr);
+                       (const int*)nullptr, 0);
   }));
   return bias_grad<T>(c, dx, n, dbias, rows, n);
 }
@@ -482,7 +504,7 @@ int bias_grad(l2l_ctx* c, const void* a, long long lda, float* out, long long ro
     dim3 grid((n + 127) / 128, (unsigned)((rows + COLSUM_ROWS - 1) / COLSUM_ROWS));
     hipLaunchKernelGGL((colsum_kernel<T, 0>), grid, dim3(256), 0, c->cs, (const T*)a, lda, (const T*)nullptr,
                        (const float*)nullptr, (const float*)nullptr, (const int32_t*)nullptr, (const T*)nullptr,
-                       (const T*)nullptr, 0, (float*)nullptr, out, (int)rows, n, rows_dev);
+                       (const T*)nullptr, 0, (float*)nullptr, out, (int)rows, n, rows_dev, 0);
   });
 }
 
@@ -763,7 +785,7 @@ int embed_fwd_t(l2l_ctx* c, const int32_t* tokens, void* x_out) {
   return timed(c, L2L_PROF_ROWWISE, 0, 2.0 * rows * H * sizeof(T), [&] {
     hipLaunchKernelGGL(embed_fwd_kernel<T>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, c->cs, tokens, E + eo[E_E],
                        E + eo[E_P], E + eo[E_GE], E + eo[E_BE], (T*)x_out, c->emean, c->erstd, (int)rows, c->cfg.seq, H,
-                       c->cfg.ln_eps);
+                       c->cfg.ln_eps, c->cfg.vocab, c->bad_ids);
   });
 }
 
@@ -806,7 +828,7 @@ int head_loss_t(l2l_ctx* c, const void* x_last, const int32_t* labels, void* dy_
     L2L_TRY(gemm(c, dt, true, g, 0, L2L_PROF_OTHER));
     L2L_TRY(timed(c, L2L_PROF_OTHER, 0, 0, [&] {
       hipLaunchKernelGGL(ce_kernel<T>, dim3(rows), dim3(256), 0, c->cs, c->logits, Vp, labels, idx, cnt, c->lab_total, (T*)c->dz,
-                         loss_out, V, (int)Vp, c->loss_scale);
+                         loss_out, V, (int)Vp, c->loss_scale, c->bad_ids);
     }));
     // dXl = dz E
     if constexpr (sizeof(T) == 2) {
@@ -852,13 +874,13 @@ int embed_bwd_t(l2l_ctx* c, const int32_t* tokens, const void* dy) {
     const size_t lds = (size_t)(turned ? 5 : 1) * H * sizeof(float);
     static_cast<void>(hipFuncSetAttribute((const void*)embed_bwd_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     hipLaunchKernelGGL(embed_bwd_kernel<T>, dim3((unsigned)S * ((nseq + EMB_SEQS - 1) / EMB_SEQS)), dim3(256), lds, c->cs, tokens, E + eo[E_E], E + eo[E_P],
-                       E + eo[E_GE], (const T*)dy, c->emean, c->erstd, c->egacc + eo[E_E], c->egacc + eo[E_P], (int)rows, S, H, turned);
+                       E + eo[E_GE], (const T*)dy, c->emean, c->erstd, c->egacc + eo[E_E], c->egacc + eo[E_P], (int)rows, S, H, turned, c->cfg.vocab);
   }));
   return timed(c, L2L_PROF_COLSUM, 0, 0, [&] {
     dim3 grid((H + 127) / 128, (unsigned)((rows + COLSUM_ROWS - 1) / COLSUM_ROWS));
     hipLaunchKernelGGL((colsum_kernel<T, 2>), grid, dim3(256), 0, c->cs, (const T*)dy, (long long)H, (const T*)nullptr, c->emean,
                        c->erstd, tokens, E + eo[E_E], E + eo[E_P], S, c->egacc + eo[E_GE], c->egacc + eo[E_BE], (int)rows, H,
-                       (const int*)nullptr);
+                       (const int*)nullptr, c->cfg.vocab);
   });
 }
 
@@ -892,7 +914,7 @@ int cls_head_t(l2l_ctx* c, const void* x_last, const int32_t* seq_labels, void* 
   L2L_TRY(gemm(c, dt, true, z, 0, L2L_PROF_OTHER));
   L2L_TRY(timed(c, L2L_PROF_OTHER, 0, 0, [&] {
     hipLaunchKernelGGL(cls_ce_kernel<T>, dim3(1), dim3(256), 0, c->cs, c->cls_z, Cp, seq_labels, (T*)c->cls_dz, loss_out, nseq, C,
-                       c->loss_scale);
+                       c->loss_scale, c->bad_ids);
   }));
   // dWc += pooled^T dz ; dbc += colsum(dz) ; dpooled = dz Wc^T
   GemmArgs wc = gemm_args(H, C, nseq, c->cls_p, H, 0, c->cls_dz, Cp, 0, G + o[C_WC], C);
@@ -949,10 +971,11 @@ int l2l_create(const l2l_config* cfg, void* compute_stream, void* copy_stream, l
   c->xs = (hipStream_t)copy_stream;
   c->T = (long long)cfg->ubatch * cfg->seq;
   int g = cfg->ubatch_group;
-  if (g == 0) {  // default: as many micro-batches per launch as keep a launch within 32768 rows
-    g = 1;
+  if (g == 0) {  // default: as many micro-batches per launch as keep a launch within 32768 rows and its widest
+    g = 1;       // activation below the 2 GiB that the MFMA kernels' 32-bit operand addressing covers
+    const long long widest = std::max<long long>(cfg->ffn, 3LL * cfg->hidden) * 2;
     for (int k = 1; k <= cfg->num_ubatches; ++k)
-      if (cfg->num_ubatches % k == 0 && k * c->T <= 32768) g = k;
+      if (cfg->num_ubatches % k == 0 && k * c->T <= 32768 && k * c->T * widest < (1LL << 31)) g = k;
   }
   // attention launches batch (sequence, head) pairs along grid z
   while (g > 1 && (long long)g * cfg->ubatch * cfg->heads > 65535) --g;
@@ -962,7 +985,17 @@ int l2l_create(const l2l_config* cfg, void* compute_stream, void* copy_stream, l
   }
   c->group = g;
   c->Mg = g * c->T;
+  // the switches of the environment are read here, once, and nowhere else
   if (const char* e = getenv("L2L_NO_FUSED_ATTENTION")) c->no_fused_attention = atoi(e) != 0;
+  if (const char* e = getenv("L2L_FORCE_SPLITS")) c->force_splits = std::max(0, atoi(e));
+  if (const char* e = getenv("L2L_SPLIT_ATOMICS")) c->split_atomics = atoi(e) != 0;
+  {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n = 0;
+    (void)hipGetLastError();
+    c->resident_cus = n;
+    if (const char* e = getenv("L2L_GEMM_RESIDENT")) if (atoi(e) == 0) c->resident_cus = 0;
+  }
   (void)hipFuncSetAttribute((const void*)attn::attn_bwd_kernel<bf16>, hipFuncAttributeMaxDynamicSharedMemorySize, attn::BWD_LDS);
   (void)hipFuncSetAttribute((const void*)attn::attn_bwd_kernel<fp16>, hipFuncAttributeMaxDynamicSharedMemorySize, attn::BWD_LDS);
   *out = c;  // from here on the caller can read l2l_last_error and must l2l_destroy
@@ -1010,6 +1043,8 @@ int l2l_create(const l2l_config* cfg, void* compute_stream, void* copy_stream, l
     c->colsum_ws_elems = (size_t)((Mg + 63) / 64) * std::max(F, 3 * H);
     L2L_TRY(dev_alloc(c, (void**)&c->colsum_ws, c->colsum_ws_elems * 4));
   }
+  L2L_TRY(dev_alloc(c, (void**)&c->bad_ids, 4));
+  HIP_TRY(c, hipMemset(c->bad_ids, 0, 4));
   float** stats[] = {&c->mean1, &c->rstd1, &c->mean2, &c->rstd2};
   for (auto s : stats) L2L_TRY(dev_alloc(c, (void**)s, Mg * 4));
   if (fused_attention_long_ok(c)) {   // per (sequence, head, query): log-sum-exp of the scores, rowsum(dO O)
@@ -1057,7 +1092,8 @@ int l2l_destroy(l2l_ctx* c) {
   for (auto e : c->ev_pool) (void)hipEventDestroy(e);
   hipEvent_t evs[] = {c->slot_staged[0], c->slot_staged[1], c->slot_released[0], c->slot_released[1], c->gacc_ready[0],
                       c->gacc_ready[1], c->gacc_drained[0], c->gacc_drained[1], c->gacc_landed[0], c->gacc_landed[1], c->egacc_landed, c->emb_staged_ev, c->emb_released_ev,
-                      c->egacc_ready, c->egacc_drained};
+                      c->egacc_ready, c->egacc_drained, c->cls_staged_ev, c->cls_released_ev, c->cls_ready, c->cls_landed, c->cls_drained,
+                      c->prof_base};
   for (hipEvent_t e : evs)
     if (e) (void)hipEventDestroy(e);
   delete c;
@@ -1071,6 +1107,15 @@ int l2l_sync(l2l_ctx* c) {
   if (!c) return L2L_E_ARG;
   HIP_TRY(c, hipStreamSynchronize(c->cs));
   HIP_TRY(c, hipStreamSynchronize(c->xs));
+  if (c->bad_ids) {   // set by the embedding and loss kernels, which clamp such ids instead of following them
+    int32_t bad = 0;
+    HIP_TRY(c, hipMemcpy(&bad, c->bad_ids, 4, hipMemcpyDeviceToHost));
+    if (bad) {
+      HIP_TRY(c, hipMemset(c->bad_ids, 0, 4));
+      return fail(c, L2L_E_ARG, "a token id or label outside its range (vocabulary %d, or the head's classes) was passed since the last l2l_sync; such ids are clamped and the results are not meaningful",
+                  c->cfg.vocab);
+    }
+  }
   return L2L_OK;
 }
 
@@ -1519,23 +1564,47 @@ int l2l_profile_read(l2l_ctx* c, int cls, long long* launches, double* ms, doubl
 }
 
 // ---- single operations ---------------------------------------------------------------------------
-int l2l_op_gemm(l2l_ctx* c, int in_dtype, int out_f32, int a_kc, int b_kc, int M, int N, int K, const void* A, long long lda,
-                const void* B, long long ldb, void* C, long long ldc, float alpha, const void* bias, const void* resid, int gelu,
-                int accumulate, int impl) {
+int l2l_op_gemm_ex(l2l_ctx* c, int in_dtype, int out_f32, int a_kc, int b_kc, int M, int N, int K, const void* A, long long lda,
+                   const void* B, long long ldb, void* C, long long ldc, float alpha, const void* bias, const void* resid,
+                   long long ldr, int epi, const void* aux, void* aux_out, long long ldaux, float* colsum, long long colsum_rows,
+                   int* colsum_rows_used, int impl) {
   if (!c) return L2L_E_ARG;
   if (!A || !B || !C) return fail(c, L2L_E_ARG, "l2l_op_gemm: null pointer");
   if (M < 0 || N < 0 || K < 0 || lda <= 0 || ldb <= 0 || ldc < N) return fail(c, L2L_E_ARG, "l2l_op_gemm: bad shape");
   if (in_dtype != L2L_F32 && in_dtype != L2L_BF16 && in_dtype != L2L_FP16) return fail(c, L2L_E_ARG, "l2l_op_gemm: bad dtype");
   if (in_dtype == L2L_F32) out_f32 = 1;
-  if (accumulate && !out_f32) return fail(c, L2L_E_ARG, "l2l_op_gemm: accumulate needs an fp32 output");
+  if (epi & ~(L2L_EPI_GELU | L2L_EPI_GELUGRAD | L2L_EPI_ACCUM | L2L_EPI_COLSUM)) return fail(c, L2L_E_ARG, "l2l_op_gemm: unknown epilogue flag in %d", epi);
+  if ((epi & L2L_EPI_ACCUM) && !out_f32) return fail(c, L2L_E_ARG, "l2l_op_gemm: accumulate needs an fp32 output");
   if (impl < 0 || (impl > 2 && impl < 100)) return fail(c, L2L_E_ARG, "l2l_op_gemm: impl %d", impl);
+  if (resid && ldr < N) return fail(c, L2L_E_ARG, "l2l_op_gemm: residual row stride %lld < N", ldr);
+  if ((epi & L2L_EPI_GELUGRAD) && (!aux || ldaux < N)) return fail(c, L2L_E_ARG, "l2l_op_gemm: GELU' needs the pre-activation and its row stride");
+  if ((epi & L2L_EPI_GELU) && aux_out && ldaux < N) return fail(c, L2L_E_ARG, "l2l_op_gemm: pre-activation row stride %lld < N", ldaux);
+  if ((epi & L2L_EPI_GELU) && (epi & L2L_EPI_GELUGRAD)) return fail(c, L2L_E_ARG, "l2l_op_gemm: GELU and GELU' share the pre-activation stride: one of them per call");
   GemmArgs g = gemm_args(M, N, K, A, lda, a_kc != 0, B, ldb, b_kc != 0, C, ldc);
   g.alpha = alpha;
   if (bias) { g.epi |= EPI_BIAS; g.bias = bias; }
-  if (gelu) g.epi |= EPI_GELU;
-  if (resid) { g.epi |= EPI_RESID; g.resid = resid; g.ldr = ldc; }
-  if (accumulate) g.epi |= EPI_ACCUM;
+  if (epi & L2L_EPI_GELU) { g.epi |= EPI_GELU; g.aux_out = aux_out; g.ldaux = ldaux; }
+  if (epi & L2L_EPI_GELUGRAD) { g.epi |= EPI_GELUGRAD; g.aux = aux; g.ldaux = ldaux; }
+  if (resid) { g.epi |= EPI_RESID; g.resid = resid; g.ldr = ldr; }
+  if (epi & L2L_EPI_ACCUM) g.epi |= EPI_ACCUM;
+  if (colsum_rows_used) *colsum_rows_used = 0;
+  if (epi & L2L_EPI_COLSUM) {
+    int rows = 0;
+    g.colsum = colsum;
+    if (!colsum || impl != 0 || M == 0 || N == 0 || !colsum_in_gemm_ok(in_dtype, out_f32 != 0, g, &rows))
+      return fail(c, L2L_E_ARG, "l2l_op_gemm: column sums are not available for this shape, layout or implementation");
+    if (rows > colsum_rows) return fail(c, L2L_E_ARG, "l2l_op_gemm: column sums need %d rows, the buffer has %lld", rows, colsum_rows);
+    if (colsum_rows_used) *colsum_rows_used = rows;
+    g.epi |= EPI_COLSUM;
+  }
   return gemm(c, in_dtype, out_f32 != 0, g, impl);
+}
+
+int l2l_op_gemm(l2l_ctx* c, int in_dtype, int out_f32, int a_kc, int b_kc, int M, int N, int K, const void* A, long long lda,
+                const void* B, long long ldb, void* C, long long ldc, float alpha, const void* bias, const void* resid, int gelu,
+                int accumulate, int impl) {
+  return l2l_op_gemm_ex(c, in_dtype, out_f32, a_kc, b_kc, M, N, K, A, lda, B, ldb, C, ldc, alpha, bias, resid, ldc,
+                        (gelu ? L2L_EPI_GELU : 0) | (accumulate ? L2L_EPI_ACCUM : 0), nullptr, nullptr, 0, nullptr, 0, nullptr, impl);
 }
 
 int l2l_op_layernorm(l2l_ctx* c, int dtype, int rows, int n, const void* x, const void* gamma, const void* beta, float eps, void* y,

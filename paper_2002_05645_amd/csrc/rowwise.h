@@ -76,11 +76,17 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T* x, const T* gamma,
 template <typename T>
 __global__ __launch_bounds__(256) void embed_fwd_kernel(const int32_t* tokens, const T* E, const T* pos, const T* gamma,
                                                         const T* beta, T* y, float* mean_out, float* rstd_out, int rows,
-                                                        int S, int n, float eps) {
+                                                        int S, int n, float eps, int V, int32_t* bad_ids) {
   const int lane = threadIdx.x & 63;
   const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (r >= rows) return;
-  EmbedRow<T> row{E + (long long)tokens[r] * n, pos + (long long)(r % S) * n};
+  // an id outside the vocabulary is reported through the flag and clamped, never followed out of the table
+  int tok = tokens[r];
+  if (tok < 0 || tok >= V) {
+    if (lane == 0) atomicOr(bad_ids, 1);
+    tok = min(max(tok, 0), V - 1);
+  }
+  EmbedRow<T> row{E + (long long)tok * n, pos + (long long)(r % S) * n};
   float mean, rstd;
   row_stats(row, n, eps, lane, mean, rstd);
   ln_write<T>(row, n, lane, mean, rstd, gamma, beta, y + (long long)r * n);
@@ -266,7 +272,7 @@ constexpr int EMB_SEQS = 16;
 template <typename T>
 __global__ __launch_bounds__(256) void embed_bwd_kernel(const int32_t* tokens, const T* E, const T* pos, const T* gamma,
                                                         const T* dy, const float* mean, const float* rstd, float* dE,
-                                                        float* dpos, int rows, int S, int n, bool turned) {
+                                                        float* dpos, int rows, int S, int n, bool turned, int V) {
   extern __shared__ float pos_acc[];   // n floats, then (turned) one row of n floats per wave
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int s = blockIdx.x % S, grp = blockIdx.x / S;
@@ -277,7 +283,7 @@ __global__ __launch_bounds__(256) void embed_bwd_kernel(const int32_t* tokens, c
   float* tw = pos_acc + (long long)(1 + w) * n;
   for (int q = grp * EMB_SEQS + w; q < q1; q += 4) {
     const int r = q * S + s;
-    const long long tok = tokens[r];
+    const long long tok = min(max(tokens[r], 0), V - 1);   // (clamped as in the forward kernel, which reports it)
     EmbedRow<T> row{E + tok * n, pos + (long long)s * n};
     float* de = dE + tok * n;
     if (turned) {
@@ -319,7 +325,7 @@ template <typename T, int MODE>
 __global__ __launch_bounds__(256) void colsum_kernel(const T* a, long long lda, const T* x, const float* mean,
                                                      const float* rstd, const int32_t* tokens, const T* E, const T* pos,
                                                      int S, float* out_a, float* out_b, int rows, int n,
-                                                     const int* rows_dev) {
+                                                     const int* rows_dev, int V) {
   __shared__ float red[4][2][128];
   if (rows_dev) rows = min(rows, *rows_dev);
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -339,7 +345,7 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T* a, long long lda, 
           x0 = to_f32(x[(long long)r * n + j]);
           x1 = to_f32(x[(long long)r * n + j + 1]);
         } else {
-          const long long tok = tokens[r];
+          const long long tok = min(max(tokens[r], 0), V - 1);
           const int s = r % S;
           x0 = to_f32(E[tok * n + j]) + to_f32(pos[(long long)s * n + j]);
           x1 = to_f32(E[tok * n + j + 1]) + to_f32(pos[(long long)s * n + j + 1]);
@@ -458,7 +464,7 @@ __global__ __launch_bounds__(256) void rows_by_index_kernel(const T* src, T* dst
 template <typename T>
 __global__ __launch_bounds__(256) void ce_kernel(const float* z, long long ldz, const int32_t* labels,
                                                  const int32_t* idx, const int32_t* cnt, const int32_t* total, T* dz,
-                                                 float* loss, int V, int Vp, float scale) {
+                                                 float* loss, int V, int Vp, float scale, int32_t* bad_ids) {
   __shared__ float red[4];
   const int i = blockIdx.x;
   if (i >= *cnt) return;
@@ -478,7 +484,11 @@ __global__ __launch_bounds__(256) void ce_kernel(const float* z, long long ldz, 
   __syncthreads();
   s = red[0] + red[1] + red[2] + red[3];
   const float inv_n = 1.0f / (float)(*total);
-  const int label = labels[idx[i]];
+  int label = labels[idx[i]];    // >= 0: the row is in the list of labelled rows
+  if (label >= V) {
+    if (t == 0) atomicOr(bad_ids, 1);
+    label = V - 1;
+  }
   const float lse = mx + __logf(s);
   if (t == 0) atomicAdd(loss, (lse - row[label]) * inv_n);
   T* d = dz + (long long)i * Vp;
@@ -528,7 +538,7 @@ __global__ __launch_bounds__(256) void tanh_kernel(const T* x, const T* t, T* y,
 // dz = scale * (softmax(z) - onehot) / N in T, zero for unlabelled sequences and in the padding columns.
 template <typename T>
 __global__ __launch_bounds__(256) void cls_ce_kernel(const float* z, int ldz, const int32_t* labels, T* dz, float* loss,
-                                                     int nseq, int C, float scale) {
+                                                     int nseq, int C, float scale, int32_t* bad_ids) {
   __shared__ int cnt[4];
   __shared__ float part[4];
   const int t = threadIdx.x, lane = t & 63, w = t >> 6;
@@ -543,7 +553,11 @@ __global__ __launch_bounds__(256) void cls_ce_kernel(const float* z, int ldz, co
   for (int q = t; q < nseq; q += 256) {
     const float* row = z + (long long)q * ldz;
     T* d = dz + (long long)q * ldz;
-    const int label = labels[q];
+    int label = labels[q];
+    if (label >= C) {   // reported and clamped, never followed past the row
+      atomicOr(bad_ids, 1);
+      label = C - 1;
+    }
     if (label < 0) {
       for (int j = 0; j < ldz; ++j) d[j] = from_f32<T>(0.f);
       continue;

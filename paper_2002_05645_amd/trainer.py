@@ -6,7 +6,6 @@ weights and Adam state, ships the configured dtype, and receives fp32 gradients 
 """
 from __future__ import annotations
 
-import os
 import queue
 import threading
 
@@ -68,7 +67,7 @@ class L2LTrainer:
         # Backward: the host enqueues at most this many layers ahead of the device (0: no limit).  Measured on
         # this runtime: gradient drains that are queued far ahead of their turn are carried out by a copy path
         # that moves 12.5 GB/s instead of 20 .. 54 GB/s, which makes deep models copy-bound.
-        self.run_ahead = int(os.environ.get("L2L_RUN_AHEAD", run_ahead))
+        self.run_ahead = int(run_ahead)
         self.L, self.H, self.S, self.V = layers, hidden, seq, vocab
         self.U, self.ub = num_ubatches, ubatch
         self.dtype = dtype
@@ -105,7 +104,6 @@ class L2LTrainer:
         torch.cuda.set_device(self.device)
         self.compute = torch.cuda.Stream(device=self.device)
         self._copy_handle = None
-        copy_cus = int(os.environ.get("L2L_COPY_CUS", copy_cus))
         if copy_cus > 0:
             # the runtime's copy kernels (stages, drains, stash traffic) confined to copy_cus of every 32 CUs
             self._copy_handle = B.stream_create_cu_masked(copy_cus)
@@ -159,7 +157,6 @@ class L2LTrainer:
         # static in eager mode, so its unscale-and-check runs piece by piece as well.)
         self._parts = []
         self._prestaged = False
-        tail_parts = int(os.environ.get("L2L_TAIL_PARTS", tail_parts))
         if eager and optimizer == "adam" and tail_parts > 1:
             step = -(-self.embed_elems // tail_parts)
             step = -(-step // 256) * 256     # (whole kilobytes of fp32)
@@ -251,10 +248,14 @@ class L2LTrainer:
             self._after_drain(1 + L)
         else:
             c.head_loss(self._stash_slot(L), labels, self.dy, self.loss_dev)
+        if host_mode:
+            # the head is the consumer of the transit slot that holds layer L - 1's output: the reload of
+            # layer L - 2's input into that slot must wait for it
+            self.stash_free[L % 2].record(self.compute)
         for l in reversed(range(L)):
             if l - 1 >= 0:
                 c.param_stage(l - 1, e.ship_ptr(l), (l - 1) % 2)
-            if host_mode:
+            if host_mode and l < L - 1:      # (layer L - 1's input is still in its slot from the forward pass)
                 self._reload(l)
             if self.run_ahead and l + self.run_ahead < L:
                 self._bwd_done[l + self.run_ahead].synchronize()
@@ -375,7 +376,12 @@ class L2LTrainer:
                 self._prestaged = self._worker_error is None
             self._work.join()             # every block was queued by device_pipeline; wait for the stragglers
             if self._worker_error is not None:
-                raise self._worker_error
+                # Blocks that were updated before the failure keep their update (an eager update cannot be taken
+                # back) while t is not advanced: after an overflow the caller lowers loss_scale and reloads the
+                # parameters, or goes on knowing that those blocks are one step ahead.
+                err, self._worker_error = self._worker_error, None
+                self._prestaged = False
+                raise err
             self.t += 1
             return
         if self.grad_dtype != "fp32" and not self._adam_from16:

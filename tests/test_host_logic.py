@@ -366,3 +366,17 @@ def test_fast_gelu_polynomials_match_exact_functions():
     big = np.abs(u) > 6                                              # tails: the limits, to fp32 rounding
     assert np.abs(gelu[big] - np.maximum(u[big], 0)).max() <= 1e-6 * 20
     assert np.abs(dgelu[big] - (u[big] > 0)).max() <= 1e-5
+
+
+@pytest.mark.parametrize("kind", ["address,undefined", "thread"])
+def test_eps_under_sanitizers_with_two_calling_threads(kind, tmp_path):
+    # csrc/eps.cpp built for the host alone under ASan + UBSan and under TSan, driven by two threads that call into one
+    # store at the same time (the trainer's eager-update thread and its main thread): no finding, and the same
+    # results as the same calls made in sequence
+    import subprocess
+    from paper_2002_05645_amd import build as bld
+    exe = bld.build_host_sanitized(kind, os.path.join(ROOT, "tests", "host", "eps_threads_driver.cpp"), str(tmp_path / "eps_threads"))
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "eps threads driver: ok" in r.stdout
+    assert "Sanitizer" not in r.stderr, r.stderr

@@ -425,3 +425,74 @@ def test_l2l_with_cls_head_equals_one_concatenated_minibatch():
         for k in a:
             assert np.allclose(a[k], b[k], rtol=1e-11, atol=1e-14), k
     assert not gemb["bv"].any()                               # the LM head is not in this graph
+
+
+def test_error_measures_on_hand_values():
+    # rel_l2 and max_rel are what every parity verdict rests on: values worked out by hand
+    b = np.array([3.0, 4.0, 0.0, 0.0])                      # ||b|| = 5, max |b| = 4
+    a = np.array([3.0, 4.0, 0.0, 1.0])                      # one entry off by 1
+    assert O.rel_l2(a, b) == pytest.approx(1.0 / 5.0, rel=1e-15)
+    assert O.max_rel(a, b) == pytest.approx(1.0 / 4.0, rel=1e-15)
+    assert O.rel_l2(b, b) == 0.0 and O.max_rel(b, b) == 0.0
+    assert O.rel_l2(2 * b, b) == pytest.approx(1.0) and O.max_rel(2 * b, b) == pytest.approx(1.0)
+    assert O.rel_l2(-b, b) == pytest.approx(2.0)            # a sign flip is an error of 2, not 0
+    # the measures are not symmetric: the second argument is the reference
+    assert O.rel_l2(b, 2 * b) == pytest.approx(0.5) and O.max_rel(b, 2 * b) == pytest.approx(0.5)
+    # zero reference: the absolute size of what was got
+    assert O.rel_l2(a, np.zeros(4)) == pytest.approx(np.sqrt(26.0)) and O.max_rel(a, np.zeros(4)) == 4.0
+    # shapes are flattened, dtypes widened
+    assert O.rel_l2(a.reshape(2, 2).astype(np.float32), b.reshape(2, 2)) == pytest.approx(0.2)
+    # what rel_l2 averages away max_rel keeps: 8 wrong rows of 32768 (each entry off by the typical size)
+    rng = np.random.default_rng(0)
+    ref = rng.normal(size=(32768, 16))
+    got = ref.copy()
+    got[:8] = 0.0
+    assert O.rel_l2(got, ref) < 2e-2 < 0.2 < O.max_rel(got, ref)
+    assert np.isnan(O.rel_l2(np.array([np.nan, 1.0]), np.array([1.0, 1.0])))      # a NaN never passes a "< tol" test
+
+
+def test_layer_forward_against_nested_scalar_loops():
+    # the whole encoder layer, every stage with non-zero weights (FFN included), written out element by element with
+    # Python scalars and math.erf / math.exp: pins qkv split, head layout, softmax axis, both residuals, both
+    # LayerNorms, GELU placement and every matrix orientation of encoder_layer_fwd and its cache
+    import math
+    n, S, H, A, F = 2, 3, 4, 2, 6
+    d = H // A
+    rng = np.random.default_rng(42)
+    p = {"Wqkv": rng.normal(size=(H, 3 * H)) * 0.5, "bqkv": rng.normal(size=3 * H) * 0.3, "Wo": rng.normal(size=(H, H)) * 0.5,
+         "bo": rng.normal(size=H) * 0.3, "g1": 1 + 0.2 * rng.normal(size=H), "be1": 0.2 * rng.normal(size=H),
+         "W1": rng.normal(size=(H, F)) * 0.7, "b1": rng.normal(size=F) * 0.3, "W2": rng.normal(size=(F, H)) * 0.7,
+         "b2": rng.normal(size=H) * 0.3, "g2": 1 + 0.2 * rng.normal(size=H), "be2": 0.2 * rng.normal(size=H)}
+    X = rng.normal(size=(n, S, H))
+    eps = 1e-5
+    Y, cache = O.encoder_layer_fwd(X, p, A, eps)
+
+    def ln(row, g, b):
+        mu = sum(row) / len(row)
+        var = sum((v - mu) ** 2 for v in row) / len(row)
+        return [g[j] * (row[j] - mu) / math.sqrt(var + eps) + b[j] for j in range(len(row))]
+
+    for q in range(n):
+        qkv = [[sum(X[q, s, i] * p["Wqkv"][i, j] for i in range(H)) + p["bqkv"][j] for j in range(3 * H)] for s in range(S)]
+        ctx = [[0.0] * H for _ in range(S)]
+        for h in range(A):
+            for s in range(S):
+                sc = [sum(qkv[s][h * d + e] * qkv[t][H + h * d + e] for e in range(d)) / math.sqrt(d) for t in range(S)]
+                m = max(sc)
+                ex = [math.exp(v - m) for v in sc]
+                den = sum(ex)
+                for e in range(d):
+                    ctx[s][h * d + e] = sum(ex[t] / den * qkv[t][2 * H + h * d + e] for t in range(S))
+        for s in range(S):
+            r1 = [X[q, s, j] + sum(ctx[s][i] * p["Wo"][i, j] for i in range(H)) + p["bo"][j] for j in range(H)]
+            y1 = ln(r1, p["g1"], p["be1"])
+            u1 = [sum(y1[i] * p["W1"][i, f] for i in range(H)) + p["b1"][f] for f in range(F)]
+            ga = [0.5 * u * (1.0 + math.erf(u / math.sqrt(2.0))) for u in u1]
+            r2 = [y1[j] + sum(ga[f] * p["W2"][f, j] for f in range(F)) + p["b2"][j] for j in range(H)]
+            y = ln(r2, p["g2"], p["be2"])
+            assert np.allclose(cache["Y1"][q, s], y1, rtol=1e-12, atol=1e-13)
+            assert np.allclose(cache["U1"][q, s], u1, rtol=1e-12, atol=1e-13)
+            assert np.allclose(cache["G"][q, s], ga, rtol=1e-12, atol=1e-13)
+            assert np.allclose(cache["C"][q, s], ctx[s], rtol=1e-12, atol=1e-13)
+            assert np.allclose(Y[q, s], y, rtol=1e-12, atol=1e-13)
+
