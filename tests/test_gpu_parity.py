@@ -1,7 +1,9 @@
 """GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
 inputs.  Tolerances: fp32 mode 1e-4 relative (rel-L2 per tensor), bf16 mode 2e-2 relative on
 gradients and loss; kernel-level cases are tighter where the arithmetic allows."""
+import json
 import math
+import os
 
 import numpy as np
 import pytest
@@ -20,6 +22,13 @@ pytestmark = pytest.mark.gpu
 TOL = {"fp32": 1e-4, "bf16": 2e-2, "fp16": 2.5e-3}
 DT = {"fp32": P.L2L_F32, "bf16": P.L2L_BF16, "fp16": P.L2L_FP16}
 OUT16 = {"fp32": 2e-6, "bf16": 3e-3, "fp16": 4e-4}      # one rounding of a 16-bit (or no rounding of an fp32) output
+# Largest single error over a tensor, in units of the tensor's largest entry (oracle's max_rel).  fp32: a handful of
+# fp32 roundings of sums of a few thousand terms.  16-bit modes: activations and activation gradients pass through a
+# dozen roundings to the format inside a layer (unit roundoff 2^-8 = 3.9e-3 for bf16, 2^-11 = 4.9e-4 for fp16) and the
+# single worst of up to 10^7 entries sits several standard deviations out.  Measured worst cases over this file:
+# fp32 1.7e-6, bf16 1.0e-2, fp16 1.6e-3; the bounds leave a factor of about three.
+MAXTOL = {"fp32": 2e-5, "bf16": 3e-2, "fp16": 5e-3}
+ULP = {"bf16": 2.0 ** -7, "fp16": 2.0 ** -10}           # spacing of the format relative to the value, at most: half of it per rounding
 
 
 @pytest.fixture(scope="module")
@@ -136,6 +145,137 @@ def test_gemm_split_k_through_workspace_and_with_atomics(monkeypatch, workspace_
         c.close()
 
 
+# every epilogue the 256 x 256 direct-to-LDS kernel has a compiled-in instantiation for (flags as the library numbers
+# them: bias 1, GELU 2, GELU' 4, residual 8, column sums 32), by the l2l_op_gemm_ex arguments that select it
+EPILOGUES = {0: dict(), 1: dict(bias=True), 9: dict(bias=True, resid=True), 3: dict(bias=True, gelu=True), 4: dict(gelugrad=True),
+             36: dict(gelugrad=True, colsum=True), 8: dict(resid=True), 32: dict(colsum=True)}
+
+
+def _gemm_ex_case(ctx, dtype, M, N, K, bias=False, resid=False, gelu=False, gelugrad=False, colsum=False, a_kc=1, b_kc=1,
+                  out_f32=False, accumulate=False, seed=0):
+    """One l2l_op_gemm_ex launch (library's choice of kernel) checked ELEMENT BY ELEMENT against
+    epilogue(rounded(A) @ rounded(B)) in fp64.  Bounds per element: an fp32 output may differ by the fp32
+    accumulation error (2e-6 of the row-times-column magnitude); a 16-bit output additionally by one rounding to the
+    format (half a unit in the last place, ULP / 2 relative).  The 16-bit epilogues evaluate Phi(u) and gelu'(u) by
+    polynomials with absolute errors below 4e-5 and 2e-4 (pinned on the CPU), which enter as 5e-5 |u| and 2.5e-4 |acc|."""
+    rng = np.random.default_rng(seed)
+    A = rng.normal(size=(M, K)).astype(np.float32)
+    Bm = (rng.normal(size=(K, N)) / math.sqrt(K)).astype(np.float32)
+    ldr, ldaux, ldc = N + 8, N + 16, N + 24
+    Ad = to_dev(A if a_kc else np.ascontiguousarray(A.T), dtype)
+    Bd = to_dev(np.ascontiguousarray(Bm.T) if b_kc else Bm, dtype)
+    lda, ldb = (K if a_kc else M), (K if b_kc else N)
+    Ar, Br = rounded(A, dtype), rounded(Bm, dtype)
+    acc = Ar @ Br
+    scale = np.abs(Ar) @ np.abs(Br)                         # magnitude of the sum of products, per output
+    tol = 2e-6 * scale
+    ref = acc.copy()
+    kw = dict(epi=0)
+    if bias:
+        bh = rng.normal(size=N).astype(np.float32)
+        kw["bias"] = to_dev(bh, dtype)
+        ref = ref + rounded(bh, dtype)
+    if gelu:
+        u = ref.copy()
+        ref = O.gelu(u)
+        tol = tol + 5e-5 * np.abs(u)
+        aux_out = to_dev(np.full((M, ldaux), 7.0, np.float32), dtype)
+        kw.update(epi=kw["epi"] | B.EPI_GELU, aux_out=aux_out, ldaux=ldaux)
+    if gelugrad:
+        auxh = (rng.normal(size=(M, ldaux)) * 1.5).astype(np.float32)
+        kw.update(epi=kw["epi"] | B.EPI_GELUGRAD, aux=to_dev(auxh, dtype), ldaux=ldaux)
+        ref = ref * O.gelu_grad(rounded(auxh, dtype)[:, :N])
+        tol = tol + 2.5e-4 * np.abs(acc)
+    if resid:
+        rh = rng.normal(size=(M, ldr)).astype(np.float32)
+        kw.update(resid=to_dev(rh, dtype), ldr=ldr)
+        ref = ref + rounded(rh, dtype)[:, :N]
+    f32out = out_f32 or dtype == "fp32"
+    C0 = rng.normal(size=(M, ldc)).astype(np.float32)
+    Cd = torch.from_numpy(C0).cuda() if f32out else to_dev(C0, dtype)
+    C0v = to_host(Cd)
+    if accumulate:
+        kw["epi"] |= B.EPI_ACCUM
+        ref = ref + C0v[:, :N]
+    cs_rows = (M + 63) // 64
+    if colsum:
+        csd = torch.full((cs_rows + 1, N), 12345.0, device="cuda")      # one canary row behind what may be written
+        kw.update(epi=kw["epi"] | B.EPI_COLSUM, colsum=csd, colsum_rows=cs_rows)
+    used = ctx.op_gemm_ex(DT[dtype], f32out, a_kc, b_kc, M, N, K, Ad, lda, Bd, ldb, Cd, ldc, 1.0, impl=0, **kw)
+    torch.cuda.synchronize()
+    got = to_host(Cd)
+    assert np.array_equal(got[:, N:], C0v[:, N:]), "wrote outside the N columns"
+    out_tol = tol if f32out else tol + 0.5 * ULP[dtype] * 1.001 * np.abs(ref)
+    excess = np.abs(got[:, :N] - ref) - out_tol
+    worst = np.unravel_index(np.argmax(excess), excess.shape)
+    assert excess[worst] <= 0, (f"element {worst}: got {got[worst]}, want {ref[worst]} +- {out_tol[worst]}; "
+                                f"{int((excess > 0).sum())} of {excess.size} out of bounds")
+    if gelu:       # the kept pre-activation: one rounding of u
+        au = to_host(aux_out)
+        assert np.all(au[:, N:] == 7.0)
+        assert np.all(np.abs(au[:, :N] - u) <= 2e-6 * scale + 0.5 * ULP[dtype] * 1.001 * np.abs(u))
+    if colsum:     # partial sums of the values before their rounding to the output format; rows beyond `used` untouched
+        assert 0 < used <= cs_rows
+        cs = to_host(csd)
+        assert np.all(cs[used:] == 12345.0), "column-sum rows beyond the reported count were written"
+        col_tol = tol.sum(axis=0) + 1e-6 * np.abs(ref).sum(axis=0)
+        assert np.all(np.abs(cs[:used].sum(axis=0) - ref.sum(axis=0)) <= col_tol)
+    return O.rel_l2(got[:, :N], ref), O.max_rel(got[:, :N], ref)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
+@pytest.mark.parametrize("epi", sorted(EPILOGUES))
+def test_gemm_every_compiled_epilogue_elementwise(ctx, dtype, epi):
+    # 256 x 256 tiles with 16-bit output and both operands K-contiguous: the instantiations with the epilogue flags
+    # compiled in (flag sets 0, 1, 9, 3, 4, 36, 8) and, for 32, the one that reads them at run time; two tile rows and
+    # columns with ragged edges, K with a tail
+    errs = _gemm_ex_case(ctx, dtype, 392, 520, 264, seed=epi, **EPILOGUES[epi])
+    _report(f"gemm_ex[{dtype}-epi{epi}]", {"C": errs[0], "max:C": errs[1]})
+
+
+@pytest.mark.parametrize("K", [136, 1032])
+@pytest.mark.parametrize("epi", [9, 3, 36])
+def test_gemm_resident_tile_walk_elementwise(ctx, K, epi):
+    # 19 x 18 = 342 tiles of 256 x 256, more than the chip has compute units: workgroups stay resident and walk the tile
+    # order, fetching the next tile's first k-tile under the epilogue of the current one; ragged M, N and K.  K = 136
+    # leaves that prefetch as most of a tile's loads, K = 1032 is the layer's depth plus a tail
+    errs = _gemm_ex_case(ctx, "bf16", 4616, 4360, K, seed=K + epi, **EPILOGUES[epi])
+    _report(f"gemm_resident[K{K}-epi{epi}]", {"C": errs[0], "max:C": errs[1]})
+
+
+def test_gemm_resident_tile_walk_other_layouts_elementwise(ctx):
+    # the same walk for the dW layout (both operands K-strided, fp32 accumulate into C: 342 tiles, no K split) and for
+    # fp16 operands
+    _gemm_ex_case(ctx, "bf16", 4616, 4360, 520, a_kc=0, b_kc=0, out_f32=True, accumulate=True, seed=5)
+    _gemm_ex_case(ctx, "fp16", 4616, 4360, 264, seed=6, **EPILOGUES[9])
+    _gemm_ex_case(ctx, "bf16", 4616, 4360, 264, a_kc=1, b_kc=0, out_f32=True, seed=7)
+
+
+def test_gemm_column_sums_row_count_at_wave_tile_edges(ctx):
+    # M = 64 and M = 320 leave wave tiles of the 128- and 256-row block tiles entirely past M: they must not write a
+    # row of partial sums (the buffer has ceil(M / 64) rows and a canary row behind them)
+    for M, N in [(64, 264), (320, 136), (448, 520), (72, 128)]:
+        _gemm_ex_case(ctx, "bf16", M, N, 264, gelugrad=True, colsum=True, seed=M)
+        _gemm_ex_case(ctx, "bf16", M, N, 264, colsum=True, seed=M + 1)
+
+
+def test_gemm_ex_rejects_bad_arguments(ctx):
+    x = torch.zeros(256, 256, device="cuda", dtype=torch.bfloat16)
+    f = torch.zeros(256, 256, device="cuda")
+    kw = dict(in_dtype=P.L2L_BF16, out_f32=False, a_kc=1, b_kc=1, M=256, N=256, K=256, A=x, lda=256, B=x, ldb=256, Cm=x, ldc=256)
+    for bad in (dict(epi=B.EPI_GELUGRAD),                                  # no pre-activation
+                dict(epi=B.EPI_GELU | B.EPI_GELUGRAD, aux=x, ldaux=256),   # both at once
+                dict(epi=64),                                              # unknown flag
+                dict(epi=B.EPI_ACCUM),                                     # accumulate into a 16-bit output
+                dict(resid=x, ldr=8),                                      # residual stride below N
+                dict(epi=B.EPI_COLSUM),                                    # no buffer
+                dict(epi=B.EPI_COLSUM, colsum=f, colsum_rows=1),           # too few rows
+                dict(epi=B.EPI_COLSUM, colsum=f, colsum_rows=8, impl=1)):  # the plain kernel has no column sums
+        with pytest.raises(P.L2LError) as e:
+            ctx.op_gemm_ex(**{**kw, **bad})
+        assert e.value.code == P.L2L_E_ARG, bad
+
+
 def test_gemm_rejects_bad_arguments(ctx):
     x = torch.zeros(64, 64, device="cuda")
     with pytest.raises(P.L2LError) as e:
@@ -176,6 +316,7 @@ def _layer_case(w: S.Workload, group=0, x_scale=1.0, check_fwd_only=False, dy_sc
         lay = P.layer_layout(cfg)
         total = P.lib().l2l_layer_packed_elems(cfg)
         p32 = S.layer_params(w, 0)
+        _progress("parameters drawn")
         flat = pack(lay, total, p32)
         host = pinned(O.bf16_bits(flat).view(np.int16) if dtype == "bf16" else O.fp16_bits(flat).view(np.int16) if dtype == "fp16" else flat)
         pr = {k: rounded(v, dtype) for k, v in p32.items()}
@@ -186,20 +327,25 @@ def _layer_case(w: S.Workload, group=0, x_scale=1.0, check_fwd_only=False, dy_sc
         c.param_stage(0, host, 0)
         c.layer_fwd(0, 0, Xd, Yd)
         c.sync()
+        _progress("device forward done")
         Xr, dYr = rounded(X, dtype), rounded(dY, dtype)
         Yref = O.layer_l2l_fwd(Xr, pr, w.heads, 1e-12)
-        errs = {"Y": O.rel_l2(to_host(Yd), Yref)}
+        _progress("oracle forward done")
+        errs = {}
+        _both(errs, "Y", to_host(Yd), Yref)
         if not check_fwd_only:
             c.layer_bwd(0, 0, Xd, dYd)
             gh = torch.empty(total, dtype=torch.float32).pin_memory()
             c.grad_drain(0, gh)
             c.drain_wait(0)
             c.sync()
+            _progress("device backward done")
             dXref, gref = O.layer_l2l_bwd(Xr, dYr, pr, w.heads, 1e-12)
-            errs["dX"] = O.rel_l2(to_host(dYd), dXref)
+            _progress("oracle backward done")
+            _both(errs, "dX", to_host(dYd), dXref)
             got = unpack(lay, S.layer_shapes(w), gh.numpy())
             for k in gref:
-                errs["d" + k] = O.rel_l2(got[k], gref[k])
+                _both(errs, "d" + k, got[k], gref[k])
             # padding of the gradient block stays zero
             mask = np.ones(total, bool)
             for off, n in lay.values():
@@ -210,9 +356,37 @@ def _layer_case(w: S.Workload, group=0, x_scale=1.0, check_fwd_only=False, dy_sc
         c.close()
 
 
-def _assert_errs(errs, tol):
-    bad = {k: v for k, v in errs.items() if not (v < tol)}
-    assert not bad, f"over tolerance {tol}: {bad}; all: {errs}"
+def _report(case, errs):
+    """every parity case leaves its error figures in gpurun_out/parity_errors.jsonl (when that folder exists)"""
+    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    if os.path.isdir(d):
+        with open(os.path.join(d, "parity_errors.jsonl"), "a") as f:
+            f.write(json.dumps({"case": case, **{k: float(v) for k, v in errs.items()}}) + "\n")
+
+
+def _progress(msg):
+    """long cases say where they are (a line in gpurun_out/progress.log), so that a quiet minute is not taken for a hang"""
+    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    if os.path.isdir(d):
+        with open(os.path.join(d, "progress.log"), "a") as f:
+            f.write(f"{os.environ.get('PYTEST_CURRENT_TEST', '?').split(' ')[0]}: {msg}\n")
+
+
+def _assert_errs(errs, tol, max_tol=None):
+    """errs: {tensor: rel-L2} and {"max:" + tensor: max |got - ref| / max |ref|}.  rel-L2 is held to `tol` (the north
+    star's bar); the largest single error to `max_tol` (default MAXTOL of the same precision), so that a few wrong
+    rows or a dropped tile, which a norm over a large tensor averages away, fail on their own."""
+    if max_tol is None:
+        max_tol = {v: MAXTOL[k] for k, v in TOL.items()}.get(tol, 4 * tol)
+    case = os.environ.get("PYTEST_CURRENT_TEST", "?").split(" ")[0]
+    _report(case, errs)
+    bad = {k: v for k, v in errs.items() if not (v < (max_tol if k.startswith("max:") else tol))}
+    assert not bad, f"over tolerance {tol} (max-error {max_tol}): {bad}; all: {errs}"
+
+
+def _both(errs, name, got, ref):
+    errs[name] = O.rel_l2(got, ref)
+    errs["max:" + name] = O.max_rel(got, ref)
 
 
 def test_layer_tiny_fp32():
@@ -282,6 +456,38 @@ def test_layer_chunked_attention_long_sequences(seq, dtype):
     _assert_errs(_layer_case(w, group=2, **kw), TOL[dtype])     # ragged last group
 
 
+@pytest.mark.parametrize("seq", [160, 512])
+def test_layer_chunked_attention_fp16_unscaled_gradient(seq):
+    # The same fp16 cases WITHOUT the factor on dY: upstream gradients of size 1e-3 times attention weights of size
+    # 1 / S put the score gradients at 1e-5 .. 1e-6, where half precision keeps 3 to 7 bits (subnormal spacing 6e-8).
+    # The forward pass is unaffected and held to the fp16 bar; the gradients are held to 8e-3, about three times
+    # that bar (the bf16 bar is 2e-2), which is what is left of them there.  With a loss scale (the mode Section 2.3's
+    # FP16 is run in) the case above applies.
+    w = S.Workload("long", 1, 128, 2, 256, seq, 50, 2, 3, "fp16", 1.0, 300 + seq)
+    errs = _layer_case(w)
+    _assert_errs({k: v for k, v in errs.items() if k.endswith("Y")}, TOL["fp16"])
+    _assert_errs({k: v for k, v in errs.items() if not k.endswith("Y")}, 8e-3, 8e-3)     # measured: 3.1e-3 at S = 512
+
+
+def test_layer_rows_below_one_wave_tile_bf16():
+    # 64 rows per launch with F >= 3 H: the GELU' GEMM (M = 64: 128 x 128 tiles of 64-row wave tiles) leaves its
+    # bias-gradient partial sums in a buffer of ceil(64 / 64) = 1 row; the wave tile past M must not write a second one
+    # (it would land in the LayerNorm statistics behind the buffer)
+    w = S.Workload("m64", 1, 128, 2, 512, 32, 50, 2, 1, "bf16", 1.0, 641)
+    _assert_errs(_layer_case(w), TOL["bf16"])
+    w = S.Workload("m320", 1, 128, 2, 512, 32, 50, 10, 1, "bf16", 1.0, 642)      # 320 rows: 256 x 128 tiles, 3 dead wave tiles
+    _assert_errs(_layer_case(w), TOL["bf16"])
+
+
+@pytest.mark.slow
+def test_layer_deep_wide_full_width_bf16():
+    # the deep-wide workload's layer at its real widths (H = 6144, 48 heads, F = 24576: 453 M parameters), one
+    # micro-batch of 8 sequences: GEMMs with K and N of 6144, 18432 and 24576, dW GEMMs of 6144 x 24576 outputs
+    # (2304 tiles), LayerNorm in its two-kernel form
+    w = S.WORKLOADS[4].scaled(num_ubatches=1)
+    _assert_errs(_layer_case(w), TOL["bf16"])
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "fp16"])
 def test_layer_unfused_attention_path_still_matches(monkeypatch, dtype):
     # the batched-GEMM attention path (used for other head widths / sequence lengths), forced at a fused shape
@@ -323,10 +529,10 @@ def _step_case(w: S.Workload, stash="device", group=0, lr=1e-4, eager=False, **t
         errs = {"loss": abs(loss - loss_ref) / abs(loss_ref)}
         ge, gl = tr.grads()
         for k in gemb_ref:
-            errs["emb.d" + k] = O.rel_l2(ge[k], gemb_ref[k])
+            _both(errs, "emb.d" + k, ge[k], gemb_ref[k])
         for l in range(w.layers):
             for k in gl_ref[l]:
-                errs[f"l{l}.d{k}"] = O.rel_l2(gl[l][k], gl_ref[l][k])
+                _both(errs, f"l{l}.d{k}", gl[l][k], gl_ref[l][k])
         # optimizer: the EPS's fp32 master after one Adam step, from ITS OWN gradients, against the oracle's Adam
         me, ml = tr.master_params()
         for k in emb:
@@ -519,7 +725,7 @@ def test_fp16_without_loss_scale_loses_the_small_gradients():
     w = S.WORKLOADS[0].scaled(dtype="fp16")
     scaled, _, _ = _step_case(w)
     unscaled, _, _ = _step_case(w, loss_scale=1.0)
-    grads = [k for k in scaled if not k.startswith("adam.") and k != "loss"]
+    grads = [k for k in scaled if not k.startswith("adam.") and not k.startswith("max:") and k != "loss"]
     assert max(unscaled[k] for k in grads) > 4 * max(scaled[k] for k in grads)
 
 
