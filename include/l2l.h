@@ -277,6 +277,23 @@ int l2l_op_gemm_ex(l2l_ctx*, int in_dtype, int out_f32, int a_kc, int b_kc, int 
                    float alpha, const void* bias, const void* resid, long long ldr, int epi,
                    const void* aux, void* aux_out, long long ldaux,
                    float* colsum, long long colsum_rows, int* colsum_rows_used, int impl);
+/* For callers that cannot allocate -- code under HIP graph capture, tight serving loops, harnesses that forbid
+   hipMalloc: C[M,N] += A B with fp32 C, i.e. l2l_op_gemm(..., out_f32 = 1, accumulate = 1) on its default
+   implementation, without a context.  Where that call splits the contraction over K and keeps the splits' partial
+   results in context memory, this one keeps them in a device array that is part of the library itself
+   (l2l_noalloc_scratch_bytes() bytes = 32 MiB, present once on every GPU the library runs on until the process
+   ends); it calls no allocating routine.  stream: hipStream_t (NULL = the null stream) on the current device.
+   in_dtype: L2L_BF16 or L2L_FP16; A, B, C, strides and a_kc / b_kc as in l2l_op_gemm; operands must satisfy the MFMA
+   kernels' rules (16-byte aligned bases, row pitches that are multiples of 8 elements and cover the extent rounded up
+   to 8, panels below 2 GiB), else L2L_E_ARG.  L2L_E_ARG with a message naming the sizes when the K-split the shape
+   calls for needs more than the array holds (splits x M x N floats).  The array keeps the last call's contents;
+   nothing in it has to start from zero (every element a call reads was written by that call).  All calls on one GPU
+   share the array: calls that overlap in time on one GPU race.  The message of the last failure of this call on the
+   calling thread: l2l_noalloc_last_error(). */
+int    l2l_op_gemm_accum_noalloc(void* stream, int in_dtype, int a_kc, int b_kc, int M, int N, int K,
+                                 const void* A, long long lda, const void* B, long long ldb, float* C, long long ldc);
+size_t l2l_noalloc_scratch_bytes(void);
+const char* l2l_noalloc_last_error(void);
 /* y = LN(x) rows of length n; mean/rstd: device float[rows] or NULL. */
 int l2l_op_layernorm(l2l_ctx*, int dtype, int rows, int n, const void* x, const void* gamma,
                      const void* beta, float eps, void* y, float* mean, float* rstd);

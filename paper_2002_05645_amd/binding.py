@@ -81,6 +81,10 @@ _SIGS = {
     "l2l_op_gemm_ex": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _P, C.c_longlong,
                                  _P, C.c_longlong, _P, C.c_longlong, C.c_float, _P, _P, C.c_longlong, C.c_int, _P, _P,
                                  C.c_longlong, _P, C.c_longlong, C.POINTER(C.c_int), C.c_int]),
+    "l2l_op_gemm_accum_noalloc": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _P, C.c_longlong, _P,
+                                            C.c_longlong, _P, C.c_longlong]),
+    "l2l_noalloc_scratch_bytes": (C.c_size_t, []),
+    "l2l_noalloc_last_error": (C.c_char_p, []),
     "l2l_op_layernorm": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, _P, _P, _P, C.c_float, _P, _P, _P]),
     "eps_create": (C.c_int, [C.c_int, C.POINTER(C.c_size_t), C.c_int, C.c_int, C.POINTER(_P)]),
     "eps_destroy": (C.c_int, [_P]),
@@ -190,6 +194,14 @@ def _ptr(x):
     if isinstance(x, np.ndarray):
         return x.ctypes.data
     return C.cast(x, C.c_void_p).value
+
+
+def op_gemm_accum_noalloc(stream, in_dtype, a_kc, b_kc, M, N, K, A, lda, B, ldb, Cm, ldc):
+    """C += A B (fp32 C) without a context and without any allocation; see include/l2l.h."""
+    rc = lib().l2l_op_gemm_accum_noalloc(stream or None, in_dtype, int(a_kc), int(b_kc), M, N, K, _ptr(A), lda, _ptr(B), ldb,
+                                         _ptr(Cm), ldc)
+    if rc != L2L_OK:
+        raise L2LError(rc, lib().l2l_noalloc_last_error().decode())
 
 
 class Context:

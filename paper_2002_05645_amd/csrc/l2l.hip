@@ -8,6 +8,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <type_traits>
 #include <utility>
 #include <vector>
@@ -1605,6 +1606,83 @@ int l2l_op_gemm(l2l_ctx* c, int in_dtype, int out_f32, int a_kc, int b_kc, int M
                 int accumulate, int impl) {
   return l2l_op_gemm_ex(c, in_dtype, out_f32, a_kc, b_kc, M, N, K, A, lda, B, ldb, C, ldc, alpha, bias, resid, ldc,
                         (gelu ? L2L_EPI_GELU : 0) | (accumulate ? L2L_EPI_ACCUM : 0), nullptr, nullptr, 0, nullptr, 0, nullptr, impl);
+}
+
+// ---- an entry point that allocates nothing --------------------------------------------------------
+// C += A B like l2l_op_gemm(..., out_f32 = 1, accumulate = 1) on the K-split path, whose kernels keep the splits'
+// partial results in a workspace: here that workspace is a file-scope device array instead of context memory, so the
+// call needs no context and makes no allocation.  Every GPU the library runs on holds its own copy of the array until
+// the process ends; calls on one GPU share it, so calls that overlap there race.
+constexpr size_t kNoallocScratchFloats = (size_t)8 << 20;   // 32 MiB
+static __device__ __align__(256) float scratch[kNoallocScratchFloats];
+
+namespace {
+constexpr int kMaxDevices = 64;
+float* g_scratch_ptr[kMaxDevices] = {};   // per device: the array's address there, from hipGetSymbolAddress
+int g_num_cus[kMaxDevices] = {};
+std::mutex g_scratch_mu;
+thread_local char g_noalloc_err[256] = "no error";
+
+int noalloc_fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_noalloc_err, sizeof(g_noalloc_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+// the current device's copy of `scratch` (looked up once per device, with that device current)
+int noalloc_scratch(float** ptr, int* cus) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) { (void)hipGetLastError(); return noalloc_fail(L2L_E_HIP, "hipGetDevice: %s", hipGetErrorString(e)); }
+  if (dev < 0 || dev >= kMaxDevices) return noalloc_fail(L2L_E_ARG, "device %d: the library keeps scratch addresses for devices 0..%d", dev, kMaxDevices - 1);
+  std::lock_guard<std::mutex> l(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    float* p = nullptr;
+    e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) { (void)hipGetLastError(); return noalloc_fail(L2L_E_HIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e)); }
+    int n = 0;
+    e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) { (void)hipGetLastError(); n = 0; }
+    g_num_cus[dev] = n;
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  *cus = g_num_cus[dev];
+  return L2L_OK;
+}
+}  // namespace
+
+size_t l2l_noalloc_scratch_bytes(void) { return kNoallocScratchFloats * sizeof(float); }
+const char* l2l_noalloc_last_error(void) { return g_noalloc_err; }
+
+int l2l_op_gemm_accum_noalloc(void* stream, int in_dtype, int a_kc, int b_kc, int M, int N, int K, const void* A, long long lda,
+                              const void* B, long long ldb, float* C, long long ldc) {
+  if (!A || !B || !C) return noalloc_fail(L2L_E_ARG, "l2l_op_gemm_accum_noalloc: null pointer");
+  if (in_dtype != L2L_BF16 && in_dtype != L2L_FP16) return noalloc_fail(L2L_E_ARG, "l2l_op_gemm_accum_noalloc: operands are bf16 or fp16");
+  if (M < 0 || N < 0 || K < 0 || lda <= 0 || ldb <= 0 || ldc < N) return noalloc_fail(L2L_E_ARG, "l2l_op_gemm_accum_noalloc: bad shape");
+  if (M == 0 || N == 0 || K == 0) return L2L_OK;   // nothing to add
+  GemmArgs g = gemm_args(M, N, K, A, lda, a_kc != 0, B, ldb, b_kc != 0, C, ldc);
+  g.epi = EPI_ACCUM;
+  if (!mfma_ok(g)) return noalloc_fail(L2L_E_ARG, "l2l_op_gemm_accum_noalloc: operand alignment, row pitch or extent not supported by the MFMA kernels");
+  if ((g.M + 63) / 64 > 65535) return noalloc_fail(L2L_E_ARG, "l2l_op_gemm_accum_noalloc: grid too large");
+  int v, splits;
+  pick_tile(g, true, &v, &splits);
+  if (kTiles[v].direct && !g.a_kc && g.b_kc) v = 3;
+  float* ws = nullptr;
+  int cus = 0;
+  L2L_TRY(noalloc_scratch(&ws, &cus));
+  g.resident = cus;
+  const hipStream_t s = (hipStream_t)stream;
+  const int how = launch_split_through_workspace(v, g, s, splits, true, in_dtype == L2L_FP16, ws, kNoallocScratchFloats);
+  if (how == SPLIT_NO_ROOM)
+    return noalloc_fail(L2L_E_ARG, "l2l_op_gemm_accum_noalloc: %d x %d outputs in %d K-splits need %zu bytes of scratch, the library holds %zu",
+                        M, N, splits, (size_t)splits * M * N * 4, kNoallocScratchFloats * sizeof(float));
+  if (how == SPLIT_NOT_APPLICABLE) launch_mfma_variant(v, g, s, splits, true, in_dtype == L2L_FP16);   // no split, or splits adding with atomics: no scratch
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return noalloc_fail(L2L_E_HIP, "kernel launch: %s", hipGetErrorString(e));
+  return L2L_OK;
 }
 
 int l2l_op_layernorm(l2l_ctx* c, int dtype, int rows, int n, const void* x, const void* gamma, const void* beta, float eps, void* y,
