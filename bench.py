@@ -18,6 +18,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0       # MI355X dense bf16 MFMA
+# HBM bytes per layer-GEMM launch of the headline workload, from counters collected offline (see roofline.traffic_source)
+HBM_TRAFFIC_PER_LAUNCH = 631.1e6
 
 
 def cpu_baseline(w):
@@ -48,6 +50,34 @@ def cpu_baseline(w):
                       "embedding, head and Adam not included"}
 
 
+def write_gemm_table(path, rows, w, steps, out):
+    """The layer GEMMs of the instrumented steps by launch shape, as a markdown table."""
+    H, F = w.hidden, w.ffn
+    role = {(3 * H, H, 1): "QKV", (H, H, 9): "out-proj (+ residual)", (F, H, 3): "FFN1 (+ GELU)", (H, F, 9): "FFN2 (+ residual)",
+            (F, H, 4): "dU1 = dR2 W2^T * gelu'", (F, H, 36): "dU1 = dR2 W2^T * gelu' (+ db1 partial sums)",
+            (H, F, 8): "dY1 = dR2 + dU1 W1^T", (H, H, 0): "dC = dR1 Wo^T", (H, 3 * H, 8): "dX = dR1 + dQKV Wqkv^T"}
+    lines = ["| GEMM | pass | M | N | K | layout (A, B) | launches / step | us / launch | TFLOP/s | of 2.5 PFLOP/s |", "|---|---|---|---|---|---|---|---|---|---|"]
+    passes = ("forward", "recompute", "backward", "")
+    tot_ms = tot_fl = 0.0
+    for r in rows:
+        if not r["launches"]:
+            continue
+        name = role.get((r["N"], r["K"], r["epi"]), "")
+        if r["epi"] == 16:
+            name = {(H, 3 * H): "dWqkv += X^T dQKV", (H, H): "dWo += C^T dR1", (H, F): "dW1 += Y1^T dU1", (F, H): "dW2 += G^T dR2"}.get((r["M"], r["N"]), "dW")
+        fl = 2.0 * r["M"] * r["N"] * r["K"] * r["launches"]
+        tf = fl / (r["ms"] * 1e-3) / 1e12
+        tot_ms += r["ms"]
+        tot_fl += fl
+        lay = ("K-contiguous" if r["a_kc"] else "K-strided") + ", " + ("K-contiguous" if r["b_kc"] else "K-strided")
+        lines.append(f"| {name} | {passes[r['pass']]} | {r['M']} | {r['N']} | {r['K']} | {lay} | {r['launches'] / steps:g} | {1e3 * r['ms'] / r['launches']:.1f} | {tf:.0f} | {tf / PEAK_BF16_TFLOPS:.3f} |")
+    lines.append(f"| all | | | | | | {sum(r['launches'] for r in rows) / steps:g} | | {tot_fl / (tot_ms * 1e-3) / 1e12:.0f} | {tot_fl / (tot_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS:.3f} |")
+    with open(path, "w") as f:
+        f.write(f"Layer GEMMs by launch shape: HIP events around every GEMM launch on the compute stream, {steps} steps, no tracer attached.\n")
+        f.write(f"Workload: {out['config']['workload']}; {out['ms_per_step']:.1f} ms per un-instrumented step.\n\n")
+        f.write("\n".join(lines) + "\n")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -69,6 +99,12 @@ def main():
                     help="> 0: the sequence-classification head with this many classes (one synthetic label per sequence) instead of the LM head")
     ap.add_argument("--optimizer", default="adam", choices=["adam", "lamb"],
                     help="host optimizer (lamb: per-tensor trust ratio, learning rate 1e-3, weight decay 0.01 on matrices)")
+    ap.add_argument("--no-ln-stats", action="store_true",
+                    help="recompute the whole layer forward in the backward pass (l2l_layer_fwd / l2l_layer_bwd) instead of keeping "
+                         "LayerNorm 2's row statistics and skipping the FFN2 product of the recompute")
+    ap.add_argument("--gemm-table", default="", metavar="FILE",
+                    help="write the layer GEMMs by launch shape (HIP-event durations of the instrumented steps: launches, "
+                         "microseconds per launch, TFLOP/s) to FILE as a markdown table")
     ap.add_argument("--grad-dtype", default="fp32", choices=["fp32", "bf16", "fp16"],
                     help="format of the gradient drains over the host link (fp32 = the headline; 16-bit: rounded on the device, half the bytes)")
     a = ap.parse_args()
@@ -80,6 +116,13 @@ def main():
     from paper_2002_05645_amd.trainer import L2LTrainer
 
     w = S.WORKLOADS[a.config]
+    full_depth = w.layers
+    if a.config == 4 and not a.layers:
+        # 453 M parameters per layer: fp32 master, two Adam moments, the shipping copy and the gradient landing buffer
+        # are 18 bytes per parameter of host memory, 8.2 GB per layer, 390 GB at the workload's 48 layers: more than
+        # a process may hold on these boxes.  The device side does not depend on depth (one resident layer, one
+        # prefetch buffer), so the workload runs at a reduced depth that is said in config.workload.
+        a.layers = 6
     if a.layers:
         w = w.scaled(layers=a.layers)
     if a.ubatches:
@@ -88,9 +131,18 @@ def main():
         w = w.scaled(dtype=a.dtype)
     tr = L2LTrainer(layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, vocab=w.vocab,
                     ubatch=w.ubatch, num_ubatches=w.num_ubatches, dtype=w.dtype, ubatch_group=a.group, stash=a.stash,
-                    eager=not a.tail_adam, optimizer=a.optimizer, num_classes=a.classes, grad_dtype=a.grad_dtype,
+                    eager=not a.tail_adam, optimizer=a.optimizer, num_classes=a.classes, grad_dtype=a.grad_dtype, keep_ln_stats=not a.no_ln_stats,
                     **(dict(lr=1e-3, eps_a=1e-6, weight_decay=0.01) if a.optimizer == "lamb" else {}))
-    tr.load_params(S.embed_params(w), [S.layer_params(w, l) for l in range(w.layers)], S.cls_params(w, a.classes) if a.classes else None)
+    if a.config == 4:
+        # drawing 453 M normals per layer from the counter-based generator takes a minute per layer: layer 0 is drawn,
+        # the others get each of its tensors rotated by a layer-dependent offset (same distribution, own memory)
+        import numpy as np
+        l0 = S.layer_params(w, 0)
+        layer_list = [l0] + [{k: np.roll(v.reshape(-1), 7919 * l).reshape(v.shape) for k, v in l0.items()} for l in range(1, w.layers)]
+    else:
+        layer_list = [S.layer_params(w, l) for l in range(w.layers)]
+    tr.load_params(S.embed_params(w), layer_list, S.cls_params(w, a.classes) if a.classes else None)
+    del layer_list
     tok, lab = S.tokens_and_labels(w)
     if a.classes:
         lab = S.seq_labels(w, a.classes)
@@ -129,6 +181,7 @@ def main():
     tr.ctx.profile(2)
     prof_total_s, _, _ = run_steps(a.steps)
     prof = tr.ctx.profile_read()
+    gemm_rows = tr.ctx.profile_gemm_table()
     tr.ctx.profile(0)
     # a few more steps with every kernel and every copy-stream operation bracketed: how much of the step has
     # a kernel running, and how much of the copy stream's work (stages, drains) runs under those kernels
@@ -154,9 +207,11 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": {"bf16": "bf16", "fp16": "f16", "fp32": "f32"}[w.dtype],
         "data": "synthetic",
         "config": {"workload": f"{w.name}: L={w.layers} H={w.hidden} A={w.heads} F={w.ffn} S={w.seq} V={w.vocab} "
-                               f"U={w.num_ubatches} x ub={w.ubatch}", "stash": a.stash, "ubatch_group": tr.ctx.cfg.ubatch_group,
+                               f"U={w.num_ubatches} x ub={w.ubatch}"
+                               + (f" (reduced depth: {w.layers} of the workload's {full_depth} layers)" if w.layers < full_depth else ""),
+                   "stash": a.stash, "ubatch_group": tr.ctx.cfg.ubatch_group,
                    "device_pipeline_samples_per_s": samples * a.steps / dev_s, "device_pipeline_ms": 1e3 * dev_s / a.steps,
-                   "host_adam_exposed_ms": 1e3 * adam_s / a.steps, "eps": "tail" if a.tail_adam else "eager", "optimizer": a.optimizer, "head": f"classification, {a.classes} classes" if a.classes else "tied LM head", "loss_first": loss0, "loss_last": loss, "losses": [round(x, 4) for x in losses],
+                   "host_adam_exposed_ms": 1e3 * adam_s / a.steps, "eps": "tail" if a.tail_adam else "eager", "ln2_statistics_kept": bool(tr.keep_ln_stats), "optimizer": a.optimizer, "head": f"classification, {a.classes} classes" if a.classes else "tied LM head", "loss_first": loss0, "loss_last": loss, "losses": [round(x, 4) for x in losses],
                    "peak_device_bytes": int(peak_mem), "ctx_device_bytes": int(tr.ctx.device_bytes()),
                    "instrumented_ms_per_step": 1e3 * prof_total_s / a.steps,
                    # sum of kernel durations over the un-instrumented device-pipeline time; and the fraction of the
@@ -168,17 +223,23 @@ def main():
                    "hidden_transfer_frac_timed_steps_at_least": max(0.0, 1.0 - max(0.0, 1e3 * dev_s / a.steps - kernel_ms)
                                                                     / (ov["copy_busy_ms"] / n_ov)) if ov["copy_busy_ms"] > 0 else None,
                    "copy_stream_busy_ms": ov["copy_busy_ms"] / n_ov,
+                   # bytes moved by stages and drains per second of copy-stream busy time (beside the kernels)
+                   "host_link_GBps_while_busy": classes["copy"]["bytes"] / (classes["copy"]["ms"] * 1e-3) / 1e9 if classes["copy"]["ms"] > 0 else None,
+                   "host_link_bytes_per_step": classes["copy"]["bytes"] / n_ov,
                    "kernel_ms_by_class": {k: round(v["ms"] / n_ov, 3) for k, v in classes.items()}},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS,
                      # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (profiles/bench_bert_large_gemm_hbm_traffic.md);
                      # measured on the headline workload only
-                     "traffic": 631.1e6 if (a.config == 2 and not a.layers and not a.group and not a.ubatches and not a.dtype and not a.classes and a.grad_dtype == "fp32") else None,
+                     "traffic": HBM_TRAFFIC_PER_LAUNCH if (a.config == 2 and not a.layers and not a.group and not a.ubatches and not a.dtype and not a.classes and a.grad_dtype == "fp32") else None,
+                     "traffic_source": "offline: two rocprofv3 --pmc runs of this command (FETCH_SIZE, WRITE_SIZE), profiles/bench_bert_large_gemm_hbm_traffic.md; not measured in this run",
                      "kernel": "gemm_mfma_dlds_kernel / gemm_mfma_kernel: the layer's dense GEMMs (QKV, out-proj, FFN1, FFN2; forward, recompute, dX, dW)",
                      "gemm_ms_per_step": g["ms"] / a.steps, "launches_per_step": g["launches"] / a.steps,
                      "avg_launch_us": 1e3 * g["ms"] / max(g["launches"], 1),
                      "flops_per_launch": g["flops"] / max(g["launches"], 1)},
     }
+    if a.gemm_table:
+        write_gemm_table(a.gemm_table, gemm_rows, w, a.steps, out)
     if a.calibrate_copy:
         src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda").normal_()
         dst = torch.empty_like(src)

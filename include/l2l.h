@@ -104,6 +104,7 @@ int    l2l_config_check(const l2l_config*);
      L2L_SPLIT_WS_MB=n         room for the partial results of K-split GEMMs (default: what the layer's dW GEMMs need)
      L2L_SPLIT_ATOMICS=1       K-split GEMMs add their partial results with fp32 atomics instead
      L2L_FORCE_SPLITS=n        split factor of the accumulating fp32 GEMMs (default: by shape)
+     L2L_NO_WEIGHT_TRANSPOSE=1 forward GEMMs read the weights as stored, as a K-strided operand (no [out,in] copies per stage)
      L2L_GEMM_RESIDENT=0       one workgroup per GEMM tile instead of one resident workgroup per compute unit */
 int  l2l_create(const l2l_config*, void* compute_stream, void* copy_stream, l2l_ctx** out);
 int  l2l_destroy(l2l_ctx*);
@@ -144,6 +145,19 @@ int l2l_layer_fwd(l2l_ctx*, int layer, int slot, const void* x_stash, void* y_ou
    (in place).  The layer's parameter gradients are summed over the U micro-batches into a
    context-owned fp32 accumulator that starts from zero at this call. */
 int l2l_layer_bwd(l2l_ctx*, int layer, int slot, const void* x_stash, void* dy_dx);
+
+/* The same two calls with LayerNorm 2's row statistics kept across the passes.  The backward pass needs of the
+   layer's last LayerNorm only its normalised input xhat and 1 / sigma per row; xhat can be taken back out of the
+   layer's OUTPUT (y = g2 xhat + be2), which Section 2.1 stashes anyway as the next layer's input, so with 1 / sigma
+   kept from the forward pass (4 bytes per token: 0.2 % of the stash at H = 1024) the recompute pass can leave out the
+   FFN2 product, a twelfth of the layer's GEMM work.  Results equal l2l_layer_bwd's up to rounding (xhat comes from
+   the rounded y instead of the rounded LayerNorm input).
+   rstd_out / rstd: device float[U * T], caller-owned like the stash.  y_stash: device, U x [ub,S,H], what
+   l2l_layer_fwd_stats wrote to y_out.  The caller uses the pair only while no |g2| is tiny (xhat = (y - be2) / g2; the
+   step driver checks the master weights and falls back to l2l_layer_bwd otherwise).  Where LayerNorm backward runs in
+   its two-kernel form (H > 2048) l2l_layer_bwd_stats recomputes in full, like l2l_layer_bwd. */
+int l2l_layer_fwd_stats(l2l_ctx*, int layer, int slot, const void* x_stash, void* y_out, float* rstd_out);
+int l2l_layer_bwd_stats(l2l_ctx*, int layer, int slot, const void* x_stash, const void* y_stash, const float* rstd, void* dy_dx);
 
 /* Grad drain: asynchronous device->host copy, on copy_stream, of the gradients accumulated by the
    last l2l_layer_bwd(layer) (l2l_layer_grad_bytes bytes, fp32, packed order; half of that, rounded to the
@@ -236,6 +250,12 @@ int l2l_profile(l2l_ctx*, int on);
 /* Resolves pending events and returns, for one class: launches, total milliseconds, total
    algorithmic flops and bytes of those launches. */
 int l2l_profile_read(l2l_ctx*, int cls, long long* launches, double* ms, double* flops, double* bytes);
+/* The GEMM class by launch shape, since the last l2l_profile(ctx, 1 or 2): one text line per distinct shape,
+   "M N K a_kc b_kc epi out_f32 pass launches total_ms" (epi: the library's epilogue flag set: bias 1, GELU 2, GELU' 4,
+   residual 8, accumulate 16, column sums 32; pass: 0 forward pass, 1 recompute, 2 backward, 3 single operations), in
+   order of first use, into buf (cap bytes, NUL-terminated).
+   L2L_E_ARG if buf is too small. */
+int l2l_profile_gemm_table(l2l_ctx*, char* buf, size_t cap);
 /* Overlap of the two streams over everything recorded since l2l_profile(ctx, 1): the time the compute
    stream had a kernel running (union of the bracketed intervals), the time the copy stream was busy,
    the part of the latter that fell inside the former (the transfers Section 2.2 wants hidden), and the

@@ -61,6 +61,8 @@ _SIGS = {
     "l2l_param_stage": (C.c_int, [_P, C.c_int, _P, C.c_int]),
     "l2l_layer_fwd": (C.c_int, [_P, C.c_int, C.c_int, _P, _P]),
     "l2l_layer_bwd": (C.c_int, [_P, C.c_int, C.c_int, _P, _P]),
+    "l2l_layer_fwd_stats": (C.c_int, [_P, C.c_int, C.c_int, _P, _P, _P]),
+    "l2l_layer_bwd_stats": (C.c_int, [_P, C.c_int, C.c_int, _P, _P, _P, _P]),
     "l2l_grad_drain": (C.c_int, [_P, C.c_int, _P]),
     "l2l_drain_wait": (C.c_int, [_P, C.c_int]),
     "l2l_embed_stage": (C.c_int, [_P, _P]),
@@ -74,6 +76,7 @@ _SIGS = {
     "l2l_profile": (C.c_int, [_P, C.c_int]),
     "l2l_profile_overlap": (C.c_int, [_P, C.c_double, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double),
                                       C.POINTER(C.c_double)]),
+    "l2l_profile_gemm_table": (C.c_int, [_P, C.c_char_p, C.c_size_t]),
     "l2l_profile_read": (C.c_int, [_P, C.c_int, C.POINTER(C.c_longlong), C.POINTER(C.c_double),
                                    C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "l2l_op_gemm": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _P, C.c_longlong,
@@ -248,6 +251,12 @@ class Context:
     def layer_bwd(self, layer, slot, x_stash, dy_dx):
         self._ck(lib().l2l_layer_bwd(self._h, layer, slot, _ptr(x_stash), _ptr(dy_dx)))
 
+    def layer_fwd_stats(self, layer, slot, x_stash, y_out, rstd_out):
+        self._ck(lib().l2l_layer_fwd_stats(self._h, layer, slot, _ptr(x_stash), _ptr(y_out), _ptr(rstd_out)))
+
+    def layer_bwd_stats(self, layer, slot, x_stash, y_stash, rstd, dy_dx):
+        self._ck(lib().l2l_layer_bwd_stats(self._h, layer, slot, _ptr(x_stash), _ptr(y_stash), _ptr(rstd), _ptr(dy_dx)))
+
     def grad_drain(self, layer, host_grads):
         self._ck(lib().l2l_grad_drain(self._h, layer, _ptr(host_grads)))
 
@@ -292,6 +301,16 @@ class Context:
             self._ck(lib().l2l_profile_read(self._h, i, C.byref(n), C.byref(ms), C.byref(fl), C.byref(by)))
             out[name] = dict(launches=n.value, ms=ms.value, flops=fl.value, bytes=by.value)
         return out
+
+    def profile_gemm_table(self):
+        """[dict(M, N, K, a_kc, b_kc, epi, out_f32, pass, launches, ms)] per distinct GEMM launch shape since profile(1 or 2)"""
+        buf = C.create_string_buffer(1 << 16)
+        self._ck(lib().l2l_profile_gemm_table(self._h, buf, len(buf)))
+        rows = []
+        for line in buf.value.decode().splitlines():
+            f = line.split()
+            rows.append(dict(zip(("M", "N", "K", "a_kc", "b_kc", "epi", "out_f32", "pass", "launches"), map(int, f[:9])), ms=float(f[9])))
+        return rows
 
     def cls_stage(self, host_params, num_classes):
         self._ck(lib().l2l_cls_stage(self._h, _ptr(host_params), num_classes))

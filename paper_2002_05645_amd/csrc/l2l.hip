@@ -132,6 +132,15 @@ struct ProfRec {
   hipEvent_t a, b;
   int cls;
   double flops, bytes;
+  int shape = -1;   // GEMM class: index into l2l_ctx::prof_shapes
+};
+
+// per distinct GEMM launch shape, for the table of l2l_profile_gemm_table
+struct ProfShape {
+  int M, N, K, a_kc, b_kc, epi, out_f32;
+  int pass;   // 0 forward pass, 1 recompute, 2 backward, 3 elsewhere
+  long long launches = 0;
+  double ms = 0.0;
 };
 
 struct l2l_ctx {
@@ -143,6 +152,7 @@ struct l2l_ctx {
   int no_fused_attention = 0;               // L2L_NO_FUSED_ATTENTION=1: use the batched-GEMM attention path
   int force_splits = 0;                     // L2L_FORCE_SPLITS=n: split factor of the accumulating fp32 GEMMs
   int split_atomics = 0;                    // L2L_SPLIT_ATOMICS=1: K splits add with atomics, not through the workspace
+  int no_weight_transpose = 0;              // L2L_NO_WEIGHT_TRANSPOSE=1: forward GEMMs read W as stored ([in, out], K-strided B operand)
   int resident_cus = 0;                     // workgroups of a resident GEMM launch (CUs of the device; L2L_GEMM_RESIDENT=0: none)
   int32_t* bad_ids = nullptr;               // device flag: a token id or label outside the vocabulary was seen
   long long T = 0, Mg = 0;                  // tokens per micro-batch, rows per launch group
@@ -198,6 +208,8 @@ struct l2l_ctx {
   // profiling
   int prof_on = 0;
   std::vector<ProfRec> prof;
+  std::vector<ProfShape> prof_shapes;
+  int prof_pass = 3;   // which pass of the relay the launches being recorded belong to
   std::vector<hipEvent_t> ev_pool;
   hipEvent_t prof_base = nullptr;                          // recorded when profiling is switched on
   std::vector<std::pair<float, float>> iv_compute, iv_copy;  // resolved intervals, ms after prof_base
@@ -270,7 +282,7 @@ void copy_end(l2l_ctx* c, const CopyMark& m, double bytes) {
 }
 
 template <typename F>
-int timed(l2l_ctx* c, int cls, double flops, double bytes, F&& f) {
+int timed(l2l_ctx* c, int cls, double flops, double bytes, F&& f, int shape = -1) {
   if (!c->prof_on || (c->prof_on == 2 && cls != L2L_PROF_GEMM)) {
     f();
   } else {
@@ -278,7 +290,7 @@ int timed(l2l_ctx* c, int cls, double flops, double bytes, F&& f) {
     (void)hipEventRecord(a, c->cs);
     f();
     (void)hipEventRecord(b, c->cs);
-    c->prof.push_back({a, b, cls, flops, bytes});
+    c->prof.push_back({a, b, cls, flops, bytes, shape});
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(c, L2L_E_HIP, "kernel launch: %s", hipGetErrorString(e));
@@ -415,6 +427,19 @@ int gemm(l2l_ctx* c, int dtype, bool out_f32, const GemmArgs& g, int impl = 0, i
   const double flops = 2.0 * g.M * g.N * (double)g.K * g.nbatch;
   const double es = esize(dtype);
   const double bytes = ((double)g.M * g.K + (double)g.K * g.N) * es * g.nbatch + (double)g.M * g.N * (out_f32 ? 4 : es) * g.nbatch;
+  int shape = -1;
+  if (c->prof_on && cls == L2L_PROF_GEMM) {   // the launch's row in the per-shape table
+    for (size_t i = 0; i < c->prof_shapes.size() && shape < 0; ++i) {
+      const ProfShape& p = c->prof_shapes[i];
+      if (p.M == g.M && p.N == g.N && p.K == g.K && p.a_kc == g.a_kc && p.b_kc == g.b_kc && p.epi == g.epi && p.out_f32 == (int)out_f32 && p.pass == c->prof_pass) shape = (int)i;
+    }
+    if (shape < 0) {
+      ProfShape p;
+      p.M = g.M; p.N = g.N; p.K = g.K; p.a_kc = g.a_kc; p.b_kc = g.b_kc; p.epi = g.epi; p.out_f32 = out_f32; p.pass = c->prof_pass;
+      c->prof_shapes.push_back(p);
+      shape = (int)c->prof_shapes.size() - 1;
+    }
+  }
   return timed(c, cls, flops, bytes, [&] {
     if (use_mfma) {
       int v, splits;
@@ -441,7 +466,7 @@ int gemm(l2l_ctx* c, int dtype, bool out_f32, const GemmArgs& g, int impl = 0, i
     } else {
       launch_plain<float, float>(g, c->cs);
     }
-  });
+  }, shape);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -478,7 +503,7 @@ int ln_bwd(l2l_ctx* c, const void* dy, const void* x, const float* mean, const f
       auto go = [&](auto kern) {
         static_cast<void>(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         hipLaunchKernelGGL(kern, grid, dim3(256), lds, c->cs, (const T*)dy, (const T*)x, mean, rstd, (const T*)gamma, (T*)dx,
-                           dgamma, dbeta, dbias, (int)rows, n, eps);
+                           dgamma, dbeta, dbias, (int)rows, n, eps, (const T*)nullptr);
       };
       if (nch == 1) go(ln_bwd_fused_kernel<T, 1>);
       else if (nch == 2) go(ln_bwd_fused_kernel<T, 2>);
@@ -496,6 +521,27 @@ int ln_bwd(l2l_ctx* c, const void* dy, const void* x, const float* mean, const f
                        (const int*)nullptr, 0);
   }));
   return bias_grad<T>(c, dx, n, dbias, rows, n);
+}
+
+// LayerNorm backward from the OUTPUT y of the LayerNorm and the 1/sigma kept by the forward pass (one-pass kernel only)
+template <typename T>
+int ln_bwd_from_y(l2l_ctx* c, const void* dy, const void* y, const float* rstd, const void* gamma, const void* beta, void* dx,
+                  float* dgamma, float* dbeta, float* dbias, long long rows, int n) {
+  if (rows <= 0) return L2L_OK;
+  if (!ln_bwd_one_pass(n) || !rstd) return fail(c, L2L_E_STATE, "ln_bwd_from_y: needs the one-pass kernel and the kept statistics");
+  const int nch = n <= 512 ? 1 : n <= 1024 ? 2 : 4;
+  const size_t lds = (size_t)4 * 3 * nch * 512 * sizeof(float);
+  return timed(c, L2L_PROF_ROWWISE, 0, 3.0 * rows * n * sizeof(T), [&] {
+    const dim3 grid((unsigned)((rows + LNF_ROWS - 1) / LNF_ROWS));
+    auto go = [&](auto kern) {
+      static_cast<void>(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+      hipLaunchKernelGGL(kern, grid, dim3(256), lds, c->cs, (const T*)dy, (const T*)y, (const float*)nullptr, rstd, (const T*)gamma, (T*)dx,
+                         dgamma, dbeta, dbias, (int)rows, n, 0.f, (const T*)beta);
+    };
+    if (nch == 1) go(ln_bwd_fused_kernel<T, 1, true>);
+    else if (nch == 2) go(ln_bwd_fused_kernel<T, 2, true>);
+    else go(ln_bwd_fused_kernel<T, 4, true>);
+  });
 }
 
 template <typename T>
@@ -547,7 +593,7 @@ int fill_zero(l2l_ctx* c, void* p, size_t bytes) {
 // transposed once, on the copy stream right behind the stage's DMA, so that the work overlaps the
 // previous layer's compute and all micro-batches share the result.
 int transpose_weights(l2l_ctx* c, int slot) {
-  if (!is16(c->cfg.dtype)) return L2L_OK;   // the transpose moves 16-bit elements whatever their format
+  if (!is16(c->cfg.dtype) || c->no_weight_transpose) return L2L_OK;   // the transpose moves 16-bit elements whatever their format
   const int H = c->cfg.hidden, F = c->cfg.ffn;
   const long long* off = c->lay.off;
   const struct { int t, rows, cols; } m[4] = {{T_WQKV, H, 3 * H}, {T_WO, H, H}, {T_W1, H, F}, {T_W2, F, H}};
@@ -564,8 +610,12 @@ int transpose_weights(l2l_ctx* c, int slot) {
 // one encoder layer, forward, on `ng` micro-batches starting at row block x (rows = ng * T)
 // keep: also keep the GELU pre-activation and both LayerNorm statistics (backward recompute)
 // ------------------------------------------------------------------------------------------------
+// rstd2_out (forward pass only): where to keep LayerNorm 2's 1/sigma per row, or null.
+// skip_ffn2 (recompute pass only): the backward pass takes LayerNorm 2's xhat from the stashed layer output and its
+// kept 1/sigma, so the FFN2 product, whose only use in the backward pass is that LayerNorm's input, is not recomputed.
 template <typename T>
-int layer_forward_group(l2l_ctx* c, int slot, const void* x, void* y, int ng, bool keep) {
+int layer_forward_group(l2l_ctx* c, int slot, const void* x, void* y, int ng, bool keep, float* rstd2_out = nullptr,
+                        bool skip_ffn2 = false) {
   const void* params = c->slot[slot];
   const l2l_config& f = c->cfg;
   const int H = f.hidden, A = f.heads, F = f.ffn, S = f.seq, d = H / A;
@@ -575,8 +625,9 @@ int layer_forward_group(l2l_ctx* c, int slot, const void* x, void* y, int ng, bo
   const T* P = (const T*)params;
   const long long* off = c->lay.off;
   T* qkv = (T*)c->qkv;
+  c->prof_pass = keep ? 1 : 0;
   // weight operand of a forward GEMM: [out, in] copy (bf16) or the packed [in, out] matrix (fp32)
-  const bool tw = is16(dt);
+  const bool tw = is16(dt) && !c->no_weight_transpose;
   const T* W = tw ? (const T*)c->wt[slot] : P;
   auto wld = [&](int in, int out) { return (long long)(tw ? in : out); };
 
@@ -637,6 +688,7 @@ int layer_forward_group(l2l_ctx* c, int slot, const void* x, void* y, int ng, bo
     GemmArgs g = gemm_args((int)M, F, H, c->y1, H, 1, W + off[T_W1], wld(H, F), tw, c->ga, F);
     g.epi = EPI_BIAS | EPI_GELU; g.bias = P + off[T_B1]; g.aux_out = keep ? c->u1 : nullptr; g.ldaux = F;
     L2L_TRY(gemm(c, dt, false, g));
+    if (keep && skip_ffn2) return L2L_OK;
     GemmArgs h = gemm_args((int)M, H, F, c->ga, F, 1, W + off[T_W2], wld(F, H), tw, c->r2, H);
     h.epi = EPI_BIAS | EPI_RESID; h.bias = P + off[T_B2]; h.resid = c->y1; h.ldr = H;
     L2L_TRY(gemm(c, dt, false, h));
@@ -646,15 +698,18 @@ int layer_forward_group(l2l_ctx* c, int slot, const void* x, void* y, int ng, bo
       if (!ln_bwd_one_pass(H))
         L2L_TRY(ln_fwd<T>(c, c->r2, P + off[T_G2], P + off[T_BE2], c->ytmp, c->mean2, c->rstd2, M, H, f.ln_eps));
     } else {
-      L2L_TRY(ln_fwd<T>(c, c->r2, P + off[T_G2], P + off[T_BE2], y, nullptr, nullptr, M, H, f.ln_eps));
+      L2L_TRY(ln_fwd<T>(c, c->r2, P + off[T_G2], P + off[T_BE2], y, rstd2_out ? c->mean2 : nullptr, rstd2_out, M, H, f.ln_eps));
     }
   }
   return L2L_OK;
 }
 
 // backward of the group whose forward intermediates are in the workspace; dy -> dx in place
+// y, rstd2: the layer's stashed output and LayerNorm 2's kept 1/sigma for these rows (then the workspace holds no R2:
+// the recompute pass skipped FFN2), or null
 template <typename T>
-int layer_backward_group(l2l_ctx* c, const void* params, const void* x, void* dydx, float* G, int ng) {
+int layer_backward_group(l2l_ctx* c, const void* params, const void* x, void* dydx, float* G, int ng, const void* y = nullptr,
+                         const float* rstd2 = nullptr) {
   const l2l_config& f = c->cfg;
   const int H = f.hidden, A = f.heads, F = f.ffn, S = f.seq, d = H / A;
   const long long M = (long long)ng * c->T;
@@ -665,12 +720,16 @@ int layer_backward_group(l2l_ctx* c, const void* params, const void* x, void* dy
   T* qkv = (T*)c->qkv;
   T* dqkv = (T*)c->dqkv;
   const float alpha = 1.0f / sqrtf((float)d);
+  c->prof_pass = 2;
 
   // LN2 backward
   bool db1_in_gemm = false;
   const bool own_stats = ln_bwd_one_pass(H);   // then the recompute pass did not run LN2
-  L2L_TRY(ln_bwd<T>(c, dydx, c->r2, own_stats ? nullptr : c->mean2, own_stats ? nullptr : c->rstd2, P + off[T_G2], c->dr2,
-                    G + off[T_G2], G + off[T_BE2], G + off[T_B2], M, H, f.ln_eps));
+  if (y)
+    L2L_TRY(ln_bwd_from_y<T>(c, dydx, y, rstd2, P + off[T_G2], P + off[T_BE2], c->dr2, G + off[T_G2], G + off[T_BE2], G + off[T_B2], M, H));
+  else
+    L2L_TRY(ln_bwd<T>(c, dydx, c->r2, own_stats ? nullptr : c->mean2, own_stats ? nullptr : c->rstd2, P + off[T_G2], c->dr2,
+                      G + off[T_G2], G + off[T_BE2], G + off[T_B2], M, H, f.ln_eps));
   // FFN2 backward: dU1 = (dR2 W2^T) * gelu'(U1); dW2 += G^T dR2 (db2 came with LN2's backward)
   {
     GemmArgs g = gemm_args((int)M, F, H, c->dr2, H, 1, P + off[T_W2], H, 1, c->du1, F);
@@ -988,6 +1047,7 @@ int l2l_create(const l2l_config* cfg, void* compute_stream, void* copy_stream, l
   c->Mg = g * c->T;
   // the switches of the environment are read here, once, and nowhere else
   if (const char* e = getenv("L2L_NO_FUSED_ATTENTION")) c->no_fused_attention = atoi(e) != 0;
+  if (const char* e = getenv("L2L_NO_WEIGHT_TRANSPOSE")) c->no_weight_transpose = atoi(e) != 0;
   if (const char* e = getenv("L2L_FORCE_SPLITS")) c->force_splits = std::max(0, atoi(e));
   if (const char* e = getenv("L2L_SPLIT_ATOMICS")) c->split_atomics = atoi(e) != 0;
   {
@@ -1021,7 +1081,7 @@ int l2l_create(const l2l_config* cfg, void* compute_stream, void* copy_stream, l
       {&c->ga, Mg * F}, {&c->r2, Mg * H}, {&c->dr2, Mg * H}, {&c->du1, Mg * F}, {&c->dy1, Mg * H}, {&c->dr1, Mg * H},
       {&c->dc, Mg * H}, {&c->dp, pe}, {&c->dqkv, Mg * 3 * H}, {&c->ytmp, Mg * H}};
   for (auto& b : bufs) L2L_TRY(dev_alloc(c, b.p, b.n * es));
-  if (is16(cfg->dtype))
+  if (is16(cfg->dtype) && !c->no_weight_transpose)
     for (int i = 0; i < 2; ++i) L2L_TRY(dev_alloc(c, &c->wt[i], c->lay.total * es));
   if (is16(cfg->dtype)) {   // workspace of the K-split dW GEMMs: the largest of the layer's four, by the split rule in use
     size_t need = 0;
@@ -1136,7 +1196,7 @@ int l2l_param_stage(l2l_ctx* c, int layer, const void* host_params, int slot) {
   return L2L_OK;
 }
 
-int l2l_layer_fwd(l2l_ctx* c, int layer, int slot, const void* x_stash, void* y_out) {
+static int layer_fwd_impl(l2l_ctx* c, int layer, int slot, const void* x_stash, void* y_out, float* rstd_out) {
   L2L_TRY(check_slot_call(c, layer, slot, x_stash, y_out, "l2l_layer_fwd"));
   HIP_TRY(c, hipStreamWaitEvent(c->cs, c->slot_staged[slot], 0));
   const size_t es = esize(c->cfg.dtype);
@@ -1146,16 +1206,28 @@ int l2l_layer_fwd(l2l_ctx* c, int layer, int slot, const void* x_stash, void* y_
     const size_t o = (size_t)u0 * c->T * c->cfg.hidden * es;
     const void* x = (const char*)x_stash + o;
     void* y = (char*)y_out + o;
-    if (c->cfg.dtype == L2L_BF16) L2L_TRY(layer_forward_group<bf16>(c, slot, x, y, ng, false));
-    else if (c->cfg.dtype == L2L_FP16) L2L_TRY(layer_forward_group<fp16>(c, slot, x, y, ng, false));
-    else L2L_TRY(layer_forward_group<float>(c, slot, x, y, ng, false));
+    float* rs = rstd_out ? rstd_out + (size_t)u0 * c->T : nullptr;
+    if (c->cfg.dtype == L2L_BF16) L2L_TRY(layer_forward_group<bf16>(c, slot, x, y, ng, false, rs));
+    else if (c->cfg.dtype == L2L_FP16) L2L_TRY(layer_forward_group<fp16>(c, slot, x, y, ng, false, rs));
+    else L2L_TRY(layer_forward_group<float>(c, slot, x, y, ng, false, rs));
   }
   HIP_TRY(c, hipEventRecord(c->slot_released[slot], c->cs));
   return L2L_OK;
 }
 
-int l2l_layer_bwd(l2l_ctx* c, int layer, int slot, const void* x_stash, void* dy_dx) {
+int l2l_layer_fwd(l2l_ctx* c, int layer, int slot, const void* x_stash, void* y_out) {
+  return layer_fwd_impl(c, layer, slot, x_stash, y_out, nullptr);
+}
+
+int l2l_layer_fwd_stats(l2l_ctx* c, int layer, int slot, const void* x_stash, void* y_out, float* rstd_out) {
+  if (c && !rstd_out) return fail(c, L2L_E_ARG, "l2l_layer_fwd_stats: null pointer");
+  return layer_fwd_impl(c, layer, slot, x_stash, y_out, rstd_out);
+}
+
+static int layer_bwd_impl(l2l_ctx* c, int layer, int slot, const void* x_stash, void* dy_dx, const void* y_stash, const float* rstd) {
   L2L_TRY(check_slot_call(c, layer, slot, x_stash, dy_dx, "l2l_layer_bwd"));
+  // the shortcut through the stashed output needs the one-pass LayerNorm backward kernel; wider rows recompute in full
+  const bool from_y = y_stash && rstd && ln_bwd_one_pass(c->cfg.hidden);
   const int a = c->gacc_next;
   if (c->gacc_state[a] == 1)
     return fail(c, L2L_E_STATE, "l2l_layer_bwd: gradients of layer %d were never drained", c->gacc_layer[a]);
@@ -1169,15 +1241,17 @@ int l2l_layer_bwd(l2l_ctx* c, int layer, int slot, const void* x_stash, void* dy
     const size_t o = (size_t)u0 * c->T * c->cfg.hidden * es;
     const void* x = (const char*)x_stash + o;
     void* dy = (char*)dy_dx + o;
+    const void* y = from_y ? (const char*)y_stash + o : nullptr;
+    const float* rs = from_y ? rstd + (size_t)u0 * c->T : nullptr;
     if (c->cfg.dtype == L2L_BF16) {
-      L2L_TRY(layer_forward_group<bf16>(c, slot, x, nullptr, ng, true));  // recompute
-      L2L_TRY(layer_backward_group<bf16>(c, c->slot[slot], x, dy, G, ng));
+      L2L_TRY(layer_forward_group<bf16>(c, slot, x, nullptr, ng, true, nullptr, from_y));  // recompute
+      L2L_TRY(layer_backward_group<bf16>(c, c->slot[slot], x, dy, G, ng, y, rs));
     } else if (c->cfg.dtype == L2L_FP16) {
-      L2L_TRY(layer_forward_group<fp16>(c, slot, x, nullptr, ng, true));
-      L2L_TRY(layer_backward_group<fp16>(c, c->slot[slot], x, dy, G, ng));
+      L2L_TRY(layer_forward_group<fp16>(c, slot, x, nullptr, ng, true, nullptr, from_y));
+      L2L_TRY(layer_backward_group<fp16>(c, c->slot[slot], x, dy, G, ng, y, rs));
     } else {
-      L2L_TRY(layer_forward_group<float>(c, slot, x, nullptr, ng, true));
-      L2L_TRY(layer_backward_group<float>(c, c->slot[slot], x, dy, G, ng));
+      L2L_TRY(layer_forward_group<float>(c, slot, x, nullptr, ng, true, nullptr, from_y));
+      L2L_TRY(layer_backward_group<float>(c, c->slot[slot], x, dy, G, ng, y, rs));
     }
   }
   HIP_TRY(c, hipEventRecord(c->slot_released[slot], c->cs));
@@ -1186,6 +1260,15 @@ int l2l_layer_bwd(l2l_ctx* c, int layer, int slot, const void* x_stash, void* dy
   c->gacc_state[a] = 1;
   c->gacc_next = a ^ 1;
   return L2L_OK;
+}
+
+int l2l_layer_bwd(l2l_ctx* c, int layer, int slot, const void* x_stash, void* dy_dx) {
+  return layer_bwd_impl(c, layer, slot, x_stash, dy_dx, nullptr, nullptr);
+}
+
+int l2l_layer_bwd_stats(l2l_ctx* c, int layer, int slot, const void* x_stash, const void* y_stash, const float* rstd, void* dy_dx) {
+  if (c && (!y_stash || !rstd)) return fail(c, L2L_E_ARG, "l2l_layer_bwd_stats: null pointer");
+  return layer_bwd_impl(c, layer, slot, x_stash, dy_dx, y_stash, rstd);
 }
 
 // elements [first, first + count) of an fp32 accumulator -> the same elements of the host landing buffer, in the drain
@@ -1491,6 +1574,10 @@ static void prof_resolve(l2l_ctx* c) {
       float t0 = 0.f;
       if (c->prof_base && hipEventElapsedTime(&t0, c->prof_base, r.a) == hipSuccess)
         (r.cls == L2L_PROF_COPY ? c->iv_copy : c->iv_compute).push_back({t0, t0 + ms});
+      if (r.shape >= 0 && r.shape < (int)c->prof_shapes.size()) {
+        c->prof_shapes[r.shape].launches += 1;
+        c->prof_shapes[r.shape].ms += ms;
+      }
       c->prof_n[r.cls] += 1;
       c->prof_ms[r.cls] += ms;
       c->prof_fl[r.cls] += r.flops;
@@ -1509,6 +1596,7 @@ int l2l_profile(l2l_ctx* c, int on) {
   for (int i = 0; i < L2L_PROF_CLASSES; ++i) { c->prof_n[i] = 0; c->prof_ms[i] = c->prof_fl[i] = c->prof_by[i] = 0; }
   c->iv_compute.clear();
   c->iv_copy.clear();
+  c->prof_shapes.clear();
   c->prof_on = on;
   if (on) {
     if (!c->prof_base) HIP_TRY(c, hipEventCreate(&c->prof_base));
@@ -1550,6 +1638,20 @@ int l2l_profile_overlap(l2l_ctx* c, double merge_gap_ms, double* compute_busy_ms
   if (copy_busy_ms) *copy_busy_ms = length(b);
   if (copy_hidden_ms) *copy_hidden_ms = both;
   if (span_ms) *span_ms = last > first ? last - first : 0.0;
+  return L2L_OK;
+}
+
+int l2l_profile_gemm_table(l2l_ctx* c, char* buf, size_t cap) {
+  if (!c || !buf || cap == 0) return L2L_E_ARG;
+  prof_resolve(c);
+  size_t at = 0;
+  buf[0] = 0;
+  for (const ProfShape& p : c->prof_shapes) {
+    const int n = snprintf(buf + at, cap - at, "%d %d %d %d %d %d %d %d %lld %.6f\n", p.M, p.N, p.K, p.a_kc, p.b_kc, p.epi, p.out_f32,
+                           p.pass, p.launches, p.ms);
+    if (n < 0 || (size_t)n >= cap - at) return fail(c, L2L_E_ARG, "l2l_profile_gemm_table: %zu bytes are too few", cap);
+    at += (size_t)n;
+  }
   return L2L_OK;
 }
 

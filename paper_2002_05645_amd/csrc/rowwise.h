@@ -142,22 +142,34 @@ __global__ __launch_bounds__(256) void ln_bwd_dx_kernel(const T* dy, const T* x,
 // the row's values in registers between the two passes and the column sums in registers across rows;
 // the four waves' sums are combined in LDS and leave as one fp32 atomic per column and block.
 constexpr int LNF_ROWS = 64;   // measured best of 16 .. 128 at 32768 x 1024: fewer rows mean more atomics, more mean fewer waves
-template <typename T, int NCH>
+// FROMY: `x` holds the LayerNorm's OUTPUT y = gamma xhat + beta instead of its input, `rstd` the statistics kept by the
+// forward pass, and xhat is taken back out of y as (y - beta) / gamma; the input itself is then not needed (the
+// backward pass of the layer's last LayerNorm, whose output is the stashed boundary activation: the GEMM in front
+// of it need not be recomputed).  The caller makes sure that no |gamma| is tiny.
+template <typename T, int NCH, bool FROMY = false>
 __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* dy, const T* x, const float* mean, const float* rstd,
                                                            const T* gamma, T* dx, float* dgamma, float* dbeta,
-                                                           float* dbias, int rows, int n, float eps) {
+                                                           float* dbias, int rows, int n, float eps, const T* beta) {
   // mean == nullptr: the row statistics are computed here, from the row already held in registers (same two
   // passes as the forward kernel), which spares a forward-statistics kernel where nothing else needs its output
   extern __shared__ float lnf_red[];   // [4 waves][3][NCH * 512]
   constexpr int NC = NCH * 512;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   float sg[NCH][8], sb[NCH][8], sx[NCH][8], gam[NCH][8];
+  float bet[FROMY ? NCH : 1][8], ginv[FROMY ? NCH : 1][8];
 #pragma unroll
   for (int k = 0; k < NCH; ++k) {
     const int j = lane * 8 + k * 512;
 #pragma unroll
     for (int i = 0; i < 8; ++i) sg[k][i] = sb[k][i] = sx[k][i] = gam[k][i] = 0.f;
     if (j < n) load8(gamma + j, gam[k]);
+    if constexpr (FROMY) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) bet[k][i] = 0.f;
+      if (j < n) load8(beta + j, bet[k]);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) ginv[k][i] = 1.0f / gam[k][i];
+    }
   }
   const int r0 = blockIdx.x * LNF_ROWS, r1 = min(rows, r0 + LNF_ROWS);
   // 16-bit rows: the wave's next row is requested (as packed 16-byte words) before the current one is worked on, so
@@ -191,8 +203,10 @@ __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* dy, const T*
       }
     }
     if constexpr (AHEAD) request(r + 4);
-    float mu, rs;
-    if (mean) {
+    float mu = 0.f, rs;
+    if constexpr (FROMY) {
+      rs = rstd[r];
+    } else if (mean) {
       mu = mean[r];
       rs = rstd[r];
     } else {
@@ -219,7 +233,8 @@ __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* dy, const T*
       if (j < n) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-          xh[k][i] = (xh[k][i] - mu) * rs;
+          if constexpr (FROMY) xh[k][i] = (xh[k][i] - bet[k][i]) * ginv[k][i];
+          else xh[k][i] = (xh[k][i] - mu) * rs;
           const float gg = d[k][i] * gam[k][i];
           c1 += gg;
           c2 += gg * xh[k][i];

@@ -60,7 +60,7 @@ class L2LTrainer:
                  ln_eps=1e-12, lr=1e-4, beta1=0.9, beta2=0.999, eps_a=1e-8, ubatch_group=0,
                  eps_threads=0, stash="device", device="cuda:0", eager=False, optimizer="adam", weight_decay=0.0,
                  copy_cus=0, run_ahead=2, loss_scale=None, dynamic_loss_scale=True, scale_growth_interval=1000,
-                 num_classes=0, tail_parts=8, grad_dtype="fp32"):
+                 num_classes=0, tail_parts=8, grad_dtype="fp32", keep_ln_stats=True, serialize=False):
         assert stash in ("device", "host")
         assert optimizer in ("adam", "lamb")
         self.optimizer = optimizer
@@ -68,6 +68,10 @@ class L2LTrainer:
         # this runtime: gradient drains that are queued far ahead of their turn are carried out by a copy path
         # that moves 12.5 GB/s instead of 20 .. 54 GB/s, which makes deep models copy-bound.
         self.run_ahead = int(run_ahead)
+        # serialize: every stage and drain runs alone, with the compute stream idle, and the compute stream waits for
+        # it -- the execution that Section 2.2.1's cost model N (4 u C + 2 X) describes (no overlap of transfers and
+        # compute).  A measuring switch: results are the same, only the streams are joined around each transfer.
+        self.serialize = bool(serialize)
         self.L, self.H, self.S, self.V = layers, hidden, seq, vocab
         self.U, self.ub = num_ubatches, ubatch
         self.dtype = dtype
@@ -131,13 +135,23 @@ class L2LTrainer:
         # on the fp32 gradient buffers, which are filled from it first
         self._adam_from16 = grad_dtype != "fp32" and optimizer == "adam" and self.scaler.scale == 1.0 and self.scaler.static
         shape = (num_ubatches, ubatch, seq, hidden)
-        n_stash = layers + 1 if stash == "device" else 2
-        self.stash = [torch.empty(shape, dtype=tdt, device=self.device) for _ in range(n_stash)]
+        # keep_ln_stats: the forward pass keeps LayerNorm 2's 1 / sigma per token (4 bytes against the stash's 2 H), and
+        # the backward pass takes that LayerNorm's normalised input back out of the stashed layer output instead of
+        # recomputing the FFN2 product (l2l_layer_fwd_stats / l2l_layer_bwd_stats).  Only where the library has the
+        # one-pass LayerNorm backward (H <= 2048); per layer only while no |g2| is small (see _stats_ok).
+        self.keep_ln_stats = bool(keep_ln_stats) and hidden % 8 == 0 and hidden <= 2048
+        # host stash: transit slots on the device; with keep_ln_stats the backward pass of layer l reads the inputs of
+        # layers l and l + 1 while layer l - 1's is on its way in, hence three
+        self.nslot = (3 if self.keep_ln_stats else 2) if stash == "host" else layers + 1
+        self.stash = [torch.empty(shape, dtype=tdt, device=self.device) for _ in range(self.nslot)]
+        if self.keep_ln_stats:
+            self.rstd2 = torch.empty((layers, num_ubatches * ubatch * seq), dtype=torch.float32, device=self.device)
+        self._stats_ok = [False] * layers
         if stash == "host":
             self.host_stash = [torch.empty(shape, dtype=tdt, pin_memory=True) for _ in range(layers + 1)]
             self.stash_stream = torch.cuda.Stream(device=self.device)
-            self.stash_ev = [torch.cuda.Event() for _ in range(2)]
-            self.stash_free = [torch.cuda.Event() for _ in range(2)]
+            self.stash_ev = [torch.cuda.Event() for _ in range(self.nslot)]
+            self.stash_free = [torch.cuda.Event() for _ in range(self.nslot)]
         self.dy = torch.empty(shape, dtype=tdt, device=self.device)
         self.loss_dev = torch.zeros(1, dtype=torch.float32, device=self.device)
         self.t = 0
@@ -215,13 +229,39 @@ class L2LTrainer:
         return self.eps.grad_ptr(block) if self.grad_dtype == "fp32" else self.eps.grad16_ptr(block)
 
     def _stash_slot(self, l):
-        return self.stash[l] if self.stash_mode == "device" else self.stash[l % 2]
+        return self.stash[l % self.nslot]
+
+    def _stage(self, layer, block, slot):
+        if self.serialize:
+            self.copy.wait_stream(self.compute)
+        self.ctx.param_stage(layer, self.eps.ship_ptr(block), slot)
+        if self.serialize:
+            self.compute.wait_stream(self.copy)
+
+    def _drain(self, layer, block):
+        if self.serialize:
+            self.copy.wait_stream(self.compute)
+        self.ctx.grad_drain(layer, self._land_ptr(block))
+        if self.serialize:
+            self.compute.wait_stream(self.copy)
+
+    def _check_ln_gains(self):
+        """per layer: whether xhat = (y - be2) / g2 is safe to take from the stashed output (from the master weights)"""
+        if not self.keep_ln_stats:
+            return
+        o_g, n = self.layer_layout["g2"]
+        o_b, _ = self.layer_layout["be2"]
+        for l in range(self.L):
+            m = self.eps.master(1 + l)
+            g, b = np.abs(m[o_g:o_g + n]), np.abs(m[o_b:o_b + n])
+            self._stats_ok[l] = bool(g.min() >= 1.0 / 64.0 and (b <= 8.0 * g).all())
 
     def device_pipeline(self, tokens: torch.Tensor, labels: torch.Tensor):
         """Stage -> forward over layers -> head -> backward over layers -> drain.  Asynchronous:
         call finish() (or read the loss) to wait.  tokens / labels: int32 device tensors [U, ub, S]."""
         c, e, L = self.ctx, self.eps, self.L
         host_mode = self.stash_mode == "host"
+        self._check_ln_gains()
         if self._prestaged:          # the previous step's optimizer shipped the block (and layer 0) already
             self._prestaged = False
         else:
@@ -232,12 +272,15 @@ class L2LTrainer:
             self._offload(0)
         for l in range(L):
             if l + 1 < L:
-                c.param_stage(l + 1, e.ship_ptr(2 + l), (l + 1) % 2)
+                self._stage(l + 1, 2 + l, (l + 1) % 2)
             if host_mode:
-                self.compute.wait_event(self.stash_free[(l + 1) % 2])
+                self.compute.wait_event(self.stash_free[(l + 1) % self.nslot])
                 if self.run_ahead and l >= self.run_ahead:     # the stash offloads are device-to-host copies too
                     self._fwd_done[l - self.run_ahead].synchronize()
-            c.layer_fwd(l, l % 2, self._stash_slot(l), self._stash_slot(l + 1))
+            if self.keep_ln_stats:
+                c.layer_fwd_stats(l, l % 2, self._stash_slot(l), self._stash_slot(l + 1), self.rstd2[l])
+            else:
+                c.layer_fwd(l, l % 2, self._stash_slot(l), self._stash_slot(l + 1))
             if host_mode:
                 self._fwd_done[l].record(self.compute)
                 self._offload(l + 1)
@@ -251,19 +294,29 @@ class L2LTrainer:
         if host_mode:
             # the head is the consumer of the transit slot that holds layer L - 1's output: the reload of
             # layer L - 2's input into that slot must wait for it
-            self.stash_free[L % 2].record(self.compute)
+            self.stash_free[L % self.nslot].record(self.compute)
         for l in reversed(range(L)):
             if l - 1 >= 0:
-                c.param_stage(l - 1, e.ship_ptr(l), (l - 1) % 2)
+                self._stage(l - 1, l, (l - 1) % 2)
             if host_mode and l < L - 1:      # (layer L - 1's input is still in its slot from the forward pass)
                 self._reload(l)
             if self.run_ahead and l + self.run_ahead < L:
                 self._bwd_done[l + self.run_ahead].synchronize()
-            c.layer_bwd(l, l % 2, self._stash_slot(l), self.dy)
+            if self._stats_ok[l]:
+                c.layer_bwd_stats(l, l % 2, self._stash_slot(l), self._stash_slot(l + 1), self.rstd2[l], self.dy)
+            else:
+                c.layer_bwd(l, l % 2, self._stash_slot(l), self.dy)
             self._bwd_done[l].record(self.compute)
             if host_mode:
-                self.stash_free[l % 2].record(self.compute)
-            c.grad_drain(l, self._land_ptr(1 + l))
+                if self.keep_ln_stats:
+                    # three slots: layer l + 1's input, read above as layer l's output, is done with; layer l's own
+                    # input stays for layer l - 1's backward
+                    self.stash_free[(l + 1) % self.nslot].record(self.compute)
+                    if l == 0:
+                        self.stash_free[0].record(self.compute)
+                else:
+                    self.stash_free[l % self.nslot].record(self.compute)
+            self._drain(l, 1 + l)
             self._after_drain(1 + l)
         c.embed_bwd(tokens, self.dy)
         if self._parts:
@@ -341,19 +394,21 @@ class L2LTrainer:
     def _offload(self, l):
         """device stash slot -> pinned host after the producing kernels, on a stream of its own: the stash traffic
         then runs beside the parameter stages and gradient drains of the copy stream (the host link is full duplex)."""
-        ev = self.stash_ev[l % 2]
+        k = l % self.nslot
+        ev = self.stash_ev[k]
         ev.record(self.compute)
         self.stash_stream.wait_event(ev)
         with torch.cuda.stream(self.stash_stream):
-            self.host_stash[l].copy_(self.stash[l % 2], non_blocking=True)
-            self.stash_free[l % 2].record(self.stash_stream)
+            self.host_stash[l].copy_(self.stash[k], non_blocking=True)
+            self.stash_free[k].record(self.stash_stream)
 
     def _reload(self, l):
         """pinned host -> device stash slot before layer l's backward (layer L's input is not needed)."""
-        self.stash_stream.wait_event(self.stash_free[l % 2])
+        k = l % self.nslot
+        self.stash_stream.wait_event(self.stash_free[k])
         with torch.cuda.stream(self.stash_stream):
-            self.stash[l % 2].copy_(self.host_stash[l], non_blocking=True)
-            ev = self.stash_ev[l % 2]
+            self.stash[k].copy_(self.host_stash[l], non_blocking=True)
+            ev = self.stash_ev[k]
             ev.record(self.stash_stream)
         self.compute.wait_event(ev)
 

@@ -26,8 +26,8 @@ OUT16 = {"fp32": 2e-6, "bf16": 3e-3, "fp16": 4e-4}      # one rounding of a 16-b
 # fp32 roundings of sums of a few thousand terms.  16-bit modes: activations and activation gradients pass through a
 # dozen roundings to the format inside a layer (unit roundoff 2^-8 = 3.9e-3 for bf16, 2^-11 = 4.9e-4 for fp16) and the
 # single worst of up to 10^7 entries sits several standard deviations out.  Measured worst cases over this file:
-# fp32 1.7e-6, bf16 1.0e-2, fp16 1.6e-3; the bounds leave a factor of about three.
-MAXTOL = {"fp32": 2e-5, "bf16": 3e-2, "fp16": 5e-3}
+# fp32 1.7e-6, bf16 1.6e-2 (the BERT-Base step through 12 layers), fp16 1.6e-3; the bounds leave a factor of 2.5 or more.
+MAXTOL = {"fp32": 2e-5, "bf16": 4e-2, "fp16": 5e-3}
 ULP = {"bf16": 2.0 ** -7, "fp16": 2.0 ** -10}           # spacing of the format relative to the value, at most: half of it per rounding
 
 
@@ -308,7 +308,9 @@ def test_layernorm(ctx, dtype, rows, n):
 
 
 # ------------------------------------------------------------------------------------- one layer, all micro-batches
-def _layer_case(w: S.Workload, group=0, x_scale=1.0, check_fwd_only=False, dy_scale=1.0):
+def _layer_case(w: S.Workload, group=0, x_scale=1.0, check_fwd_only=False, dy_scale=1.0, stats=False):
+    """stats: l2l_layer_fwd_stats / l2l_layer_bwd_stats (LayerNorm 2's 1 / sigma kept, FFN2 not recomputed) instead of
+    l2l_layer_fwd / l2l_layer_bwd"""
     dtype = w.dtype
     cfg = P.make_config(w.hidden, w.heads, w.ffn, w.seq, w.ubatch, w.num_ubatches, dtype, 1e-12, 0, group)
     c = P.Context(cfg)
@@ -325,7 +327,11 @@ def _layer_case(w: S.Workload, group=0, x_scale=1.0, check_fwd_only=False, dy_sc
         Xd, dYd = to_dev(X, dtype), to_dev(dY, dtype)
         Yd = torch.empty_like(Xd)
         c.param_stage(0, host, 0)
-        c.layer_fwd(0, 0, Xd, Yd)
+        if stats:
+            rstd = torch.full((w.num_ubatches * w.ubatch * w.seq,), float("nan"), device="cuda")
+            c.layer_fwd_stats(0, 0, Xd, Yd, rstd)
+        else:
+            c.layer_fwd(0, 0, Xd, Yd)
         c.sync()
         _progress("device forward done")
         Xr, dYr = rounded(X, dtype), rounded(dY, dtype)
@@ -334,7 +340,10 @@ def _layer_case(w: S.Workload, group=0, x_scale=1.0, check_fwd_only=False, dy_sc
         errs = {}
         _both(errs, "Y", to_host(Yd), Yref)
         if not check_fwd_only:
-            c.layer_bwd(0, 0, Xd, dYd)
+            if stats:
+                c.layer_bwd_stats(0, 0, Xd, Yd, rstd, dYd)
+            else:
+                c.layer_bwd(0, 0, Xd, dYd)
             gh = torch.empty(total, dtype=torch.float32).pin_memory()
             c.grad_drain(0, gh)
             c.drain_wait(0)
@@ -414,6 +423,30 @@ def test_layer_fp16():
     _assert_errs(_layer_case(w, group=2), TOL["fp16"])
     w = S.WORKLOADS[1].scaled(num_ubatches=2, ubatch=4, dtype="fp16")
     _assert_errs(_layer_case(w), TOL["fp16"])
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16", "fp16"])
+def test_layer_with_kept_layernorm_statistics(dtype):
+    # l2l_layer_fwd_stats / l2l_layer_bwd_stats: the backward pass takes LayerNorm 2's xhat from the stashed output and
+    # the kept 1 / sigma and does not recompute FFN2; same oracle, same bars as the plain pair
+    w = S.Workload("ragged-stats", 1, 96, 3, 200, 24, 50, 3, 3, dtype, 1.0, 277)
+    _assert_errs(_layer_case(w, group=2, stats=True), TOL[dtype])
+    w = S.Workload("fused-stats", 1, 128, 2, 256, 64, 50, 3, 2, dtype, 1.0, 278)
+    _assert_errs(_layer_case(w, stats=True), TOL[dtype])
+    if dtype != "fp32":
+        w = S.Workload("long-stats", 1, 128, 2, 256, 256, 50, 2, 3, dtype, 1.0, 279)      # chunked attention, ragged last group
+        _assert_errs(_layer_case(w, group=2, stats=True, **(dict(dy_scale=256.0) if dtype == "fp16" else {})), TOL[dtype])
+
+
+def test_layer_with_kept_statistics_wide_rows_recomputes_in_full():
+    # H = 2304 > 2048: LayerNorm backward has no one-pass form there, l2l_layer_bwd_stats recomputes like l2l_layer_bwd
+    w = S.Workload("wide-stats", 1, 2304, 36, 256, 32, 50, 2, 2, "bf16", 1.0, 280)
+    _assert_errs(_layer_case(w, stats=True), TOL["bf16"])
+
+
+@pytest.mark.slow
+def test_layer_bert_large_full_shape_bf16_kept_statistics():
+    _assert_errs(_layer_case(S.WORKLOADS[2], stats=True), TOL["bf16"])
 
 
 def test_layer_single_sequence_single_ubatch():
@@ -633,9 +666,48 @@ def test_two_lamb_steps_match_oracle_fp32(eager):
         tr.close()
 
 
-def test_step_tiny_fp32_host_stash():
-    errs, _, _ = _step_case(S.WORKLOADS[0], stash="host")
+@pytest.mark.parametrize("keep_ln_stats", [True, False])
+def test_step_tiny_fp32_host_stash(keep_ln_stats):
+    # three transit slots with kept LayerNorm statistics (a layer's backward reads its input and its output), two without
+    errs, _, _ = _step_case(S.WORKLOADS[0].scaled(layers=5), stash="host", keep_ln_stats=keep_ln_stats)
     _assert_errs({k: v for k, v in errs.items() if not k.startswith("adam.")}, TOL["fp32"])
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_step_without_kept_layernorm_statistics(dtype):
+    # the literal recompute of Section 2.1 (l2l_layer_fwd / l2l_layer_bwd): every step test above runs the pair that
+    # keeps LayerNorm 2's statistics, this one the plain pair
+    errs, _, _ = _step_case(S.WORKLOADS[0].scaled(dtype=dtype), keep_ln_stats=False)
+    _assert_errs({k: v for k, v in errs.items() if not k.startswith("adam.")}, TOL[dtype])
+
+
+def test_step_falls_back_to_full_recompute_where_a_layernorm_gain_is_tiny():
+    # xhat = (y - be2) / g2 needs |g2| away from zero: the driver checks the master weights per layer and runs the
+    # plain backward where they are not
+    w = S.WORKLOADS[0]
+    tr = L2LTrainer(layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, vocab=w.vocab, ubatch=w.ubatch,
+                    num_ubatches=w.num_ubatches, dtype="fp32", eps_threads=4)
+    try:
+        emb = S.embed_params(w)
+        layers = [S.layer_params(w, l) for l in range(w.layers)]
+        layers[1]["g2"][5] = 1e-6
+        layers[1]["g2"][9] = 0.0
+        tr.load_params(emb, layers)
+        tok, lab = S.tokens_and_labels(w)
+        loss = tr.step(torch.from_numpy(tok).cuda(), torch.from_numpy(lab).cuda())
+        assert tr._stats_ok == [True, False]
+        loss_ref, gemb, gl = O.run_l2l(emb, layers, tok, lab, w.heads, 1e-12)
+        assert abs(loss - loss_ref) / abs(loss_ref) < 1e-4
+        ge, glayers = tr.grads()
+        errs = {}
+        for k in gemb:
+            _both(errs, "emb." + k, ge[k], gemb[k])
+        for l in range(w.layers):
+            for k in gl[l]:
+                _both(errs, f"l{l}.{k}", glayers[l][k], gl[l][k])
+        _assert_errs(errs, TOL["fp32"])
+    finally:
+        tr.close()
 
 
 @pytest.mark.parametrize("head_rows,label_prob", [(5, 1.0), (64, 1.0), (64, 0.3)])
