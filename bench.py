@@ -54,6 +54,7 @@ def write_gemm_table(path, rows, w, steps, out):
     """The layer GEMMs of the instrumented steps by launch shape, as a markdown table."""
     H, F = w.hidden, w.ffn
     role = {(3 * H, H, 1): "QKV", (H, H, 9): "out-proj (+ residual)", (F, H, 3): "FFN1 (+ GELU)", (H, F, 9): "FFN2 (+ residual)",
+            (F, H, 67): "FFN1 (+ GELU, keeps gelu')", (F, H, 128): "dU1 = dR2 W2^T * gelu'", (F, H, 160): "dU1 = dR2 W2^T * gelu' (+ db1 partial sums)",
             (F, H, 4): "dU1 = dR2 W2^T * gelu'", (F, H, 36): "dU1 = dR2 W2^T * gelu' (+ db1 partial sums)",
             (H, F, 8): "dY1 = dR2 + dU1 W1^T", (H, H, 0): "dC = dR1 Wo^T", (H, 3 * H, 8): "dX = dR1 + dQKV Wqkv^T"}
     lines = ["| GEMM | pass | M | N | K | layout (A, B) | launches / step | us / launch | TFLOP/s | of 2.5 PFLOP/s |", "|---|---|---|---|---|---|---|---|---|---|"]
@@ -102,6 +103,9 @@ def main():
     ap.add_argument("--no-ln-stats", action="store_true",
                     help="recompute the whole layer forward in the backward pass (l2l_layer_fwd / l2l_layer_bwd) instead of keeping "
                          "LayerNorm 2's row statistics and skipping the FFN2 product of the recompute")
+    ap.add_argument("--serialize", action="store_true",
+                    help="run every stage and drain alone, with the compute stream waiting for it (the execution Section 2.2.1's "
+                         "cost model describes); a measuring switch: under a tracer it keeps kernels and copies apart")
     ap.add_argument("--gemm-table", default="", metavar="FILE",
                     help="write the layer GEMMs by launch shape (HIP-event durations of the instrumented steps: launches, "
                          "microseconds per launch, TFLOP/s) to FILE as a markdown table")
@@ -131,7 +135,7 @@ def main():
         w = w.scaled(dtype=a.dtype)
     tr = L2LTrainer(layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, vocab=w.vocab,
                     ubatch=w.ubatch, num_ubatches=w.num_ubatches, dtype=w.dtype, ubatch_group=a.group, stash=a.stash,
-                    eager=not a.tail_adam, optimizer=a.optimizer, num_classes=a.classes, grad_dtype=a.grad_dtype, keep_ln_stats=not a.no_ln_stats,
+                    eager=not a.tail_adam, optimizer=a.optimizer, num_classes=a.classes, grad_dtype=a.grad_dtype, keep_ln_stats=not a.no_ln_stats, serialize=a.serialize,
                     **(dict(lr=1e-3, eps_a=1e-6, weight_decay=0.01) if a.optimizer == "lamb" else {}))
     if a.config == 4:
         # drawing 453 M normals per layer from the counter-based generator takes a minute per layer: layer 0 is drawn,
@@ -200,7 +204,7 @@ def main():
     peak_mem = torch.cuda.max_memory_allocated() + tr.ctx.device_bytes()
     out = {
         # the headline workload carries the baseline's metric name; sweeps and the other workloads say what they are
-        "metric": "train samples/sec, BERT-Large L2L batch 256" if (w.name == "bert-large" and samples == 256)
+        "metric": "train samples/sec, BERT-Large L2L batch 256" if (w.name == "bert-large" and samples == 256 and not a.serialize)
                   else f"train samples/sec, {w.name} L2L batch {samples}",
         "value": samples * a.steps / total_s,
         "unit": "samples/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_step,
@@ -211,7 +215,7 @@ def main():
                                + (f" (reduced depth: {w.layers} of the workload's {full_depth} layers)" if w.layers < full_depth else ""),
                    "stash": a.stash, "ubatch_group": tr.ctx.cfg.ubatch_group,
                    "device_pipeline_samples_per_s": samples * a.steps / dev_s, "device_pipeline_ms": 1e3 * dev_s / a.steps,
-                   "host_adam_exposed_ms": 1e3 * adam_s / a.steps, "eps": "tail" if a.tail_adam else "eager", "ln2_statistics_kept": bool(tr.keep_ln_stats), "optimizer": a.optimizer, "head": f"classification, {a.classes} classes" if a.classes else "tied LM head", "loss_first": loss0, "loss_last": loss, "losses": [round(x, 4) for x in losses],
+                   "host_adam_exposed_ms": 1e3 * adam_s / a.steps, "eps": "tail" if a.tail_adam else "eager", "ln2_statistics_kept": bool(tr.keep_ln_stats), "transfers": "serialised" if a.serialize else "overlapped", "optimizer": a.optimizer, "head": f"classification, {a.classes} classes" if a.classes else "tied LM head", "loss_first": loss0, "loss_last": loss, "losses": [round(x, 4) for x in losses],
                    "peak_device_bytes": int(peak_mem), "ctx_device_bytes": int(tr.ctx.device_bytes()),
                    "instrumented_ms_per_step": 1e3 * prof_total_s / a.steps,
                    # sum of kernel durations over the un-instrumented device-pipeline time; and the fraction of the

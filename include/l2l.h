@@ -286,12 +286,16 @@ int l2l_op_gemm(l2l_ctx*, int in_dtype, int out_f32, int a_kc, int b_kc, int M, 
    L2L_EPI_GELU: GELU after the bias; aux_out (or NULL) receives the pre-activation, [M,N] in in_dtype, row stride ldaux.
    L2L_EPI_GELUGRAD: the result is multiplied by gelu'(aux), aux: [M,N] in in_dtype, row stride ldaux (the FFN2
      backward GEMM that turns dG into dU1).  Not together with L2L_EPI_GELU.
+   L2L_EPI_KEEPGRAD (with L2L_EPI_GELU and aux_out): aux_out receives gelu'(u) instead of u -- what the recompute
+     pass's FFN1 GEMM leaves for the backward pass.
+   L2L_EPI_MULAUX: the result is multiplied element-wise by aux ([M,N] in in_dtype, row stride ldaux): the FFN2
+     backward GEMM with gelu'(U1) kept that way.  Not together with L2L_EPI_GELU or L2L_EPI_GELUGRAD.
    L2L_EPI_ACCUM: C += result (fp32 C).
    L2L_EPI_COLSUM: also leaves partial column sums of the stored values: colsum is device fp32 [colsum_rows][N];
      *colsum_rows_used (host int, may be NULL) receives how many rows were written; their sum over rows is the column
      sum of C (the bias gradient db1 = colsum(dU1) without a pass over dU1).  Only where the direct-to-LDS MFMA
      kernel takes the launch with 16-byte aligned rows (impl = 0, 16-bit output): otherwise L2L_E_ARG. */
-enum { L2L_EPI_GELU = 1, L2L_EPI_GELUGRAD = 2, L2L_EPI_ACCUM = 4, L2L_EPI_COLSUM = 8 };
+enum { L2L_EPI_GELU = 1, L2L_EPI_GELUGRAD = 2, L2L_EPI_ACCUM = 4, L2L_EPI_COLSUM = 8, L2L_EPI_KEEPGRAD = 16, L2L_EPI_MULAUX = 32 };
 int l2l_op_gemm_ex(l2l_ctx*, int in_dtype, int out_f32, int a_kc, int b_kc, int M, int N, int K,
                    const void* A, long long lda, const void* B, long long ldb, void* C, long long ldc,
                    float alpha, const void* bias, const void* resid, long long ldr, int epi,

@@ -17,7 +17,7 @@ L2L_F32, L2L_BF16, L2L_FP16 = 0, 1, 2
 DTYPES = {"fp32": L2L_F32, "bf16": L2L_BF16, "fp16": L2L_FP16}
 PROF_GEMM, PROF_ATTN, PROF_ROWWISE, PROF_COLSUM, PROF_OTHER = range(5)
 PROF_NAMES = ("gemm", "attn", "rowwise", "colsum", "other", "copy")
-EPI_GELU, EPI_GELUGRAD, EPI_ACCUM, EPI_COLSUM = 1, 2, 4, 8
+EPI_GELU, EPI_GELUGRAD, EPI_ACCUM, EPI_COLSUM, EPI_KEEPGRAD, EPI_MULAUX = 1, 2, 4, 8, 16, 32
 
 
 class l2l_config(C.Structure):

@@ -16,7 +16,7 @@ HIPCC = os.path.join(ROCM, "bin", "hipcc")
 HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 instructions
              "-munsafe-fp-atomics",      # fp32 atomics on device memory go to the hardware atomic units
-             "-Wno-unused-result"]
+             "-Wno-unused-result"] + os.environ.get("L2L_EXTRA_HIPFLAGS", "").split()   # (experiments: extra -D switches)
 with open(os.path.join(CSRC, "gemm_variants.h")) as _f:
     NUM_GEMM_VARIANTS = int(re.search(r"kNumGemmVariants\s*=\s*(\d+)", _f.read()).group(1))
 HOST_FLAGS = ["-O3", "-std=c++17", "-fPIC", "-mavx2", "-mfma", "-mf16c", "-fno-math-errno", "-fopenmp-simd",   # (sqrt without errno, simd reductions: the optimizer loops vectorise)

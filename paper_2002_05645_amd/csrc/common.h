@@ -127,16 +127,41 @@ __device__ __forceinline__ float gelu_grad_fast_f(float u) {
   return fmaf(p, s, 0.5f);
 }
 
+// GELU and its derivative from one evaluation of Phi: gelu(u) = u Phi(u), gelu'(u) = Phi(u) + u phi(u) with the
+// density phi(u) = exp(-u^2 / 2) / sqrt(2 pi) from the hardware's exponential (one transcendental instruction
+// instead of the second polynomial; |error| of gelu' = that of Phi, < 4e-5).  For the forward GEMM of a recompute
+// pass, which has u in registers and can leave gelu'(u) behind for the backward pass.
+__device__ __forceinline__ void gelu_and_grad_fast_f(float u, float& gelu, float& grad) {
+  const float s = __builtin_amdgcn_fmed3f(u, -4.0f, 4.0f) * 0.25f;
+  const float t = s * s;
+  float p = -1.372012435e+00f;
+  p = fmaf(p, t, 7.008298544e+00f);
+  p = fmaf(p, t, -1.555825966e+01f);
+  p = fmaf(p, t, 1.997211423e+01f);
+  p = fmaf(p, t, -1.672855746e+01f);
+  p = fmaf(p, t, 9.811292493e+00f);
+  p = fmaf(p, t, -4.228097766e+00f);
+  p = fmaf(p, t, 1.595222051e+00f);
+  const float cdf = fmaf(p, s, 0.5f);
+  gelu = u * cdf;
+  // exp(-u^2 / 2) = 2^(-u^2 log2(e) / 2); beyond |u| = 13 the argument is clamped (the density is 0 to fp32 there)
+  const float e = __builtin_amdgcn_exp2f(fmaxf(u * u * -0.72134752044448170f, -126.0f));
+  grad = fmaf(u * e, 0.39894228040143268f, cdf);
+}
+
 // GELU of the 16-bit epilogues: the polynomial forms.  Their absolute errors (4e-5 and 2e-4) are below half a unit
 // in the last place of bf16 everywhere and of fp16 (2.4e-4 relative) wherever the result exceeds 0.2 and 0.8; below
 // that they stay under one unit.
 template <typename E> __device__ __forceinline__ float gelu_epi(float u) { return gelu_fast_f(u); }
 template <typename E> __device__ __forceinline__ float gelu_grad_epi(float u) { return gelu_grad_fast_f(u); }
+template <typename E> __device__ __forceinline__ void gelu_and_grad_epi(float u, float& g, float& d) { gelu_and_grad_fast_f(u, g, d); }
 
 // Epilogue flags of the GEMM kernels.
 // EPI_COLSUM: also leave the column sums of the stored values in GemmArgs::colsum (a bias gradient that would
 // otherwise cost a pass over the output); the direct-to-LDS kernel's 16-byte epilogue path only.
-enum { EPI_BIAS = 1, EPI_GELU = 2, EPI_GELUGRAD = 4, EPI_RESID = 8, EPI_ACCUM = 16, EPI_COLSUM = 32 };
+// EPI_KEEPGRAD (with EPI_GELU and aux_out): aux_out receives gelu'(u) instead of the pre-activation u.
+// EPI_MULAUX: the result is multiplied by aux element-wise (aux = gelu'(u) kept by such a forward GEMM).
+enum { EPI_BIAS = 1, EPI_GELU = 2, EPI_GELUGRAD = 4, EPI_RESID = 8, EPI_ACCUM = 16, EPI_COLSUM = 32, EPI_KEEPGRAD = 64, EPI_MULAUX = 128 };
 
 // One GEMM launch: C[M,N] = epi(alpha * sum_k A(m,k) B(k,n)), optionally batched over z.
 struct GemmArgs {
@@ -153,8 +178,8 @@ struct GemmArgs {
   const void* bias;       // [N]
   const void* resid;      // [M,N], row stride ldr
   long long ldr;
-  const void* aux;        // EPI_GELUGRAD: pre-activation [M,N], row stride ldaux
-  void* aux_out;          // EPI_GELU: where to keep the pre-activation (or null)
+  const void* aux;        // EPI_GELUGRAD: pre-activation [M,N], row stride ldaux; EPI_MULAUX: the factor
+  void* aux_out;          // EPI_GELU: where to keep the pre-activation, or with EPI_KEEPGRAD gelu' of it (or null)
   long long ldaux;
   const int* m_dev;       // optional device-side bound on M (rows beyond it are not computed)
   const int* k_dev;       // optional device-side bound on K
@@ -162,6 +187,8 @@ struct GemmArgs {
                           // split s stores its partial result at C + s * split_stride (elements) and the caller adds them up
   int resident;           // direct-to-LDS kernel: > 0 = launch at most this many workgroups (one per compute unit) and let
                           // each walk its share of the tile order; 0 = one workgroup per tile
+  int stagger_groups;     // resident launches: > 1 = workgroup i starts ((i / 8) % stagger_groups) * stagger_ticks late, so that the
+  int stagger_ticks;      // groups reach their epilogues (bursts of HBM traffic) one after the other; ticks of the 100 MHz clock
   float* colsum;          // EPI_COLSUM: fp32 [ceil(M / WM)][N] (WM = rows of a wave's tile): row r receives the column sums
                           // of the values stored to rows r WM .. r WM + WM - 1 of C (plain stores; the caller adds the rows up)
 };
@@ -172,7 +199,7 @@ __host__ __device__ inline bool gemm_vec_ok(const GemmArgs& g, int epi, const vo
   const auto al16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
   return (g.N % 8 == 0) && (g.ldc % 8 == 0) && al16(C) && (!(epi & EPI_BIAS) || al16(g.bias)) &&
          (!(epi & EPI_RESID) || (g.ldr % 8 == 0 && al16(g.resid))) &&
-         (!(epi & EPI_GELUGRAD) || (g.ldaux % 8 == 0 && al16(g.aux))) &&
+         (!(epi & (EPI_GELUGRAD | EPI_MULAUX)) || (g.ldaux % 8 == 0 && al16(g.aux))) &&
          (!((epi & EPI_GELU) && g.aux_out) || (g.ldaux % 8 == 0 && al16(g.aux_out))) &&
          (!(epi & EPI_COLSUM) || al16(g.colsum));
 }

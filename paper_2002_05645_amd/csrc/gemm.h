@@ -20,10 +20,11 @@ template <typename T, typename TC>
 __device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, TC* C, long long m, long long n, float v) {
   if (g.epi & EPI_BIAS) v += to_f32(((const T*)g.bias)[n]);
   if (g.epi & EPI_GELU) {
-    if (g.aux_out) ((T*)g.aux_out)[m * g.ldaux + n] = from_f32<T>(v);
+    if (g.aux_out) ((T*)g.aux_out)[m * g.ldaux + n] = from_f32<T>((g.epi & EPI_KEEPGRAD) ? gelu_grad_f(v) : v);
     v = gelu_f(v);
   }
   if (g.epi & EPI_GELUGRAD) v *= gelu_grad_f(to_f32(((const T*)g.aux)[m * g.ldaux + n]));
+  if (g.epi & EPI_MULAUX) v *= to_f32(((const T*)g.aux)[m * g.ldaux + n]);
   if (g.epi & EPI_RESID) v += to_f32(((const T*)g.resid)[m * g.ldr + n]);
   TC* c = C + m * g.ldc + n;
   if (g.epi & EPI_ACCUM) v += to_f32(*c);
@@ -249,14 +250,25 @@ __device__ __forceinline__ void epilogue8(const GemmArgs& g, TC* C, long long m,
     for (int i = 0; i < 8; ++i) v[i] += t[i];
   }
   if (g.epi & EPI_GELU) {
-    if (g.aux_out) store8((E*)g.aux_out + m * g.ldaux + n, v);
+    if (g.aux_out && (g.epi & EPI_KEEPGRAD)) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] = gelu_epi<E>(v[i]);
+      for (int i = 0; i < 8; ++i) gelu_and_grad_epi<E>(v[i], v[i], t[i]);
+      store8((E*)g.aux_out + m * g.ldaux + n, t);
+    } else {
+      if (g.aux_out) store8((E*)g.aux_out + m * g.ldaux + n, v);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = gelu_epi<E>(v[i]);
+    }
   }
   if (g.epi & EPI_GELUGRAD) {
     load8((const E*)g.aux + m * g.ldaux + n, t);
 #pragma unroll
     for (int i = 0; i < 8; ++i) v[i] *= gelu_grad_epi<E>(t[i]);
+  }
+  if (g.epi & EPI_MULAUX) {
+    load8((const E*)g.aux + m * g.ldaux + n, t);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] *= t[i];
   }
   if (g.epi & EPI_RESID) {
     load8((const E*)g.resid + m * g.ldr + n, t);
@@ -375,7 +387,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_kernel(G
   const bool vec_ok = (N % 8 == 0) && (g.ldc % 8 == 0) && al16(C) &&
                       (!(g.epi & EPI_BIAS) || al16(g.bias)) &&
                       (!(g.epi & EPI_RESID) || (g.ldr % 8 == 0 && al16(g.resid))) &&
-                      (!(g.epi & EPI_GELUGRAD) || (g.ldaux % 8 == 0 && al16(g.aux))) &&
+                      (!(g.epi & (EPI_GELUGRAD | EPI_MULAUX)) || (g.ldaux % 8 == 0 && al16(g.aux))) &&
                       (!((g.epi & EPI_GELU) && g.aux_out) || (g.ldaux % 8 == 0 && al16(g.aux_out)));
   static_for<0, FM>([&](auto ic) {
     constexpr int i = decltype(ic)::value;
@@ -578,6 +590,14 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
     ra = make_rsrc(A, tile_bytes<AKC>(g.lda, M - m0, K));
     rb = make_rsrc(B, tile_bytes<BKC>(g.ldb, N - n0, K));
   };
+  // Workgroups that walk several tiles would all reach their epilogues at the same moments, and the epilogues'
+  // traffic (outputs, residuals, kept activations: not cached, unlike the operand panels) then comes in bursts that
+  // HBM serves at its own pace with every compute unit waiting; started a little apart, the groups take turns.
+  if (g.stagger_groups > 1 && gridDim.x < tiles_m * tiles_n) {
+    const long long wait = (long long)((blockIdx.x >> 3) % g.stagger_groups) * g.stagger_ticks;
+    const long long t_end = (long long)wall_clock64() + wait;
+    while ((long long)wall_clock64() < t_end) __builtin_amdgcn_s_sleep(16);
+  }
   int staged_vb = -1;   // the tile whose first k-tile is already on its way into stage 0 (issued under the previous epilogue)
   for (int vb = blockIdx.x; vb < tiles_m * tiles_n; vb += gridDim.x) {
   int tm, tn;
@@ -677,8 +697,16 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
   float csum8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};   // EPI_COLSUM: this lane's share of its 8 columns' sums
   // one 16-byte operand per pass is prefetched: the residual, or the pre-activation of GELU' (no epilogue of the
   // layer uses both; a launch that did would take the residual from memory in the pass itself)
-  const bool pre_aux = (epi & EPI_GELUGRAD) != 0, pre_res = !pre_aux && (epi & EPI_RESID);
-  u32x4 pre[2];
+  const bool pre_aux = (epi & (EPI_GELUGRAD | EPI_MULAUX)) != 0, pre_res = !pre_aux && (epi & EPI_RESID);
+  // A residual / kept-activation chunk is requested PD - 1 passes before the pass that uses it.  A pass takes a
+  // few hundred nanoseconds, a load from memory comes back after about one microsecond: requested one pass ahead
+  // every pass waited (measured: 11 us per 256 x 256 tile on top of a store-only epilogue, three passes ahead 6 us;
+  // four passes ahead would cost the first spilled registers).
+#ifndef L2L_EPI_DEPTH
+#define L2L_EPI_DEPTH 4
+#endif
+  constexpr int PD = L2L_EPI_DEPTH;
+  u32x4 pre[PD];
   // row offsets: the lane's own part (row prow of a pass, its 8 columns) once per tile; the pass's first row is the
   // same for the whole wave, so its product with the row stride is scalar work
   const long long pre_ld = pre_aux ? g.ldaux : g.ldr;
@@ -692,7 +720,10 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
   };
   if (vec_ok && !atomic) {
     if ((epi & EPI_BIAS) && ncol < N) load8((const E*)g.bias + ncol, bias8);
-    fetch(0, 0, pre[0]);
+    static_for<0, PD - 1>([&](auto qc) {
+      constexpr int q = decltype(qc)::value;
+      if constexpr (q < FM * PASSES) fetch(q / PASSES, q % PASSES, pre[q]);
+    });
   }
   // The first k-tile of this workgroup's next tile goes into stage 0 now, under the epilogue (issued after the
   // epilogue's own first loads: loads return in order, and the passes must not wait for 64 KB of operands).
@@ -732,11 +763,11 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     const int mrow0 = m0 + wm * WM + i * 32, ncol0 = n0 + wn * WN;
     if (vec_ok && !atomic) {
-      // a lane keeps its 8 columns through the tile: bias8 was loaded once, and the residual / pre-activation
-      // values of a pass were requested one pass earlier (pre[]), so that no pass waits for memory
+      // a lane keeps its 8 columns through the tile: bias8 was loaded once, and the residual / kept-activation
+      // values of a pass were requested PD - 1 passes earlier (pre[])
       static_for<0, PASSES>([&](auto pc) {
         constexpr int p = decltype(pc)::value, idx = i * PASSES + p;
-        if constexpr (idx + 1 < FM * PASSES) fetch((idx + 1) / PASSES, (idx + 1) % PASSES, pre[(idx + 1) & 1]);
+        if constexpr (idx + PD - 1 < FM * PASSES) fetch((idx + PD - 1) / PASSES, (idx + PD - 1) % PASSES, pre[(idx + PD - 1) % PD]);
         const int row = p * RPP + prow;
         const int m = mrow0 + row;
         if (m < M && ncol < N) {
@@ -747,17 +778,28 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
             for (int e = 0; e < 8; ++e) v[e] += bias8[e];
           }
           if (epi & EPI_GELU) {
-            if (g.aux_out) store8((E*)g.aux_out + (long long)m * g.ldaux + ncol, v);
+            if ((epi & EPI_KEEPGRAD) && g.aux_out) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = gelu_epi<E>(v[e]);
+              for (int e = 0; e < 8; ++e) gelu_and_grad_epi<E>(v[e], v[e], tt[e]);
+              store8((E*)g.aux_out + (long long)m * g.ldaux + ncol, tt);
+            } else {
+              if (g.aux_out) store8((E*)g.aux_out + (long long)m * g.ldaux + ncol, v);
+#pragma unroll
+              for (int e = 0; e < 8; ++e) v[e] = gelu_epi<E>(v[e]);
+            }
           }
           if (pre_aux) {
-            unpack8<E>(pre[idx & 1], tt);
+            unpack8<E>(pre[idx % PD], tt);
+            if (epi & EPI_MULAUX) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_epi<E>(tt[e]);
+              for (int e = 0; e < 8; ++e) v[e] *= tt[e];
+            } else {
+#pragma unroll
+              for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_epi<E>(tt[e]);
+            }
           }
           if (epi & EPI_RESID) {
-            if (pre_res) unpack8<E>(pre[idx & 1], tt);
+            if (pre_res) unpack8<E>(pre[idx % PD], tt);
             else load8((const E*)g.resid + (long long)m * g.ldr + ncol, tt);
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[e] += tt[e];

@@ -57,7 +57,7 @@ void launch_direct_one(const GemmArgs& g, hipStream_t s, int splits) {
 template <int BM, int BN, int WM, int WN, typename TC, typename E>
 void launch_direct(const GemmArgs& g, hipStream_t s, int splits) {
   // The 256 x 256 tile with 16-bit output and both operands K-contiguous carries the layer's forward, recompute and
-  // dX GEMMs: their seven epilogues get kernels with the flags compiled in (a third off the epilogue's time); any
+  // dX GEMMs: their eight epilogues get kernels with the flags compiled in (a third off the epilogue's time); any
   // other combination runs the kernel that reads the flags at run time.
   if constexpr (BM == 256 && BN == 256 && sizeof(TC) == 2) {
     if (g.a_kc && g.b_kc && g.alpha == 1.0f) {
@@ -67,8 +67,9 @@ void launch_direct(const GemmArgs& g, hipStream_t s, int splits) {
         L2L_EPI_CASE(EPI_BIAS)
         L2L_EPI_CASE(EPI_BIAS | EPI_RESID)
         L2L_EPI_CASE(EPI_BIAS | EPI_GELU)
-        L2L_EPI_CASE(EPI_GELUGRAD)
-        L2L_EPI_CASE(EPI_GELUGRAD | EPI_COLSUM)
+        L2L_EPI_CASE(EPI_BIAS | EPI_GELU | EPI_KEEPGRAD)
+        L2L_EPI_CASE(EPI_MULAUX)
+        L2L_EPI_CASE(EPI_MULAUX | EPI_COLSUM)
         L2L_EPI_CASE(EPI_RESID)
 #undef L2L_EPI_CASE
         default: break;

@@ -153,6 +153,7 @@ struct l2l_ctx {
   int force_splits = 0;                     // L2L_FORCE_SPLITS=n: split factor of the accumulating fp32 GEMMs
   int split_atomics = 0;                    // L2L_SPLIT_ATOMICS=1: K splits add with atomics, not through the workspace
   int no_weight_transpose = 0;              // L2L_NO_WEIGHT_TRANSPOSE=1: forward GEMMs read W as stored ([in, out], K-strided B operand)
+  int stagger_groups = 0, stagger_ns = 0;   // L2L_GEMM_STAGGER_GROUPS / L2L_GEMM_STAGGER_NS: start-time stagger of resident GEMM workgroups
   int resident_cus = 0;                     // workgroups of a resident GEMM launch (CUs of the device; L2L_GEMM_RESIDENT=0: none)
   int32_t* bad_ids = nullptr;               // device flag: a token id or label outside the vocabulary was seen
   long long T = 0, Mg = 0;                  // tokens per micro-batch, rows per launch group
@@ -449,6 +450,8 @@ int gemm(l2l_ctx* c, int dtype, bool out_f32, const GemmArgs& g, int impl = 0, i
       if (c->force_splits > 0 && out_f32 && g.epi == EPI_ACCUM) splits = c->force_splits;
       GemmArgs gr = g;
       gr.resident = c->resident_cus;
+      gr.stagger_groups = c->stagger_groups;
+      gr.stagger_ticks = c->stagger_ns / 10;
       // K split over grid.y: with a workspace the splits store their partial tiles (16-byte stores) and one kernel
       // adds them into C; without, they add into C with fp32 atomics, which run at the L2's atomic rate (65536 per
       // workgroup: 40 % of the time of a 1024 x 1024 x 32768 GEMM) and in no fixed order
@@ -686,7 +689,9 @@ int layer_forward_group(l2l_ctx* c, int slot, const void* x, void* y, int ng, bo
   // FFN1 + bias + GELU, FFN2 + bias + residual, LayerNorm 2
   {
     GemmArgs g = gemm_args((int)M, F, H, c->y1, H, 1, W + off[T_W1], wld(H, F), tw, c->ga, F);
-    g.epi = EPI_BIAS | EPI_GELU; g.bias = P + off[T_B1]; g.aux_out = keep ? c->u1 : nullptr; g.ldaux = F;
+    // (the recompute pass leaves gelu'(U1) behind instead of U1: the backward pass needs U1 for nothing else, and
+    // here it costs one exponential next to the Phi(U1) that GELU needs anyway)
+    g.epi = EPI_BIAS | EPI_GELU | (keep ? EPI_KEEPGRAD : 0); g.bias = P + off[T_B1]; g.aux_out = keep ? c->u1 : nullptr; g.ldaux = F;
     L2L_TRY(gemm(c, dt, false, g));
     if (keep && skip_ffn2) return L2L_OK;
     GemmArgs h = gemm_args((int)M, H, F, c->ga, F, 1, W + off[T_W2], wld(F, H), tw, c->r2, H);
@@ -733,7 +738,7 @@ int layer_backward_group(l2l_ctx* c, const void* params, const void* x, void* dy
   // FFN2 backward: dU1 = (dR2 W2^T) * gelu'(U1); dW2 += G^T dR2 (db2 came with LN2's backward)
   {
     GemmArgs g = gemm_args((int)M, F, H, c->dr2, H, 1, P + off[T_W2], H, 1, c->du1, F);
-    g.epi = EPI_GELUGRAD; g.aux = c->u1; g.ldaux = F;
+    g.epi = EPI_MULAUX; g.aux = c->u1; g.ldaux = F;   // u1 holds gelu'(U1), kept by the recompute pass
     // db1 = colsum(dU1) comes out of this GEMM's epilogue where it can: one row of partial sums per 128 rows of dU1,
     // added up by the column-sum kernel (256 x F floats instead of M x F elements)
     int ws_rows = 0;
@@ -1049,6 +1054,8 @@ int l2l_create(const l2l_config* cfg, void* compute_stream, void* copy_stream, l
   if (const char* e = getenv("L2L_NO_FUSED_ATTENTION")) c->no_fused_attention = atoi(e) != 0;
   if (const char* e = getenv("L2L_NO_WEIGHT_TRANSPOSE")) c->no_weight_transpose = atoi(e) != 0;
   if (const char* e = getenv("L2L_FORCE_SPLITS")) c->force_splits = std::max(0, atoi(e));
+  if (const char* e = getenv("L2L_GEMM_STAGGER_GROUPS")) c->stagger_groups = std::min(32, std::max(0, atoi(e)));
+  if (const char* e = getenv("L2L_GEMM_STAGGER_NS")) c->stagger_ns = std::min(20000, std::max(0, atoi(e)));
   if (const char* e = getenv("L2L_SPLIT_ATOMICS")) c->split_atomics = atoi(e) != 0;
   {
     int dev = 0, n = 0;
@@ -1676,7 +1683,11 @@ int l2l_op_gemm_ex(l2l_ctx* c, int in_dtype, int out_f32, int a_kc, int b_kc, in
   if (M < 0 || N < 0 || K < 0 || lda <= 0 || ldb <= 0 || ldc < N) return fail(c, L2L_E_ARG, "l2l_op_gemm: bad shape");
   if (in_dtype != L2L_F32 && in_dtype != L2L_BF16 && in_dtype != L2L_FP16) return fail(c, L2L_E_ARG, "l2l_op_gemm: bad dtype");
   if (in_dtype == L2L_F32) out_f32 = 1;
-  if (epi & ~(L2L_EPI_GELU | L2L_EPI_GELUGRAD | L2L_EPI_ACCUM | L2L_EPI_COLSUM)) return fail(c, L2L_E_ARG, "l2l_op_gemm: unknown epilogue flag in %d", epi);
+  if (epi & ~(L2L_EPI_GELU | L2L_EPI_GELUGRAD | L2L_EPI_ACCUM | L2L_EPI_COLSUM | L2L_EPI_KEEPGRAD | L2L_EPI_MULAUX))
+    return fail(c, L2L_E_ARG, "l2l_op_gemm: unknown epilogue flag in %d", epi);
+  if ((epi & L2L_EPI_KEEPGRAD) && (!(epi & L2L_EPI_GELU) || !aux_out)) return fail(c, L2L_E_ARG, "l2l_op_gemm: keeping gelu' goes with GELU and a buffer for it");
+  if ((epi & L2L_EPI_MULAUX) && (!aux || ldaux < N || (epi & (L2L_EPI_GELU | L2L_EPI_GELUGRAD))))
+    return fail(c, L2L_E_ARG, "l2l_op_gemm: the element-wise factor needs its buffer and row stride, and excludes GELU and GELU'");
   if ((epi & L2L_EPI_ACCUM) && !out_f32) return fail(c, L2L_E_ARG, "l2l_op_gemm: accumulate needs an fp32 output");
   if (impl < 0 || (impl > 2 && impl < 100)) return fail(c, L2L_E_ARG, "l2l_op_gemm: impl %d", impl);
   if (resid && ldr < N) return fail(c, L2L_E_ARG, "l2l_op_gemm: residual row stride %lld < N", ldr);
@@ -1687,6 +1698,8 @@ int l2l_op_gemm_ex(l2l_ctx* c, int in_dtype, int out_f32, int a_kc, int b_kc, in
   g.alpha = alpha;
   if (bias) { g.epi |= EPI_BIAS; g.bias = bias; }
   if (epi & L2L_EPI_GELU) { g.epi |= EPI_GELU; g.aux_out = aux_out; g.ldaux = ldaux; }
+  if (epi & L2L_EPI_KEEPGRAD) g.epi |= EPI_KEEPGRAD;
+  if (epi & L2L_EPI_MULAUX) { g.epi |= EPI_MULAUX; g.aux = aux; g.ldaux = ldaux; }
   if (epi & L2L_EPI_GELUGRAD) { g.epi |= EPI_GELUGRAD; g.aux = aux; g.ldaux = ldaux; }
   if (resid) { g.epi |= EPI_RESID; g.resid = resid; g.ldr = ldr; }
   if (epi & L2L_EPI_ACCUM) g.epi |= EPI_ACCUM;

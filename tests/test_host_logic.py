@@ -368,6 +368,19 @@ def test_fast_gelu_polynomials_match_exact_functions():
     assert np.abs(dgelu[big] - (u[big] > 0)).max() <= 1e-5
 
 
+def test_gelu_gradient_from_phi_and_the_density_matches_the_exact_function():
+    # the recompute pass's FFN1 epilogue forms gelu'(u) = Phi(u) + u phi(u) from the polynomial Phi and an exponential
+    # (csrc/common.h, gelu_and_grad_fast_f): the same arithmetic in fp32 here, against the exact derivative
+    u = np.linspace(-20.0, 20.0, 800001).astype(np.float32)
+    cdf = _fast_form("gelu_fast_f", 4.0)(u)
+    arg = np.maximum((u * u).astype(np.float32) * np.float32(-0.72134752044448170), np.float32(-126.0)).astype(np.float32)
+    dens = np.exp2(arg).astype(np.float32)
+    grad = ((u * dens).astype(np.float32) * np.float32(0.39894228040143268) + cdf).astype(np.float32)
+    assert np.abs(grad - O.gelu_grad(u.astype(np.float64))).max() < 6e-5
+    big = np.abs(u) > 6
+    assert np.abs(grad[big] - (u[big] > 0)).max() <= 1e-6
+
+
 @pytest.mark.parametrize("kind", ["address,undefined", "thread"])
 def test_eps_under_sanitizers_with_two_calling_threads(kind, tmp_path):
     # csrc/eps.cpp built for the host alone under ASan + UBSan and under TSan, driven by two threads that call into one
