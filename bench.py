@@ -19,7 +19,7 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0       # MI355X dense bf16 MFMA
 # HBM bytes per layer-GEMM launch of the headline workload, from counters collected offline (see roofline.traffic_source)
-HBM_TRAFFIC_PER_LAUNCH = 631.1e6
+HBM_TRAFFIC_PER_LAUNCH = 553.9e6
 
 
 def cpu_baseline(w):

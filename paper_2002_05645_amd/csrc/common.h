@@ -187,8 +187,6 @@ struct GemmArgs {
                           // split s stores its partial result at C + s * split_stride (elements) and the caller adds them up
   int resident;           // direct-to-LDS kernel: > 0 = launch at most this many workgroups (one per compute unit) and let
                           // each walk its share of the tile order; 0 = one workgroup per tile
-  int stagger_groups;     // resident launches: > 1 = workgroup i starts ((i / 8) % stagger_groups) * stagger_ticks late, so that the
-  int stagger_ticks;      // groups reach their epilogues (bursts of HBM traffic) one after the other; ticks of the 100 MHz clock
   float* colsum;          // EPI_COLSUM: fp32 [ceil(M / WM)][N] (WM = rows of a wave's tile): row r receives the column sums
                           // of the values stored to rows r WM .. r WM + WM - 1 of C (plain stores; the caller adds the rows up)
 };

@@ -590,14 +590,6 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_mfma_dlds_ker
     ra = make_rsrc(A, tile_bytes<AKC>(g.lda, M - m0, K));
     rb = make_rsrc(B, tile_bytes<BKC>(g.ldb, N - n0, K));
   };
-  // Workgroups that walk several tiles would all reach their epilogues at the same moments, and the epilogues'
-  // traffic (outputs, residuals, kept activations: not cached, unlike the operand panels) then comes in bursts that
-  // HBM serves at its own pace with every compute unit waiting; started a little apart, the groups take turns.
-  if (g.stagger_groups > 1 && gridDim.x < tiles_m * tiles_n) {
-    const long long wait = (long long)((blockIdx.x >> 3) % g.stagger_groups) * g.stagger_ticks;
-    const long long t_end = (long long)wall_clock64() + wait;
-    while ((long long)wall_clock64() < t_end) __builtin_amdgcn_s_sleep(16);
-  }
   int staged_vb = -1;   // the tile whose first k-tile is already on its way into stage 0 (issued under the previous epilogue)
   for (int vb = blockIdx.x; vb < tiles_m * tiles_n; vb += gridDim.x) {
   int tm, tn;

@@ -153,7 +153,6 @@ struct l2l_ctx {
   int force_splits = 0;                     // L2L_FORCE_SPLITS=n: split factor of the accumulating fp32 GEMMs
   int split_atomics = 0;                    // L2L_SPLIT_ATOMICS=1: K splits add with atomics, not through the workspace
   int no_weight_transpose = 0;              // L2L_NO_WEIGHT_TRANSPOSE=1: forward GEMMs read W as stored ([in, out], K-strided B operand)
-  int stagger_groups = 0, stagger_ns = 0;   // L2L_GEMM_STAGGER_GROUPS / L2L_GEMM_STAGGER_NS: start-time stagger of resident GEMM workgroups
   int resident_cus = 0;                     // workgroups of a resident GEMM launch (CUs of the device; L2L_GEMM_RESIDENT=0: none)
   int32_t* bad_ids = nullptr;               // device flag: a token id or label outside the vocabulary was seen
   long long T = 0, Mg = 0;                  // tokens per micro-batch, rows per launch group
@@ -450,8 +449,6 @@ int gemm(l2l_ctx* c, int dtype, bool out_f32, const GemmArgs& g, int impl = 0, i
       if (c->force_splits > 0 && out_f32 && g.epi == EPI_ACCUM) splits = c->force_splits;
       GemmArgs gr = g;
       gr.resident = c->resident_cus;
-      gr.stagger_groups = c->stagger_groups;
-      gr.stagger_ticks = c->stagger_ns / 10;
       // K split over grid.y: with a workspace the splits store their partial tiles (16-byte stores) and one kernel
       // adds them into C; without, they add into C with fp32 atomics, which run at the L2's atomic rate (65536 per
       // workgroup: 40 % of the time of a 1024 x 1024 x 32768 GEMM) and in no fixed order
@@ -1054,8 +1051,6 @@ int l2l_create(const l2l_config* cfg, void* compute_stream, void* copy_stream, l
   if (const char* e = getenv("L2L_NO_FUSED_ATTENTION")) c->no_fused_attention = atoi(e) != 0;
   if (const char* e = getenv("L2L_NO_WEIGHT_TRANSPOSE")) c->no_weight_transpose = atoi(e) != 0;
   if (const char* e = getenv("L2L_FORCE_SPLITS")) c->force_splits = std::max(0, atoi(e));
-  if (const char* e = getenv("L2L_GEMM_STAGGER_GROUPS")) c->stagger_groups = std::min(32, std::max(0, atoi(e)));
-  if (const char* e = getenv("L2L_GEMM_STAGGER_NS")) c->stagger_ns = std::min(20000, std::max(0, atoi(e)));
   if (const char* e = getenv("L2L_SPLIT_ATOMICS")) c->split_atomics = atoi(e) != 0;
   {
     int dev = 0, n = 0;
