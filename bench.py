@@ -103,6 +103,8 @@ def main():
     ap.add_argument("--no-ln-stats", action="store_true",
                     help="recompute the whole layer forward in the backward pass (l2l_layer_fwd / l2l_layer_bwd) instead of keeping "
                          "LayerNorm 2's row statistics and skipping the FFN2 product of the recompute")
+    ap.add_argument("--stash-copy", default="rows", choices=["rows", "plain"],
+                    help="host-stash mode: how the stash moves (rows: l2l_memcpy_rows_async, DMA engines; plain: torch copy_)")
     ap.add_argument("--serialize", action="store_true",
                     help="run every stage and drain alone, with the compute stream waiting for it (the execution Section 2.2.1's "
                          "cost model describes); a measuring switch: under a tracer it keeps kernels and copies apart")
@@ -135,7 +137,7 @@ def main():
         w = w.scaled(dtype=a.dtype)
     tr = L2LTrainer(layers=w.layers, hidden=w.hidden, heads=w.heads, ffn=w.ffn, seq=w.seq, vocab=w.vocab,
                     ubatch=w.ubatch, num_ubatches=w.num_ubatches, dtype=w.dtype, ubatch_group=a.group, stash=a.stash,
-                    eager=not a.tail_adam, optimizer=a.optimizer, num_classes=a.classes, grad_dtype=a.grad_dtype, keep_ln_stats=not a.no_ln_stats, serialize=a.serialize,
+                    eager=not a.tail_adam, optimizer=a.optimizer, num_classes=a.classes, grad_dtype=a.grad_dtype, keep_ln_stats=not a.no_ln_stats, serialize=a.serialize, stash_copy=a.stash_copy,
                     **(dict(lr=1e-3, eps_a=1e-6, weight_decay=0.01) if a.optimizer == "lamb" else {}))
     if a.config == 4:
         # drawing 453 M normals per layer from the counter-based generator takes a minute per layer: layer 0 is drawn,

@@ -104,6 +104,7 @@ int    l2l_config_check(const l2l_config*);
      L2L_SPLIT_WS_MB=n         room for the partial results of K-split GEMMs (default: what the layer's dW GEMMs need)
      L2L_SPLIT_ATOMICS=1       K-split GEMMs add their partial results with fp32 atomics instead
      L2L_FORCE_SPLITS=n        split factor of the accumulating fp32 GEMMs (default: by shape)
+     L2L_COPY_ROWS=0           gradient drains issued as plain copies (the runtime's copy kernel) instead of rows of 64 KiB (DMA engine)
      L2L_NO_WEIGHT_TRANSPOSE=1 forward GEMMs read the weights as stored, as a K-strided operand (no [out,in] copies per stage)
      L2L_GEMM_RESIDENT=0       one workgroup per GEMM tile instead of one resident workgroup per compute unit */
 int  l2l_create(const l2l_config*, void* compute_stream, void* copy_stream, l2l_ctx** out);
@@ -125,6 +126,13 @@ int  l2l_sync(l2l_ctx*);
    L2L_E_ARG for a bad count or a null pointer, L2L_E_HIP if the runtime refuses. */
 int  l2l_stream_create_cu_masked(int cus_per_32, void** out);
 int  l2l_stream_destroy(void* stream);
+/* Asynchronous copy between pinned host memory and device memory on `stream` (a hipStream_t), issued as rows of
+   64 KiB so that the runtime carries it out with a DMA engine in either direction (a plain device-to-host
+   hipMemcpyAsync is carried out by a copy kernel here, whose workgroups occupy compute units for the length of the
+   transfer).  For the stash offload and reload of Section 2.1's constant-memory mode, which move a layer boundary
+   activation per layer visit beside the layer's kernels.  to_host: 1 = device to host, 0 = host to device.
+   L2L_E_ARG for null pointers, L2L_E_HIP if the runtime refuses. */
+int  l2l_memcpy_rows_async(void* dst, const void* src, size_t bytes, int to_host, void* stream);
 
 /* ---- the four calls of the relay (Algorithm 2; Section 2.1) -------------------------------------- */
 

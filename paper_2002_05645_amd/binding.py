@@ -108,6 +108,7 @@ _SIGS = {
     "l2l_set_loss_scale": (C.c_int, [_P, C.c_float]),
     "l2l_stream_create_cu_masked": (C.c_int, [C.c_int, C.POINTER(C.c_void_p)]),
     "l2l_stream_destroy": (C.c_int, [C.c_void_p]),
+    "l2l_memcpy_rows_async": (C.c_int, [_P, _P, C.c_size_t, C.c_int, _P]),
     "eps_adam_step": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_double, C.c_double, C.c_double, C.c_double]),
     "eps_adam_step_range": (C.c_int, [_P, C.c_int, C.c_longlong, C.c_longlong, C.c_int, C.c_double, C.c_double, C.c_double,
                                       C.c_double]),
@@ -184,6 +185,13 @@ def stream_destroy(handle: int):
     rc = lib().l2l_stream_destroy(handle)
     if rc != L2L_OK:
         raise L2LError(rc, "l2l_stream_destroy")
+
+
+def memcpy_rows_async(dst, src, nbytes, to_host, stream):
+    """pinned host <-> device copy through a DMA engine in either direction; see include/l2l.h"""
+    rc = lib().l2l_memcpy_rows_async(_ptr(dst), _ptr(src), int(nbytes), int(bool(to_host)), stream or None)
+    if rc != L2L_OK:
+        raise L2LError(rc, "l2l_memcpy_rows_async")
 
 
 def _ptr(x):

@@ -152,6 +152,7 @@ struct l2l_ctx {
   int no_fused_attention = 0;               // L2L_NO_FUSED_ATTENTION=1: use the batched-GEMM attention path
   int force_splits = 0;                     // L2L_FORCE_SPLITS=n: split factor of the accumulating fp32 GEMMs
   int split_atomics = 0;                    // L2L_SPLIT_ATOMICS=1: K splits add with atomics, not through the workspace
+  int copy_rows = 1;                        // drains issued as rows (DMA engine); L2L_COPY_ROWS=0: as plain copies (the runtime's copy kernel)
   int no_weight_transpose = 0;              // L2L_NO_WEIGHT_TRANSPOSE=1: forward GEMMs read W as stored ([in, out], K-strided B operand)
   int resident_cus = 0;                     // workgroups of a resident GEMM launch (CUs of the device; L2L_GEMM_RESIDENT=0: none)
   int32_t* bad_ids = nullptr;               // device flag: a token id or label outside the vocabulary was seen
@@ -1049,6 +1050,7 @@ int l2l_create(const l2l_config* cfg, void* compute_stream, void* copy_stream, l
   c->Mg = g * c->T;
   // the switches of the environment are read here, once, and nowhere else
   if (const char* e = getenv("L2L_NO_FUSED_ATTENTION")) c->no_fused_attention = atoi(e) != 0;
+  if (const char* e = getenv("L2L_COPY_ROWS")) c->copy_rows = atoi(e) != 0;
   if (const char* e = getenv("L2L_NO_WEIGHT_TRANSPOSE")) c->no_weight_transpose = atoi(e) != 0;
   if (const char* e = getenv("L2L_FORCE_SPLITS")) c->force_splits = std::max(0, atoi(e));
   if (const char* e = getenv("L2L_SPLIT_ATOMICS")) c->split_atomics = atoi(e) != 0;
@@ -1273,11 +1275,27 @@ int l2l_layer_bwd_stats(l2l_ctx* c, int layer, int slot, const void* x_stash, co
   return layer_bwd_impl(c, layer, slot, x_stash, dy_dx, y_stash, rstd);
 }
 
+// A host <-> device copy issued as rows of 64 KiB (hipMemcpy2DAsync) plus a plain copy of the remainder.  This
+// runtime carries a plain device-to-host hipMemcpyAsync out with a copy kernel, whose workgroups sit on the compute
+// units for the length of the transfer; a resident GEMM workgroup needs a compute unit's whole register file and
+// cannot be placed beside them.  Written as rows, the same bytes go through a DMA engine in either direction.
+static hipError_t memcpy_rows_async(void* dst, const void* src, size_t bytes, hipMemcpyKind kind, hipStream_t s) {
+  constexpr size_t ROW = 64 << 10;
+  const size_t rows = bytes / ROW, body = rows * ROW;
+  if (rows > 0) {
+    const hipError_t e = hipMemcpy2DAsync(dst, ROW, src, ROW, ROW, rows, kind, s);
+    if (e != hipSuccess) return e;
+  }
+  if (bytes > body) return hipMemcpyAsync((char*)dst + body, (const char*)src + body, bytes - body, kind, s);
+  return hipSuccess;
+}
+
 // elements [first, first + count) of an fp32 accumulator -> the same elements of the host landing buffer, in the drain
 // format, on the copy stream
 static int drain_copy(l2l_ctx* c, void* host, const float* acc, long long first, long long count) {
   if (c->drain_dtype == L2L_F32) {
-    HIP_TRY(c, hipMemcpyAsync((float*)host + first, acc + first, count * 4, hipMemcpyDeviceToHost, c->xs));
+    if (c->copy_rows) HIP_TRY(c, memcpy_rows_async((float*)host + first, acc + first, count * 4, hipMemcpyDeviceToHost, c->xs));
+    else HIP_TRY(c, hipMemcpyAsync((float*)host + first, acc + first, count * 4, hipMemcpyDeviceToHost, c->xs));
     return L2L_OK;
   }
   if ((size_t)count > c->drain_stage_elems) return fail(c, L2L_E_STATE, "drain: %lld elements exceed the 16-bit staging buffer", count);
@@ -1286,7 +1304,8 @@ static int drain_copy(l2l_ctx* c, void* host, const float* acc, long long first,
   else hipLaunchKernelGGL(narrow_kernel<fp16>, dim3(blocks), dim3(256), 0, c->xs, acc + first, (fp16*)c->drain_stage, count);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(c, L2L_E_HIP, "narrow launch: %s", hipGetErrorString(e));
-  HIP_TRY(c, hipMemcpyAsync((char*)host + first * 2, c->drain_stage, count * 2, hipMemcpyDeviceToHost, c->xs));
+  if (c->copy_rows) HIP_TRY(c, memcpy_rows_async((char*)host + first * 2, c->drain_stage, count * 2, hipMemcpyDeviceToHost, c->xs));
+  else HIP_TRY(c, hipMemcpyAsync((char*)host + first * 2, c->drain_stage, count * 2, hipMemcpyDeviceToHost, c->xs));
   return L2L_OK;
 }
 static double drain_bytes(const l2l_ctx* c, long long count) { return (double)count * (c->drain_dtype == L2L_F32 ? 4 : 2); }
@@ -1555,6 +1574,16 @@ int l2l_stream_create_cu_masked(int cus_per_32, void** out) {
     return L2L_E_HIP;
   }
   *out = (void*)s;
+  return L2L_OK;
+}
+
+int l2l_memcpy_rows_async(void* dst, const void* src, size_t bytes, int to_host, void* stream) {
+  if (!dst || !src) return L2L_E_ARG;
+  if (bytes == 0) return L2L_OK;
+  if (memcpy_rows_async(dst, src, bytes, to_host ? hipMemcpyDeviceToHost : hipMemcpyHostToDevice, (hipStream_t)stream) != hipSuccess) {
+    (void)hipGetLastError();
+    return L2L_E_HIP;
+  }
   return L2L_OK;
 }
 

@@ -60,7 +60,7 @@ class L2LTrainer:
                  ln_eps=1e-12, lr=1e-4, beta1=0.9, beta2=0.999, eps_a=1e-8, ubatch_group=0,
                  eps_threads=0, stash="device", device="cuda:0", eager=False, optimizer="adam", weight_decay=0.0,
                  copy_cus=0, run_ahead=2, loss_scale=None, dynamic_loss_scale=True, scale_growth_interval=1000,
-                 num_classes=0, tail_parts=8, grad_dtype="fp32", keep_ln_stats=True, serialize=False):
+                 num_classes=0, tail_parts=8, grad_dtype="fp32", keep_ln_stats=True, serialize=False, stash_copy="rows"):
         assert stash in ("device", "host")
         assert optimizer in ("adam", "lamb")
         self.optimizer = optimizer
@@ -72,6 +72,10 @@ class L2LTrainer:
         # it -- the execution that Section 2.2.1's cost model N (4 u C + 2 X) describes (no overlap of transfers and
         # compute).  A measuring switch: results are the same, only the streams are joined around each transfer.
         self.serialize = bool(serialize)
+        # stash traffic of the host-stash mode: "rows" = l2l_memcpy_rows_async (a DMA engine in both directions),
+        # "plain" = torch's copy_ (device to host by the runtime's copy kernel)
+        assert stash_copy in ("rows", "plain")
+        self.stash_copy = stash_copy
         self.L, self.H, self.S, self.V = layers, hidden, seq, vocab
         self.U, self.ub = num_ubatches, ubatch
         self.dtype = dtype
@@ -399,7 +403,11 @@ class L2LTrainer:
         ev.record(self.compute)
         self.stash_stream.wait_event(ev)
         with torch.cuda.stream(self.stash_stream):
-            self.host_stash[l].copy_(self.stash[k], non_blocking=True)
+            if self.stash_copy == "rows":
+                B.memcpy_rows_async(self.host_stash[l], self.stash[k], self.stash[k].numel() * self.stash[k].element_size(), True,
+                                    self.stash_stream.cuda_stream)
+            else:
+                self.host_stash[l].copy_(self.stash[k], non_blocking=True)
             self.stash_free[k].record(self.stash_stream)
 
     def _reload(self, l):
@@ -407,7 +415,11 @@ class L2LTrainer:
         k = l % self.nslot
         self.stash_stream.wait_event(self.stash_free[k])
         with torch.cuda.stream(self.stash_stream):
-            self.stash[k].copy_(self.host_stash[l], non_blocking=True)
+            if self.stash_copy == "rows":
+                B.memcpy_rows_async(self.stash[k], self.host_stash[l], self.stash[k].numel() * self.stash[k].element_size(), False,
+                                    self.stash_stream.cuda_stream)
+            else:
+                self.stash[k].copy_(self.host_stash[l], non_blocking=True)
             ev = self.stash_ev[k]
             ev.record(self.stash_stream)
         self.compute.wait_event(ev)
