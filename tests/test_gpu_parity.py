@@ -966,6 +966,25 @@ def test_embedding_block_staged_and_drained_in_pieces():
     assert np.abs(grads[0]).max() > 0
 
 
+def test_row_copies_move_every_byte_in_both_directions():
+    # l2l_memcpy_rows_async: rows of 64 KiB plus a plain copy of the remainder; sizes below, at and across the row size
+    stream = torch.cuda.Stream()
+    rng = np.random.default_rng(3)
+    for n in (1, 1000, 65536, 65536 * 3 + 123, 5 * 1024 * 1024 + 8):
+        src = torch.from_numpy(rng.integers(0, 256, size=n, dtype=np.uint8)).pin_memory()
+        dev = torch.zeros(n + 64, dtype=torch.uint8, device="cuda")
+        back = torch.zeros(n + 64, dtype=torch.uint8).pin_memory()
+        torch.cuda.synchronize()
+        B.memcpy_rows_async(dev, src, n, False, stream.cuda_stream)
+        B.memcpy_rows_async(back, dev, n, True, stream.cuda_stream)
+        stream.synchronize()
+        assert torch.equal(dev[:n].cpu(), src) and not dev[n:].any(), n
+        assert torch.equal(back[:n], src) and not back[n:].any(), n
+    B.memcpy_rows_async(dev, src, 0, False, stream.cuda_stream)          # nothing to move: no error
+    with pytest.raises(P.L2LError):
+        B.memcpy_rows_async(None, src, 8, False, stream.cuda_stream)
+
+
 # ------------------------------------------------------------------------------------- call-order errors
 def test_call_order_errors():
     cfg = P.make_config(64, 2, 128, 16, 2, 2, "fp32", 1e-5, 0)
