@@ -376,18 +376,24 @@ def _layer_case(w: S.Workload, group=0, x_scale=1.0, check_fwd_only=False, dy_sc
         c.close()
 
 
+def _report_dir():
+    """where the cases leave their error figures and progress lines: the folder named by L2L_TEST_REPORT_DIR, if any"""
+    d = os.environ.get("L2L_TEST_REPORT_DIR", "")
+    return d if d and os.path.isdir(d) else None
+
+
 def _report(case, errs):
-    """every parity case leaves its error figures in gpurun_out/parity_errors.jsonl (when that folder exists)"""
-    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
-    if os.path.isdir(d):
+    """every parity case leaves its error figures in parity_errors.jsonl of the report folder"""
+    d = _report_dir()
+    if d:
         with open(os.path.join(d, "parity_errors.jsonl"), "a") as f:
             f.write(json.dumps({"case": case, **{k: float(v) for k, v in errs.items()}}) + "\n")
 
 
 def _progress(msg):
-    """long cases say where they are (a line in gpurun_out/progress.log), so that a quiet minute is not taken for a hang"""
-    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
-    if os.path.isdir(d):
+    """long cases say where they are (a line in progress.log of the report folder), so that a quiet minute is not taken for a hang"""
+    d = _report_dir()
+    if d:
         with open(os.path.join(d, "progress.log"), "a") as f:
             f.write(f"{os.environ.get('PYTEST_CURRENT_TEST', '?').split(' ')[0]}: {msg}\n")
 

@@ -97,8 +97,8 @@ def test_serialised_and_overlapped_steps_follow_the_cost_model():
            f"(model {model_overlap:.3f}); u C forward {uC_f:.3f}, backward with recompute {uC_b:.3f}, stage {X_s:.3f}, drain {X_d:.3f}")
     print(msg)
     import os
-    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
-    if os.path.isdir(d):
+    d = os.environ.get("L2L_TEST_REPORT_DIR", "")
+    if d and os.path.isdir(d):
         with open(os.path.join(d, "timing_model.txt"), "a") as f:
             f.write(msg + "\n")
     assert abs(per_layer["serial"] - model_serial) <= 0.15 * model_serial, msg

@@ -428,7 +428,7 @@ def test_l2l_with_cls_head_equals_one_concatenated_minibatch():
 
 
 def test_error_measures_on_hand_values():
-    # rel_l2 and max_rel are what every parity verdict rests on: values worked out by hand
+    # rel_l2 and max_rel are what every parity comparison rests on: values worked out by hand
     b = np.array([3.0, 4.0, 0.0, 0.0])                      # ||b|| = 5, max |b| = 4
     a = np.array([3.0, 4.0, 0.0, 1.0])                      # one entry off by 1
     assert O.rel_l2(a, b) == pytest.approx(1.0 / 5.0, rel=1e-15)
