@@ -15,7 +15,8 @@
 // [row][64] LDS image through ds_read_b64_tr_b16.
 //
 // LDS images are [row][64] 16-bit elements (128-byte rows) with the 16-byte chunk c of row r at slot
-// c ^ ((r >> 1) & 7): conflict-free for 16-byte fragment reads, two-way for the transpose reads.
+// c ^ ((r >> 1) & 7): conflict-free for 16-byte fragment reads, two-way for the transpose reads (a layout that
+// spreads the four rows of a transposing read over all banks, slot c ^ (2 (r % 4) + (r / 4) % 2), measured the same).
 #pragma once
 #include "gemm.h"
 
@@ -26,6 +27,14 @@ typedef __attribute__((ext_vector_type(8))) short s16x8;
 
 __device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
 
+// Orders a wave's own LDS traffic for the compiler (LDS executes a wave's accesses in order; a wave that exchanges data
+// between its lanes through a region nobody else touches needs no barrier)
+__device__ __forceinline__ void wave_lds_order() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // rows [0, S) of a [S][64] slice with row pitch `ld` elements, straight into LDS (1 KiB = 8 rows per instruction)
 __device__ __forceinline__ void load_rows(__amdgpu_buffer_rsrc_t rs, uint32_t ld, int S, char* dst, int wave, int nwaves, int lane) {
   for (int blk = wave; blk < S / 8; blk += nwaves) {
@@ -35,6 +44,26 @@ __device__ __forceinline__ void load_rows(__amdgpu_buffer_rsrc_t rs, uint32_t ld
     __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void*)(dst + blk * 1024), 16, (int)off, 0, 0, 0);
   }
 }
+
+// rows 32 w .. 32 w + 31 of the slice, into the same rows of the image (four instructions)
+__device__ __forceinline__ void load_rows_own(__amdgpu_buffer_rsrc_t rs, uint32_t ld, char* dst, int wave, int lane) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int blk = wave * 4 + i, row = blk * 8 + (lane >> 3);
+    const int c = swz(row, lane & 7);
+    const uint32_t off = ((uint32_t)row * ld + (uint32_t)c * 8) * 2u;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void*)(dst + blk * 1024), 16, (int)off, 0, 0, 0);
+  }
+}
+
+// at most n (1..4) vector-memory loads of this wave still outstanding; LDS reads all returned
+__device__ __forceinline__ void wait_vm_upto(int n) {
+  if (n >= 4) __builtin_amdgcn_s_waitcnt(0x0F74);
+  else if (n == 3) __builtin_amdgcn_s_waitcnt(0x0F73);
+  else if (n == 2) __builtin_amdgcn_s_waitcnt(0x0F72);
+  else __builtin_amdgcn_s_waitcnt(0x0F71);
+}
+__device__ __forceinline__ void wait_lds0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
 
 // fragment with rows as the M/N index: 8 consecutive columns (k = 16 step + 8 (lane / 32) ..) of row `row`
 __device__ __forceinline__ bf16x8 frag_rows(const char* img, int row, int step, int lane) {
@@ -90,6 +119,59 @@ __device__ __forceinline__ void store_T(const f32x16 (&acc)[2], E* out, long lon
     }
 }
 
+// Accumulators on their way out through LDS, so that global memory sees whole rows (a direct store puts 32 rows x 16
+// bytes into every instruction): `stage` is a region that only this wave touches.
+// NT = 2: 32 rows of 64 columns (128-byte rows, slot c ^ (r & 7)); NT = 1: 32 rows of 32 columns (64-byte rows in a
+// 2 KiB region, slot c ^ ((r >> 1) & 3))
+template <int NT> __device__ __forceinline__ int stage_swz(int r) { return NT == 2 ? (r & 7) : ((r >> 1) & 3); }
+
+template <typename E, int NT>
+__device__ __forceinline__ void stage_T(const f32x16 (&acc)[NT], char* stage, int lane, float scale) {
+  const int q = lane & 31;
+  char* p = stage + q * (NT * 64) + 8 * (lane >> 5);
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk) {
+      typename Vec<E>::x4 v;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) v[i] = from_f32<E>(acc[t][blk * 4 + i] * scale);
+      *(typename Vec<E>::x4*)(p + (((t * 4 + blk) ^ stage_swz<NT>(q)) * 16)) = v;
+    }
+}
+
+// rows 0..31 of the staged image (4 NT lanes per row, 16 / NT rows per instruction) to out[row * ld + ..];
+// colsum (or null, NT = 2 only): this wave's 64 column sums of what it stores, taken in fp32 from the rounded values
+template <typename E, int NT>
+__device__ __forceinline__ void store_staged(const char* stage, E* out, long long ld, int lane, float* colsum = nullptr) {
+  constexpr int LPR = 4 * NT, RPI = 64 / LPR;   // lanes per row, rows per instruction
+  const int c = lane & (LPR - 1);
+  float cs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int i = 0; i < 32 / RPI; ++i) {
+    const int r = i * RPI + lane / LPR;
+    const bf16x8 v = *(const bf16x8*)(stage + r * (NT * 64) + ((c ^ stage_swz<NT>(r)) * 16));
+    *(bf16x8*)(out + (long long)r * ld + c * 8) = v;
+    if (NT == 2 && colsum) {
+      const typename Vec<E>::x8 e = __builtin_bit_cast(typename Vec<E>::x8, v);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) cs[j] += to_f32(e[j]);
+    }
+  }
+  if (NT == 2 && colsum) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      cs[j] += __shfl_xor(cs[j], 8, 64);
+      cs[j] += __shfl_xor(cs[j], 16, 64);
+      cs[j] += __shfl_xor(cs[j], 32, 64);
+    }
+    if (lane < 8) {
+      *(float4*)(colsum + c * 8) = float4{cs[0], cs[1], cs[2], cs[3]};
+      *(float4*)(colsum + c * 8 + 4) = float4{cs[4], cs[5], cs[6], cs[7]};
+    }
+  }
+}
+
 constexpr int SMAX = 128;   // longest sequence the fused kernels take
 constexpr int NKB = SMAX / 32;
 
@@ -105,35 +187,47 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const E* qkv, E* out, int
   const long long ld = 3LL * H;
   const E* base = qkv + (long long)b * S * ld + h * 64;
   const uint32_t bytes = (uint32_t)(((long long)(S - 1) * ld + 64) * 2);
-  load_rows(make_rsrc(base + H, bytes), (uint32_t)ld, S, Ks, wave, 4, lane);
-  load_rows(make_rsrc(base + 2 * H, bytes), (uint32_t)ld, S, Vs, wave, 4, lane);
   const int nkb = S / 32;
   const bool active = wave < nkb;
-  // this wave's queries as B-operand fragments, straight from memory
+  // Wave w's 32 queries pass through rows 32 w .. of the image of V, which are its own until it has asked for those
+  // rows of V itself (whole 128-byte rows from memory, like K and V; fragments read straight from memory would put
+  // 32 rows x 32 bytes into every load).  Loads return in order: once only the nkb loads of K are outstanding, Q is in.
+  if (active) load_rows_own(make_rsrc(base, bytes), (uint32_t)ld, Vs, wave, lane);
+  load_rows(make_rsrc(base + H, bytes), (uint32_t)ld, S, Ks, wave, 4, lane);
   bf16x8 qf[4];
   if (active) {
-    const E* qrow = base + (long long)(wave * 32 + (lane & 31)) * ld + (lane >> 5) * 8;
+    wait_vm_upto(nkb);
+    wave_lds_order();
 #pragma unroll
-    for (int st = 0; st < 4; ++st) qf[st] = *(const bf16x8*)(qrow + st * 16);
+    for (int st = 0; st < 4; ++st) qf[st] = frag_rows(Vs, wave * 32 + (lane & 31), st, lane);
+    wait_lds0();   // the fragments are in registers before the loads of V may write over them
+    wave_lds_order();
+    load_rows_own(make_rsrc(base + 2 * H, bytes), (uint32_t)ld, Vs, wave, lane);
+    wait_vm_upto(4);   // K is in (this wave's part), V on its way
+  } else {
+    wait_vm0();
   }
-  wait_vm0();
   __syncthreads();
-  if (!active) return;
 
   f32x16 st_[NKB];
   float m = -INFINITY;
+  if (active) {
 #pragma unroll
-  for (int kb = 0; kb < NKB; ++kb) {
-    if (kb < nkb) {
-      f32x16 a = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int kb = 0; kb < NKB; ++kb) {
+      if (kb < nkb) {
+        f32x16 a = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int s4 = 0; s4 < 4; ++s4)
-        a = mfma_32x32x16<E>(frag_rows(Ks, kb * 32 + (lane & 31), s4, lane), qf[s4], a);
+        for (int s4 = 0; s4 < 4; ++s4)
+          a = mfma_32x32x16<E>(frag_rows(Ks, kb * 32 + (lane & 31), s4, lane), qf[s4], a);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { a[r] *= alpha; m = fmaxf(m, a[r]); }
-      st_[kb] = a;
+        for (int r = 0; r < 16; ++r) { a[r] *= alpha; m = fmaxf(m, a[r]); }
+        st_[kb] = a;
+      }
     }
   }
+  wait_vm0();
+  __syncthreads();   // V is in; nobody reads the image of K any more: rows 32 w .. of it are wave w's way out for its context rows
+  if (!active) return;
   m = xor32_max(m);
   float sum = 0.f;
 #pragma unroll
@@ -158,7 +252,10 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const E* qkv, E* out, int
         for (int t = 0; t < 2; ++t) o[t] = mfma_32x32x16<E>(frag_keys_T(Vs, kb, s2, t, lane), pf, o[t]);
       }
     }
-  store_T(o, out + ((long long)b * S + wave * 32) * H + h * 64, H, lane, inv);
+  char* stage = Ks + wave * 4096;
+  stage_T<E, 2>(o, stage, lane, inv);
+  wave_lds_order();
+  store_staged<E, 2>(stage, out + ((long long)b * S + wave * 32) * H + h * 64, H, lane);
 }
 
 
@@ -199,19 +296,6 @@ __device__ __forceinline__ bf16x8 frag_queries_T(const char* img, int s, int t, 
   return __builtin_bit_cast(bf16x8, v);
 }
 
-// one transposed 32 x 32 accumulator (rows = 32 columns of the output, lane = output row), as store_T
-template <typename E>
-__device__ __forceinline__ void store_T1(const f32x16& acc, E* out, long long ld, int lane, float scale) {
-  E* p = out + (long long)(lane & 31) * ld + 4 * (lane >> 5);
-#pragma unroll
-  for (int blk = 0; blk < 4; ++blk) {
-    typename Vec<E>::x4 v;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) v[i] = from_f32<E>(acc[blk * 4 + i] * scale);
-    *(typename Vec<E>::x4*)(p + blk * 8) = v;
-  }
-}
-
 // 64 KB: two workgroups fit a CU, so that one's loads and stores run under the other's MFMAs
 constexpr int BWD_LDS = 4 * SMAX * 128;
 
@@ -221,7 +305,8 @@ constexpr int BWD_LDS = 4 * SMAX * 128;
 // that half of P and dS in LDS, over the images of K and V, which nobody needs any more, and then wave w takes key
 // block w % 2 of the half and columns 32 (w / 2) .. of the head: dV = P^T dO, dK = alpha dS^T Q.
 template <typename E>
-__global__ __launch_bounds__(256) void attn_bwd_kernel(const E* qkv, const E* dout, E* dqkv, int S, int H, int A, float alpha) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_kernel(const E* qkv, const E* dout, E* dqkv, float* dq_colsum, int S, int H, int A,
+                                                       float alpha) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   char* Ks = lds;
   char* Vs = lds + SMAX * 128;
@@ -246,7 +331,7 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(const E* qkv, const E* do
 
   E* dqkv_b = dqkv + (long long)b * S * ld + h * 64;
   const int qrow = wave * 32 + (lane & 31);
-  f32x16 p_[NKB], ds_[NKB];
+  f32x16 p_[NKB], ds_[NKB], dq[2];
   if (active) {
     bf16x8 qf[4], of[4];
 #pragma unroll
@@ -285,7 +370,6 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(const E* qkv, const E* do
         for (int r = 0; r < 16; ++r) { p_[kb][r] *= inv; dsum += p_[kb][r] * ds_[kb][r]; }
       }
     dsum = xor32_sum(dsum);
-    f32x16 dq[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t) dq[t] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -300,13 +384,33 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(const E* qkv, const E* do
           for (int t = 0; t < 2; ++t) dq[t] = mfma_32x32x16<E>(frag_keys_T(Ks, kb, s2, t, lane), df, dq[t]);
         }
       }
-    store_T(dq, dqkv_b + (long long)wave * 32 * ld, ld, lane, alpha);
   }
-  // phase 2: keys 64 half .. 64 half + 63
+  // phase 2: keys 64 half .. 64 half + 63.  Results leave through LDS (whole rows for global memory): rows 32 w .. of
+  // the images of P and dS belong to wave w alone between the two barriers below, so they serve as its way out first,
+  // for dQ (first half) or for the previous half's dV and dK
+  f32x16 dv[1], dk[1];
+  E* dkv_out = nullptr;
+  char* stage = Ps + wave * 4096;
+  const auto flush_dkv = [&]() {
+    stage_T<E, 1>(dv, stage, lane, 1.0f);
+    stage_T<E, 1>(dk, stage + 2048, lane, alpha);
+    wave_lds_order();
+    store_staged<E, 1>(stage, dkv_out + 2 * H, ld, lane);
+    store_staged<E, 1>(stage + 2048, dkv_out + H, ld, lane);
+    wave_lds_order();
+  };
 #pragma unroll
   for (int half = 0; half < NKB / 2; ++half) {
     if (2 * half >= nkb) break;
     __syncthreads();   // K and V (first half) or the previous half's P and dS are no longer read
+    if (half == 0 && active) {
+      stage_T<E, 2>(dq, stage, lane, alpha);
+      wave_lds_order();
+      store_staged<E, 2>(stage, dqkv_b + (long long)wave * 32 * ld, ld, lane,
+                         dq_colsum ? dq_colsum + ((long long)(b * nkb + wave) * H + h * 64) : nullptr);
+      wave_lds_order();
+    }
+    if (half > 0 && dkv_out) flush_dkv();
     if (active) {
 #pragma unroll
       for (int kb2 = 0; kb2 < 2; ++kb2)
@@ -317,19 +421,20 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(const E* qkv, const E* do
     }
     __syncthreads();
     const int kb2 = wave & 1, t = wave >> 1, kb = 2 * half + kb2;
+    dkv_out = nullptr;
     if (kb < nkb) {
-      f32x16 dv = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      f32x16 dk = dv;
+      dv[0] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      dk[0] = dv[0];
       for (int s = 0; s < S / 16; ++s) {
         const bf16x8 pf = pq_frag(Ps, s, kb2, lane), df = pq_frag(Ds, s, kb2, lane);
-        dv = mfma_32x32x16<E>(frag_queries_T(Os, s, t, lane), pf, dv);
-        dk = mfma_32x32x16<E>(frag_queries_T(Qs, s, t, lane), df, dk);
+        dv[0] = mfma_32x32x16<E>(frag_queries_T(Os, s, t, lane), pf, dv[0]);
+        dk[0] = mfma_32x32x16<E>(frag_queries_T(Qs, s, t, lane), df, dk[0]);
       }
-      E* out = dqkv_b + (long long)kb * 32 * ld + t * 32;
-      store_T1(dv, out + 2 * H, ld, lane, 1.0f);
-      store_T1(dk, out + H, ld, lane, alpha);
+      dkv_out = dqkv_b + (long long)kb * 32 * ld + t * 32;
     }
   }
+  __syncthreads();   // the last half's P and dS are no longer read
+  if (dkv_out) flush_dkv();
 }
 
 // ---- long sequences: S a multiple of 32 beyond SMAX -----------------------------------------------------

@@ -516,10 +516,11 @@ int ln_bwd(l2l_ctx* c, const void* dy, const void* x, const float* mean, const f
                        mean, rstd, (const T*)gamma, (T*)dx, (int)rows, n);
   }));
   L2L_TRY(timed(c, L2L_PROF_COLSUM, 0, 2.0 * rows * n * sizeof(T), [&] {
-    dim3 grid((n + 127) / 128, (unsigned)((rows + COLSUM_ROWS - 1) / COLSUM_ROWS));
+    const int rpb = colsum_rows_per_block(rows, n);
+    dim3 grid((n + 127) / 128, (unsigned)((rows + rpb - 1) / rpb));
     hipLaunchKernelGGL((colsum_kernel<T, 1>), grid, dim3(256), 0, c->cs, (const T*)dy, (long long)n, (const T*)x, mean, rstd,
                        (const int32_t*)nullptr, (const T*)nullptr, (const T*)nullptr, 0, dgamma, dbeta, (int)rows, n,
-                       (const int*)nullptr, 0);
+                       (const int*)nullptr, 0, rpb);
   }));
   return bias_grad<T>(c, dx, n, dbias, rows, n);
 }
@@ -549,10 +550,11 @@ template <typename T>
 int bias_grad(l2l_ctx* c, const void* a, long long lda, float* out, long long rows, int n, const int* rows_dev) {
   if (rows <= 0) return L2L_OK;
   return timed(c, L2L_PROF_COLSUM, 0, 1.0 * rows * n * sizeof(T), [&] {
-    dim3 grid((n + 127) / 128, (unsigned)((rows + COLSUM_ROWS - 1) / COLSUM_ROWS));
+    const int rpb = colsum_rows_per_block(rows, n);
+    dim3 grid((n + 127) / 128, (unsigned)((rows + rpb - 1) / rpb));
     hipLaunchKernelGGL((colsum_kernel<T, 0>), grid, dim3(256), 0, c->cs, (const T*)a, lda, (const T*)nullptr,
                        (const float*)nullptr, (const float*)nullptr, (const int32_t*)nullptr, (const T*)nullptr,
-                       (const T*)nullptr, 0, (float*)nullptr, out, (int)rows, n, rows_dev, 0);
+                       (const T*)nullptr, 0, (float*)nullptr, out, (int)rows, n, rows_dev, 0, rpb);
   });
 }
 
@@ -770,13 +772,25 @@ int layer_backward_group(l2l_ctx* c, const void* params, const void* x, void* dy
     L2L_TRY(gemm(c, dt, true, w));
   }
   // attention backward per (sequence, head)
+  // The bias gradient of the QKV projection is colsum(dQKV).  With the fused kernel it does not take a pass over dQKV:
+  // the Q part comes out of the kernel (one row of partial sums per 32 queries), the V part equals colsum(dC) because
+  // every row of P sums to one, and the K part is zero because every row of dS sums to zero (a bias on the keys
+  // shifts all scores of a query alike, which the softmax does not see).
+  bool dbqkv_done = false;
   if (fused_attention_ok(c)) {
+    const long long part_rows = (long long)nseq * (S / 32);
+    float* dq_part = c->colsum_ws && (size_t)part_rows * H <= c->colsum_ws_elems ? c->colsum_ws : nullptr;
     const double fl = 10.0 * S * S * d * nseq * A;
     L2L_TRY(timed(c, L2L_PROF_ATTN, fl, (3.0 + 1.0 + 3.0) * M * H * sizeof(T), [&] {
       using E = attn_elem<T>;
       hipLaunchKernelGGL(attn::attn_bwd_kernel<E>, dim3(nseq * A), dim3(256), attn::BWD_LDS, c->cs, (const E*)qkv,
-                         (const E*)c->dc, (E*)dqkv, S, H, A, alpha);
+                         (const E*)c->dc, (E*)dqkv, dq_part, S, H, A, alpha);
     }));
+    if (dq_part) {
+      L2L_TRY(bias_grad<float>(c, dq_part, H, G + off[T_BQKV], part_rows, H));
+      L2L_TRY(bias_grad<T>(c, c->dc, H, G + off[T_BQKV] + 2 * H, M, H));
+      dbqkv_done = true;
+    }
   } else if (fused_attention_long_ok(c)) {
     using E = attn_elem<T>;
     const dim3 grid(nseq * A * ((S + attn::CH - 1) / attn::CH));
@@ -834,7 +848,7 @@ int layer_backward_group(l2l_ctx* c, const void* params, const void* x, void* dy
     GemmArgs w = gemm_args(H, 3 * H, (int)M, x, H, 0, dqkv, 3 * H, 0, G + off[T_WQKV], 3 * H);
     w.epi = EPI_ACCUM;
     L2L_TRY(gemm(c, dt, true, w));
-    L2L_TRY(bias_grad<T>(c, dqkv, 3 * H, G + off[T_BQKV], M, 3 * H));
+    if (!dbqkv_done) L2L_TRY(bias_grad<T>(c, dqkv, 3 * H, G + off[T_BQKV], M, 3 * H));
   }
   return L2L_OK;
 }
@@ -940,10 +954,11 @@ int embed_bwd_t(l2l_ctx* c, const int32_t* tokens, const void* dy) {
                        E + eo[E_GE], (const T*)dy, c->emean, c->erstd, c->egacc + eo[E_E], c->egacc + eo[E_P], (int)rows, S, H, turned, c->cfg.vocab);
   }));
   return timed(c, L2L_PROF_COLSUM, 0, 0, [&] {
-    dim3 grid((H + 127) / 128, (unsigned)((rows + COLSUM_ROWS - 1) / COLSUM_ROWS));
+    const int rpb = colsum_rows_per_block(rows, H);
+    dim3 grid((H + 127) / 128, (unsigned)((rows + rpb - 1) / rpb));
     hipLaunchKernelGGL((colsum_kernel<T, 2>), grid, dim3(256), 0, c->cs, (const T*)dy, (long long)H, (const T*)nullptr, c->emean,
                        c->erstd, tokens, E + eo[E_E], E + eo[E_P], S, c->egacc + eo[E_GE], c->egacc + eo[E_BE], (int)rows, H,
-                       (const int*)nullptr, c->cfg.vocab);
+                       (const int*)nullptr, c->cfg.vocab, rpb);
   });
 }
 

@@ -333,23 +333,30 @@ __global__ __launch_bounds__(256) void embed_bwd_kernel(const int32_t* tokens, c
 // ---- column reductions -----------------------------------------------------------------------------
 // out_a[j] += sum_t a[t,j] * w(t,j), out_b[j] += sum_t a[t,j], with w = xhat of a LayerNorm input
 // (MODE 1: plain rows x; MODE 2: embedding rows) or out_b only (MODE 0: bias gradient).
-// Block: 128 columns x ROWS_PER_BLOCK rows; lanes own column pairs; waves stride rows; LDS combine;
-// one fp32 atomic per column per block.
+// Block: 128 columns x rpb rows (rpb = gridDim.y's share of the rows, a multiple of 4); lanes own column pairs; waves
+// stride rows, eight loads in flight each; LDS combine; one fp32 atomic per column per block.
 constexpr int COLSUM_ROWS = 128;
+// rows per block: COLSUM_ROWS, fewer where that would leave most of the chip without a block
+inline int colsum_rows_per_block(long long rows, int n) {
+  int rpb = COLSUM_ROWS;
+  while (rpb > 16 && ((rows + rpb - 1) / rpb) * ((n + 127) / 128) < 1024) rpb /= 2;
+  return rpb;
+}
 template <typename T, int MODE>
 __global__ __launch_bounds__(256) void colsum_kernel(const T* a, long long lda, const T* x, const float* mean,
                                                      const float* rstd, const int32_t* tokens, const T* E, const T* pos,
                                                      int S, float* out_a, float* out_b, int rows, int n,
-                                                     const int* rows_dev, int V) {
+                                                     const int* rows_dev, int V, int rpb) {
   __shared__ float red[4][2][128];
   if (rows_dev) rows = min(rows, *rows_dev);
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int j = blockIdx.x * 128 + lane * 2;
-  const int r0 = blockIdx.y * COLSUM_ROWS;
+  const int r0 = blockIdx.y * rpb;
   if (r0 >= rows) return;
-  const int r1 = min(rows, r0 + COLSUM_ROWS);
+  const int r1 = min(rows, r0 + rpb);
   float sa0 = 0.f, sa1 = 0.f, sb0 = 0.f, sb1 = 0.f;
   if (j < n) {
+#pragma unroll 8
     for (int r = r0 + w; r < r1; r += 4) {
       const float d0 = to_f32(a[(long long)r * lda + j]), d1 = to_f32(a[(long long)r * lda + j + 1]);
       sb0 += d0;
