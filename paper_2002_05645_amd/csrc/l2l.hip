@@ -486,6 +486,12 @@ int ln_fwd(l2l_ctx* c, const void* x, const void* gamma, const void* beta, void*
 template <typename T>
 int bias_grad(l2l_ctx* c, const void* a, long long lda, float* out, long long rows, int n, const int* rows_dev = nullptr);
 
+// whether the one-pass kernel may take its rows through the LDS ring: every column group in use (the kernel counts
+// one store per group and row), and the ring's slots fit the buffer the column sums are combined in
+constexpr int LNF_RING = 3;
+static_assert(4 * LNF_RING * 2 * 1024 <= 4 * 3 * 512 * (int)sizeof(float), "ring slots must fit the reduction buffer");
+bool ln_bwd_ring_ok(int n, int nch) { return (n + 511) / 512 == nch; }
+
 // whether LayerNorm backward runs as the one-pass kernel, which can also compute the row statistics itself
 bool ln_bwd_one_pass(int n) { return n % 8 == 0 && n <= 2048; }
 
@@ -506,6 +512,14 @@ int ln_bwd(l2l_ctx* c, const void* dy, const void* x, const float* mean, const f
         hipLaunchKernelGGL(kern, grid, dim3(256), lds, c->cs, (const T*)dy, (const T*)x, mean, rstd, (const T*)gamma, (T*)dx,
                            dgamma, dbeta, dbias, (int)rows, n, eps, (const T*)nullptr);
       };
+      if constexpr (sizeof(T) == 2) {
+        if (ln_bwd_ring_ok(n, nch)) {   // rows through LDS (same LDS size: the ring's slots are the reduction's buffer)
+          if (nch == 1) go(ln_bwd_fused_kernel<T, 1, false, LNF_RING>);
+          else if (nch == 2) go(ln_bwd_fused_kernel<T, 2, false, LNF_RING>);
+          else go(ln_bwd_fused_kernel<T, 4, false, LNF_RING>);
+          return;
+        }
+      }
       if (nch == 1) go(ln_bwd_fused_kernel<T, 1>);
       else if (nch == 2) go(ln_bwd_fused_kernel<T, 2>);
       else go(ln_bwd_fused_kernel<T, 4>);
@@ -540,6 +554,14 @@ int ln_bwd_from_y(l2l_ctx* c, const void* dy, const void* y, const float* rstd, 
       hipLaunchKernelGGL(kern, grid, dim3(256), lds, c->cs, (const T*)dy, (const T*)y, (const float*)nullptr, rstd, (const T*)gamma, (T*)dx,
                          dgamma, dbeta, dbias, (int)rows, n, 0.f, (const T*)beta);
     };
+    if constexpr (sizeof(T) == 2) {
+      if (ln_bwd_ring_ok(n, nch)) {
+        if (nch == 1) go(ln_bwd_fused_kernel<T, 1, true, LNF_RING>);
+        else if (nch == 2) go(ln_bwd_fused_kernel<T, 2, true, LNF_RING>);
+        else go(ln_bwd_fused_kernel<T, 4, true, LNF_RING>);
+        return;
+      }
+    }
     if (nch == 1) go(ln_bwd_fused_kernel<T, 1, true>);
     else if (nch == 2) go(ln_bwd_fused_kernel<T, 2, true>);
     else go(ln_bwd_fused_kernel<T, 4, true>);

@@ -3,6 +3,7 @@
 // One wavefront owns one row; reductions use wavefront shuffles; statistics are fp32.
 #pragma once
 #include "common.h"
+#include "gemm.h"
 
 // Row sources: a plain row, or the embedding sum E[tok] + Ppos[s] formed on the fly.
 template <typename T>
@@ -146,7 +147,21 @@ constexpr int LNF_ROWS = 64;   // measured best of 16 .. 128 at 32768 x 1024: fe
 // forward pass, and xhat is taken back out of y as (y - beta) / gamma; the input itself is then not needed (the
 // backward pass of the layer's last LayerNorm, whose output is the stashed boundary activation: the GEMM in front
 // of it need not be recomputed).  The caller makes sure that no |gamma| is tiny.
-template <typename T, int NCH, bool FROMY = false>
+//
+// RING > 0 (16-bit rows, every one of the NCH column groups in use): rows come in through LDS.  Each wave owns RING
+// slots of [x | dy][NCH KiB] and keeps the loads of its next RING - 1 rows in flight as direct-to-LDS loads, which need
+// no registers to land in: with rows requested into registers one ahead, a CU has 32 to 48 KB on their way, half of what
+// the memory system needs to stay busy.  The slots sit where the column sums are combined once the rows are done.
+// A wave's vector-memory operations complete in the order issued, so "row i is in" is a count of the operations
+// issued after its request: the later requests' loads and the stores of dx in between (the row statistics are
+// fetched up front for that reason: no other vector-memory operation may sit in the loop).
+template <int N>
+__device__ __forceinline__ void wait_vm_le() {   // at most N vector-memory operations of this wave outstanding
+  static_assert(N >= 0 && N < 64, "vmcnt has six bits");
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
+}
+
+template <typename T, int NCH, bool FROMY = false, int RING = 0>
 __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* dy, const T* x, const float* mean, const float* rstd,
                                                            const T* gamma, T* dx, float* dgamma, float* dbeta,
                                                            float* dbias, int rows, int n, float eps, const T* beta) {
@@ -172,9 +187,11 @@ __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* dy, const T*
     }
   }
   const int r0 = blockIdx.x * LNF_ROWS, r1 = min(rows, r0 + LNF_ROWS);
-  // 16-bit rows: the wave's next row is requested (as packed 16-byte words) before the current one is worked on, so
-  // that its two reductions and its store run under the loads
-  constexpr bool AHEAD = sizeof(T) == 2;
+  // 16-bit rows without the ring: the wave's next row is requested (as packed 16-byte words) before the current one is
+  // worked on, so that its two reductions and its store run under the loads
+  constexpr bool RINGED = RING > 0;
+  constexpr bool AHEAD = sizeof(T) == 2 && !RINGED;
+  static_assert(!RINGED || sizeof(T) == 2, "the ring takes 16-bit rows");
   u32x4 xr[NCH], dr[NCH];
   const auto request = [&](int r) {
 #pragma unroll
@@ -186,14 +203,57 @@ __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* dy, const T*
       }
     }
   };
+  constexpr int SLOT = 2 * NCH * 1024;   // bytes of one ring slot
+  char* ring = (char*)lnf_red + w * (RINGED ? RING : 0) * SLOT;
+  const int nblk = r1 - r0;
+  __amdgpu_buffer_rsrc_t rx, rd;
+  float st_mu = 0.f, st_rs = 0.f;   // lane i: the statistics of this wave's i-th row
+  if constexpr (RINGED) {
+    rx = make_rsrc(x + (long long)r0 * n, (uint32_t)nblk * (uint32_t)n * 2u);
+    rd = make_rsrc(dy + (long long)r0 * n, (uint32_t)nblk * (uint32_t)n * 2u);
+    const int rl = r0 + w + 4 * lane;
+    if (lane < LNF_ROWS / 4 && rl < r1) {
+      if (rstd) st_rs = rstd[rl];
+      if (!FROMY && mean) st_mu = mean[rl];
+    }
+  }
+  // the wave's i-th row into slot i % RING; past the block's last row the last row again, so that every request is 2 NCH loads
+  const auto request_ring = [&](int i) {
+    const uint32_t rr = (uint32_t)min(w + 4 * i, nblk - 1);
+    char* dst = ring + (i % (RINGED ? RING : 1)) * SLOT;
+#pragma unroll
+    for (int k = 0; k < NCH; ++k) {
+      const uint32_t off = (rr * (uint32_t)n + (uint32_t)(k * 512 + lane * 8)) * 2u;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (__attribute__((address_space(3))) void*)(dst + k * 1024), 16, (int)off, 0, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rd, (__attribute__((address_space(3))) void*)(dst + (NCH + k) * 1024), 16, (int)off, 0, 0, 0);
+    }
+  };
   if constexpr (AHEAD) request(r0 + w);
-  for (int r = r0 + w; r < r1; r += 4) {
+  if constexpr (RINGED) {
+#pragma unroll
+    for (int i = 0; i < RING - 1; ++i) request_ring(i);
+  }
+  int it = 0;
+  for (int r = r0 + w; r < r1; r += 4, ++it) {
     float xh[NCH][8], d[NCH][8];
+    if constexpr (RINGED) {
+      request_ring(it + RING - 1);
+      // issued since row `it` was asked for: RING - 1 requests, and the stores (NCH each) of the rows worked on since
+      if (it < RING - 1) wait_vm_le<(RING - 1) * 2 * NCH>();
+      else wait_vm_le<(RING - 1) * 3 * NCH>();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      const char* src = ring + (it % (RINGED ? RING : 1)) * SLOT + lane * 16;
+#pragma unroll
+      for (int k = 0; k < NCH; ++k) {
+        xr[k] = *(const u32x4*)(src + k * 1024);
+        dr[k] = *(const u32x4*)(src + (NCH + k) * 1024);
+      }
+    }
 #pragma unroll
     for (int k = 0; k < NCH; ++k) {
       const int j = lane * 8 + k * 512;
       if (j < n) {
-        if constexpr (AHEAD) {
+        if constexpr (AHEAD || RINGED) {
           unpack8<T>(xr[k], xh[k]);
           unpack8<T>(dr[k], d[k]);
         } else {
@@ -204,11 +264,18 @@ __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* dy, const T*
     }
     if constexpr (AHEAD) request(r + 4);
     float mu = 0.f, rs;
-    if constexpr (FROMY) {
+    if constexpr (RINGED && FROMY) {
+      rs = __shfl(st_rs, it, 64);
+    } else if constexpr (FROMY) {
       rs = rstd[r];
     } else if (mean) {
-      mu = mean[r];
-      rs = rstd[r];
+      if constexpr (RINGED) {
+        mu = __shfl(st_mu, it, 64);
+        rs = __shfl(st_rs, it, 64);
+      } else {
+        mu = mean[r];
+        rs = rstd[r];
+      }
     } else {
       float s = 0.f, q = 0.f;
 #pragma unroll
@@ -258,6 +325,10 @@ __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* dy, const T*
         store8(dx + (long long)r * n + j, v);
       }
     }
+  }
+  if constexpr (RINGED) {   // the slots become the place where the column sums meet: every wave is done with its own first
+    wait_vm_le<0>();
+    __syncthreads();
   }
 #pragma unroll
   for (int k = 0; k < NCH; ++k) {
