@@ -409,8 +409,8 @@ int launch_split_through_workspace(int v, const GemmArgs& g, hipStream_t s, int 
   if ((size_t)splits * slice > ws_elems) return SPLIT_NO_ROOM;
   GemmArgs p = g;
   p.C = ws; p.ldc = g.N; p.split_stride = slice; p.epi = 0;
-  launch_mfma_variant(v, p, s, splits, out_f32, fp16_in);
   const unsigned blocks = (unsigned)std::min<long long>((slice / 4 + 255) / 256, 4096);
+  launch_mfma_variant(v, p, s, splits, out_f32, fp16_in);
   hipLaunchKernelGGL(split_sum_kernel, dim3(blocks), dim3(256), 0, s, ws, splits, (long long)g.M, g.N, (float*)g.C, g.ldc);
   return SPLIT_LAUNCHED;
 }
@@ -488,9 +488,14 @@ int bias_grad(l2l_ctx* c, const void* a, long long lda, float* out, long long ro
 
 // whether the one-pass kernel may take its rows through the LDS ring: every column group in use (the kernel counts
 // one store per group and row), and the ring's slots fit the buffer the column sums are combined in
-constexpr int LNF_RING = 3;
-static_assert(4 * LNF_RING * 2 * 1024 <= 4 * 3 * 512 * (int)sizeof(float), "ring slots must fit the reduction buffer");
-bool ln_bwd_ring_ok(int n, int nch) { return (n + 511) / 512 == nch; }
+constexpr int LNF_RING = 3;   // slots per wave: two rows on their way while one is worked on (five slots measured the same)
+bool ln_bwd_ring_ok(int n, int nch) { return (n + 511) / 512 == nch && 4 * LNF_RING * 2 * nch * 1024 <= 80 * 1024; }   // (two blocks per CU)
+// dynamic LDS of the one-pass kernel: the buffer the four waves' column sums meet in, or the ring's slots if those take more
+size_t ln_bwd_lds_bytes(int n, int nch, bool is16) {
+  const size_t red = (size_t)4 * 3 * nch * 512 * sizeof(float);
+  const size_t ring = is16 && ln_bwd_ring_ok(n, nch) ? (size_t)4 * LNF_RING * 2 * nch * 1024 : 0;
+  return std::max(red, ring);
+}
 
 // whether LayerNorm backward runs as the one-pass kernel, which can also compute the row statistics itself
 bool ln_bwd_one_pass(int n) { return n % 8 == 0 && n <= 2048; }
@@ -504,7 +509,7 @@ int ln_bwd(l2l_ctx* c, const void* dy, const void* x, const float* mean, const f
   if (!mean && !ln_bwd_one_pass(n)) return fail(c, L2L_E_STATE, "ln_bwd: statistics missing");
   if (ln_bwd_one_pass(n)) {   // one pass, column sums included
     const int nch = n <= 512 ? 1 : n <= 1024 ? 2 : 4;
-    const size_t lds = (size_t)4 * 3 * nch * 512 * sizeof(float);
+    const size_t lds = ln_bwd_lds_bytes(n, nch, sizeof(T) == 2);
     return timed(c, L2L_PROF_ROWWISE, 0, 3.0 * rows * n * sizeof(T), [&] {
       const dim3 grid((unsigned)((rows + LNF_ROWS - 1) / LNF_ROWS));
       auto go = [&](auto kern) {
@@ -546,7 +551,7 @@ int ln_bwd_from_y(l2l_ctx* c, const void* dy, const void* y, const float* rstd, 
   if (rows <= 0) return L2L_OK;
   if (!ln_bwd_one_pass(n) || !rstd) return fail(c, L2L_E_STATE, "ln_bwd_from_y: needs the one-pass kernel and the kept statistics");
   const int nch = n <= 512 ? 1 : n <= 1024 ? 2 : 4;
-  const size_t lds = (size_t)4 * 3 * nch * 512 * sizeof(float);
+  const size_t lds = ln_bwd_lds_bytes(n, nch, sizeof(T) == 2);
   return timed(c, L2L_PROF_ROWWISE, 0, 3.0 * rows * n * sizeof(T), [&] {
     const dim3 grid((unsigned)((rows + LNF_ROWS - 1) / LNF_ROWS));
     auto go = [&](auto kern) {
@@ -731,12 +736,24 @@ int layer_forward_group(l2l_ctx* c, int slot, const void* x, void* y, int ng, bo
   return L2L_OK;
 }
 
+// LayerNorm 2's backward from the stashed output, on its own: it needs nothing of the recompute pass, so it can run in
+// front of it (see layer_bwd_impl) and leave dR2 in the workspace
+template <typename T>
+int layer_ln2_backward_from_y(l2l_ctx* c, const void* params, const void* dydx, float* G, int ng, const void* y, const float* rstd2) {
+  const int H = c->cfg.hidden;
+  const long long M = (long long)ng * c->T;
+  const T* P = (const T*)params;
+  const long long* off = c->lay.off;
+  c->prof_pass = 2;
+  return ln_bwd_from_y<T>(c, dydx, y, rstd2, P + off[T_G2], P + off[T_BE2], c->dr2, G + off[T_G2], G + off[T_BE2], G + off[T_B2], M, H);
+}
+
 // backward of the group whose forward intermediates are in the workspace; dy -> dx in place
 // y, rstd2: the layer's stashed output and LayerNorm 2's kept 1/sigma for these rows (then the workspace holds no R2:
 // the recompute pass skipped FFN2), or null
 template <typename T>
 int layer_backward_group(l2l_ctx* c, const void* params, const void* x, void* dydx, float* G, int ng, const void* y = nullptr,
-                         const float* rstd2 = nullptr) {
+                         const float* rstd2 = nullptr, bool ln2_done = false) {
   const l2l_config& f = c->cfg;
   const int H = f.hidden, A = f.heads, F = f.ffn, S = f.seq, d = H / A;
   const long long M = (long long)ng * c->T;
@@ -752,7 +769,9 @@ int layer_backward_group(l2l_ctx* c, const void* params, const void* x, void* dy
   // LN2 backward
   bool db1_in_gemm = false;
   const bool own_stats = ln_bwd_one_pass(H);   // then the recompute pass did not run LN2
-  if (y)
+  if (ln2_done) {
+    // layer_ln2_backward_from_y ran ahead of the recompute pass: dR2 is in the workspace
+  } else if (y)
     L2L_TRY(ln_bwd_from_y<T>(c, dydx, y, rstd2, P + off[T_G2], P + off[T_BE2], c->dr2, G + off[T_G2], G + off[T_BE2], G + off[T_B2], M, H));
   else
     L2L_TRY(ln_bwd<T>(c, dydx, c->r2, own_stats ? nullptr : c->mean2, own_stats ? nullptr : c->rstd2, P + off[T_G2], c->dr2,
@@ -1284,15 +1303,22 @@ static int layer_bwd_impl(l2l_ctx* c, int layer, int slot, const void* x_stash, 
     void* dy = (char*)dy_dx + o;
     const void* y = from_y ? (const char*)y_stash + o : nullptr;
     const float* rs = from_y ? rstd + (size_t)u0 * c->T : nullptr;
+    // With the stashed output in hand LayerNorm 2's backward goes first: the recompute pass ends with the FFN1 GEMM,
+    // whose 2 M F elements of output are still on their way to memory when the next kernel starts; a GEMM after it
+    // does not notice, a kernel bound by memory does (measured: LayerNorm 2's backward 70 us behind that GEMM, 45 us
+    // in front of the recompute pass).
     if (c->cfg.dtype == L2L_BF16) {
+      if (from_y) L2L_TRY(layer_ln2_backward_from_y<bf16>(c, c->slot[slot], dy, G, ng, y, rs));
       L2L_TRY(layer_forward_group<bf16>(c, slot, x, nullptr, ng, true, nullptr, from_y));  // recompute
-      L2L_TRY(layer_backward_group<bf16>(c, c->slot[slot], x, dy, G, ng, y, rs));
+      L2L_TRY(layer_backward_group<bf16>(c, c->slot[slot], x, dy, G, ng, y, rs, from_y));
     } else if (c->cfg.dtype == L2L_FP16) {
+      if (from_y) L2L_TRY(layer_ln2_backward_from_y<fp16>(c, c->slot[slot], dy, G, ng, y, rs));
       L2L_TRY(layer_forward_group<fp16>(c, slot, x, nullptr, ng, true, nullptr, from_y));
-      L2L_TRY(layer_backward_group<fp16>(c, c->slot[slot], x, dy, G, ng, y, rs));
+      L2L_TRY(layer_backward_group<fp16>(c, c->slot[slot], x, dy, G, ng, y, rs, from_y));
     } else {
+      if (from_y) L2L_TRY(layer_ln2_backward_from_y<float>(c, c->slot[slot], dy, G, ng, y, rs));
       L2L_TRY(layer_forward_group<float>(c, slot, x, nullptr, ng, true, nullptr, from_y));
-      L2L_TRY(layer_backward_group<float>(c, c->slot[slot], x, dy, G, ng, y, rs));
+      L2L_TRY(layer_backward_group<float>(c, c->slot[slot], x, dy, G, ng, y, rs, from_y));
     }
   }
   HIP_TRY(c, hipEventRecord(c->slot_released[slot], c->cs));
