@@ -366,6 +366,17 @@ def _layer_case(w: S.Workload, group=0, x_scale=1.0, check_fwd_only=False, dy_sc
             got = unpack(lay, S.layer_shapes(w), gh.numpy())
             for k in gref:
                 _both(errs, "d" + k, got[k], gref[k])
+            # The QKV bias gradient part by part: its K part is zero in exact arithmetic (every row of dS sums to zero;
+            # the oracle's is rounding noise, the fused attention path writes zeros) and would drown in the norm of the
+            # whole vector; the Q and V parts come from different kernels on that path.
+            H = w.hidden
+            gq, gk, gv = (got["bqkv"][i * H:(i + 1) * H] for i in range(3))
+            rq, rk, rv = (gref["bqkv"][i * H:(i + 1) * H] for i in range(3))
+            scale = np.abs(gref["bqkv"]).max()
+            assert np.abs(rk).max() <= 1e-9 * scale
+            errs["part:dbqkv[Q]"] = O.rel_l2(gq, rq)
+            errs["part:dbqkv[V]"] = O.rel_l2(gv, rv)
+            errs["max:dbqkv[K]"] = float(np.abs(gk).max() / scale)
             # padding of the gradient block stays zero
             mask = np.ones(total, bool)
             for off, n in lay.values():
@@ -406,7 +417,9 @@ def _assert_errs(errs, tol, max_tol=None):
         max_tol = {v: MAXTOL[k] for k, v in TOL.items()}.get(tol, 4 * tol)
     case = os.environ.get("PYTEST_CURRENT_TEST", "?").split(" ")[0]
     _report(case, errs)
-    bad = {k: v for k, v in errs.items() if not (v < (max_tol if k.startswith("max:") else tol))}
+    # ("part:" entries: a slice of a tensor on its own, which may be small beside the rest of it and then carries a larger
+    # share of the rounding; held to ten times the bar, which a slice computed wrongly still misses by far)
+    bad = {k: v for k, v in errs.items() if not (v < (max_tol if k.startswith("max:") else 10 * tol if k.startswith("part:") else tol))}
     assert not bad, f"over tolerance {tol} (max-error {max_tol}): {bad}; all: {errs}"
 
 

@@ -218,6 +218,23 @@ def test_all_gradients_by_finite_differences():
             assert err < 2e-7, (gname, k, err)
 
 
+def test_qkv_bias_gradient_parts_have_closed_forms():
+    # d loss / d (bias of K) = 0: a bias on the keys moves all scores of a query alike, which softmax does not see;
+    # d loss / d (bias of V) = colsum(dC) = colsum(dR1) Wo^T = dbo Wo^T: every row of P sums to one.  Neither is how the
+    # oracle computes them (it sums dK and dV over the tokens).
+    H, A, F, S = 8, 2, 16, 6
+    rng = np.random.default_rng(11)
+    _, layers = tiny_model(H, A, F, S, 11, 1, rng)
+    p = layers[0]
+    X = rng.normal(0, 1, (2, 3, S, H))
+    dY = rng.normal(0, 1, (2, 3, S, H))
+    _, g = O.layer_l2l_bwd(X, dY, p, A, EPS)
+    bq, bk, bv = (g["bqkv"][i * H:(i + 1) * H] for i in range(3))
+    assert np.abs(bk).max() < 1e-13 * np.abs(bq).max()
+    assert np.allclose(bv, g["bo"] @ p["Wo"].T, rtol=1e-12, atol=1e-14)
+    assert np.abs(bq).max() > 1e-3 and np.abs(bv).max() > 1e-3   # (the other two parts are not trivially zero)
+
+
 def test_layer_input_gradient_by_finite_differences():
     H, A, F, S = 8, 2, 16, 4
     rng = np.random.default_rng(5)
