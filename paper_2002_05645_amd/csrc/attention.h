@@ -448,7 +448,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 constexpr int CH = 128;
 
 template <typename E, bool RAGGED>
-__global__ __launch_bounds__(256) void attn_fwd_long_kernel(const E* qkv, E* out, float* lse, int S, int H, int A, float alpha) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RAGGED ? 2 : 3)))
+void attn_fwd_long_kernel(const E* qkv, E* out, float* lse, int S, int H, int A, float alpha) {
   __shared__ __attribute__((aligned(1024))) char lds[2 * CH * 128];
   char* Ks = lds;
   char* Vs = lds + CH * 128;
@@ -524,7 +525,8 @@ __global__ __launch_bounds__(256) void attn_fwd_long_kernel(const E* qkv, E* out
 // dQ = alpha dS K for 128 queries per workgroup; also leaves dsum[row] = rowsum(dO O) for the dK / dV kernel.
 // ctx: [rows, H], the forward pass's output.
 template <typename E, bool RAGGED>
-__global__ __launch_bounds__(256) void attn_bwd_dq_long_kernel(const E* qkv, const E* dout, const E* ctx, const float* lse,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3)))
+void attn_bwd_dq_long_kernel(const E* qkv, const E* dout, const E* ctx, const float* lse,
                                                                float* dsum, E* dqkv, int S, int H, int A, float alpha) {
   __shared__ __attribute__((aligned(1024))) char lds[2 * CH * 128];
   char* Ks = lds;
@@ -597,7 +599,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_long_kernel(const E* qkv, con
 // S = Q K^T with the queries along the register axis and the keys along the lanes, so P and dS leave the accumulators
 // as the B operands of the products over queries, and a wave needs nobody else's P or dS.
 template <typename E, bool RAGGED>
-__global__ __launch_bounds__(256) void attn_bwd_dkv_long_kernel(const E* qkv, const E* dout, const float* lse, const float* dsum,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
+void attn_bwd_dkv_long_kernel(const E* qkv, const E* dout, const float* lse, const float* dsum,
                                                                 E* dqkv, int S, int H, int A, float alpha) {
   __shared__ __attribute__((aligned(1024))) char lds[2 * CH * 128];
   __shared__ __attribute__((aligned(16))) float Ls[CH], Dsm[CH];
