@@ -304,9 +304,12 @@ constexpr int BWD_LDS = 4 * SMAX * 128;
 // dQ = alpha dS K; P and dS stay in registers.  Phase 2, once per half of the keys (0..63, 64..127): the waves park
 // that half of P and dS in LDS, over the images of K and V, which nobody needs any more, and then wave w takes key
 // block w % 2 of the half and columns 32 (w / 2) .. of the head: dV = P^T dO, dK = alpha dS^T Q.
+// dq_colsum (or null): fp32 [rows / 32][H]; row (b S + 32 w) / 32 receives the column sums of the 32 rows of dQ that wave
+// w stores (the Q part of the QKV bias gradient, which the caller adds up over the rows).
+// Two waves per SIMD (two workgroups per CU) is what the 64 KB of LDS allow and what the registers are held to.
 template <typename E>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_kernel(const E* qkv, const E* dout, E* dqkv, float* dq_colsum, int S, int H, int A,
-                                                       float alpha) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void attn_bwd_kernel(const E* qkv, const E* dout, E* dqkv, float* dq_colsum, int S, int H, int A, float alpha) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   char* Ks = lds;
   char* Vs = lds + SMAX * 128;
@@ -447,6 +450,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 // (the same number: sum_k P_k dO . V_k = dO . O), computed by the dQ kernel from the stored context and passed on.
 constexpr int CH = 128;
 
+// (Each of the three kernels below states the least number of waves per SIMD it is to be compiled for: left alone, the
+// compiler has settled on fewer, with more registers per wave and a third more time per launch.)
 template <typename E, bool RAGGED>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RAGGED ? 2 : 3)))
 void attn_fwd_long_kernel(const E* qkv, E* out, float* lse, int S, int H, int A, float alpha) {
