@@ -237,6 +237,9 @@ __global__ __launch_bounds__(256) void ln_bwd_fused_kernel(const T* dy, const T*
   for (int r = r0 + w; r < r1; r += 4, ++it) {
     float xh[NCH][8], d[NCH][8];
     if constexpr (RINGED) {
+      // (the count below takes the previous rows' stores as issued: nothing may be moved across this point)
+      asm volatile("" ::: "memory");
+      __builtin_amdgcn_sched_barrier(0);
       request_ring(it + RING - 1);
       // issued since row `it` was asked for: RING - 1 requests, and the stores (NCH each) of the rows worked on since
       if (it < RING - 1) wait_vm_le<(RING - 1) * 2 * NCH>();
