@@ -56,12 +56,15 @@ __device__ __forceinline__ void load_rows_own(__amdgpu_buffer_rsrc_t rs, uint32_
   }
 }
 
-// at most n (1..4) vector-memory loads of this wave still outstanding; LDS reads all returned
+// at most n (1..4) vector-memory loads of this wave still outstanding (nothing is scheduled across the wait: the
+// callers count the loads they have issued)
 __device__ __forceinline__ void wait_vm_upto(int n) {
+  __builtin_amdgcn_sched_barrier(0);
   if (n >= 4) __builtin_amdgcn_s_waitcnt(0x0F74);
   else if (n == 3) __builtin_amdgcn_s_waitcnt(0x0F73);
   else if (n == 2) __builtin_amdgcn_s_waitcnt(0x0F72);
   else __builtin_amdgcn_s_waitcnt(0x0F71);
+  __builtin_amdgcn_sched_barrier(0);
 }
 __device__ __forceinline__ void wait_lds0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
 
